@@ -1,0 +1,191 @@
+/*
+ * gsr.h - C ABI of the MI355X (gfx950) GSR-GNN training-step library.
+ *
+ * One training step of the deep grouped-reversible GNN stack of arxiv 2603.27156
+ * ("GSR-GNN"): forward, inverse recomputation in place of stored activations, backward.
+ *
+ *   layer (Section 3, eq. (6)):   Y_0 = sum_{j=2..C} X_j,   Y_i = f_i(Y_{i-1}, A) + X_i,  i = 1..C
+ *   inverse (Section 3, eq. (7)): X_i = Y_i - f_i(Y_{i-1}, A),  i = C..1
+ *   block (Section 4.1, eq. (10)): f_i(Z, A) = ( A * scatter(GS(Z, k)) ) * W_i
+ *   GS (Section 4.1):             per row, the k largest entries by signed value -> (V, I)
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
+ *     ordinary host memory.  The library never frees or reallocates caller memory.
+ *   - gsr_graph_create / gsr_graph_destroy own the device memory of the graph they build.
+ *     No other call allocates device memory; scratch comes from the caller's `workspace`.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream)
+ *     and is asynchronous unless stated.  Calls on one graph / workspace must be ordered.
+ *   - Every call returns a gsr_status_t and never throws or aborts.  gsr_last_error()
+ *     gives a thread-local message for the last failure on the calling thread.
+ *   - Weights W_i are dg x dg, row-major, "in -> out":  O[n][o] = sum_m H[n][m] W_i[m][o].
+ *   - Results are deterministic: no floating-point atomics are used anywhere.
+ */
+#ifndef GSR_H_
+#define GSR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum gsr_status {
+    GSR_OK = 0,
+    GSR_ERR_INVALID_ARG = 1,         /* null pointer, negative size, inconsistent sizes */
+    GSR_ERR_BAD_CSR = 2,             /* non-monotone row pointers, column out of range */
+    GSR_ERR_UNSUPPORTED = 3,         /* C < 2, k < 1, k > D/C, D % C != 0, D/C not in {32, 64}, dtype */
+    GSR_ERR_WORKSPACE_TOO_SMALL = 4, /* workspace_bytes below gsr_workspace_size() */
+    GSR_ERR_HIP = 5                  /* a HIP runtime call failed (message has the HIP error) */
+} gsr_status_t;
+
+/* Storage type of activation planes, gradient planes and compressed values.  All arithmetic
+ * accumulates in float32; weights and weight gradients are always float32. */
+typedef enum gsr_dtype { GSR_F32 = 0, GSR_BF16 = 1 } gsr_dtype_t;
+
+/* Scale applied to the k retained values of a row inside a block.  NONE is the operator as
+ * Section 4.1 defines it.  RMS divides the kept values by sqrt(mean_c Z[n][c]^2 + eps) of
+ * the whole row (no learnable parameters); the selection itself always uses the raw row. */
+typedef enum gsr_norm { GSR_NORM_NONE = 0, GSR_NORM_RMS = 1 } gsr_norm_t;
+
+/* Memory layout of an N x D plane handed to the layer / step calls.
+ * ROW_MAJOR:     element (n, group i, c) at  n*D + i*(D/C) + c      (Split/Concat of eq. (1)
+ *                and Algorithm 1 are then plain column slices).
+ * GROUP_PLANAR:  element (n, group i, c) at  i*N*(D/C) + n*(D/C) + c  (what gsr_step uses
+ *                internally: every per-group pass is one contiguous stream). */
+typedef enum gsr_layout { GSR_LAYOUT_ROW_MAJOR = 0, GSR_LAYOUT_GROUP_PLANAR = 1 } gsr_layout_t;
+
+/* gsr_graph_create flags */
+#define GSR_GRAPH_SYMMETRISE 1u      /* store A + A^T (pattern union)                      */
+#define GSR_GRAPH_ADD_SELF_LOOPS 2u  /* exactly one diagonal entry per row                 */
+#define GSR_GRAPH_GCN_NORM 4u        /* values = d_i^-1/2 d_j^-1/2, d = stored row length  */
+#define GSR_GRAPH_ROWPTR_I64 8u      /* `rowptr` points at int64 (else int32)              */
+
+typedef enum gsr_adj_norm { GSR_ADJ_UNIT = 0, GSR_ADJ_GCN_SYM = 1 } gsr_adj_norm_t;
+
+typedef struct gsr_graph gsr_graph_t; /* opaque */
+
+typedef struct gsr_config {
+    int64_t n;      /* nodes N */
+    int32_t d;      /* feature width D */
+    int32_t c;      /* groups C (>= 2); D/C must be 32 or 64 */
+    int32_t l;      /* layers L (gsr_step only) */
+    int32_t k;      /* retained elements per row per group, 1 <= k <= D/C */
+    int32_t dtype;  /* gsr_dtype_t */
+    int32_t norm;   /* gsr_norm_t */
+    float eps;      /* RMS epsilon */
+    int32_t layout; /* gsr_layout_t of caller-side N x D planes */
+} gsr_config_t;
+
+const char* gsr_last_error(void);
+const char* gsr_version(void);
+
+/* Process-wide tunables, read by the next gsr_graph_create:
+ *   "hub_threshold"   rows with more stored entries than this are reduced in two passes
+ *                     (default 512; Section 2 notes nets with more than 8,000 neighbours)
+ *   "hub_chunk"       neighbours per first-pass partial sum (default 256)
+ *   "max_workgroups"  workgroups of the persistent kernels, multiple of 8 (0: 2 per CU) */
+gsr_status_t gsr_set_option(const char* key, int64_t value);
+
+/* ---- graph: adjacency A of Section 3 (forward aggregates over G, backward over G^T) ----
+ *
+ * Builds the device CSR used by every other call from a host CSR of n rows and nnz entries
+ * (`rowptr`: n+1 int32 or int64; `colidx`: nnz int32 in [0,n), any order, duplicates
+ * allowed).  With SYMMETRISE / ADD_SELF_LOOPS the pattern is transformed first (duplicates
+ * merged, columns ascending).  Values: GCN_NORM computes d_i^-1/2 d_j^-1/2 on the device with
+ * the fixed float32 recipe  dinv = 1.0f/sqrtf((float)deg), a_ij = dinv_i*dinv_j; otherwise
+ * `vals` (host, nnz floats, entries of duplicate positions are summed) or 1.0 when NULL.
+ * The transpose needed by the backward pass is built too unless the result is symmetric.
+ * Synchronous.  *out is owned by the caller until gsr_graph_destroy. */
+gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const void* rowptr,
+                              const int32_t* colidx, const float* vals, uint32_t flags, void* stream);
+
+/* Recompute the stored values on the device: all ones, or the GCN symmetric normalisation of
+ * the stored pattern as defined above.  Asynchronous on `stream`. */
+gsr_status_t gsr_graph_normalize(gsr_graph_t* g, int32_t mode /* gsr_adj_norm_t */, void* stream);
+
+/* Sizes of the stored matrix.  Any output pointer may be NULL.  n_hub_rows = rows whose
+ * length exceeds the split threshold and are reduced in two deterministic passes. */
+gsr_status_t gsr_graph_info(const gsr_graph_t* g, int64_t* n, int64_t* nnz, int64_t* max_degree,
+                            int64_t* n_hub_rows);
+
+/* Copy the stored CSR to host arrays (n+1 int64, nnz int32, nnz float).  Synchronous.
+ * Any output pointer may be NULL. */
+gsr_status_t gsr_graph_export(const gsr_graph_t* g, int64_t* rowptr, int32_t* colidx, float* vals);
+
+gsr_status_t gsr_graph_destroy(gsr_graph_t* g);
+
+/* ---- operators exposed as the paper defines them ----
+ *
+ * GS(X, k) -> (V, I), Section 4.1.  x: device, n rows of dg values of `dtype`, row stride ld
+ * elements; dg in [1, 64].  vals_out: device n*k of `dtype`; idx_out: device n*k int32, slots
+ * in ascending column order.  Largest by signed value; ties to the lowest column; -0 == +0;
+ * inputs must be finite.  norm/eps as in gsr_norm_t (V is the scaled value). */
+gsr_status_t gsr_group_sparse(const void* x, int64_t n, int32_t dg, int64_t ld, int32_t k, int32_t dtype,
+                              int32_t norm, float eps, void* vals_out, int32_t* idx_out, void* stream);
+
+/* Y = A X (transpose = 0) or A^T X (transpose = 1) for dense float32 X: device n x width, row
+ * strides ldx / ldy elements.  The plain neighbour aggregation of Section 3, eq. (2). */
+gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t width, float* y,
+                      int64_t ldy, int32_t transpose, void* stream);
+
+/* H = A * scatter(V, I): the forward block's aggregation of a compressed embedding, Section
+ * 4.1 eq. (10), every neighbour contributing at its own recorded columns.  vals: device n*k
+ * of `dtype`; idx: device n*k int32 (distinct per row, any order); dg in {32, 64};
+ * h_out: device n*dg float32 (dense).  workspace: device scratch of at least
+ * gsr_spmm_compressed_workspace() bytes.  Synchronises the stream once to report indices
+ * that are out of range or repeated (GSR_ERR_INVALID_ARG) instead of reading out of bounds. */
+size_t gsr_spmm_compressed_workspace(const gsr_graph_t* g, int32_t k, int32_t dg);
+gsr_status_t gsr_spmm_compressed(const gsr_graph_t* g, const void* vals, const int32_t* idx, int32_t k,
+                                 int32_t dg, int32_t dtype, float* h_out, void* workspace,
+                                 size_t workspace_bytes, void* stream);
+
+/* ---- layers and the step ----
+ *
+ * Bytes of device workspace the layer / step calls need for (cfg, g).  gsr_step's figure
+ * includes its activation and gradient arena and does not grow with cfg->l (the reversible
+ * scheme's memory is independent of depth, Sections 1 and 2). */
+gsr_status_t gsr_workspace_size(const gsr_config_t* cfg, const gsr_graph_t* g, size_t* layer_bytes,
+                                size_t* step_bytes);
+
+/* eq. (6), in place: x_inout (device, N x D of cfg->dtype in cfg->layout) holds X on entry and
+ * Y = Concat(Y_1..Y_C) on return.  w: device, C matrices dg x dg float32. */
+gsr_status_t gsr_layer_forward(const gsr_graph_t* g, const gsr_config_t* cfg, const float* w,
+                               void* x_inout, void* workspace, size_t workspace_bytes, void* stream);
+
+/* eq. (7), in place: y_inout holds Y on entry and X on return (groups C..2, then Y_0, then 1). */
+gsr_status_t gsr_layer_inverse(const gsr_graph_t* g, const gsr_config_t* cfg, const float* w,
+                               void* y_inout, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of one layer fused with its inverse (Algorithm 2's structure; eq. (3), eq. (11)):
+ * y_inout: Y on entry, the rebuilt X on return; dy_inout: dL/dY on entry, dL/dX on return;
+ * dw_out: device, C x dg x dg float32, overwritten with dL/dW_i.  Each block's input is
+ * rebuilt and consumed once; gradients are read only at the positions recorded by I.
+ * Needs a graph whose transpose is available (symmetric, or built by gsr_graph_create). */
+gsr_status_t gsr_layer_backward(const gsr_graph_t* g, const gsr_config_t* cfg, const float* w,
+                                void* y_inout, void* dy_inout, float* dw_out, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
+/* One training step over cfg->l layers (Algorithm 1 then Algorithm 2; no parameter update):
+ * forward sweep, scalar linear head + mean-squared-error loss, backward sweep with inverse
+ * recomputation.  Nothing is kept per layer.
+ *   x0        device N x D (cfg->dtype, cfg->layout), read only
+ *   w_all     device L x C x dg x dg float32
+ *   w_out     device D float32;  b_out: device 1 float32;  target: device N float32
+ *   loss_out  device 1 float32                      (required)
+ *   yhat_out  device N float32                      (optional, may be NULL)
+ *   dw_all    device L x C x dg x dg float32        (required)
+ *   dw_out    device D float32;  db_out: device 1   (required)
+ *   dx0_out, x0_rebuilt_out, xl_out: device N x D (cfg->dtype, cfg->layout), optional:
+ *             dL/dX^0, the input as rebuilt by the inverse sweep, and X^L. */
+gsr_status_t gsr_step(const gsr_graph_t* g, const gsr_config_t* cfg, const void* x0, const float* w_all,
+                      const float* w_out, const float* b_out, const float* target, float* loss_out,
+                      float* yhat_out, float* dw_all, float* dw_out, float* db_out, void* dx0_out,
+                      void* x0_rebuilt_out, void* xl_out, void* workspace, size_t workspace_bytes,
+                      void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSR_H_ */

@@ -1,0 +1,415 @@
+// Graph construction: adjacency A of Section 3 of the paper as a device CSR, its transpose
+// for the backward pass (gradients flow through G^T), the symmetric GCN normalisation, and
+// the split plan for very long rows.  Also: error strings, options, workspace carving.
+#include "gsr_internal.h"
+
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+namespace gsr {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+gsr_status_t fail(gsr_status_t st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+Options& options() {
+    static Options o;
+    return o;
+}
+
+// ---- normalisation kernels ----------------------------------------------------------------
+
+// dinv[i] = 1/sqrt(stored length of row i), float32, correctly rounded divide and sqrt.
+__global__ void k_dinv(int n, const int32_t* __restrict__ rp, float* __restrict__ dinv) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dinv[i] = 1.0f / sqrtf((float)(rp[i + 1] - rp[i]));
+}
+
+// a_ij = dinv_i * dinv_j for every stored entry; one thread per row chunk keeps it simple and
+// the work is done once per graph.
+__global__ void k_gcn_values(int n, const int32_t* __restrict__ rp, const int32_t* __restrict__ ci,
+                             const float* __restrict__ dinv, float* __restrict__ av) {
+    int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    int lane = threadIdx.x & 63;
+    int nwaves = (gridDim.x * blockDim.x) >> 6;
+    for (int i = wave; i < n; i += nwaves) {
+        float di = dinv[i];
+        for (int e = rp[i] + lane; e < rp[i + 1]; e += 64) av[e] = di * dinv[ci[e]];
+    }
+}
+
+__global__ void k_fill(int64_t n, float v, float* __restrict__ out) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = v;
+}
+
+static gsr_status_t normalise_csr(const Csr& c, int64_t n, int64_t nnz, int32_t mode, hipStream_t s,
+                                  float* dinv_scratch) {
+    if (nnz == 0 || n == 0) return GSR_OK;
+    if (mode == GSR_ADJ_UNIT) {
+        hipLaunchKernelGGL(k_fill, dim3((unsigned)((nnz + 255) / 256)), dim3(256), 0, s, nnz, 1.0f, c.av);
+    } else {
+        hipLaunchKernelGGL(k_dinv, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (int)n, c.rp, dinv_scratch);
+        int blocks = (int)std::min<int64_t>((n + 3) / 4, 4096);
+        hipLaunchKernelGGL(k_gcn_values, dim3(blocks), dim3(256), 0, s, (int)n, c.rp, c.ci, dinv_scratch, c.av);
+    }
+    GSR_HIP_CHECK(hipGetLastError());
+    return GSR_OK;
+}
+
+// ---- host-side structure building -----------------------------------------------------------
+
+struct HostCsr {
+    std::vector<int32_t> rp;
+    std::vector<int32_t> ci;
+    std::vector<float> av;
+};
+
+static void free_csr(Csr& c) {
+    if (c.rp) (void)hipFree(c.rp);
+    if (c.ci) (void)hipFree(c.ci);
+    if (c.av) (void)hipFree(c.av);
+    if (c.hub.rows) (void)hipFree(c.hub.rows);
+    if (c.hub.cptr) (void)hipFree(c.hub.cptr);
+    if (c.hub.crow) (void)hipFree(c.hub.crow);
+    if (c.hub.ce0) (void)hipFree(c.hub.ce0);
+    if (c.hub.ce1) (void)hipFree(c.hub.ce1);
+    c = Csr();
+}
+
+template <typename V>
+static gsr_status_t upload(const std::vector<V>& h, V** d) {
+    size_t bytes = std::max<size_t>(h.size(), 1) * sizeof(V);
+    GSR_HIP_CHECK(hipMalloc((void**)d, bytes));
+    if (!h.empty()) GSR_HIP_CHECK(hipMemcpy(*d, h.data(), h.size() * sizeof(V), hipMemcpyHostToDevice));
+    return GSR_OK;
+}
+
+static gsr_status_t upload_csr(const HostCsr& h, int64_t n, int64_t threshold, int64_t chunk, Csr* out) {
+    GSR_TRY(upload(h.rp, &out->rp));
+    GSR_TRY(upload(h.ci, &out->ci));
+    GSR_TRY(upload(h.av, &out->av));
+    std::vector<int32_t> rows, cptr, crow, ce0, ce1;
+    cptr.push_back(0);
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t len = h.rp[i + 1] - h.rp[i];
+        if (len <= threshold) continue;
+        rows.push_back((int32_t)i);
+        for (int64_t e = h.rp[i]; e < h.rp[i + 1]; e += chunk) {
+            crow.push_back((int32_t)i);
+            ce0.push_back((int32_t)e);
+            ce1.push_back((int32_t)std::min<int64_t>(e + chunk, h.rp[i + 1]));
+        }
+        cptr.push_back((int32_t)crow.size());
+    }
+    out->hub.n_hub = (int32_t)rows.size();
+    out->hub.n_chunks = (int32_t)crow.size();
+    GSR_TRY(upload(rows, &out->hub.rows));
+    GSR_TRY(upload(cptr, &out->hub.cptr));
+    GSR_TRY(upload(crow, &out->hub.crow));
+    GSR_TRY(upload(ce0, &out->hub.ce0));
+    GSR_TRY(upload(ce1, &out->hub.ce1));
+    return GSR_OK;
+}
+
+// Sort the columns of every row, merge duplicates (values summed).
+static void canonicalise(int64_t n, std::vector<int64_t>& rp64, std::vector<int32_t>& ci, std::vector<float>& av,
+                         HostCsr* out) {
+    out->rp.assign(n + 1, 0);
+    out->ci.clear();
+    out->av.clear();
+    out->ci.reserve(ci.size());
+    out->av.reserve(ci.size());
+    std::vector<std::pair<int32_t, float>> row;
+    for (int64_t i = 0; i < n; ++i) {
+        row.clear();
+        for (int64_t e = rp64[i]; e < rp64[i + 1]; ++e) row.emplace_back(ci[e], av[e]);
+        std::stable_sort(row.begin(), row.end(),
+                         [](const std::pair<int32_t, float>& a, const std::pair<int32_t, float>& b) {
+                             return a.first < b.first;
+                         });
+        for (size_t p = 0; p < row.size(); ++p) {
+            if (p > 0 && row[p].first == row[p - 1].first) {
+                out->av.back() += row[p].second;
+            } else {
+                out->ci.push_back(row[p].first);
+                out->av.push_back(row[p].second);
+            }
+        }
+        out->rp[i + 1] = (int32_t)out->ci.size();
+    }
+}
+
+static void transpose_host(int64_t n, const HostCsr& a, HostCsr* t) {
+    int64_t nnz = (int64_t)a.ci.size();
+    t->rp.assign(n + 1, 0);
+    t->ci.assign(nnz, 0);
+    t->av.assign(nnz, 0.f);
+    for (int64_t e = 0; e < nnz; ++e) t->rp[a.ci[e] + 1]++;
+    for (int64_t i = 0; i < n; ++i) t->rp[i + 1] += t->rp[i];
+    std::vector<int32_t> fill(t->rp.begin(), t->rp.end() - 1);
+    for (int64_t i = 0; i < n; ++i)
+        for (int32_t e = a.rp[i]; e < a.rp[i + 1]; ++e) {
+            int32_t p = fill[a.ci[e]]++;
+            t->ci[p] = (int32_t)i;
+            t->av[p] = a.av[e];
+        }
+}
+
+LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
+    LayerWs w;
+    memset(&w, 0, sizeof(w));
+    size_t n = (size_t)cfg->n, dg = (size_t)(cfg->d / cfg->c), b = dtype_size(cfg->dtype);
+    size_t off = 0;
+    for (int s = 0; s < cfg->c && s < 8; ++s) {
+        w.rec_vals[s] = off;
+        off += align_up(n * (size_t)cfg->k * b);
+        w.rec_mask[s] = off;
+        off += align_up(n * (dg == 32 ? 4 : 8));
+    }
+    w.y0 = off;
+    off += align_up(n * dg * b);
+    w.dw_partial = off;
+    off += align_up((size_t)g->grid * dg * dg * sizeof(float));
+    w.hub_partial = off;
+    size_t chunks = (size_t)std::max(g->a.hub.n_chunks, g->at.hub.n_chunks);
+    off += align_up(std::max<size_t>(chunks, 1) * dg * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+StepWs carve_step(const gsr_config_t* cfg, const gsr_graph_t* g) {
+    StepWs w;
+    size_t n = (size_t)cfg->n, b = dtype_size(cfg->dtype);
+    size_t off = 0;
+    w.act = off;
+    off += align_up(n * (size_t)cfg->d * b);
+    w.grad = off;
+    off += align_up(n * (size_t)cfg->d * b);
+    w.head = off;
+    off += align_up((size_t)g->grid * ((size_t)cfg->d + 2) * sizeof(float));
+    w.layer = off;
+    off += carve_layer(cfg, g).total;
+    w.total = off;
+    return w;
+}
+
+gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool need_l) {
+    if (!cfg || !g) return fail(GSR_ERR_INVALID_ARG, "null config or graph");
+    if (cfg->n != g->n) return fail(GSR_ERR_INVALID_ARG, "config n=%lld differs from graph n=%lld",
+                                    (long long)cfg->n, (long long)g->n);
+    if (cfg->c < 2 || cfg->c > 8) return fail(GSR_ERR_UNSUPPORTED, "groups C=%d outside [2,8]", cfg->c);
+    if (cfg->d <= 0 || cfg->d % cfg->c != 0) return fail(GSR_ERR_UNSUPPORTED, "D=%d not divisible by C=%d", cfg->d, cfg->c);
+    int dg = cfg->d / cfg->c;
+    if (dg != 32 && dg != 64) return fail(GSR_ERR_UNSUPPORTED, "D/C=%d: only 32 and 64 are built", dg);
+    if (cfg->k < 1 || cfg->k > dg) return fail(GSR_ERR_UNSUPPORTED, "k=%d outside [1, D/C=%d]", cfg->k, dg);
+    if (cfg->dtype != GSR_F32 && cfg->dtype != GSR_BF16) return fail(GSR_ERR_UNSUPPORTED, "dtype %d", cfg->dtype);
+    if (cfg->norm != GSR_NORM_NONE && cfg->norm != GSR_NORM_RMS) return fail(GSR_ERR_UNSUPPORTED, "norm %d", cfg->norm);
+    if (cfg->layout != GSR_LAYOUT_ROW_MAJOR && cfg->layout != GSR_LAYOUT_GROUP_PLANAR)
+        return fail(GSR_ERR_UNSUPPORTED, "layout %d", cfg->layout);
+    if (need_l && cfg->l < 1) return fail(GSR_ERR_INVALID_ARG, "layers L=%d", cfg->l);
+    if (!(cfg->eps >= 0.f)) return fail(GSR_ERR_INVALID_ARG, "eps must be >= 0");
+    return GSR_OK;
+}
+
+}  // namespace gsr
+
+using namespace gsr;
+
+extern "C" {
+
+const char* gsr_last_error(void) { return g_err; }
+const char* gsr_version(void) { return "gsr-mi355x 0.1 (gfx950)"; }
+
+gsr_status_t gsr_set_option(const char* key, int64_t value) {
+    if (!key) return fail(GSR_ERR_INVALID_ARG, "null key");
+    Options& o = options();
+    if (!strcmp(key, "hub_threshold")) {
+        if (value < 1) return fail(GSR_ERR_INVALID_ARG, "hub_threshold must be >= 1");
+        o.hub_threshold = value;
+    } else if (!strcmp(key, "hub_chunk")) {
+        if (value < 1) return fail(GSR_ERR_INVALID_ARG, "hub_chunk must be >= 1");
+        o.hub_chunk = value;
+    } else if (!strcmp(key, "max_workgroups")) {
+        if (value < 0 || value % 8 != 0) return fail(GSR_ERR_INVALID_ARG, "max_workgroups must be a multiple of 8");
+        o.max_workgroups = value;
+    } else {
+        return fail(GSR_ERR_INVALID_ARG, "unknown option '%s'", key);
+    }
+    return GSR_OK;
+}
+
+gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const void* rowptr,
+                              const int32_t* colidx, const float* vals, uint32_t flags, void* stream) {
+    if (!out) return fail(GSR_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (n < 0 || nnz < 0) return fail(GSR_ERR_INVALID_ARG, "negative size");
+    if (!rowptr || (nnz > 0 && !colidx)) return fail(GSR_ERR_INVALID_ARG, "null CSR array");
+    if (n >= (int64_t)1 << 31) return fail(GSR_ERR_UNSUPPORTED, "n >= 2^31");
+    if ((flags & GSR_GRAPH_GCN_NORM) && vals) return fail(GSR_ERR_INVALID_ARG, "GCN_NORM and explicit values are exclusive");
+
+    // ---- validate and widen the input
+    std::vector<int64_t> rp64(n + 1);
+    for (int64_t i = 0; i <= n; ++i)
+        rp64[i] = (flags & GSR_GRAPH_ROWPTR_I64) ? ((const int64_t*)rowptr)[i] : (int64_t)((const int32_t*)rowptr)[i];
+    if (rp64[0] != 0 || rp64[n] != nnz) return fail(GSR_ERR_BAD_CSR, "rowptr[0]=%lld, rowptr[n]=%lld, nnz=%lld",
+                                                    (long long)rp64[0], (long long)rp64[n], (long long)nnz);
+    for (int64_t i = 0; i < n; ++i)
+        if (rp64[i + 1] < rp64[i]) return fail(GSR_ERR_BAD_CSR, "row pointers decrease at row %lld", (long long)i);
+    for (int64_t e = 0; e < nnz; ++e)
+        if (colidx[e] < 0 || colidx[e] >= n) return fail(GSR_ERR_BAD_CSR, "column %d out of range at entry %lld", colidx[e], (long long)e);
+
+    // ---- pattern transforms: symmetrise, self-loops
+    std::vector<int64_t> rp2;
+    std::vector<int32_t> ci2;
+    std::vector<float> av2;
+    const bool sym = flags & GSR_GRAPH_SYMMETRISE, loops = flags & GSR_GRAPH_ADD_SELF_LOOPS;
+    if (sym || loops) {
+        std::vector<int64_t> cnt(n + 1, 0);
+        for (int64_t i = 0; i < n; ++i) {
+            for (int64_t e = rp64[i]; e < rp64[i + 1]; ++e) {
+                int32_t j = colidx[e];
+                if (loops && j == i) continue;      // existing diagonal entries collapse into the one self-loop
+                cnt[i + 1]++;
+                if (sym && j != i) cnt[j + 1]++;
+            }
+            if (loops) cnt[i + 1]++;
+        }
+        for (int64_t i = 0; i < n; ++i) cnt[i + 1] += cnt[i];
+        ci2.resize(cnt[n]);
+        av2.resize(cnt[n]);
+        std::vector<int64_t> fill(cnt.begin(), cnt.end() - 1);
+        for (int64_t i = 0; i < n; ++i) {
+            if (loops) { ci2[fill[i]] = (int32_t)i; av2[fill[i]++] = 1.0f; }
+            for (int64_t e = rp64[i]; e < rp64[i + 1]; ++e) {
+                int32_t j = colidx[e];
+                if (loops && j == i) continue;
+                float v = vals ? vals[e] : 1.0f;
+                ci2[fill[i]] = j; av2[fill[i]++] = v;
+                if (sym && j != i) { ci2[fill[j]] = (int32_t)i; av2[fill[j]++] = v; }
+            }
+        }
+        rp2 = cnt;
+    } else {
+        rp2 = rp64;
+        ci2.assign(colidx, colidx + nnz);
+        av2.resize(nnz);
+        for (int64_t e = 0; e < nnz; ++e) av2[e] = vals ? vals[e] : 1.0f;
+    }
+    if ((int64_t)ci2.size() >= ((int64_t)1 << 31)) return fail(GSR_ERR_UNSUPPORTED, "more than 2^31 stored entries");
+    HostCsr a;
+    canonicalise(n, rp2, ci2, av2, &a);
+    // duplicates of a unit-weight pattern stay unit weight (pattern union, not a multigraph)
+    if (!vals) std::fill(a.av.begin(), a.av.end(), 1.0f);
+    std::vector<int64_t>().swap(rp2);
+    std::vector<int32_t>().swap(ci2);
+    std::vector<float>().swap(av2);
+
+    HostCsr t;
+    transpose_host(n, a, &t);
+    bool symmetric = (a.rp == t.rp) && (a.ci == t.ci) && (a.av == t.av);
+
+    gsr_graph_t* g = new (std::nothrow) gsr_graph_t();
+    if (!g) return fail(GSR_ERR_INVALID_ARG, "out of host memory");
+    g->n = n;
+    g->nnz = (int64_t)a.ci.size();
+    for (int64_t i = 0; i < n; ++i) g->max_degree = std::max<int64_t>(g->max_degree, a.rp[i + 1] - a.rp[i]);
+    g->symmetric = symmetric;
+    g->has_transpose = true;
+    g->hub_threshold = (int32_t)options().hub_threshold;
+
+    hipError_t e = hipGetDevice(&g->device);
+    if (e != hipSuccess) { delete g; return fail(GSR_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e)); }
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, g->device);
+    if (e != hipSuccess) { delete g; return fail(GSR_ERR_HIP, "hipGetDeviceProperties: %s", hipGetErrorString(e)); }
+    g->num_cus = prop.multiProcessorCount;
+    int grid = options().max_workgroups > 0 ? (int)options().max_workgroups : g->num_cus * 2;
+    g->grid = std::max(8, grid / 8 * 8);
+
+    gsr_status_t st = upload_csr(a, n, options().hub_threshold, options().hub_chunk, &g->a);
+    if (st == GSR_OK) {
+        if (symmetric) g->at = g->a;
+        else st = upload_csr(t, n, options().hub_threshold, options().hub_chunk, &g->at);
+    }
+    if (st == GSR_OK && (flags & GSR_GRAPH_GCN_NORM)) st = gsr_graph_normalize(g, GSR_ADJ_GCN_SYM, stream);
+    if (st == GSR_OK) {
+        e = hipStreamSynchronize((hipStream_t)stream);
+        if (e != hipSuccess) st = fail(GSR_ERR_HIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    }
+    if (st != GSR_OK) { gsr_graph_destroy(g); return st; }
+    *out = g;
+    return GSR_OK;
+}
+
+gsr_status_t gsr_graph_normalize(gsr_graph_t* g, int32_t mode, void* stream) {
+    if (!g) return fail(GSR_ERR_INVALID_ARG, "graph is null");
+    if (mode != GSR_ADJ_UNIT && mode != GSR_ADJ_GCN_SYM) return fail(GSR_ERR_INVALID_ARG, "unknown normalisation %d", mode);
+    if (mode == GSR_ADJ_GCN_SYM && !g->symmetric)
+        return fail(GSR_ERR_UNSUPPORTED, "symmetric GCN normalisation needs a symmetric stored pattern");
+    hipStream_t s = (hipStream_t)stream;
+    float* dinv = nullptr;
+    GSR_HIP_CHECK(hipMalloc((void**)&dinv, std::max<size_t>((size_t)g->n, 1) * sizeof(float)));
+    gsr_status_t st = normalise_csr(g->a, g->n, g->nnz, mode, s, dinv);
+    if (st == GSR_OK && !g->symmetric) st = normalise_csr(g->at, g->n, g->nnz, mode, s, dinv);
+    hipError_t e = hipStreamSynchronize(s);
+    (void)hipFree(dinv);
+    if (st == GSR_OK && e != hipSuccess) st = fail(GSR_ERR_HIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    return st;
+}
+
+gsr_status_t gsr_graph_info(const gsr_graph_t* g, int64_t* n, int64_t* nnz, int64_t* max_degree, int64_t* n_hub_rows) {
+    if (!g) return fail(GSR_ERR_INVALID_ARG, "graph is null");
+    if (n) *n = g->n;
+    if (nnz) *nnz = g->nnz;
+    if (max_degree) *max_degree = g->max_degree;
+    if (n_hub_rows) *n_hub_rows = g->a.hub.n_hub;
+    return GSR_OK;
+}
+
+gsr_status_t gsr_graph_export(const gsr_graph_t* g, int64_t* rowptr, int32_t* colidx, float* vals) {
+    if (!g) return fail(GSR_ERR_INVALID_ARG, "graph is null");
+    GSR_HIP_CHECK(hipDeviceSynchronize());
+    if (rowptr) {
+        std::vector<int32_t> rp(g->n + 1);
+        GSR_HIP_CHECK(hipMemcpy(rp.data(), g->a.rp, (g->n + 1) * sizeof(int32_t), hipMemcpyDeviceToHost));
+        for (int64_t i = 0; i <= g->n; ++i) rowptr[i] = rp[i];
+    }
+    if (colidx && g->nnz) GSR_HIP_CHECK(hipMemcpy(colidx, g->a.ci, g->nnz * sizeof(int32_t), hipMemcpyDeviceToHost));
+    if (vals && g->nnz) GSR_HIP_CHECK(hipMemcpy(vals, g->a.av, g->nnz * sizeof(float), hipMemcpyDeviceToHost));
+    return GSR_OK;
+}
+
+gsr_status_t gsr_graph_destroy(gsr_graph_t* g) {
+    if (!g) return GSR_OK;
+    if (!g->symmetric) free_csr(g->at);
+    free_csr(g->a);
+    delete g;
+    return GSR_OK;
+}
+
+gsr_status_t gsr_workspace_size(const gsr_config_t* cfg, const gsr_graph_t* g, size_t* layer_bytes, size_t* step_bytes) {
+    GSR_TRY(validate_config(cfg, g, false));
+    if (layer_bytes) *layer_bytes = carve_layer(cfg, g).total;
+    if (step_bytes) *step_bytes = carve_step(cfg, g).total;
+    return GSR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,100 @@
+// Internal declarations shared by the translation units of libgsr (host side).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gsr.h"
+
+namespace gsr {
+
+// ---- error plumbing -------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+gsr_status_t fail(gsr_status_t st, const char* fmt, ...);
+
+#define GSR_HIP_CHECK(expr)                                                                  \
+    do {                                                                                     \
+        hipError_t _e = (expr);                                                              \
+        if (_e != hipSuccess)                                                                \
+            return gsr::fail(GSR_ERR_HIP, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), \
+                             __FILE__, __LINE__);                                            \
+    } while (0)
+
+#define GSR_TRY(expr)                          \
+    do {                                       \
+        gsr_status_t _s = (expr);              \
+        if (_s != GSR_OK) return _s;           \
+    } while (0)
+
+// ---- tunables (gsr_set_option) ----------------------------------------------------------
+struct Options {
+    int64_t hub_threshold = 512;  // rows longer than this are reduced in two passes
+    int64_t hub_chunk = 256;      // neighbours per first-pass partial
+    int64_t max_workgroups = 0;   // 0: derive from the device (multiple of 8)
+};
+Options& options();
+
+// ---- CSR on the device --------------------------------------------------------------------
+// Rows longer than `hub_threshold` ("hub" rows: clock/reset-like nets) are cut into chunks of
+// `hub_chunk` neighbours.  A first kernel reduces every chunk to one partial row, the main
+// kernel then adds a hub row's partials in chunk order, so the summation order is fixed.
+struct HubPlan {
+    int32_t n_hub = 0;        // hub rows
+    int32_t n_chunks = 0;     // chunks over all hub rows
+    int32_t* rows = nullptr;  // device [n_hub]    ascending row ids
+    int32_t* cptr = nullptr;  // device [n_hub+1]  first chunk of each hub row
+    int32_t* crow = nullptr;  // device [n_chunks] row of the chunk
+    int32_t* ce0 = nullptr;   // device [n_chunks] first edge
+    int32_t* ce1 = nullptr;   // device [n_chunks] one past the last edge
+};
+
+struct Csr {
+    int32_t* rp = nullptr;  // device [n+1]
+    int32_t* ci = nullptr;  // device [nnz]
+    float* av = nullptr;    // device [nnz]
+    HubPlan hub;
+};
+
+}  // namespace gsr
+
+struct gsr_graph {
+    int64_t n = 0, nnz = 0, max_degree = 0;
+    gsr::Csr a;              // A
+    gsr::Csr at;             // A^T (aliases `a` when symmetric)
+    bool symmetric = false;
+    bool has_transpose = false;
+    int32_t hub_threshold = 512;
+    int device = 0;
+    int num_cus = 256;
+    int grid = 512;          // workgroups of the persistent row-tile kernels (multiple of 8)
+};
+
+namespace gsr {
+
+// gsr_graph.hip
+gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool need_l);
+
+// Workspace carving shared by gsr_workspace_size and the layer / step calls.
+struct LayerWs {
+    size_t rec_vals[8];  // per slot: compressed values  [n][k] of T
+    size_t rec_mask[8];  // per slot: column bit mask    [n] of uint32 (dg=32) / uint64 (dg=64)
+    size_t y0;           // Y_0 plane [n][dg] of T (C > 2)
+    size_t dw_partial;   // [grid][dg*dg] float
+    size_t hub_partial;  // [max(n_chunks A, n_chunks A^T)][dg] float
+    size_t total;
+};
+struct StepWs {
+    size_t act;   // [C][n][dg] of T
+    size_t grad;  // [C][n][dg] of T
+    size_t head;  // [grid][D + 2] float
+    size_t layer; // LayerWs starts here
+    size_t total;
+};
+LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g);
+StepWs carve_step(const gsr_config_t* cfg, const gsr_graph_t* g);
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+inline size_t dtype_size(int32_t dtype) { return dtype == GSR_BF16 ? 2 : 4; }
+
+}  // namespace gsr

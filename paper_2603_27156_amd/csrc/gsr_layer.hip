@@ -1,0 +1,594 @@
+// The grouped reversible layer (Section 3, eq. (6)/(7)), its backward fused with the inverse
+// (Algorithm 2's structure; eq. (3), eq. (11)) and the whole training step.
+//
+// Kernels (all persistent over 16-row tiles, one wave per tile, no cross-wave synchronisation
+// inside the sweep):
+//   k_block   H = A*scatter(V,I) of Y_{i-1} gathered from compressed records; O = H W_i on the
+//             matrix cores; Y_i = X_i + O (forward) or X_i = Y_i - O (inverse), in place; the GS
+//             record of the row just written is emitted in the same pass.  With WITH_DW it also
+//             accumulates dW_i += H^T dY_i, so the recomputed H is consumed where it is rebuilt.
+//   k_grad    Q = A^T dY_i (dense-row gather); dH = Q W_i^T on the matrix cores; only the k
+//             positions recorded by I are read; back through the RMS scale; dY_{i-1} += dZ.
+//   k_sum     Y_0 = sum_{j>=2} X_j and/or the GS record of a plane.
+//   k_head    scalar linear head, squared error, dX^L, partial sums for dw_out / db / loss.
+#include "gsr_internal.h"
+#include "gsr_device.h"
+
+#include <algorithm>
+
+namespace gsr {
+
+CsrView make_view(const gsr_graph_t* g, bool transpose);
+
+template <int DG, typename T>
+__device__ __forceinline__ void emit_record(float yq, bool ok, int row, int c, int sub, int k, int norm, float eps,
+                                            T* __restrict__ out_vals, typename MaskOf<DG>::type* __restrict__ out_mask) {
+    using M = typename MaskOf<DG>::type;
+    M mask;
+    const bool sel = topk_select<DG>(ok ? yq : 0.f, k, c, sub, &mask);
+    float scale = 1.f;
+    if (norm == GSR_NORM_RMS) {
+        const float ss = sub_sum<DG>(ok ? yq * yq : 0.f);
+        scale = 1.0f / sqrtf(ss / (float)DG + eps);
+    }
+    if (ok && sel) out_vals[(size_t)row * k + popc<DG>(mask & (((M)1 << c) - 1))] = from_float<T>(yq * scale);
+    if (ok && c == 0) out_mask[row] = mask;
+}
+
+// ---- block: forward / inverse (+ weight gradient) ------------------------------------------------
+template <int DG, typename T>
+struct BlockArgs {
+    using M = typename MaskOf<DG>::type;
+    CsrView g;
+    int n, tiles;
+    const T* rec_vals;      // record of Y_{i-1}: values, ascending column order  [n][k]
+    const M* rec_mask;      //                    column bit mask                 [n]
+    int k;
+    const float* hub_part;  // first-pass partial rows of hub rows
+    const float* w;         // W_i [DG][DG]
+    T* plane;               // X_i on entry / Y_i on return (or the reverse), row stride ld
+    int64_t ld;
+    T* out_vals;            // record of the row written (NULL: none)
+    M* out_mask;
+    int norm;
+    float eps;
+    const T* dy;            // dY_i, row stride ldg            (WITH_DW)
+    int64_t ldg;
+    float* dw_partial;      // [gridDim.x][DG*DG]              (WITH_DW)
+};
+
+template <int DG, typename T, int SIGN, bool WITH_DW>
+__global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
+    constexpr int G = 64 / DG, LR = DG + 1, ST = 16 * LR;
+    __shared__ float lds[4 * (WITH_DW ? 2 : 1) * ST];
+    const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
+    float* st_h = lds + wave * (WITH_DW ? 2 : 1) * ST;
+    float* st_g = st_h + ST;
+    WFrag<DG> wf;
+    load_wfrag<DG>(a.w, false, wf);
+    f32x4 dw[WITH_DW ? DG / 16 : 1][WITH_DW ? DG / 16 : 1];
+    if constexpr (WITH_DW) {
+#pragma unroll
+        for (int mb = 0; mb < DG / 16; ++mb)
+#pragma unroll
+            for (int ob = 0; ob < DG / 16; ++ob) dw[mb][ob] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const TileSweep ts = tile_sweep(a.tiles);
+    for (int t = ts.first; t < ts.end; t += ts.step) {
+        const int r0 = t * 16;
+#pragma unroll 1
+        for (int it = 0; it < 16 / G; ++it) {
+            const int r = it * G + sub, row = r0 + r;
+            const bool ok = row < a.n;
+            st_h[r * LR + c] = row_records<DG, T>(a.g, a.rec_vals, a.rec_mask, a.k, a.hub_part, row, ok, c);
+            if constexpr (WITH_DW) st_g[r * LR + c] = ok ? to_float(a.dy[(size_t)row * a.ldg + c]) : 0.f;
+        }
+        wave_sync();
+        f32x4 acc[DG / 16];
+        mfma_tile<DG>(st_h, wf, acc);
+        if constexpr (WITH_DW) mfma_outer<DG>(st_h, st_g, dw);
+        wave_sync();
+        store_tile<DG>(st_h, acc);
+        wave_sync();
+#pragma unroll 1
+        for (int it = 0; it < 16 / G; ++it) {
+            const int r = it * G + sub, row = r0 + r;
+            const bool ok = row < a.n;
+            const float o = st_h[r * LR + c];
+            const float x = ok ? to_float(a.plane[(size_t)row * a.ld + c]) : 0.f;
+            const T yt = from_float<T>(SIGN > 0 ? x + o : x - o);
+            if (ok) a.plane[(size_t)row * a.ld + c] = yt;
+            if (a.out_mask) emit_record<DG, T>(to_float(yt), ok, row, c, sub, a.k, a.norm, a.eps, a.out_vals, a.out_mask);
+        }
+        wave_sync();
+    }
+    if constexpr (WITH_DW) {
+        // workgroup partial of dW_i: the four waves add their accumulators in wave order
+        for (int w = 0; w < 4; ++w) {
+            __syncthreads();
+            if (wave == w) {
+#pragma unroll
+                for (int mb = 0; mb < DG / 16; ++mb)
+#pragma unroll
+                    for (int ob = 0; ob < DG / 16; ++ob)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int m = 16 * mb + 4 * (lane >> 4) + r, o = 16 * ob + (lane & 15);
+                            if (w == 0) lds[m * DG + o] = dw[mb][ob][r];
+                            else lds[m * DG + o] += dw[mb][ob][r];
+                        }
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < DG * DG; i += 256) a.dw_partial[(size_t)blockIdx.x * DG * DG + i] = lds[i];
+    }
+}
+
+// dW_i[e] = sum over workgroup partials, ascending
+__global__ void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems, float* __restrict__ out) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= elems) return;
+    float acc = 0.f;
+    for (int p = 0; p < nparts; ++p) acc += partial[(size_t)p * elems + e];
+    out[e] = acc;
+}
+
+// ---- block: data gradient ---------------------------------------------------------------------------
+template <int DG, typename T>
+struct GradArgs {
+    using M = typename MaskOf<DG>::type;
+    CsrView gt;             // A^T
+    int n, tiles;
+    const T* dy;            // dY_i (complete), row stride ldg
+    int64_t ldg;
+    const float* hub_part;
+    const float* w;         // W_i
+    const M* own_mask;      // columns recorded for Y_{i-1}
+    const T* z;             // Y_{i-1} rows (RMS only), row stride ldz
+    int64_t ldz;
+    int norm;
+    float eps;
+    T* dst;                 // dY_{i-1} plane(s): ndst planes, dst_gs apart, row stride ldd
+    int64_t ldd, dst_gs;
+    int ndst;
+};
+
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_grad(GradArgs<DG, T> a) {
+    constexpr int G = 64 / DG, LR = DG + 1, ST = 16 * LR;
+    __shared__ float lds[4 * ST];
+    const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
+    float* st = lds + wave * ST;
+    WFrag<DG> wf;
+    load_wfrag<DG>(a.w, true, wf);
+    const TileSweep ts = tile_sweep(a.tiles);
+    for (int t = ts.first; t < ts.end; t += ts.step) {
+        const int r0 = t * 16;
+#pragma unroll 1
+        for (int it = 0; it < 16 / G; ++it) {
+            const int r = it * G + sub, row = r0 + r;
+            st[r * LR + c] = row_dense<DG, T>(a.gt, a.dy, a.ldg, a.hub_part, row, row < a.n, c);
+        }
+        wave_sync();
+        f32x4 acc[DG / 16];
+        mfma_tile<DG>(st, wf, acc);      // dH = Q W^T
+        wave_sync();
+        store_tile<DG>(st, acc);
+        wave_sync();
+#pragma unroll 1
+        for (int it = 0; it < 16 / G; ++it) {
+            const int r = it * G + sub, row = r0 + r;
+            const bool ok = row < a.n;
+            const float gdh = st[r * LR + c];
+            const bool sel = ok && ((a.own_mask[row] >> c) & 1);
+            float dz = sel ? gdh : 0.f;
+            bool touch = sel;
+            if (a.norm == GSR_NORM_RMS) {
+                const float zz = ok ? to_float(a.z[(size_t)row * a.ldz + c]) : 0.f;
+                const float ss = sub_sum<DG>(zz * zz);
+                const float rr = sqrtf(ss / (float)DG + a.eps);
+                const float dot = sub_sum<DG>(sel ? gdh * zz : 0.f);
+                dz = (sel ? gdh / rr : 0.f) - zz * (dot / ((float)DG * rr * rr * rr));
+                touch = ok;
+            }
+            if (touch)
+                for (int j = 0; j < a.ndst; ++j) {
+                    T* p = a.dst + (size_t)j * a.dst_gs + (size_t)row * a.ldd + c;
+                    *p = from_float<T>(to_float(*p) + dz);
+                }
+        }
+        wave_sync();
+    }
+}
+
+// ---- group sum / record of a plane --------------------------------------------------------------------
+template <int DG, typename T>
+struct SumArgs {
+    using M = typename MaskOf<DG>::type;
+    int n;
+    const T* src;           // nsrc planes, src_gs apart, row stride ld
+    int64_t ld, src_gs;
+    int nsrc;
+    T* y0;                  // dense [n][DG] copy of the sum (NULL: not kept)
+    int k, norm;
+    float eps;
+    T* out_vals;
+    M* out_mask;
+};
+
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
+    constexpr int G = 64 / DG;
+    const int lane = lane_id(), c = lane % DG, sub = lane / DG;
+    const int nwaves = (gridDim.x * blockDim.x) >> 6;
+    for (int r0 = ((blockIdx.x * blockDim.x + threadIdx.x) >> 6) * G; r0 < a.n; r0 += nwaves * G) {
+        const int row = r0 + sub;
+        const bool ok = row < a.n;
+        float s = 0.f;
+        if (ok) {
+            s = to_float(a.src[(size_t)row * a.ld + c]);
+            for (int j = 1; j < a.nsrc; ++j) s += to_float(a.src[(size_t)j * a.src_gs + (size_t)row * a.ld + c]);
+        }
+        const T st = from_float<T>(s);
+        if (ok && a.y0) a.y0[(size_t)row * DG + c] = st;
+        emit_record<DG, T>(to_float(st), ok, row, c, sub, a.k, a.norm, a.eps, a.out_vals, a.out_mask);
+    }
+}
+
+// ---- head: yhat = X w + b, loss = mean (yhat - t)^2 ----------------------------------------------------
+template <typename T>
+struct HeadArgs {
+    int n, d, dg;
+    const T* act;           // element (row, grp, c) at grp*gs + row*ld + c
+    T* grad;                // same layout
+    int64_t ld, gs;
+    const float* w_out;
+    const float* b_out;
+    const float* target;
+    float* yhat;            // may be NULL
+    float* partial;         // [gridDim.x][d + 2]: dw (d), db, sum of squared errors
+};
+
+constexpr int HEAD_MAXQ = 8;  // d <= 512
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_head(HeadArgs<T> a) {
+    __shared__ float red[4][HEAD_MAXQ * 64 + 2];
+    const int lane = lane_id(), wave = threadIdx.x >> 6;
+    const int nq = (a.d + 63) / 64;
+    float wv[HEAD_MAXQ], dwacc[HEAD_MAXQ];
+    size_t off[HEAD_MAXQ];
+#pragma unroll
+    for (int q = 0; q < HEAD_MAXQ; ++q) {
+        const int cc = q * 64 + lane;
+        const bool in = q < nq && cc < a.d;
+        wv[q] = in ? a.w_out[cc] : 0.f;
+        dwacc[q] = 0.f;
+        off[q] = in ? (size_t)(cc / a.dg) * a.gs + (cc % a.dg) : 0;
+    }
+    const float bias = a.b_out[0];
+    float db = 0.f, sse = 0.f;
+    const int nwaves = (gridDim.x * blockDim.x) >> 6;
+    for (int row = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; row < a.n; row += nwaves) {
+        float xv[HEAD_MAXQ];
+        float dot = 0.f;
+#pragma unroll
+        for (int q = 0; q < HEAD_MAXQ; ++q) {
+            const bool in = q < nq && q * 64 + lane < a.d;
+            xv[q] = in ? to_float(a.act[off[q] + (size_t)row * a.ld]) : 0.f;
+            dot += xv[q] * wv[q];
+        }
+        const float y = sub_sum<64>(dot) + bias;
+        const float e = y - a.target[row];
+        const float gy = 2.0f * e / (float)a.n;
+        if (lane == 0 && a.yhat) a.yhat[row] = y;
+        db += gy;
+        sse += e * e;
+#pragma unroll
+        for (int q = 0; q < HEAD_MAXQ; ++q) {
+            const bool in = q < nq && q * 64 + lane < a.d;
+            dwacc[q] += xv[q] * gy;
+            if (in) a.grad[off[q] + (size_t)row * a.ld] = from_float<T>(gy * wv[q]);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < HEAD_MAXQ; ++q) red[wave][q * 64 + lane] = dwacc[q];
+    if (lane == 0) { red[wave][HEAD_MAXQ * 64] = db; red[wave][HEAD_MAXQ * 64 + 1] = sse; }
+    __syncthreads();
+    for (int i = threadIdx.x; i < a.d + 2; i += 256) {
+        const int src = i < a.d ? i : HEAD_MAXQ * 64 + (i - a.d);
+        a.partial[(size_t)blockIdx.x * (a.d + 2) + i] = ((red[0][src] + red[1][src]) + red[2][src]) + red[3][src];
+    }
+}
+
+__global__ void k_head_reduce(const float* __restrict__ partial, int nparts, int d, int n, float* __restrict__ dw_out,
+                              float* __restrict__ db_out, float* __restrict__ loss_out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= d + 2) return;
+    float acc = 0.f;
+    for (int p = 0; p < nparts; ++p) acc += partial[(size_t)p * (d + 2) + i];
+    if (i < d) dw_out[i] = acc;
+    else if (i == d) db_out[0] = acc;
+    else loss_out[0] = acc / (float)n;
+}
+
+// ---- layout copy: (row, grp, c) between two stride sets ---------------------------------------------------
+template <typename T>
+__global__ void k_copy_planes(int64_t n, int dg, int ngroups, const T* __restrict__ src, int64_t s_ld, int64_t s_gs,
+                              T* __restrict__ dst, int64_t d_ld, int64_t d_gs) {
+    const int64_t total = n * dg * ngroups;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int c = (int)(i % dg);
+        const int64_t t = i / dg;
+        const int grp = (int)(t % ngroups);
+        const int64_t row = t / ngroups;
+        dst[grp * d_gs + row * d_ld + c] = src[grp * s_gs + row * s_ld + c];
+    }
+}
+
+// ======================================== host orchestration ===============================================
+
+template <typename T>
+struct Planes {
+    T* base;
+    int64_t ld, gs;
+    T* grp(int i) const { return base + (size_t)i * gs; }
+};
+
+template <typename T>
+static Planes<T> caller_planes(void* p, const gsr_config_t* cfg) {
+    const int dg = cfg->d / cfg->c;
+    if (cfg->layout == GSR_LAYOUT_ROW_MAJOR) return Planes<T>{(T*)p, (int64_t)cfg->d, (int64_t)dg};
+    return Planes<T>{(T*)p, (int64_t)dg, (int64_t)cfg->n * dg};
+}
+
+template <int DG, typename T>
+struct Ctx {
+    using M = typename MaskOf<DG>::type;
+    const gsr_graph_t* g;
+    const gsr_config_t* cfg;
+    hipStream_t s;
+    char* ws;
+    LayerWs lw;
+    int tiles;
+    T* rec_vals(int slot) const { return (T*)(ws + lw.rec_vals[slot]); }
+    M* rec_mask(int slot) const { return (M*)(ws + lw.rec_mask[slot]); }
+    T* y0() const { return (T*)(ws + lw.y0); }
+    float* dw_partial() const { return (float*)(ws + lw.dw_partial); }
+    float* hub_part() const { return (float*)(ws + lw.hub_partial); }
+};
+
+template <int DG, typename T>
+static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0, int slot) {
+    SumArgs<DG, T> a;
+    a.n = (int)x.cfg->n; a.src = src; a.ld = ld; a.src_gs = gs; a.nsrc = nsrc; a.y0 = y0;
+    a.k = x.cfg->k; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
+    a.out_vals = x.rec_vals(slot); a.out_mask = x.rec_mask(slot);
+    hipLaunchKernelGGL((k_sum<DG, T>), dim3((unsigned)x.g->grid * 2), dim3(256), 0, x.s, a);
+}
+
+template <int DG, typename T>
+static void launch_hub_records(const Ctx<DG, T>& x, int slot) {
+    const HubPlan& h = x.g->a.hub;
+    if (h.n_chunks == 0) return;
+    HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+    hipLaunchKernelGGL((k_hub_records<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
+                       make_view(x.g, false), hc, (const T*)x.rec_vals(slot),
+                       (const typename MaskOf<DG>::type*)x.rec_mask(slot), x.cfg->k, x.hub_part());
+}
+
+template <int DG, typename T>
+static void launch_hub_dense(const Ctx<DG, T>& x, const T* plane, int64_t ld) {
+    const HubPlan& h = x.g->at.hub;
+    if (h.n_chunks == 0) return;
+    HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+    hipLaunchKernelGGL((k_hub_dense<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
+                       make_view(x.g, true), hc, plane, ld, x.hub_part());
+}
+
+// mode 0: forward (+), 1: inverse (-), 2: inverse (-) with dW
+template <int DG, typename T>
+static void launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const float* w, T* plane, int64_t ld, int out_slot,
+                         const T* dy, int64_t ldg) {
+    launch_hub_records<DG, T>(x, in_slot);
+    BlockArgs<DG, T> a;
+    a.g = make_view(x.g, false);
+    a.n = (int)x.cfg->n; a.tiles = x.tiles;
+    a.rec_vals = x.rec_vals(in_slot); a.rec_mask = x.rec_mask(in_slot); a.k = x.cfg->k;
+    a.hub_part = x.hub_part(); a.w = w; a.plane = plane; a.ld = ld;
+    a.out_vals = out_slot >= 0 ? x.rec_vals(out_slot) : nullptr;
+    a.out_mask = out_slot >= 0 ? x.rec_mask(out_slot) : nullptr;
+    a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
+    const dim3 grid((unsigned)x.g->grid), block(256);
+    if (mode == 0) hipLaunchKernelGGL((k_block<DG, T, +1, false>), grid, block, 0, x.s, a);
+    else if (mode == 1) hipLaunchKernelGGL((k_block<DG, T, -1, false>), grid, block, 0, x.s, a);
+    else hipLaunchKernelGGL((k_block<DG, T, -1, true>), grid, block, 0, x.s, a);
+}
+
+template <int DG, typename T>
+static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const float* w, int mask_slot, const T* z,
+                        int64_t ldz, T* dst, int64_t ldd, int64_t dst_gs, int ndst) {
+    launch_hub_dense<DG, T>(x, dy, ldg);
+    GradArgs<DG, T> a;
+    a.gt = make_view(x.g, true);
+    a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
+    a.own_mask = x.rec_mask(mask_slot); a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
+    a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
+    hipLaunchKernelGGL((k_grad<DG, T>), dim3((unsigned)x.g->grid), dim3(256), 0, x.s, a);
+}
+
+// eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of
+// the previous layer's Y_2, emitted when that plane was written).
+template <int DG, typename T>
+static void layer_forward_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& p, bool slot0_ready) {
+    const int C = x.cfg->c;
+    if (!slot0_ready) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, 0);
+    for (int i = 1; i <= C; ++i) {
+        const int out_slot = i < C ? i : (C == 2 ? 0 : -1);
+        launch_block<DG, T>(x, 0, i - 1, w + (size_t)(i - 1) * DG * DG, p.grp(i - 1), p.ld, out_slot, nullptr, 0);
+    }
+}
+
+// eq. (7)
+template <int DG, typename T>
+static void layer_inverse_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& p) {
+    const int C = x.cfg->c;
+    for (int i = 1; i < C; ++i) launch_sum<DG, T>(x, p.grp(i - 1), p.ld, p.gs, 1, nullptr, i);
+    for (int i = C; i >= 1; --i) {
+        if (i == 1 && C > 2) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, 0);
+        const int out_slot = (i == 2 && C == 2) ? 0 : -1;
+        launch_block<DG, T>(x, 1, i - 1, w + (size_t)(i - 1) * DG * DG, p.grp(i - 1), p.ld, out_slot, nullptr, 0);
+    }
+}
+
+// Backward fused with the inverse.  slots_ready: slots 1..C-1 already hold the records of
+// Y_1..Y_{C-1} of this layer (left by the forward sweep, or by the layer above while it rebuilt
+// its input).  On return slots 1..C-1 hold the records of X_1..X_{C-1}, i.e. of the layer below.
+template <int DG, typename T>
+static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& y, const Planes<T>& dy, float* dw_out,
+                                bool slots_ready) {
+    const int C = x.cfg->c;
+    if (!slots_ready)
+        for (int i = 1; i < C; ++i) launch_sum<DG, T>(x, y.grp(i - 1), y.ld, y.gs, 1, nullptr, i);
+    for (int i = C; i >= 1; --i) {
+        const float* wi = w + (size_t)(i - 1) * DG * DG;
+        const T* z;      // rows of Y_{i-1}
+        int64_t ldz;
+        if (i >= 2) { z = y.grp(i - 2); ldz = y.ld; }
+        else if (C == 2) { z = y.grp(1); ldz = y.ld; }      // Y_0 = X_2, rebuilt just before
+        else {
+            launch_sum<DG, T>(x, y.grp(1), y.ld, y.gs, C - 1, x.y0(), 0);
+            z = x.y0(); ldz = DG;
+        }
+        const int out_slot = i < C ? i : (C == 2 ? 0 : -1);
+        launch_block<DG, T>(x, 2, i - 1, wi, y.grp(i - 1), y.ld, out_slot, dy.grp(i - 1), dy.ld);
+        hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 255) / 256), dim3(256), 0, x.s, (const float*)x.dw_partial(),
+                           x.g->grid, DG * DG, dw_out + (size_t)(i - 1) * DG * DG);
+        if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, i - 1, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1);
+        else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, 0, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1);
+    }
+}
+
+template <int DG, typename T>
+static Ctx<DG, T> make_ctx(const gsr_graph_t* g, const gsr_config_t* cfg, void* ws, hipStream_t s) {
+    Ctx<DG, T> x;
+    x.g = g; x.cfg = cfg; x.s = s; x.ws = (char*)ws; x.lw = carve_layer(cfg, g);
+    x.tiles = (int)((cfg->n + 15) / 16);
+    return x;
+}
+
+enum LayerOp { OP_FWD, OP_INV, OP_BWD };
+
+template <int DG, typename T>
+static gsr_status_t layer_call(LayerOp op, const gsr_graph_t* g, const gsr_config_t* cfg, const float* w, void* y, void* dy,
+                               float* dw, void* ws, hipStream_t s) {
+    Ctx<DG, T> x = make_ctx<DG, T>(g, cfg, ws, s);
+    Planes<T> py = caller_planes<T>(y, cfg);
+    if (op == OP_FWD) layer_forward_impl<DG, T>(x, w, py, false);
+    else if (op == OP_INV) layer_inverse_impl<DG, T>(x, w, py);
+    else layer_backward_impl<DG, T>(x, w, py, caller_planes<T>(dy, cfg), dw, false);
+    GSR_HIP_CHECK(hipGetLastError());
+    return GSR_OK;
+}
+
+static gsr_status_t layer_dispatch(LayerOp op, const gsr_graph_t* g, const gsr_config_t* cfg, const float* w, void* y, void* dy,
+                                   float* dw, void* ws, size_t ws_bytes, void* stream) {
+    GSR_TRY(validate_config(cfg, g, false));
+    if (cfg->n == 0) return GSR_OK;
+    if (!w || !y || !ws || (op == OP_BWD && (!dy || !dw))) return fail(GSR_ERR_INVALID_ARG, "null pointer");
+    if (op == OP_BWD && !g->has_transpose) return fail(GSR_ERR_UNSUPPORTED, "graph has no transpose");
+    const size_t need = carve_layer(cfg, g).total;
+    if (ws_bytes < need) return fail(GSR_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < %zu bytes", ws_bytes, need);
+    hipStream_t s = (hipStream_t)stream;
+    const int dg = cfg->d / cfg->c;
+    if (cfg->dtype == GSR_F32) {
+        if (dg == 32) return layer_call<32, float>(op, g, cfg, w, y, dy, dw, ws, s);
+        return layer_call<64, float>(op, g, cfg, w, y, dy, dw, ws, s);
+    }
+    if (dg == 32) return layer_call<32, bf16_t>(op, g, cfg, w, y, dy, dw, ws, s);
+    return layer_call<64, bf16_t>(op, g, cfg, w, y, dy, dw, ws, s);
+}
+
+template <int DG, typename T>
+static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, const void* x0, const float* w_all,
+                              const float* w_out, const float* b_out, const float* target, float* loss_out, float* yhat_out,
+                              float* dw_all, float* dw_out, float* db_out, void* dx0_out, void* x0_rebuilt_out, void* xl_out,
+                              void* ws, hipStream_t s) {
+    const StepWs sw = carve_step(cfg, g);
+    char* base = (char*)ws;
+    Ctx<DG, T> x = make_ctx<DG, T>(g, cfg, base + sw.layer, s);
+    const int C = cfg->c, L = cfg->l;
+    const int64_t n = cfg->n;
+    const Planes<T> act{(T*)(base + sw.act), (int64_t)DG, n * DG};
+    const Planes<T> grad{(T*)(base + sw.grad), (int64_t)DG, n * DG};
+    const Planes<T> in = caller_planes<T>(const_cast<void*>(x0), cfg);
+    const dim3 cgrid((unsigned)g->grid * 4), cblock(256);
+    auto copy = [&](const Planes<T>& from, const Planes<T>& to) {
+        hipLaunchKernelGGL((k_copy_planes<T>), cgrid, cblock, 0, s, n, DG, C, (const T*)from.base, from.ld, from.gs, to.base,
+                           to.ld, to.gs);
+    };
+    copy(in, act);
+    const size_t wl = (size_t)C * DG * DG;
+    for (int l = 0; l < L; ++l) layer_forward_impl<DG, T>(x, w_all + l * wl, act, C == 2 && l > 0);
+    if (xl_out) copy(act, caller_planes<T>(xl_out, cfg));
+    HeadArgs<T> h;
+    h.n = (int)n; h.d = cfg->d; h.dg = DG; h.act = act.base; h.grad = grad.base; h.ld = act.ld; h.gs = act.gs;
+    h.w_out = w_out; h.b_out = b_out; h.target = target; h.yhat = yhat_out; h.partial = (float*)(base + sw.head);
+    hipLaunchKernelGGL((k_head<T>), dim3((unsigned)g->grid), dim3(256), 0, s, h);
+    hipLaunchKernelGGL(k_head_reduce, dim3((cfg->d + 2 + 255) / 256), dim3(256), 0, s, (const float*)h.partial, g->grid, cfg->d,
+                       (int)n, dw_out, db_out, loss_out);
+    for (int l = L - 1; l >= 0; --l) layer_backward_impl<DG, T>(x, w_all + l * wl, act, grad, dw_all + l * wl, true);
+    if (dx0_out) copy(grad, caller_planes<T>(dx0_out, cfg));
+    if (x0_rebuilt_out) copy(act, caller_planes<T>(x0_rebuilt_out, cfg));
+    GSR_HIP_CHECK(hipGetLastError());
+    return GSR_OK;
+}
+
+}  // namespace gsr
+
+using namespace gsr;
+
+extern "C" {
+
+gsr_status_t gsr_layer_forward(const gsr_graph_t* g, const gsr_config_t* cfg, const float* w, void* x_inout, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    return layer_dispatch(OP_FWD, g, cfg, w, x_inout, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+gsr_status_t gsr_layer_inverse(const gsr_graph_t* g, const gsr_config_t* cfg, const float* w, void* y_inout, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    return layer_dispatch(OP_INV, g, cfg, w, y_inout, nullptr, nullptr, workspace, workspace_bytes, stream);
+}
+
+gsr_status_t gsr_layer_backward(const gsr_graph_t* g, const gsr_config_t* cfg, const float* w, void* y_inout, void* dy_inout,
+                                float* dw_out, void* workspace, size_t workspace_bytes, void* stream) {
+    return layer_dispatch(OP_BWD, g, cfg, w, y_inout, dy_inout, dw_out, workspace, workspace_bytes, stream);
+}
+
+gsr_status_t gsr_step(const gsr_graph_t* g, const gsr_config_t* cfg, const void* x0, const float* w_all, const float* w_out,
+                      const float* b_out, const float* target, float* loss_out, float* yhat_out, float* dw_all, float* dw_out,
+                      float* db_out, void* dx0_out, void* x0_rebuilt_out, void* xl_out, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+    GSR_TRY(validate_config(cfg, g, true));
+    if (cfg->d > HEAD_MAXQ * 64) return fail(GSR_ERR_UNSUPPORTED, "D=%d above %d", cfg->d, HEAD_MAXQ * 64);
+    if (!x0 || !w_all || !w_out || !b_out || !target || !loss_out || !dw_all || !dw_out || !db_out || !workspace)
+        return fail(GSR_ERR_INVALID_ARG, "null pointer");
+    if (!g->has_transpose) return fail(GSR_ERR_UNSUPPORTED, "graph has no transpose");
+    const size_t need = carve_step(cfg, g).total;
+    if (workspace_bytes < need) return fail(GSR_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < %zu bytes", workspace_bytes, need);
+    if (cfg->n == 0) return fail(GSR_ERR_INVALID_ARG, "empty graph");
+    hipStream_t s = (hipStream_t)stream;
+    const int dg = cfg->d / cfg->c;
+#define GSR_STEP(DGV, TV)                                                                                            \
+    return step_impl<DGV, TV>(g, cfg, x0, w_all, w_out, b_out, target, loss_out, yhat_out, dw_all, dw_out, db_out, \
+                              dx0_out, x0_rebuilt_out, xl_out, workspace, s)
+    if (cfg->dtype == GSR_F32) {
+        if (dg == 32) GSR_STEP(32, float);
+        GSR_STEP(64, float);
+    }
+    if (dg == 32) GSR_STEP(32, bf16_t);
+    GSR_STEP(64, bf16_t);
+#undef GSR_STEP
+}
+
+}  // extern "C"

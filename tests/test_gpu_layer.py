@@ -1,0 +1,200 @@
+"""GPU parity of the grouped reversible layer (forward, inverse, backward fused with the
+inverse) and of the whole training step against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2603_27156_amd as gsr
+from paper_2603_27156_amd import synth
+from gpu_util import Case, assert_close, rel_norm, BF16_REL
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+ROW, PLANAR = gsr.GSR_LAYOUT_ROW_MAJOR, gsr.GSR_LAYOUT_GROUP_PLANAR
+
+
+def workloads():
+    w0 = synth.workload(0)
+    return {
+        "cfg0": w0,                                                                   # dg 32, C 2, no norm
+        "cfg1s": synth.scaled(synth.workload(1), 3001, l=3),                          # dg 64, C 2, ragged tail
+        "cfg2s": synth.scaled(synth.workload(2), 5003, l=2),                          # dg 64, C 4, hub rows
+        "cfg4s": synth.scaled(synth.workload(4), 4001, l=2, dtype="f32"),             # dg 32, C 8, int64 rowptr
+        "tiny": synth.scaled(w0, 13, levels=3, l=2),                                  # fewer rows than one tile
+    }
+
+
+_cases = {}
+
+
+def case(name, layout=ROW) -> Case:
+    key = (name, layout)
+    if key not in _cases:
+        _cases[key] = Case(workloads()[name], 0, layout)
+    return _cases[key]
+
+
+def layer_inputs(c: Case, depth: int):
+    """Layer input of realistic distribution: X0 pushed through `depth` oracle layers."""
+    X = c.x0_on_grid()
+    for l in range(depth):
+        X = oracle.layer_forward(c.og, c.ocfg, c.inp.weights[l], X)
+    return X
+
+
+@pytest.mark.parametrize("name,layout,depth", [
+    ("cfg0", ROW, 0), ("cfg0", PLANAR, 1), ("cfg1s", ROW, 1), ("cfg1s", PLANAR, 0),
+    ("cfg2s", PLANAR, 1), ("cfg2s", ROW, 0), ("cfg4s", PLANAR, 1), ("cfg4s", ROW, 0), ("tiny", ROW, 0),
+])
+def test_layer_forward_inverse_backward(name, layout, depth):
+    c = case(name, layout)
+    w = c.w
+    print(f"[case] {name} layout={layout} n={w.n} D={w.d} C={w.c} k={w.k} norm={w.norm}", flush=True)
+    W = c.inp.weights[depth]
+    X = layer_inputs(c, depth)
+    Wd = torch.from_numpy(W).to(c.dev)
+
+    # forward, eq. (6)
+    Y_ref = oracle.layer_forward(c.og, c.ocfg, W, X)
+    y = c.to_dev(X)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y)
+    assert_close("Y", c.to_host(y), Y_ref)
+
+    # inverse, eq. (7), from the oracle's Y
+    X_ref = oracle.layer_inverse(c.og, c.ocfg, W, Y_ref)
+    x = c.to_dev(Y_ref)
+    gsr.gsr_layer_inverse(c.gg, c.gcfg, Wd, x)
+    assert_close("X rebuilt", c.to_host(x), X_ref)
+    assert_close("inverse(forward(X)) vs X", c.to_host(x), X, rtol=1e-4, atol=1e-4)
+
+    # backward fused with the inverse
+    rng = np.random.default_rng(17)
+    dY = (rng.standard_normal((w.n, w.d)) * 1e-3).astype(np.float32).astype(np.float64)
+    Xb_ref, dX_ref, dW_ref = oracle.layer_backward(c.og, c.ocfg, W, Y_ref, dY)
+    yb, dyb = c.to_dev(Y_ref), c.to_dev(dY)
+    dW = torch.empty((w.c, w.dg, w.dg), dtype=torch.float32, device=c.dev)
+    gsr.gsr_layer_backward(c.gg, c.gcfg, Wd, yb, dyb, dW)
+    assert_close("X rebuilt (backward)", c.to_host(yb), Xb_ref)
+    assert_close("dX", c.to_host(dyb), dX_ref)
+    assert_close("dW", dW.cpu().numpy(), dW_ref)
+    assert torch.equal(yb, x)            # the fused call rebuilds exactly what the inverse call does
+
+
+@pytest.mark.parametrize("name,layout", [("cfg0", ROW), ("cfg0", PLANAR), ("cfg1s", ROW), ("cfg2s", ROW),
+                                         ("cfg4s", PLANAR), ("tiny", ROW)])
+def test_step_against_oracle(name, layout):
+    c = case(name, layout)
+    w = c.w
+    print(f"[case] step {name} layout={layout} n={w.n} D={w.d} C={w.c} L={w.l}", flush=True)
+    ref = oracle.step(c.og, c.ocfg, w.l, c.x0_on_grid(), c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target)
+    out = run_step(c)
+    assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
+    assert_close("yhat", out["yhat"], ref["yhat"])
+    assert_close("XL", out["XL"], ref["XL"])
+    assert_close("X0 rebuilt", out["X0rec"], ref["X0rec"])
+    assert_close("dW", out["dW"], ref["dW"])
+    assert_close("dw_out", out["dwout"], ref["dwout"])
+    assert np.isclose(out["dbout"], ref["dbout"], rtol=1e-4, atol=1e-7)
+    assert_close("dX0", out["dX0"], ref["dX0"])
+    assert_close("X0 rebuilt vs X0", out["X0rec"], c.x0_on_grid(), rtol=1e-4, atol=1e-4)
+
+
+def run_step(c: Case, l=None, raw=False):
+    w = c.w
+    L = w.l if l is None else l
+    cfg = gsr.Config(**{**c.gcfg.__dict__, "l": L})
+    dv = c.dev
+    f32 = dict(dtype=torch.float32, device=dv)
+    x0 = c.to_dev(c.inp.x0)
+    W = torch.from_numpy(np.ascontiguousarray(c.inp.weights[:L])).to(dv)
+    w_out = torch.from_numpy(c.inp.w_out).to(dv)
+    b_out = torch.tensor([c.inp.b_out], **f32)
+    target = torch.from_numpy(c.inp.target).to(dv)
+    loss, db = torch.zeros(1, **f32), torch.zeros(1, **f32)
+    yhat = torch.empty(w.n, **f32)
+    dW = torch.empty_like(W)
+    dwout = torch.empty(w.d, **f32)
+    dx0, x0r, xl = torch.empty_like(x0), torch.empty_like(x0), torch.empty_like(x0)
+    gsr.gsr_step(c.gg, cfg, x0, W, w_out, b_out, target, loss, dW, dwout, db, yhat_out=yhat, dx0_out=dx0,
+                 x0_rebuilt_out=x0r, xl_out=xl)
+    torch.cuda.synchronize()
+    if raw:
+        return dict(loss=loss, yhat=yhat, XL=xl, X0rec=x0r, dW=dW, dwout=dwout, dbout=db, dX0=dx0)
+    return dict(loss=float(loss.item()), yhat=yhat.cpu().numpy(), XL=c.to_host(xl), X0rec=c.to_host(x0r),
+                dW=dW.cpu().numpy(), dwout=dwout.cpu().numpy(), dbout=float(db.item()), dX0=c.to_host(dx0))
+
+
+@pytest.mark.parametrize("name", ["cfg0", "cfg2s"])
+def test_step_is_deterministic_and_equals_the_chain_of_layer_calls(name):
+    c = case(name, PLANAR)
+    w = c.w
+    a = run_step(c, raw=True)
+    b = run_step(c, raw=True)
+    for key in a:
+        assert torch.equal(a[key], b[key]), key          # no float atomics: bit-identical reruns
+    # the same kernels called layer by layer through the ABI
+    x = c.to_dev(c.inp.x0)
+    Wd = torch.from_numpy(np.ascontiguousarray(c.inp.weights[:w.l])).to(c.dev)
+    for l in range(w.l):
+        gsr.gsr_layer_forward(c.gg, c.gcfg, Wd[l], x)
+    assert torch.equal(x, a["XL"])
+    g = a["yhat"].sub(torch.from_numpy(c.inp.target).to(c.dev))          # only to seed the backward chain
+    dW = torch.empty_like(Wd)
+    gx = None
+    # dX^L as the step computed it cannot be read back; rebuild it with the head's formula on the host
+    yh = a["yhat"].cpu().numpy().astype(np.float32)
+    gy = (np.float32(2.0) * (yh - c.inp.target) / np.float32(w.n)).astype(np.float32)
+    dXL = (gy[:, None] * c.inp.w_out[None, :]).astype(np.float32)
+    dy = c.to_dev(dXL)
+    for l in reversed(range(w.l)):
+        gsr.gsr_layer_backward(c.gg, c.gcfg, Wd[l], x, dy, dW[l])
+    assert torch.equal(x, a["X0rec"])
+    assert torch.equal(dW, a["dW"]) and torch.equal(dy, a["dX0"])
+
+
+def test_workspace_does_not_grow_with_depth():
+    c = case("cfg2s", PLANAR)
+    sizes = []
+    for L in (8, 56, 224, 448):
+        cfg = gsr.Config(**{**c.gcfg.__dict__, "l": L})
+        sizes.append(gsr.gsr_workspace_size(c.gg, cfg))
+    assert len(set(sizes)) == 1
+    layer_b, step_b = sizes[0]
+    plane = c.w.n * c.w.d * 4
+    assert step_b < 2 * plane + layer_b + (1 << 21)            # two planes (activations, gradients) + layer scratch
+    small = torch.empty(step_b - 256, dtype=torch.uint8, device=c.dev)
+    with pytest.raises(gsr.GsrError) as e:
+        run_step_with_workspace(c, small)
+    assert e.value.status == gsr.GSR_ERR_WORKSPACE_TOO_SMALL
+
+
+def run_step_with_workspace(c, ws):
+    w = c.w
+    f32 = dict(dtype=torch.float32, device=c.dev)
+    x0 = c.to_dev(c.inp.x0)
+    W = torch.from_numpy(np.ascontiguousarray(c.inp.weights[:w.l])).to(c.dev)
+    gsr.gsr_step(c.gg, c.gcfg, x0, W, torch.from_numpy(c.inp.w_out).to(c.dev), torch.zeros(1, **f32),
+                 torch.from_numpy(c.inp.target).to(c.dev), torch.zeros(1, **f32), torch.empty_like(W),
+                 torch.empty(w.d, **f32), torch.zeros(1, **f32), workspace=ws)
+
+
+@pytest.mark.parametrize("k", [1, 32])
+def test_degenerate_k(k):
+    """k = 1 (a single survivor per row) and k = D/C (GS keeps everything: a linear GCN block)."""
+    w = synth.scaled(synth.workload(0), 1500, l=2, k=k)
+    c = Case(w, 3, PLANAR)
+    ref = oracle.step(c.og, c.ocfg, w.l, c.x0_on_grid(), c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target)
+    out = run_step(c)
+    for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+        assert_close(key, out[key], ref[key])
+
+
+def test_bf16_storage_variant():
+    w = synth.scaled(synth.workload(4), 4001, l=2)            # bf16 storage, dg 32, C 8
+    c = Case(w, 0, PLANAR)
+    ref = oracle.step(c.og, c.ocfg, w.l, c.x0_on_grid(), c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target)
+    out = run_step(c)
+    assert np.isclose(out["loss"], ref["loss"], rtol=BF16_REL)
+    for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+        assert rel_norm(out[key], ref[key]) <= BF16_REL, (key, rel_norm(out[key], ref[key]))
