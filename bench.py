@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Benchmark of the GSR-GNN training step (forward + inverse recomputation + backward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg2-bf16] [--layers L]
+
+A "step" is one gsr_step call: L grouped reversible layers forward, head + loss, and the backward
+sweep that rebuilds every layer input instead of storing it.  Inputs are synthetic (seeded circuit
+DAG, N(0,1) features, Glorot weights) and resident in HBM before the timed region.  Prints ONE JSON
+line: node-layers/s, the roofline of the dominant kernel (HIP events recorded by the library on the
+stream it launches on, inside the timed region) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(n, nnz, dg, k, c, b, rms):
+    """Bytes each kernel class must move per launch, every array touched once (neighbour gathers
+    counted once per source row: the compulsory traffic), averaged over the C launches of a layer.
+    n rows, nnz stored adjacency entries, b bytes per stored element, mask = dg/8 bytes per row."""
+    mask = dg // 8
+    rec = k * b + mask                       # compressed record of one row
+    csr = nnz * 8 + n * 4                    # column indices + edge values + row pointers
+    emit_fwd = (c - 1) / c if c > 2 else 1.0  # launches that also write the record of their output
+    emit_bwd = (c - 1) / c if c > 2 else 1.0
+    row = dg * b
+    fwd = n * (rec + 2 * row + emit_fwd * rec) + csr
+    bwd = n * (rec + 3 * row + emit_bwd * rec) + csr
+    ndst = ((c - 1) + (c - 1)) / c           # block 1 updates C-1 planes, blocks 2..C one plane each
+    grad = n * (row + mask + (row if rms else 0) + 2 * row * ndst) + csr
+    return {"block_forward": fwd, "block_backward": bwd, "grad": grad}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--layers", type=int, default=0, help="override L")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="no per-kernel events in the timed region")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2603_27156_amd as gsr
+    from paper_2603_27156_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    gsr.lib()
+    dev = torch.device("cuda:0")
+
+    idx = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg2-bf16": 2, "cfg4": 4}[args.workload]
+    w = synth.workload(idx)
+    if args.workload == "cfg2-bf16":
+        w = synth.workload(2, dtype="bf16", name="cfg2-1M-bf16")
+    if args.layers > 0:
+        w = synth.workload(idx, l=args.layers, dtype=w.dtype, name=w.name)
+    t_gen = time.time()
+    inp = synth.make_inputs(w, 0)
+    g = gsr.gsr_graph_create(inp.rowptr, inp.colidx)
+    info = gsr.gsr_graph_info(g)
+    t_gen = time.time() - t_gen
+
+    bf16 = w.dtype == "bf16"
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    cfg = gsr.Config(n=w.n, d=w.d, c=w.c, k=w.k, l=w.l, dtype=gsr.GSR_BF16 if bf16 else gsr.GSR_F32,
+                     norm=gsr.GSR_NORM_RMS if w.norm == "rms" else gsr.GSR_NORM_NONE, eps=1e-5,
+                     layout=gsr.GSR_LAYOUT_GROUP_PLANAR)
+    f32 = dict(dtype=torch.float32, device=dev)
+    x0 = torch.from_numpy(inp.x0).to(dev).to(tdt).view(w.n, w.c, w.dg).permute(1, 0, 2).contiguous()
+    W = torch.from_numpy(inp.weights).to(dev)
+    w_out = torch.from_numpy(inp.w_out).to(dev)
+    b_out = torch.zeros(1, **f32)
+    target = torch.from_numpy(inp.target).to(dev)
+    loss, db = torch.zeros(1, **f32), torch.zeros(1, **f32)
+    dW, dw = torch.empty_like(W), torch.empty(w.d, **f32)
+    dx0, x0r = torch.empty_like(x0), torch.empty_like(x0)
+    ws_bytes = gsr.gsr_workspace_size(g, cfg)[1]
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+
+    def step():
+        gsr.gsr_step(g, cfg, x0, W, w_out, b_out, target, loss, dW, dw, db, dx0_out=dx0, x0_rebuilt_out=x0r,
+                     workspace=ws)
+
+    mask = 0 if args.no_profile else (1 << gsr.KERNEL_CLASSES) - 1
+    gsr.gsr_set_option("profile", mask)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    gsr.gsr_profile_reset()
+    torch.cuda.reset_peak_memory_stats()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    gsr.gsr_set_option("profile", 0)
+    ms_per_step = dt * 1e3 / args.steps
+    value = w.n * w.l * args.steps / dt
+    rebuilt_err = float((x0r.float() - x0.float()).abs().max().item())
+
+    kernels = {}
+    for kc in range(gsr.KERNEL_CLASSES):
+        ms, cnt = gsr.gsr_profile_read(kc)
+        if cnt:
+            kernels[gsr.gsr_profile_class_name(kc)] = {"launches_per_step": cnt // args.steps,
+                                                       "avg_us": 1e3 * ms / cnt, "ms_per_step": ms / args.steps}
+    roofline = None
+    if kernels:
+        ab = algorithmic_bytes(w.n, info["nnz"], w.dg, w.k, w.c, 2 if bf16 else 4, w.norm == "rms")
+        cand = {k: v for k, v in kernels.items() if k in ab}
+        dom = max(cand, key=lambda k: cand[k]["ms_per_step"])
+        achieved = ab[dom] / (cand[dom]["avg_us"] * 1e-6) / 1e9
+        roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "algorithmic_bytes_per_launch": ab[dom], "avg_launch_us": cand[dom]["avg_us"]}
+        for k in cand:
+            kernels[k]["algorithmic_GBps"] = ab[k] / (cand[k]["avg_us"] * 1e-6) / 1e9
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        ws_n = min(w.n, 200_000)
+        sw = synth.scaled(w, ws_n, l=2) if ws_n < w.n else synth.workload(idx, l=min(w.l, 2), dtype=w.dtype)
+        sinp = synth.make_inputs(sw, 0)
+        og = oracle.graph_build(sinp.rowptr, sinp.colidx)
+        ocfg = oracle.Cfg(sw.d, sw.c, sw.k, oracle.NORM_RMS if sw.norm == "rms" else oracle.NORM_NONE, 1e-5,
+                          oracle.STORE_BF16 if bf16 else oracle.STORE_F32)
+        tc = time.perf_counter()
+        oracle.step(og, ocfg, sw.l, sinp.x0, sinp.weights, sinp.w_out, 0.0, sinp.target, want=())
+        tc = time.perf_counter() - tc
+        cpu_baseline = {"value": sw.n * sw.l / tc, "unit": "node-layers/s", "cores": oracle.num_threads(),
+                        "kind": "oracle", "seconds": tc,
+                        "sample": f"same recipe at N={sw.n} nodes, L={sw.l} layers (D={sw.d}, C={sw.c}, k={sw.k}), one full step"}
+
+    out = {
+        "metric": "node-layers/sec (fwd+inverse+bwd)", "value": value, "unit": "node-layers/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16-storage/f32-accumulate" if bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "n": w.n, "nnz": info["nnz"], "max_degree": info["max_degree"], "d": w.d,
+                   "c": w.c, "k": w.k, "l": w.l, "norm": w.norm, "hub_rows": info["n_hub_rows"]},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
+        "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()), "workspace_bytes": int(ws_bytes),
+        "loss": float(loss.item()), "x0_rebuild_max_abs_err": rebuilt_err, "setup_seconds": t_gen,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -85,8 +85,19 @@ const char* gsr_version(void);
  *   "hub_threshold"   rows with more stored entries than this are reduced in two passes
  *                     (default 512; Section 2 notes nets with more than 8,000 neighbours)
  *   "hub_chunk"       neighbours per first-pass partial sum (default 256)
- *   "max_workgroups"  workgroups of the persistent kernels, multiple of 8 (0: 2 per CU) */
+ *   "max_workgroups"  workgroups of the persistent kernels, multiple of 8 (0: 2 per CU)
+ *   "profile"         bit mask of kernel classes to time (see gsr_profile_read); read at once */
 gsr_status_t gsr_set_option(const char* key, int64_t value);
+
+/* Measurement aid.  gsr_set_option("profile", mask) makes the layer / step calls bracket every
+ * launch of kernel class i (bit i of mask) with HIP events on the caller's stream.
+ * gsr_profile_read waits for the recorded events and returns the summed duration and number
+ * of launches of one class since the last gsr_profile_reset.  Classes: 0 block forward,
+ * 1 block inverse, 2 block inverse + weight gradient, 3 data gradient, 4 group sum / record,
+ * 5 hub first pass, 6 dW reduction, 7 head, 8 layout copy.  Not thread-safe. */
+gsr_status_t gsr_profile_read(int32_t kernel_class, double* total_ms, int64_t* launches);
+gsr_status_t gsr_profile_reset(void);
+const char* gsr_profile_class_name(int32_t kernel_class);
 
 /* ---- graph: adjacency A of Section 3 (forward aggregates over G, backward over G^T) ----
  *

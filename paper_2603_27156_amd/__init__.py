@@ -26,7 +26,8 @@ GSR_GRAPH_SYMMETRISE, GSR_GRAPH_ADD_SELF_LOOPS, GSR_GRAPH_GCN_NORM, GSR_GRAPH_RO
 GSR_ADJ_UNIT, GSR_ADJ_GCN_SYM = 0, 1
 
 EXPORTED = [
-    "gsr_last_error", "gsr_version", "gsr_set_option", "gsr_graph_create", "gsr_graph_normalize", "gsr_graph_info",
+    "gsr_last_error", "gsr_version", "gsr_set_option", "gsr_profile_read", "gsr_profile_reset",
+    "gsr_profile_class_name", "gsr_graph_create", "gsr_graph_normalize", "gsr_graph_info",
     "gsr_graph_export", "gsr_graph_destroy", "gsr_group_sparse", "gsr_spmm", "gsr_spmm_compressed_workspace",
     "gsr_spmm_compressed", "gsr_workspace_size", "gsr_layer_forward", "gsr_layer_inverse", "gsr_layer_backward",
     "gsr_step",
@@ -57,6 +58,7 @@ def lib():
         l = C.CDLL(LIB_PATH)
         l.gsr_last_error.restype = C.c_char_p
         l.gsr_version.restype = C.c_char_p
+        l.gsr_profile_class_name.restype = C.c_char_p
         l.gsr_spmm_compressed_workspace.restype = C.c_size_t
         l.gsr_spmm_compressed_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         _lib = l
@@ -87,6 +89,24 @@ def gsr_version() -> str:
 
 def gsr_set_option(key: str, value: int) -> None:
     _check(lib().gsr_set_option(key.encode(), C.c_int64(value)))
+
+
+KERNEL_CLASSES = 9
+
+
+def gsr_profile_reset() -> None:
+    _check(lib().gsr_profile_reset())
+
+
+def gsr_profile_read(kernel_class: int) -> Tuple[float, int]:
+    """(summed milliseconds, launches) of one kernel class since the last reset."""
+    ms, cnt = C.c_double(), C.c_int64()
+    _check(lib().gsr_profile_read(C.c_int32(kernel_class), C.byref(ms), C.byref(cnt)))
+    return ms.value, cnt.value
+
+
+def gsr_profile_class_name(kernel_class: int) -> str:
+    return lib().gsr_profile_class_name(C.c_int32(kernel_class)).decode()
 
 
 @dataclass

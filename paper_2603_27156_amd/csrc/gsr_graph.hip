@@ -34,6 +34,48 @@ Options& options() {
     return o;
 }
 
+// ---- per-kernel timing ------------------------------------------------------------------------
+struct ProfRec {
+    int kc;
+    hipEvent_t e0, e1;
+};
+static std::vector<ProfRec> g_prof_open;          // recorded, not yet read
+static std::vector<std::pair<hipEvent_t, hipEvent_t>> g_prof_pool;
+static double g_prof_ms[KC_COUNT];
+static int64_t g_prof_n[KC_COUNT];
+
+ProfScope::ProfScope(KernelClass kc, hipStream_t s) : slot(-1), stream(s) {
+    if (!((options().profile >> kc) & 1)) return;
+    ProfRec r;
+    r.kc = kc;
+    if (!g_prof_pool.empty()) {
+        r.e0 = g_prof_pool.back().first;
+        r.e1 = g_prof_pool.back().second;
+        g_prof_pool.pop_back();
+    } else if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) {
+        return;
+    }
+    if (hipEventRecord(r.e0, s) != hipSuccess) return;
+    g_prof_open.push_back(r);
+    slot = (int)g_prof_open.size() - 1;
+}
+
+ProfScope::~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(g_prof_open[slot].e1, stream);
+}
+
+static void prof_collect() {
+    for (ProfRec& r : g_prof_open) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.e1) == hipSuccess && hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
+            g_prof_ms[r.kc] += ms;
+            g_prof_n[r.kc] += 1;
+        }
+        g_prof_pool.emplace_back(r.e0, r.e1);
+    }
+    g_prof_open.clear();
+}
+
 // ---- normalisation kernels ----------------------------------------------------------------
 
 // dinv[i] = 1/sqrt(stored length of row i), float32, correctly rounded divide and sqrt.
@@ -250,10 +292,33 @@ gsr_status_t gsr_set_option(const char* key, int64_t value) {
     } else if (!strcmp(key, "max_workgroups")) {
         if (value < 0 || value % 8 != 0) return fail(GSR_ERR_INVALID_ARG, "max_workgroups must be a multiple of 8");
         o.max_workgroups = value;
+    } else if (!strcmp(key, "profile")) {
+        if (value < 0 || value >= ((int64_t)1 << KC_COUNT)) return fail(GSR_ERR_INVALID_ARG, "profile mask out of range");
+        o.profile = value;
     } else {
         return fail(GSR_ERR_INVALID_ARG, "unknown option '%s'", key);
     }
     return GSR_OK;
+}
+
+gsr_status_t gsr_profile_read(int32_t kernel_class, double* total_ms, int64_t* launches) {
+    if (kernel_class < 0 || kernel_class >= KC_COUNT) return fail(GSR_ERR_INVALID_ARG, "kernel class %d", kernel_class);
+    prof_collect();
+    if (total_ms) *total_ms = g_prof_ms[kernel_class];
+    if (launches) *launches = g_prof_n[kernel_class];
+    return GSR_OK;
+}
+
+gsr_status_t gsr_profile_reset(void) {
+    prof_collect();
+    for (int i = 0; i < KC_COUNT; ++i) { g_prof_ms[i] = 0.0; g_prof_n[i] = 0; }
+    return GSR_OK;
+}
+
+const char* gsr_profile_class_name(int32_t kernel_class) {
+    static const char* names[KC_COUNT] = {"block_forward", "block_inverse", "block_backward", "grad", "group_sum",
+                                          "hub_first_pass", "dw_reduce", "head", "layout_copy"};
+    return (kernel_class >= 0 && kernel_class < KC_COUNT) ? names[kernel_class] : "";
 }
 
 gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const void* rowptr,

@@ -32,8 +32,31 @@ struct Options {
     int64_t hub_threshold = 512;  // rows longer than this are reduced in two passes
     int64_t hub_chunk = 256;      // neighbours per first-pass partial
     int64_t max_workgroups = 0;   // 0: derive from the device (multiple of 8)
+    int64_t profile = 0;          // bit i set: time kernel class i with HIP events
 };
 Options& options();
+
+// ---- per-kernel timing (gsr_set_option("profile", mask)) -----------------------------------
+enum KernelClass {
+    KC_BLOCK_FWD = 0,  // k_block, forward
+    KC_BLOCK_INV,      // k_block, inverse only
+    KC_BLOCK_BWD,      // k_block, inverse + weight gradient
+    KC_GRAD,           // k_grad
+    KC_SUM,            // k_sum (group sum / record of a plane)
+    KC_HUB,            // first pass over hub rows
+    KC_DW_REDUCE,
+    KC_HEAD,
+    KC_COPY,
+    KC_COUNT
+};
+// Records a HIP event on `s` before and after the launches made while it is alive, if the
+// class is enabled.  Durations are collected by gsr_profile_read.
+struct ProfScope {
+    ProfScope(KernelClass kc, hipStream_t s);
+    ~ProfScope();
+    int slot;
+    hipStream_t stream;
+};
 
 // ---- CSR on the device --------------------------------------------------------------------
 // Rows longer than `hub_threshold` ("hub" rows: clock/reset-like nets) are cut into chunks of

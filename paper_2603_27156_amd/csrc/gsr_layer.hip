@@ -364,6 +364,7 @@ static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs
     a.n = (int)x.cfg->n; a.src = src; a.ld = ld; a.src_gs = gs; a.nsrc = nsrc; a.y0 = y0;
     a.k = x.cfg->k; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.out_vals = x.rec_vals(slot); a.out_mask = x.rec_mask(slot);
+    ProfScope prof(KC_SUM, x.s);
     hipLaunchKernelGGL((k_sum<DG, T>), dim3((unsigned)x.g->grid * 2), dim3(256), 0, x.s, a);
 }
 
@@ -372,6 +373,7 @@ static void launch_hub_records(const Ctx<DG, T>& x, int slot) {
     const HubPlan& h = x.g->a.hub;
     if (h.n_chunks == 0) return;
     HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+    ProfScope prof(KC_HUB, x.s);
     hipLaunchKernelGGL((k_hub_records<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
                        make_view(x.g, false), hc, (const T*)x.rec_vals(slot),
                        (const typename MaskOf<DG>::type*)x.rec_mask(slot), x.cfg->k, x.hub_part());
@@ -382,6 +384,7 @@ static void launch_hub_dense(const Ctx<DG, T>& x, const T* plane, int64_t ld) {
     const HubPlan& h = x.g->at.hub;
     if (h.n_chunks == 0) return;
     HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+    ProfScope prof(KC_HUB, x.s);
     hipLaunchKernelGGL((k_hub_dense<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
                        make_view(x.g, true), hc, plane, ld, x.hub_part());
 }
@@ -400,6 +403,7 @@ static void launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const float
     a.out_mask = out_slot >= 0 ? x.rec_mask(out_slot) : nullptr;
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
     const dim3 grid((unsigned)x.g->grid), block(256);
+    ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
     if (mode == 0) hipLaunchKernelGGL((k_block<DG, T, +1, false>), grid, block, 0, x.s, a);
     else if (mode == 1) hipLaunchKernelGGL((k_block<DG, T, -1, false>), grid, block, 0, x.s, a);
     else hipLaunchKernelGGL((k_block<DG, T, -1, true>), grid, block, 0, x.s, a);
@@ -414,6 +418,7 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
     a.own_mask = x.rec_mask(mask_slot); a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
+    ProfScope prof(KC_GRAD, x.s);
     hipLaunchKernelGGL((k_grad<DG, T>), dim3((unsigned)x.g->grid), dim3(256), 0, x.s, a);
 }
 
@@ -462,8 +467,11 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         }
         const int out_slot = i < C ? i : (C == 2 ? 0 : -1);
         launch_block<DG, T>(x, 2, i - 1, wi, y.grp(i - 1), y.ld, out_slot, dy.grp(i - 1), dy.ld);
-        hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 255) / 256), dim3(256), 0, x.s, (const float*)x.dw_partial(),
-                           x.g->grid, DG * DG, dw_out + (size_t)(i - 1) * DG * DG);
+        {
+            ProfScope prof(KC_DW_REDUCE, x.s);
+            hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 255) / 256), dim3(256), 0, x.s, (const float*)x.dw_partial(),
+                               x.g->grid, DG * DG, dw_out + (size_t)(i - 1) * DG * DG);
+        }
         if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, i - 1, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1);
         else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, 0, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1);
     }
@@ -524,6 +532,7 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
     const Planes<T> in = caller_planes<T>(const_cast<void*>(x0), cfg);
     const dim3 cgrid((unsigned)g->grid * 4), cblock(256);
     auto copy = [&](const Planes<T>& from, const Planes<T>& to) {
+        ProfScope prof(KC_COPY, s);
         hipLaunchKernelGGL((k_copy_planes<T>), cgrid, cblock, 0, s, n, DG, C, (const T*)from.base, from.ld, from.gs, to.base,
                            to.ld, to.gs);
     };
@@ -534,9 +543,12 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
     HeadArgs<T> h;
     h.n = (int)n; h.d = cfg->d; h.dg = DG; h.act = act.base; h.grad = grad.base; h.ld = act.ld; h.gs = act.gs;
     h.w_out = w_out; h.b_out = b_out; h.target = target; h.yhat = yhat_out; h.partial = (float*)(base + sw.head);
-    hipLaunchKernelGGL((k_head<T>), dim3((unsigned)g->grid), dim3(256), 0, s, h);
-    hipLaunchKernelGGL(k_head_reduce, dim3((cfg->d + 2 + 255) / 256), dim3(256), 0, s, (const float*)h.partial, g->grid, cfg->d,
-                       (int)n, dw_out, db_out, loss_out);
+    {
+        ProfScope prof(KC_HEAD, s);
+        hipLaunchKernelGGL((k_head<T>), dim3((unsigned)g->grid), dim3(256), 0, s, h);
+        hipLaunchKernelGGL(k_head_reduce, dim3((cfg->d + 2 + 255) / 256), dim3(256), 0, s, (const float*)h.partial, g->grid,
+                           cfg->d, (int)n, dw_out, db_out, loss_out);
+    }
     for (int l = L - 1; l >= 0; --l) layer_backward_impl<DG, T>(x, w_all + l * wl, act, grad, dw_all + l * wl, true);
     if (dx0_out) copy(grad, caller_planes<T>(dx0_out, cfg));
     if (x0_rebuilt_out) copy(act, caller_planes<T>(x0_rebuilt_out, cfg));
