@@ -48,6 +48,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override L")
+    ap.add_argument("--max-workgroups", type=int, default=0, help="override the persistent grid (multiple of 8)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events in the timed region")
     args = ap.parse_args()
@@ -72,6 +73,8 @@ def main() -> int:
         w = synth.workload(2, dtype="bf16", name="cfg2-1M-bf16")
     if args.layers > 0:
         w = synth.workload(idx, l=args.layers, dtype=w.dtype, name=w.name)
+    if args.max_workgroups:
+        gsr.gsr_set_option("max_workgroups", args.max_workgroups)
     t_gen = time.time()
     inp = synth.make_inputs(w, 0)
     g = gsr.gsr_graph_create(inp.rowptr, inp.colidx)

@@ -45,12 +45,19 @@ struct MaskOf<64> { using type = uint64_t; };
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 
-// Orders this wave's LDS traffic: everything before is complete and visible to the other lanes
-// of the wave before anything after is issued.  (A wave runs in lock step; only the compiler
-// and the LDS queue need to be told.)
+// Orders this wave's LDS traffic for the compiler.  The hardware executes the LDS instructions of
+// one wave in issue order, so a write followed by another lane's read needs no wait, only the
+// guarantee that the compiler keeps the two in program order.
 __device__ __forceinline__ void wave_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+    asm volatile("" ::: "memory");
     __builtin_amdgcn_wave_barrier();
+}
+
+// LDS += v without a return value (ds_add_f32).  Only used where no two lanes of the same
+// instruction address the same word and one wave owns the buffer: the additions then happen in
+// program order and the result does not depend on timing.
+__device__ __forceinline__ void lds_add(float* p, float v) {
+    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
 __device__ __forceinline__ uint64_t ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
@@ -68,12 +75,28 @@ __device__ __forceinline__ int popc(typename MaskOf<DG>::type m) {
     else return __popc(m);
 }
 
-// sum over the DG lanes of this lane's row, same value (and same order) in every lane
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true);
+    return v + __builtin_bit_cast(float, moved);
+}
+
+__device__ __forceinline__ float read_lane(float v, int l) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+}
+
+// Sum over the DG lanes of this lane's row, the same value (same association) in every lane:
+// butterfly inside each group of 16 lanes with DPP (xor 1, xor 2, half-row mirror, row mirror),
+// then the four group sums are combined as (g0 + g1) + (g2 + g3).
 template <int DG>
 __device__ __forceinline__ float sub_sum(float v) {
-#pragma unroll
-    for (int off = DG / 2; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror
+    v = dpp_add<0x140>(v);   // row_mirror
+    const float lo = read_lane(v, 0) + read_lane(v, 16), hi = read_lane(v, 32) + read_lane(v, 48);
+    if constexpr (DG == 64) return lo + hi;
+    else return (threadIdx.x & 32) ? hi : lo;
 }
 
 // ---- GS: exact top-k of a row ----------------------------------------------------------------
@@ -105,6 +128,46 @@ __device__ __forceinline__ bool topk_select(float x, int k, int c, int sub, type
     const bool sel = (key > thr) || (key == thr && popc<DG>(eq & below) < need);
     *mask_out = sub_bits<DG>(ballot(sel), sub);
     return sel;
+}
+
+// The same search for R rows at once (independent bisections interleaved so that their
+// dependent ballot -> popcount -> compare chains overlap).
+template <int DG, int R>
+__device__ __forceinline__ void topk_select_multi(const float (&x)[R], int k, int c, int sub, bool (&sel)[R],
+                                                  typename MaskOf<DG>::type (&mask_out)[R]) {
+    using M = typename MaskOf<DG>::type;
+    uint32_t key[R], thr[R];
+    bool done[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        uint32_t u = __float_as_uint(x[r]);
+        if (u == 0x80000000u) u = 0u;
+        key[r] = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+        thr[r] = 0u;
+        done[r] = (k >= DG);
+    }
+    for (int bit = 31; bit >= 0; --bit) {
+        bool all = true;
+#pragma unroll
+        for (int r = 0; r < R; ++r) all = all && done[r];
+        if (ballot(!all) == 0ull) break;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t cand = thr[r] | (1u << bit);
+            const int cnt = popc<DG>(sub_bits<DG>(ballot(key[r] >= cand), sub));
+            if (cnt >= k) thr[r] = cand;
+            done[r] = done[r] || (cnt == k);
+        }
+    }
+    const M below = ((M)1 << c) - 1;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const M gt = sub_bits<DG>(ballot(key[r] > thr[r]), sub);
+        const M eq = sub_bits<DG>(ballot(key[r] == thr[r]), sub);
+        const int need = k - popc<DG>(gt);
+        sel[r] = (key[r] > thr[r]) || (key[r] == thr[r] && popc<DG>(eq & below) < need);
+        mask_out[r] = sub_bits<DG>(ballot(sel[r]), sub);
+    }
 }
 
 // ---- CSR views -------------------------------------------------------------------------------
@@ -190,6 +253,141 @@ __device__ __forceinline__ float gather_dense(const CsrView& g, const T* __restr
         for (int u = 0; u < U; ++u) acc += a[u] * v[u];
     }
     return acc;
+}
+
+// ---- tile-staged gathers ----------------------------------------------------------------------------
+// A wave owns 16 consecutive rows.  Their neighbour lists are one contiguous edge range, so the
+// dependent chain row pointer -> column index -> neighbour data is walked once per tile, 64 edges
+// per step, instead of once per row: lane l loads edge l of the chunk, finds the row it belongs
+// to, and parks (column, value, row) in LDS.  The neighbour data of many edges is then in flight
+// at once, and every contribution is added into the LDS tile H[row][col] in edge order.
+struct EdgeRec {
+    int j;      // neighbour (column of A)
+    float a;    // a_ij
+    int r;      // row of the tile, 0..15
+    int pad;
+};
+
+// Row pointers of the tile's 17 row boundaries (clamped at n) into s_rp.  Returns whether one of
+// the rows is a split ("hub") row.
+__device__ __forceinline__ bool tile_begin(const CsrView& g, int r0, int n, int* s_rp, int lane) {
+    int rpv = 0;
+    if (lane < 17) {
+        const int row = r0 + lane < n ? r0 + lane : n;
+        rpv = g.rp[row];
+        s_rp[lane] = rpv;
+    }
+    wave_sync();
+    const bool hub = lane < 16 && (s_rp[lane + 1] - rpv) > g.hub_threshold;
+    return ballot(hub) != 0ull;
+}
+
+// stage up to 64 edges [eb, min(eb+64, e_b)) into ebuf; returns how many
+__device__ __forceinline__ int stage_edges(const CsrView& g, int eb, int e_b, const int* s_rp, EdgeRec* ebuf, int lane) {
+    const int e = eb + lane;
+    const bool ok = e < e_b;
+    EdgeRec me;
+    me.j = ok ? g.ci[e] : 0;
+    me.a = ok ? g.av[e] : 0.f;
+    int r = 0;
+#pragma unroll
+    for (int step = 8; step >= 1; step >>= 1)
+        if (s_rp[r + step] <= e) r += step;
+    me.r = r;
+    me.pad = 0;
+    wave_sync();          // readers of the previous chunk are done
+    ebuf[lane] = me;
+    wave_sync();
+    return e_b - eb < 64 ? e_b - eb : 64;
+}
+
+// H[r][col] += a_ij * V[j][t] for every edge in [e_a, e_b) and every recorded slot t of j.
+// Lane = (edge of a group, slot): 64 / KP edges per load instruction, KP = k rounded up to a power
+// of two; the record of j is k values plus their k column bytes.  The LDS additions of one group
+// are issued edge by edge, so no instruction carries two contributions to the same word.
+template <int DG, typename T>
+__device__ __forceinline__ void range_gather_records(const CsrView& g, const T* __restrict__ vals,
+                                                     const uint8_t* __restrict__ idx, int k, int kpl, int e_a, int e_b,
+                                                     const int* s_rp, EdgeRec* ebuf, float* st_h, int lane) {
+    constexpr int LR = DG + 1, GB = 8;
+    const int epg = 64 >> kpl, q = lane >> kpl, t = lane & ((1 << kpl) - 1);
+    for (int eb = e_a; eb < e_b; eb += 64) {
+        const int cnt = stage_edges(g, eb, e_b, s_rp, ebuf, lane);
+        const int ngroups = (cnt + epg - 1) >> (6 - kpl);
+        for (int g0 = 0; g0 < ngroups; g0 += GB) {
+            float v[GB];
+            int dst[GB];
+#pragma unroll
+            for (int u = 0; u < GB; ++u) {
+                const int ei = (g0 + u) * epg + q;
+                const bool ok = ei < cnt && t < k;
+                const EdgeRec er = ebuf[ok ? ei : 0];
+                const size_t off = (size_t)er.j * k + t;
+                v[u] = ok ? er.a * to_float(vals[off]) : 0.f;
+                dst[u] = ok ? er.r * LR + (int)idx[off] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < GB; ++u)
+                for (int qq = 0; qq < epg; ++qq)
+                    if (qq == q && dst[u] >= 0) lds_add(st_h + dst[u], v[u]);
+        }
+    }
+}
+
+// Q[r][c] += a_ij * X[j][c] for every edge in [e_a, e_b): lane c of a (sub-)wave owns column c.
+template <int DG, typename T>
+__device__ __forceinline__ void range_gather_dense(const CsrView& g, const T* __restrict__ x, int64_t ld, int e_a, int e_b,
+                                                   const int* s_rp, EdgeRec* ebuf, float* st, int lane) {
+    constexpr int LR = DG + 1, G = 64 / DG, GB = 16;
+    const int c = lane % DG, sub = lane / DG;
+    for (int eb = e_a; eb < e_b; eb += 64) {
+        const int cnt = stage_edges(g, eb, e_b, s_rp, ebuf, lane);
+        const int nit = (cnt + G - 1) / G;
+        for (int i0 = 0; i0 < nit; i0 += GB) {
+            float v[GB];
+            int dst[GB];
+#pragma unroll
+            for (int u = 0; u < GB; ++u) {
+                const int ei = (i0 + u) * G + sub;
+                const bool ok = ei < cnt;
+                const EdgeRec er = ebuf[ok ? ei : 0];
+                v[u] = ok ? er.a * to_float(x[(size_t)er.j * ld + c]) : 0.f;
+                dst[u] = ok ? er.r * LR + c : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < GB; ++u)
+#pragma unroll
+                for (int s2 = 0; s2 < G; ++s2)
+                    if (s2 == sub && dst[u] >= 0) lds_add(st + dst[u], v[u]);
+        }
+    }
+}
+
+// Walks the tile's rows: maximal runs of ordinary rows go through `range(e_a, e_b)`, split rows
+// receive the sum of their first-pass partial rows.  st must be zero on entry.
+template <int DG, typename Range>
+__device__ __forceinline__ void tile_gather(const CsrView& g, const float* __restrict__ hub_part, bool has_hub, int r0,
+                                            const int* s_rp, float* st, int lane, Range range) {
+    constexpr int LR = DG + 1;
+    if (!has_hub) {
+        range(s_rp[0], s_rp[16]);
+        return;
+    }
+    int run = 0;
+    for (int r = 0; r <= 16; ++r) {
+        const bool hub = r < 16 && (s_rp[r + 1] - s_rp[r]) > g.hub_threshold;
+        if (r == 16 || hub) {
+            if (s_rp[r] > s_rp[run]) range(s_rp[run], s_rp[r]);
+            run = r + 1;
+        }
+        if (hub && lane < DG) st[r * LR + lane] = hub_row_sum<DG>(g, hub_part, r0 + r, lane);
+    }
+}
+
+template <int DG>
+__device__ __forceinline__ void zero_tile(float* st, int lane) {
+#pragma unroll
+    for (int i = lane; i < 16 * (DG + 1); i += 64) st[i] = 0.f;
 }
 
 // ---- 16-row MFMA tiles -------------------------------------------------------------------------

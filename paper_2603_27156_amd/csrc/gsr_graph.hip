@@ -223,6 +223,8 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     for (int s = 0; s < cfg->c && s < 8; ++s) {
         w.rec_vals[s] = off;
         off += align_up(n * (size_t)cfg->k * b);
+        w.rec_idx[s] = off;
+        off += align_up(n * (size_t)cfg->k);
         w.rec_mask[s] = off;
         off += align_up(n * (dg == 32 ? 4 : 8));
     }

@@ -1,12 +1,13 @@
 // The grouped reversible layer (Section 3, eq. (6)/(7)), its backward fused with the inverse
 // (Algorithm 2's structure; eq. (3), eq. (11)) and the whole training step.
 //
-// Kernels (all persistent over 16-row tiles, one wave per tile, no cross-wave synchronisation
-// inside the sweep):
-//   k_block   H = A*scatter(V,I) of Y_{i-1} gathered from compressed records; O = H W_i on the
-//             matrix cores; Y_i = X_i + O (forward) or X_i = Y_i - O (inverse), in place; the GS
-//             record of the row just written is emitted in the same pass.  With WITH_DW it also
-//             accumulates dW_i += H^T dY_i, so the recomputed H is consumed where it is rebuilt.
+// Kernels (persistent over 16-row tiles, one wave per tile, no cross-wave synchronisation inside
+// the sweep):
+//   k_block   H = A*scatter(V,I) of Y_{i-1} gathered from compressed records into an LDS tile;
+//             O = H W_i on the matrix cores; Y_i = X_i + O (forward) or X_i = Y_i - O (inverse),
+//             in place; the GS record of the row just written is emitted in the same pass.  With
+//             WITH_DW it also accumulates dW_i += H^T dY_i, so the recomputed H is consumed
+//             where it is rebuilt.
 //   k_grad    Q = A^T dY_i (dense-row gather); dH = Q W_i^T on the matrix cores; only the k
 //             positions recorded by I are read; back through the RMS scale; dY_{i-1} += dZ.
 //   k_sum     Y_0 = sum_{j>=2} X_j and/or the GS record of a plane.
@@ -20,36 +21,64 @@ namespace gsr {
 
 CsrView make_view(const gsr_graph_t* g, bool transpose);
 
+// Compressed record of a row ("CBSR" of Section 4.3): the k kept values in ascending column
+// order (already RMS-scaled), their k column bytes, and the row's column bit mask.
 template <int DG, typename T>
-__device__ __forceinline__ void emit_record(float yq, bool ok, int row, int c, int sub, int k, int norm, float eps,
-                                            T* __restrict__ out_vals, typename MaskOf<DG>::type* __restrict__ out_mask) {
+struct Record {
     using M = typename MaskOf<DG>::type;
-    M mask;
-    const bool sel = topk_select<DG>(ok ? yq : 0.f, k, c, sub, &mask);
-    float scale = 1.f;
-    if (norm == GSR_NORM_RMS) {
-        const float ss = sub_sum<DG>(ok ? yq * yq : 0.f);
-        scale = 1.0f / sqrtf(ss / (float)DG + eps);
+    T* vals;        // [n][k]
+    uint8_t* idx;   // [n][k]
+    M* mask;        // [n]
+};
+
+// GS of R rows held in row layout (yq[r] = this lane's column of row r) and their records.
+template <int DG, typename T, int R>
+__device__ __forceinline__ void emit_records(const float (&yq)[R], const bool (&ok)[R], const int (&row)[R], int c, int sub,
+                                             int k, int norm, float eps, const Record<DG, T>& out) {
+    using M = typename MaskOf<DG>::type;
+    float x[R];
+    bool sel[R];
+    M mask[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) x[r] = ok[r] ? yq[r] : 0.f;
+    topk_select_multi<DG, R>(x, k, c, sub, sel, mask);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float scale = 1.f;
+        if (norm == GSR_NORM_RMS) {
+            const float sq = x[r] * x[r];
+            const float ss = sub_sum<DG>(sq);
+            scale = 1.0f / sqrtf(ss / (float)DG + eps);
+        }
+        if (ok[r] && sel[r]) {
+            const size_t at = (size_t)row[r] * k + popc<DG>(mask[r] & (((M)1 << c) - 1));
+            out.vals[at] = from_float<T>(x[r] * scale);
+            out.idx[at] = (uint8_t)c;
+        }
+        if (ok[r] && c == 0) out.mask[row[r]] = mask[r];
     }
-    if (ok && sel) out_vals[(size_t)row * k + popc<DG>(mask & (((M)1 << c) - 1))] = from_float<T>(yq * scale);
-    if (ok && c == 0) out_mask[row] = mask;
 }
+
+// per-wave LDS: tile(s) of 16 x (DG+1) floats, 64 staged edges, 17 row pointers
+template <int DG, int TILES>
+struct WaveLds {
+    float st[TILES][16 * (DG + 1)];
+    EdgeRec ebuf[64];
+    int rp[32];
+};
 
 // ---- block: forward / inverse (+ weight gradient) ------------------------------------------------
 template <int DG, typename T>
 struct BlockArgs {
-    using M = typename MaskOf<DG>::type;
     CsrView g;
     int n, tiles;
-    const T* rec_vals;      // record of Y_{i-1}: values, ascending column order  [n][k]
-    const M* rec_mask;      //                    column bit mask                 [n]
-    int k;
-    const float* hub_part;  // first-pass partial rows of hub rows
+    Record<DG, T> in;       // record of Y_{i-1}
+    int k, kpl;             // kpl = log2 of k rounded up to a power of two
+    const float* hub_part;  // first-pass partial rows of split rows
     const float* w;         // W_i [DG][DG]
     T* plane;               // X_i on entry / Y_i on return (or the reverse), row stride ld
     int64_t ld;
-    T* out_vals;            // record of the row written (NULL: none)
-    M* out_mask;
+    Record<DG, T> out;      // record of the row written (out.mask == NULL: none)
     int norm;
     float eps;
     const T* dy;            // dY_i, row stride ldg            (WITH_DW)
@@ -59,11 +88,12 @@ struct BlockArgs {
 
 template <int DG, typename T, int SIGN, bool WITH_DW>
 __global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
-    constexpr int G = 64 / DG, LR = DG + 1, ST = 16 * LR;
-    __shared__ float lds[4 * (WITH_DW ? 2 : 1) * ST];
+    constexpr int G = 64 / DG, LR = DG + 1, NT = WITH_DW ? 2 : 1, RPW = 16 / G, ER = 4;
+    __shared__ WaveLds<DG, NT> lds[4];
     const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
-    float* st_h = lds + wave * (WITH_DW ? 2 : 1) * ST;
-    float* st_g = st_h + ST;
+    WaveLds<DG, NT>& L = lds[wave];
+    float* st_h = L.st[0];
+    float* st_g = L.st[NT - 1];
     WFrag<DG> wf;
     load_wfrag<DG>(a.w, false, wf);
     f32x4 dw[WITH_DW ? DG / 16 : 1][WITH_DW ? DG / 16 : 1];
@@ -76,12 +106,22 @@ __global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
     const TileSweep ts = tile_sweep(a.tiles);
     for (int t = ts.first; t < ts.end; t += ts.step) {
         const int r0 = t * 16;
-#pragma unroll 1
-        for (int it = 0; it < 16 / G; ++it) {
-            const int r = it * G + sub, row = r0 + r;
-            const bool ok = row < a.n;
-            st_h[r * LR + c] = row_records<DG, T>(a.g, a.rec_vals, a.rec_mask, a.k, a.hub_part, row, ok, c);
-            if constexpr (WITH_DW) st_g[r * LR + c] = ok ? to_float(a.dy[(size_t)row * a.ldg + c]) : 0.f;
+        wave_sync();
+        const bool has_hub = tile_begin(a.g, r0, a.n, L.rp, lane);
+        zero_tile<DG>(st_h, lane);
+        tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
+            range_gather_records<DG, T>(a.g, a.in.vals, a.in.idx, a.k, a.kpl, __builtin_amdgcn_readfirstlane(e_a),
+                                        __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st_h, lane);
+        });
+        if constexpr (WITH_DW) {
+            float gy[RPW];
+#pragma unroll
+            for (int it = 0; it < RPW; ++it) {
+                const int row = r0 + it * G + sub;
+                gy[it] = row < a.n ? to_float(a.dy[(size_t)row * a.ldg + c]) : 0.f;
+            }
+#pragma unroll
+            for (int it = 0; it < RPW; ++it) st_g[(it * G + sub) * LR + c] = gy[it];
         }
         wave_sync();
         f32x4 acc[DG / 16];
@@ -90,20 +130,34 @@ __global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
         wave_sync();
         store_tile<DG>(st_h, acc);
         wave_sync();
-#pragma unroll 1
-        for (int it = 0; it < 16 / G; ++it) {
-            const int r = it * G + sub, row = r0 + r;
-            const bool ok = row < a.n;
-            const float o = st_h[r * LR + c];
-            const float x = ok ? to_float(a.plane[(size_t)row * a.ld + c]) : 0.f;
-            const T yt = from_float<T>(SIGN > 0 ? x + o : x - o);
-            if (ok) a.plane[(size_t)row * a.ld + c] = yt;
-            if (a.out_mask) emit_record<DG, T>(to_float(yt), ok, row, c, sub, a.k, a.norm, a.eps, a.out_vals, a.out_mask);
+        float xv[RPW];
+#pragma unroll
+        for (int it = 0; it < RPW; ++it) {
+            const int row = r0 + it * G + sub;
+            xv[it] = row < a.n ? to_float(a.plane[(size_t)row * a.ld + c]) : 0.f;
         }
-        wave_sync();
+#pragma unroll
+        for (int i0 = 0; i0 < RPW; i0 += ER) {
+            float yq[ER];
+            bool ok[ER];
+            int row[ER];
+#pragma unroll
+            for (int u = 0; u < ER; ++u) {
+                const int r = (i0 + u) * G + sub;
+                row[u] = r0 + r;
+                ok[u] = row[u] < a.n;
+                const float o = st_h[r * LR + c];
+                const T yt = from_float<T>(SIGN > 0 ? xv[i0 + u] + o : xv[i0 + u] - o);
+                if (ok[u]) a.plane[(size_t)row[u] * a.ld + c] = yt;
+                yq[u] = to_float(yt);
+            }
+            if (a.out.mask) emit_records<DG, T, ER>(yq, ok, row, c, sub, a.k, a.norm, a.eps, a.out);
+        }
     }
     if constexpr (WITH_DW) {
         // workgroup partial of dW_i: the four waves add their accumulators in wave order
+        float* red = reinterpret_cast<float*>(lds);
+        static_assert(sizeof(lds) >= DG * DG * sizeof(float), "LDS too small for the dW reduction");
         for (int w = 0; w < 4; ++w) {
             __syncthreads();
             if (wave == w) {
@@ -114,13 +168,13 @@ __global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const int m = 16 * mb + 4 * (lane >> 4) + r, o = 16 * ob + (lane & 15);
-                            if (w == 0) lds[m * DG + o] = dw[mb][ob][r];
-                            else lds[m * DG + o] += dw[mb][ob][r];
+                            if (w == 0) red[m * DG + o] = dw[mb][ob][r];
+                            else red[m * DG + o] += dw[mb][ob][r];
                         }
             }
         }
         __syncthreads();
-        for (int i = threadIdx.x; i < DG * DG; i += 256) a.dw_partial[(size_t)blockIdx.x * DG * DG + i] = lds[i];
+        for (int i = threadIdx.x; i < DG * DG; i += 256) a.dw_partial[(size_t)blockIdx.x * DG * DG + i] = red[i];
     }
 }
 
@@ -155,40 +209,53 @@ struct GradArgs {
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_grad(GradArgs<DG, T> a) {
-    constexpr int G = 64 / DG, LR = DG + 1, ST = 16 * LR;
-    __shared__ float lds[4 * ST];
+    constexpr int G = 64 / DG, LR = DG + 1, RPW = 16 / G;
+    __shared__ WaveLds<DG, 1> lds[4];
     const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
-    float* st = lds + wave * ST;
+    WaveLds<DG, 1>& L = lds[wave];
+    float* st = L.st[0];
     WFrag<DG> wf;
     load_wfrag<DG>(a.w, true, wf);
     const TileSweep ts = tile_sweep(a.tiles);
     for (int t = ts.first; t < ts.end; t += ts.step) {
         const int r0 = t * 16;
-#pragma unroll 1
-        for (int it = 0; it < 16 / G; ++it) {
-            const int r = it * G + sub, row = r0 + r;
-            st[r * LR + c] = row_dense<DG, T>(a.gt, a.dy, a.ldg, a.hub_part, row, row < a.n, c);
-        }
+        wave_sync();
+        const bool has_hub = tile_begin(a.gt, r0, a.n, L.rp, lane);
+        zero_tile<DG>(st, lane);
+        tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, [&](int e_a, int e_b) {
+            range_gather_dense<DG, T>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
+                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st, lane);
+        });
         wave_sync();
         f32x4 acc[DG / 16];
         mfma_tile<DG>(st, wf, acc);      // dH = Q W^T
         wave_sync();
         store_tile<DG>(st, acc);
         wave_sync();
-#pragma unroll 1
-        for (int it = 0; it < 16 / G; ++it) {
+        // everything the rows need from memory, issued together
+        float zz[RPW];
+        bool sel[RPW];
+#pragma unroll
+        for (int it = 0; it < RPW; ++it) {
+            const int row = r0 + it * G + sub;
+            const bool ok = row < a.n;
+            sel[it] = ok && ((a.own_mask[ok ? row : 0] >> c) & 1);
+            zz[it] = (ok && a.norm == GSR_NORM_RMS) ? to_float(a.z[(size_t)row * a.ldz + c]) : 0.f;
+        }
+#pragma unroll
+        for (int it = 0; it < RPW; ++it) {
             const int r = it * G + sub, row = r0 + r;
             const bool ok = row < a.n;
             const float gdh = st[r * LR + c];
-            const bool sel = ok && ((a.own_mask[row] >> c) & 1);
-            float dz = sel ? gdh : 0.f;
-            bool touch = sel;
+            float dz = sel[it] ? gdh : 0.f;
+            bool touch = sel[it];
             if (a.norm == GSR_NORM_RMS) {
-                const float zz = ok ? to_float(a.z[(size_t)row * a.ldz + c]) : 0.f;
-                const float ss = sub_sum<DG>(zz * zz);
+                const float sq = zz[it] * zz[it];
+                const float ss = sub_sum<DG>(sq);
                 const float rr = sqrtf(ss / (float)DG + a.eps);
-                const float dot = sub_sum<DG>(sel ? gdh * zz : 0.f);
-                dz = (sel ? gdh / rr : 0.f) - zz * (dot / ((float)DG * rr * rr * rr));
+                const float pr = sel[it] ? gdh * zz[it] : 0.f;
+                const float dot = sub_sum<DG>(pr);
+                dz = (sel[it] ? gdh / rr : 0.f) - zz[it] * (dot / ((float)DG * rr * rr * rr));
                 touch = ok;
             }
             if (touch)
@@ -197,14 +264,12 @@ __global__ __launch_bounds__(256) void k_grad(GradArgs<DG, T> a) {
                     *p = from_float<T>(to_float(*p) + dz);
                 }
         }
-        wave_sync();
     }
 }
 
 // ---- group sum / record of a plane --------------------------------------------------------------------
 template <int DG, typename T>
 struct SumArgs {
-    using M = typename MaskOf<DG>::type;
     int n;
     const T* src;           // nsrc planes, src_gs apart, row stride ld
     int64_t ld, src_gs;
@@ -212,26 +277,32 @@ struct SumArgs {
     T* y0;                  // dense [n][DG] copy of the sum (NULL: not kept)
     int k, norm;
     float eps;
-    T* out_vals;
-    M* out_mask;
+    Record<DG, T> out;
 };
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
-    constexpr int G = 64 / DG;
+    constexpr int G = 64 / DG, ER = 4;
     const int lane = lane_id(), c = lane % DG, sub = lane / DG;
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    for (int r0 = ((blockIdx.x * blockDim.x + threadIdx.x) >> 6) * G; r0 < a.n; r0 += nwaves * G) {
-        const int row = r0 + sub;
-        const bool ok = row < a.n;
-        float s = 0.f;
-        if (ok) {
-            s = to_float(a.src[(size_t)row * a.ld + c]);
-            for (int j = 1; j < a.nsrc; ++j) s += to_float(a.src[(size_t)j * a.src_gs + (size_t)row * a.ld + c]);
+    for (int r0 = ((blockIdx.x * blockDim.x + threadIdx.x) >> 6) * (G * ER); r0 < a.n; r0 += nwaves * G * ER) {
+        float yq[ER];
+        bool ok[ER];
+        int row[ER];
+#pragma unroll
+        for (int u = 0; u < ER; ++u) {
+            row[u] = r0 + u * G + sub;
+            ok[u] = row[u] < a.n;
+            float s = 0.f;
+            if (ok[u]) {
+                s = to_float(a.src[(size_t)row[u] * a.ld + c]);
+                for (int j = 1; j < a.nsrc; ++j) s += to_float(a.src[(size_t)j * a.src_gs + (size_t)row[u] * a.ld + c]);
+            }
+            const T st = from_float<T>(s);
+            if (ok[u] && a.y0) a.y0[(size_t)row[u] * DG + c] = st;
+            yq[u] = to_float(st);
         }
-        const T st = from_float<T>(s);
-        if (ok && a.y0) a.y0[(size_t)row * DG + c] = st;
-        emit_record<DG, T>(to_float(st), ok, row, c, sub, a.k, a.norm, a.eps, a.out_vals, a.out_mask);
+        emit_records<DG, T, ER>(yq, ok, row, c, sub, a.k, a.norm, a.eps, a.out);
     }
 }
 
@@ -351,8 +422,19 @@ struct Ctx {
     char* ws;
     LayerWs lw;
     int tiles;
-    T* rec_vals(int slot) const { return (T*)(ws + lw.rec_vals[slot]); }
-    M* rec_mask(int slot) const { return (M*)(ws + lw.rec_mask[slot]); }
+    Record<DG, T> rec(int slot) const {
+        Record<DG, T> r;
+        if (slot < 0) { r.vals = nullptr; r.idx = nullptr; r.mask = nullptr; return r; }
+        r.vals = (T*)(ws + lw.rec_vals[slot]);
+        r.idx = (uint8_t*)(ws + lw.rec_idx[slot]);
+        r.mask = (M*)(ws + lw.rec_mask[slot]);
+        return r;
+    }
+    int kpl() const {
+        int l = 0;
+        while ((1 << l) < cfg->k) ++l;
+        return l;
+    }
     T* y0() const { return (T*)(ws + lw.y0); }
     float* dw_partial() const { return (float*)(ws + lw.dw_partial); }
     float* hub_part() const { return (float*)(ws + lw.hub_partial); }
@@ -363,7 +445,7 @@ static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs
     SumArgs<DG, T> a;
     a.n = (int)x.cfg->n; a.src = src; a.ld = ld; a.src_gs = gs; a.nsrc = nsrc; a.y0 = y0;
     a.k = x.cfg->k; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
-    a.out_vals = x.rec_vals(slot); a.out_mask = x.rec_mask(slot);
+    a.out = x.rec(slot);
     ProfScope prof(KC_SUM, x.s);
     hipLaunchKernelGGL((k_sum<DG, T>), dim3((unsigned)x.g->grid * 2), dim3(256), 0, x.s, a);
 }
@@ -375,8 +457,8 @@ static void launch_hub_records(const Ctx<DG, T>& x, int slot) {
     HubChunks hc{h.ce0, h.ce1, h.n_chunks};
     ProfScope prof(KC_HUB, x.s);
     hipLaunchKernelGGL((k_hub_records<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
-                       make_view(x.g, false), hc, (const T*)x.rec_vals(slot),
-                       (const typename MaskOf<DG>::type*)x.rec_mask(slot), x.cfg->k, x.hub_part());
+                       make_view(x.g, false), hc, (const T*)x.rec(slot).vals,
+                       (const typename MaskOf<DG>::type*)x.rec(slot).mask, x.cfg->k, x.hub_part());
 }
 
 template <int DG, typename T>
@@ -397,10 +479,9 @@ static void launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const float
     BlockArgs<DG, T> a;
     a.g = make_view(x.g, false);
     a.n = (int)x.cfg->n; a.tiles = x.tiles;
-    a.rec_vals = x.rec_vals(in_slot); a.rec_mask = x.rec_mask(in_slot); a.k = x.cfg->k;
+    a.in = x.rec(in_slot); a.k = x.cfg->k; a.kpl = x.kpl();
     a.hub_part = x.hub_part(); a.w = w; a.plane = plane; a.ld = ld;
-    a.out_vals = out_slot >= 0 ? x.rec_vals(out_slot) : nullptr;
-    a.out_mask = out_slot >= 0 ? x.rec_mask(out_slot) : nullptr;
+    a.out = x.rec(out_slot);
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
     const dim3 grid((unsigned)x.g->grid), block(256);
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
@@ -416,7 +497,7 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     GradArgs<DG, T> a;
     a.gt = make_view(x.g, true);
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
-    a.own_mask = x.rec_mask(mask_slot); a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
+    a.own_mask = x.rec(mask_slot).mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
     ProfScope prof(KC_GRAD, x.s);
     hipLaunchKernelGGL((k_grad<DG, T>), dim3((unsigned)x.g->grid), dim3(256), 0, x.s, a);
