@@ -131,7 +131,8 @@ __device__ __forceinline__ bool topk_select(float x, int k, int c, int sub, type
 }
 
 // The same search for R rows at once (independent bisections interleaved so that their
-// dependent ballot -> popcount -> compare chains overlap).
+// dependent ballot -> popcount -> compare chains overlap).  With one row per wave (DG = 64) every
+// quantity of the search is wave-uniform and lives in scalar registers.
 template <int DG, int R>
 __device__ __forceinline__ void topk_select_multi(const float (&x)[R], int k, int c, int sub, bool (&sel)[R],
                                                   typename MaskOf<DG>::type (&mask_out)[R]) {
@@ -150,24 +151,45 @@ __device__ __forceinline__ void topk_select_multi(const float (&x)[R], int k, in
         bool all = true;
 #pragma unroll
         for (int r = 0; r < R; ++r) all = all && done[r];
-        if (ballot(!all) == 0ull) break;
+        if constexpr (DG == 64) {
+            if (all) break;
+        } else {
+            if (ballot(!all) == 0ull) break;
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const uint32_t cand = thr[r] | (1u << bit);
             const int cnt = popc<DG>(sub_bits<DG>(ballot(key[r] >= cand), sub));
-            if (cnt >= k) thr[r] = cand;
+            thr[r] = cnt >= k ? cand : thr[r];
             done[r] = done[r] || (cnt == k);
         }
     }
-    const M below = ((M)1 << c) - 1;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const M gt = sub_bits<DG>(ballot(key[r] > thr[r]), sub);
-        const M eq = sub_bits<DG>(ballot(key[r] == thr[r]), sub);
-        const int need = k - popc<DG>(gt);
-        sel[r] = (key[r] > thr[r]) || (key[r] == thr[r] && popc<DG>(eq & below) < need);
-        mask_out[r] = sub_bits<DG>(ballot(sel[r]), sub);
+        const bool ge = key[r] >= thr[r];
+        const M ge_m = sub_bits<DG>(ballot(ge), sub);
+        bool exact = popc<DG>(ge_m) == k;       // no tie at the threshold: the set is {key >= thr}
+        if constexpr (DG != 64) exact = ballot(!exact) == 0ull;
+        if (exact) {
+            sel[r] = ge;
+            mask_out[r] = ge_m;
+        } else {
+            const M below = ((M)1 << c) - 1;
+            const M gt = sub_bits<DG>(ballot(key[r] > thr[r]), sub);
+            const M eq = sub_bits<DG>(ballot(key[r] == thr[r]), sub);
+            const int need = k - popc<DG>(gt);
+            sel[r] = (key[r] > thr[r]) || (key[r] == thr[r] && popc<DG>(eq & below) < need);
+            mask_out[r] = sub_bits<DG>(ballot(sel[r]), sub);
+        }
     }
+}
+
+// number of set bits of this row's mask below this lane's column
+template <int DG>
+__device__ __forceinline__ int rank_in_mask(typename MaskOf<DG>::type m, uint64_t wave_mask, int sub) {
+    const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(wave_mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)wave_mask, 0));
+    if constexpr (DG == 64) return below;
+    else return sub ? below - __popc((uint32_t)wave_mask) : below;
 }
 
 // ---- CSR views -------------------------------------------------------------------------------
@@ -303,8 +325,9 @@ __device__ __forceinline__ int stage_edges(const CsrView& g, int eb, int e_b, co
 
 // H[r][col] += a_ij * V[j][t] for every edge in [e_a, e_b) and every recorded slot t of j.
 // Lane = (edge of a group, slot): 64 / KP edges per load instruction, KP = k rounded up to a power
-// of two; the record of j is k values plus their k column bytes.  The LDS additions of one group
-// are issued edge by edge, so no instruction carries two contributions to the same word.
+// of two; the record of j is k values plus their k column bytes.  The LDS read-add-writes of one
+// group are issued edge by edge (LDS float atomics are far slower than a read and a write), so no
+// instruction carries two contributions to the same word and the order of additions is fixed.
 template <int DG, typename T>
 __device__ __forceinline__ void range_gather_records(const CsrView& g, const T* __restrict__ vals,
                                                      const uint8_t* __restrict__ idx, int k, int kpl, int e_a, int e_b,
@@ -319,52 +342,70 @@ __device__ __forceinline__ void range_gather_records(const CsrView& g, const T* 
             int dst[GB];
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
+                // loads are unconditional (index clamped to a staged edge); what must not count adds 0
+                // into the dump words behind the tile
                 const int ei = (g0 + u) * epg + q;
                 const bool ok = ei < cnt && t < k;
-                const EdgeRec er = ebuf[ok ? ei : 0];
-                const size_t off = (size_t)er.j * k + t;
-                v[u] = ok ? er.a * to_float(vals[off]) : 0.f;
-                dst[u] = ok ? er.r * LR + (int)idx[off] : -1;
+                const EdgeRec er = ebuf[ei < cnt ? ei : cnt - 1];
+                const size_t off = (size_t)er.j * k + (t < k ? t : 0);
+                const float val = to_float(vals[off]);
+                const int col = (int)idx[off];
+                v[u] = ok ? er.a * val : 0.f;
+                dst[u] = ok ? er.r * LR + col : 16 * LR + lane;
             }
 #pragma unroll
             for (int u = 0; u < GB; ++u)
                 for (int qq = 0; qq < epg; ++qq)
-                    if (qq == q && dst[u] >= 0) lds_add(st_h + dst[u], v[u]);
+                    if (qq == q) st_h[dst[u]] += v[u];
         }
     }
 }
 
-// Q[r][c] += a_ij * X[j][c] for every edge in [e_a, e_b): lane c of a (sub-)wave owns column c.
+// Q[r][c] += a_ij * X[j][c] for every edge in [e_a, e_b): lane c of a (sub-)wave owns column c and
+// sums the edges of one row in a register; the sum goes to the LDS tile when the row changes.
+// With two rows per wave (DG = 32) the half-waves take alternate edges and flush one after the
+// other, so two partial sums of the same row never meet in one instruction.
 template <int DG, typename T>
 __device__ __forceinline__ void range_gather_dense(const CsrView& g, const T* __restrict__ x, int64_t ld, int e_a, int e_b,
-                                                   const int* s_rp, EdgeRec* ebuf, float* st, int lane) {
+                                                   const int* s_rp, EdgeRec* ebuf, float* st, int lane, int dbg = 0) {
     constexpr int LR = DG + 1, G = 64 / DG, GB = 16;
     const int c = lane % DG, sub = lane / DG;
+    float acc = 0.f;
+    int cur = 16;                      // row being summed; 16 = the dump row
+    auto flush = [&](int next) {
+#pragma unroll
+        for (int s2 = 0; s2 < G; ++s2)
+            if (s2 == sub && next != cur) st[cur * LR + c] += acc;
+        if (next != cur) { acc = 0.f; cur = next; }
+    };
     for (int eb = e_a; eb < e_b; eb += 64) {
         const int cnt = stage_edges(g, eb, e_b, s_rp, ebuf, lane);
         const int nit = (cnt + G - 1) / G;
         for (int i0 = 0; i0 < nit; i0 += GB) {
             float v[GB];
-            int dst[GB];
+            int rr[GB];
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
                 const int ei = (i0 + u) * G + sub;
                 const bool ok = ei < cnt;
-                const EdgeRec er = ebuf[ok ? ei : 0];
-                v[u] = ok ? er.a * to_float(x[(size_t)er.j * ld + c]) : 0.f;
-                dst[u] = ok ? er.r * LR + c : -1;
+                const EdgeRec er = ebuf[ok ? ei : cnt - 1];
+                const float val = to_float(x[(size_t)er.j * ld + c]);
+                v[u] = ok ? er.a * val : 0.f;
+                rr[u] = ok ? er.r : -1;
             }
 #pragma unroll
-            for (int u = 0; u < GB; ++u)
-#pragma unroll
-                for (int s2 = 0; s2 < G; ++s2)
-                    if (s2 == sub && dst[u] >= 0) lds_add(st + dst[u], v[u]);
+            for (int u = 0; u < GB; ++u) {
+                flush(rr[u] >= 0 ? rr[u] : cur);
+                acc += v[u];
+            }
         }
     }
+    flush(16);
 }
 
 // Walks the tile's rows: maximal runs of ordinary rows go through `range(e_a, e_b)`, split rows
-// receive the sum of their first-pass partial rows.  st must be zero on entry.
+// receive the sum of their first-pass partial rows.  st must be zero on entry; it is 16 rows of
+// DG+1 floats followed by 64 dump words.
 template <int DG, typename Range>
 __device__ __forceinline__ void tile_gather(const CsrView& g, const float* __restrict__ hub_part, bool has_hub, int r0,
                                             const int* s_rp, float* st, int lane, Range range) {
@@ -391,31 +432,31 @@ __device__ __forceinline__ void zero_tile(float* st, int lane) {
 }
 
 // ---- 16-row MFMA tiles -------------------------------------------------------------------------
-// A wave multiplies its 16 x DG tile (staged in LDS, row stride DG+1) by a DG x DG matrix held
-// in registers as v_mfma_f32_16x16x4_f32 B-operands:
+// A wave multiplies its 16 x DG tile (staged in LDS, row stride DG+1) by a DG x DG matrix with
+// v_mfma_f32_16x16x4_f32:
 //   A[i][kk]: lane = kk*16 + i;  B[kk][j]: lane = kk*16 + j;  D[4*(lane/16)+r][lane%16] in reg r.
 using f32x4 = __attribute__((__vector_size__(4 * sizeof(float)))) float;
 
+// The DG x DG weight matrix sits in LDS (row stride DG + 8, which spreads the four k-rows of a
+// B operand over different banks), loaded once per workgroup; transposed = true stores W^T.
 template <int DG>
-struct WFrag {
-    float b[DG / 4][DG / 16];
+struct WLds {
+    static constexpr int WP = DG + 8;
+    float w[DG * WP];
 };
 
-// transposed = false: B = W (tile * W);  true: B = W^T (tile * W^T)
 template <int DG>
-__device__ __forceinline__ void load_wfrag(const float* __restrict__ w, bool transposed, WFrag<DG>& f) {
-    const int lane = lane_id();
-#pragma unroll
-    for (int s = 0; s < DG / 4; ++s)
-#pragma unroll
-        for (int cb = 0; cb < DG / 16; ++cb) {
-            const int kk = 4 * s + (lane >> 4), j = 16 * cb + (lane & 15);
-            f.b[s][cb] = transposed ? w[j * DG + kk] : w[kk * DG + j];
-        }
+__device__ __forceinline__ void load_w_lds(const float* __restrict__ w, bool transposed, WLds<DG>& l) {
+    for (int i = threadIdx.x; i < DG * DG; i += blockDim.x) {
+        const int r = i / DG, cc = i % DG;
+        l.w[r * WLds<DG>::WP + cc] = transposed ? w[cc * DG + r] : w[i];
+    }
+    __syncthreads();
 }
 
+// acc = tile (16 x DG, LDS, row stride DG+1) * B (DG x DG, LDS)
 template <int DG>
-__device__ __forceinline__ void mfma_tile(const float* st, const WFrag<DG>& f, f32x4 (&acc)[DG / 16]) {
+__device__ __forceinline__ void mfma_tile(const float* st, const WLds<DG>& wl, f32x4 (&acc)[DG / 16]) {
     const int lane = lane_id();
 #pragma unroll
     for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -423,8 +464,10 @@ __device__ __forceinline__ void mfma_tile(const float* st, const WFrag<DG>& f, f
     for (int s = 0; s < DG / 4; ++s) {
         const float a = st[(lane & 15) * (DG + 1) + 4 * s + (lane >> 4)];
 #pragma unroll
-        for (int cb = 0; cb < DG / 16; ++cb)
-            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, f.b[s][cb], acc[cb], 0, 0, 0);
+        for (int cb = 0; cb < DG / 16; ++cb) {
+            const float b = wl.w[(4 * s + (lane >> 4)) * WLds<DG>::WP + 16 * cb + (lane & 15)];
+            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[cb], 0, 0, 0);
+        }
     }
 }
 

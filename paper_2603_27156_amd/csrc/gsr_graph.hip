@@ -294,6 +294,8 @@ gsr_status_t gsr_set_option(const char* key, int64_t value) {
     } else if (!strcmp(key, "max_workgroups")) {
         if (value < 0 || value % 8 != 0) return fail(GSR_ERR_INVALID_ARG, "max_workgroups must be a multiple of 8");
         o.max_workgroups = value;
+    } else if (!strcmp(key, "debug_skip")) {
+        o.debug_skip = value;
     } else if (!strcmp(key, "profile")) {
         if (value < 0 || value >= ((int64_t)1 << KC_COUNT)) return fail(GSR_ERR_INVALID_ARG, "profile mask out of range");
         o.profile = value;
@@ -408,7 +410,7 @@ gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const v
     e = hipGetDeviceProperties(&prop, g->device);
     if (e != hipSuccess) { delete g; return fail(GSR_ERR_HIP, "hipGetDeviceProperties: %s", hipGetErrorString(e)); }
     g->num_cus = prop.multiProcessorCount;
-    int grid = options().max_workgroups > 0 ? (int)options().max_workgroups : g->num_cus * 2;
+    int grid = options().max_workgroups > 0 ? (int)options().max_workgroups : g->num_cus * 4;
     g->grid = std::max(8, grid / 8 * 8);
 
     gsr_status_t st = upload_csr(a, n, options().hub_threshold, options().hub_chunk, &g->a);

@@ -48,10 +48,11 @@ __device__ __forceinline__ void emit_records(const float (&yq)[R], const bool (&
         if (norm == GSR_NORM_RMS) {
             const float sq = x[r] * x[r];
             const float ss = sub_sum<DG>(sq);
-            scale = 1.0f / sqrtf(ss / (float)DG + eps);
+            scale = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + eps);
         }
+        const uint64_t wave_mask = ballot(sel[r]);
         if (ok[r] && sel[r]) {
-            const size_t at = (size_t)row[r] * k + popc<DG>(mask[r] & (((M)1 << c) - 1));
+            const size_t at = (size_t)row[r] * k + rank_in_mask<DG>(mask[r], wave_mask, sub);
             out.vals[at] = from_float<T>(x[r] * scale);
             out.idx[at] = (uint8_t)c;
         }
@@ -62,7 +63,7 @@ __device__ __forceinline__ void emit_records(const float (&yq)[R], const bool (&
 // per-wave LDS: tile(s) of 16 x (DG+1) floats, 64 staged edges, 17 row pointers
 template <int DG, int TILES>
 struct WaveLds {
-    float st[TILES][16 * (DG + 1)];
+    float st[TILES][16 * (DG + 1) + 64];   // tile + 64 dump words for contributions that must not count
     EdgeRec ebuf[64];
     int rp[32];
 };
@@ -84,18 +85,19 @@ struct BlockArgs {
     const T* dy;            // dY_i, row stride ldg            (WITH_DW)
     int64_t ldg;
     float* dw_partial;      // [gridDim.x][DG*DG]              (WITH_DW)
+    int dbg;                // timing experiments: parts to leave out (results are then wrong)
 };
 
 template <int DG, typename T, int SIGN, bool WITH_DW>
-__global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
     constexpr int G = 64 / DG, LR = DG + 1, NT = WITH_DW ? 2 : 1, RPW = 16 / G, ER = 4;
     __shared__ WaveLds<DG, NT> lds[4];
     const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
     WaveLds<DG, NT>& L = lds[wave];
     float* st_h = L.st[0];
     float* st_g = L.st[NT - 1];
-    WFrag<DG> wf;
-    load_wfrag<DG>(a.w, false, wf);
+    __shared__ WLds<DG> wl;
+    load_w_lds<DG>(a.w, false, wl);
     f32x4 dw[WITH_DW ? DG / 16 : 1][WITH_DW ? DG / 16 : 1];
     if constexpr (WITH_DW) {
 #pragma unroll
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
         wave_sync();
         const bool has_hub = tile_begin(a.g, r0, a.n, L.rp, lane);
         zero_tile<DG>(st_h, lane);
-        tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
+        if (!(a.dbg & 1)) tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
             range_gather_records<DG, T>(a.g, a.in.vals, a.in.idx, a.k, a.kpl, __builtin_amdgcn_readfirstlane(e_a),
                                         __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st_h, lane);
         });
@@ -118,23 +120,26 @@ __global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
 #pragma unroll
             for (int it = 0; it < RPW; ++it) {
                 const int row = r0 + it * G + sub;
-                gy[it] = row < a.n ? to_float(a.dy[(size_t)row * a.ldg + c]) : 0.f;
+                const float g = to_float(a.dy[(size_t)(row < a.n ? row : a.n - 1) * a.ldg + c]);
+                gy[it] = row < a.n ? g : 0.f;
             }
 #pragma unroll
             for (int it = 0; it < RPW; ++it) st_g[(it * G + sub) * LR + c] = gy[it];
         }
         wave_sync();
-        f32x4 acc[DG / 16];
-        mfma_tile<DG>(st_h, wf, acc);
-        if constexpr (WITH_DW) mfma_outer<DG>(st_h, st_g, dw);
-        wave_sync();
-        store_tile<DG>(st_h, acc);
-        wave_sync();
+        if (!(a.dbg & 2)) {
+            f32x4 acc[DG / 16];
+            mfma_tile<DG>(st_h, wl, acc);
+            if constexpr (WITH_DW) mfma_outer<DG>(st_h, st_g, dw);
+            wave_sync();
+            store_tile<DG>(st_h, acc);
+            wave_sync();
+        }
         float xv[RPW];
 #pragma unroll
         for (int it = 0; it < RPW; ++it) {
             const int row = r0 + it * G + sub;
-            xv[it] = row < a.n ? to_float(a.plane[(size_t)row * a.ld + c]) : 0.f;
+            xv[it] = to_float(a.plane[(size_t)(row < a.n ? row : a.n - 1) * a.ld + c]);
         }
 #pragma unroll
         for (int i0 = 0; i0 < RPW; i0 += ER) {
@@ -148,10 +153,10 @@ __global__ __launch_bounds__(256) void k_block(BlockArgs<DG, T> a) {
                 ok[u] = row[u] < a.n;
                 const float o = st_h[r * LR + c];
                 const T yt = from_float<T>(SIGN > 0 ? xv[i0 + u] + o : xv[i0 + u] - o);
-                if (ok[u]) a.plane[(size_t)row[u] * a.ld + c] = yt;
+                if (ok[u] && !(a.dbg & 8)) a.plane[(size_t)row[u] * a.ld + c] = yt;
                 yq[u] = to_float(yt);
             }
-            if (a.out.mask) emit_records<DG, T, ER>(yq, ok, row, c, sub, a.k, a.norm, a.eps, a.out);
+            if (a.out.mask && !(a.dbg & 4)) emit_records<DG, T, ER>(yq, ok, row, c, sub, a.k, a.norm, a.eps, a.out);
         }
     }
     if constexpr (WITH_DW) {
@@ -205,33 +210,37 @@ struct GradArgs {
     T* dst;                 // dY_{i-1} plane(s): ndst planes, dst_gs apart, row stride ldd
     int64_t ldd, dst_gs;
     int ndst;
+    int dbg;
 };
 
 template <int DG, typename T>
-__global__ __launch_bounds__(256) void k_grad(GradArgs<DG, T> a) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
     constexpr int G = 64 / DG, LR = DG + 1, RPW = 16 / G;
     __shared__ WaveLds<DG, 1> lds[4];
     const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
     WaveLds<DG, 1>& L = lds[wave];
     float* st = L.st[0];
-    WFrag<DG> wf;
-    load_wfrag<DG>(a.w, true, wf);
+    __shared__ WLds<DG> wl;
+    load_w_lds<DG>(a.w, true, wl);
     const TileSweep ts = tile_sweep(a.tiles);
     for (int t = ts.first; t < ts.end; t += ts.step) {
         const int r0 = t * 16;
         wave_sync();
         const bool has_hub = tile_begin(a.gt, r0, a.n, L.rp, lane);
         zero_tile<DG>(st, lane);
-        tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, [&](int e_a, int e_b) {
+        if (!(a.dbg & 1)) tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, [&](int e_a, int e_b) {
             range_gather_dense<DG, T>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
-                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st, lane);
+                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st, lane, a.dbg);
         });
         wave_sync();
-        f32x4 acc[DG / 16];
-        mfma_tile<DG>(st, wf, acc);      // dH = Q W^T
-        wave_sync();
-        store_tile<DG>(st, acc);
-        wave_sync();
+        if (!(a.dbg & 2)) {
+            f32x4 acc[DG / 16];
+            mfma_tile<DG>(st, wl, acc);      // dH = Q W^T
+            wave_sync();
+            store_tile<DG>(st, acc);
+            wave_sync();
+        }
+        if (a.dbg & 8) continue;
         // everything the rows need from memory, issued together
         float zz[RPW];
         bool sel[RPW];
@@ -239,30 +248,47 @@ __global__ __launch_bounds__(256) void k_grad(GradArgs<DG, T> a) {
         for (int it = 0; it < RPW; ++it) {
             const int row = r0 + it * G + sub;
             const bool ok = row < a.n;
-            sel[it] = ok && ((a.own_mask[ok ? row : 0] >> c) & 1);
-            zz[it] = (ok && a.norm == GSR_NORM_RMS) ? to_float(a.z[(size_t)row * a.ldz + c]) : 0.f;
+            const int rowc = ok ? row : a.n - 1;
+            sel[it] = ok && ((a.own_mask[rowc] >> c) & 1);
+            const float zv = a.norm == GSR_NORM_RMS ? to_float(a.z[(size_t)rowc * a.ldz + c]) : 0.f;
+            zz[it] = ok ? zv : 0.f;
         }
+        float dzv[RPW];
+        bool touch[RPW];
 #pragma unroll
         for (int it = 0; it < RPW; ++it) {
             const int r = it * G + sub, row = r0 + r;
             const bool ok = row < a.n;
             const float gdh = st[r * LR + c];
             float dz = sel[it] ? gdh : 0.f;
-            bool touch = sel[it];
-            if (a.norm == GSR_NORM_RMS) {
+            touch[it] = sel[it];
+            if (a.norm == GSR_NORM_RMS && !(a.dbg & 4)) {
+                // V = Z[I] * rinv, rinv = (mean Z^2 + eps)^-1/2:
+                // dZ_c = [c in I] g_c rinv - Z_c (sum_t g_t Z_{I_t}) rinv^3 / DG
                 const float sq = zz[it] * zz[it];
                 const float ss = sub_sum<DG>(sq);
-                const float rr = sqrtf(ss / (float)DG + a.eps);
+                const float rinv = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + a.eps);
                 const float pr = sel[it] ? gdh * zz[it] : 0.f;
                 const float dot = sub_sum<DG>(pr);
-                dz = (sel[it] ? gdh / rr : 0.f) - zz[it] * (dot / ((float)DG * rr * rr * rr));
-                touch = ok;
+                const float coef = dot * (rinv * rinv * rinv) * (1.0f / (float)DG);
+                dz = (sel[it] ? gdh * rinv : 0.f) - zz[it] * coef;
+                touch[it] = ok;
             }
-            if (touch)
-                for (int j = 0; j < a.ndst; ++j) {
-                    T* p = a.dst + (size_t)j * a.dst_gs + (size_t)row * a.ldd + c;
-                    *p = from_float<T>(to_float(*p) + dz);
-                }
+            dzv[it] = dz;
+        }
+        for (int j = 0; j < a.ndst; ++j) {
+            T* plane = a.dst + (size_t)j * a.dst_gs;
+            float old[RPW];
+#pragma unroll
+            for (int it = 0; it < RPW; ++it) {
+                const int row = r0 + it * G + sub;
+                old[it] = to_float(plane[(size_t)(row < a.n ? row : a.n - 1) * a.ldd + c]);
+            }
+#pragma unroll
+            for (int it = 0; it < RPW; ++it) {
+                const int row = r0 + it * G + sub;
+                if (touch[it]) plane[(size_t)row * a.ldd + c] = from_float<T>(old[it] + dzv[it]);
+            }
         }
     }
 }
@@ -440,6 +466,21 @@ struct Ctx {
     float* hub_part() const { return (float*)(ws + lw.hub_partial); }
 };
 
+// Workgroups of 256 threads one CU keeps resident for a kernel, and the persistent grid that
+// fills the chip with them: a multiple of 8 (one share per XCD), never above g->grid, which
+// sizes the per-workgroup partial buffers.
+static int resident_blocks(const void* kernel) {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, 256, 0) != hipSuccess || nb < 1) nb = 1;
+    return nb;
+}
+static unsigned persistent_grid(const gsr_graph_t* g, int per_cu) {
+    int grid = g->num_cus * per_cu / 8 * 8;
+    if (grid > g->grid) grid = g->grid;
+    if (grid < 8) grid = 8;
+    return (unsigned)grid;
+}
+
 template <int DG, typename T>
 static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0, int slot) {
     SumArgs<DG, T> a;
@@ -473,7 +514,7 @@ static void launch_hub_dense(const Ctx<DG, T>& x, const T* plane, int64_t ld) {
 
 // mode 0: forward (+), 1: inverse (-), 2: inverse (-) with dW
 template <int DG, typename T>
-static void launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const float* w, T* plane, int64_t ld, int out_slot,
+static unsigned launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const float* w, T* plane, int64_t ld, int out_slot,
                          const T* dy, int64_t ldg) {
     launch_hub_records<DG, T>(x, in_slot);
     BlockArgs<DG, T> a;
@@ -483,11 +524,24 @@ static void launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const float
     a.hub_part = x.hub_part(); a.w = w; a.plane = plane; a.ld = ld;
     a.out = x.rec(out_slot);
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
-    const dim3 grid((unsigned)x.g->grid), block(256);
+    a.dbg = (int)options().debug_skip;
+    const dim3 block(256);
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
-    if (mode == 0) hipLaunchKernelGGL((k_block<DG, T, +1, false>), grid, block, 0, x.s, a);
-    else if (mode == 1) hipLaunchKernelGGL((k_block<DG, T, -1, false>), grid, block, 0, x.s, a);
-    else hipLaunchKernelGGL((k_block<DG, T, -1, true>), grid, block, 0, x.s, a);
+    unsigned grid;
+    if (mode == 0) {
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false>);
+        grid = persistent_grid(x.g, per_cu);
+        hipLaunchKernelGGL((k_block<DG, T, +1, false>), dim3(grid), block, 0, x.s, a);
+    } else if (mode == 1) {
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false>);
+        grid = persistent_grid(x.g, per_cu);
+        hipLaunchKernelGGL((k_block<DG, T, -1, false>), dim3(grid), block, 0, x.s, a);
+    } else {
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true>);
+        grid = persistent_grid(x.g, per_cu);
+        hipLaunchKernelGGL((k_block<DG, T, -1, true>), dim3(grid), block, 0, x.s, a);
+    }
+    return grid;
 }
 
 template <int DG, typename T>
@@ -499,8 +553,10 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
     a.own_mask = x.rec(mask_slot).mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
+    a.dbg = (int)options().debug_skip;
     ProfScope prof(KC_GRAD, x.s);
-    hipLaunchKernelGGL((k_grad<DG, T>), dim3((unsigned)x.g->grid), dim3(256), 0, x.s, a);
+    static const int per_cu = resident_blocks((const void*)k_grad<DG, T>);
+    hipLaunchKernelGGL((k_grad<DG, T>), dim3(persistent_grid(x.g, per_cu)), dim3(256), 0, x.s, a);
 }
 
 // eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of
@@ -547,11 +603,11 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
             z = x.y0(); ldz = DG;
         }
         const int out_slot = i < C ? i : (C == 2 ? 0 : -1);
-        launch_block<DG, T>(x, 2, i - 1, wi, y.grp(i - 1), y.ld, out_slot, dy.grp(i - 1), dy.ld);
+        const unsigned nparts = launch_block<DG, T>(x, 2, i - 1, wi, y.grp(i - 1), y.ld, out_slot, dy.grp(i - 1), dy.ld);
         {
             ProfScope prof(KC_DW_REDUCE, x.s);
             hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 255) / 256), dim3(256), 0, x.s, (const float*)x.dw_partial(),
-                               x.g->grid, DG * DG, dw_out + (size_t)(i - 1) * DG * DG);
+                               (int)nparts, DG * DG, dw_out + (size_t)(i - 1) * DG * DG);
         }
         if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, i - 1, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1);
         else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, 0, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1);

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void k_group_sparse(const T* __restrict__ x, i
         float scale = 1.f;
         if (norm == GSR_NORM_RMS) {
             const float ss = sub_sum<64>(real ? v * v : 0.f);
-            scale = 1.0f / sqrtf(ss / (float)dg + eps);
+            scale = __builtin_amdgcn_rsqf(ss * (1.0f / (float)dg) + eps);
         }
         if (sel) {
             const int pos = __popcll(mask & (((uint64_t)1 << lane) - 1));
