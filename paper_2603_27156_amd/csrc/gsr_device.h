@@ -138,30 +138,68 @@ __device__ __forceinline__ void topk_select_multi(const float (&x)[R], int k, in
                                                   typename MaskOf<DG>::type (&mask_out)[R]) {
     using M = typename MaskOf<DG>::type;
     uint32_t key[R], thr[R];
-    bool done[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         uint32_t u = __float_as_uint(x[r]);
         if (u == 0x80000000u) u = 0u;
         key[r] = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
         thr[r] = 0u;
-        done[r] = (k >= DG);
     }
-    for (int bit = 31; bit >= 0; --bit) {
-        bool all = true;
-#pragma unroll
-        for (int r = 0; r < R; ++r) all = all && done[r];
-        if constexpr (DG == 64) {
-            if (all) break;
-        } else {
-            if (ballot(!all) == 0ull) break;
-        }
+    if constexpr (DG == 64) {
+        // Interval bisection with a data-driven start.  Invariant per row: at least k keys are
+        // >= lo and fewer than k are >= hi.  hi starts just above the row maximum; lo starts 4
+        // binades below it (16x in value), which holds the k-th largest of almost every row, and
+        // falls back to 0 when a count says it does not.  A row is closed as soon as a candidate
+        // splits off exactly k keys.
+        uint32_t lo[R], hi[R];
+        uint32_t open = 0u;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const uint32_t cand = thr[r] | (1u << bit);
-            const int cnt = popc<DG>(sub_bits<DG>(ballot(key[r] >= cand), sub));
-            thr[r] = cnt >= k ? cand : thr[r];
-            done[r] = done[r] || (cnt == k);
+            uint32_t m = key[r];
+            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0xB1, 0xF, 0xF, true));
+            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x4E, 0xF, 0xF, true));
+            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x141, 0xF, 0xF, true));
+            m = max(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x140, 0xF, 0xF, true));
+            const uint32_t m01 = max((uint32_t)__builtin_amdgcn_readlane((int)m, 0), (uint32_t)__builtin_amdgcn_readlane((int)m, 16));
+            const uint32_t m23 = max((uint32_t)__builtin_amdgcn_readlane((int)m, 32), (uint32_t)__builtin_amdgcn_readlane((int)m, 48));
+            const uint32_t top = max(m01, m23);
+            const uint32_t guess = top > (4u << 23) ? top - (4u << 23) : 0u;
+            const int cnt = __popcll(ballot(key[r] >= guess));
+            lo[r] = cnt >= k ? guess : 0u;
+            hi[r] = top + 1u;
+            if (cnt != k && k < DG) open |= 1u << r;
+            if (k >= DG) lo[r] = 0u;
+        }
+        // 33 halvings bring any 32-bit interval down to one value (rows with a tie at the k-th
+        // position never see an exact count and run the full course)
+        for (int round = 0; round < 33 && open != 0u; ++round) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint32_t mid = lo[r] + ((hi[r] - lo[r]) >> 1);
+                const int cnt = __popcll(ballot(key[r] >= mid));
+                lo[r] = cnt >= k ? mid : lo[r];
+                hi[r] = cnt >= k ? hi[r] : mid;
+                open = cnt == k ? open & ~(1u << r) : open;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) thr[r] = lo[r];
+    } else {
+        bool done[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) done[r] = (k >= DG);
+        for (int bit = 31; bit >= 0; --bit) {
+            bool all = true;
+#pragma unroll
+            for (int r = 0; r < R; ++r) all = all && done[r];
+            if (ballot(!all) == 0ull) break;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint32_t cand = thr[r] | (1u << bit);
+                const int cnt = popc<DG>(sub_bits<DG>(ballot(key[r] >= cand), sub));
+                thr[r] = cnt >= k ? cand : thr[r];
+                done[r] = done[r] || (cnt == k);
+            }
         }
     }
 #pragma unroll
@@ -233,7 +271,7 @@ __device__ __forceinline__ float gather_records(const CsrView& g, const T* __res
     using M = typename MaskOf<DG>::type;
     const M below = ((M)1 << c) - 1;
     float acc = 0.f;
-    constexpr int U = 4;
+    constexpr int U = 8;
     for (int e = e0; ballot(e < e1) != 0ull; e += U * stride) {
         int j[U]; float a[U]; M m[U]; float v[U];
 #pragma unroll
@@ -260,7 +298,7 @@ template <int DG, typename T>
 __device__ __forceinline__ float gather_dense(const CsrView& g, const T* __restrict__ x, int64_t ld,
                                               int e0, int e1, int c, int stride = 1) {
     float acc = 0.f;
-    constexpr int U = 4;
+    constexpr int U = 8;
     for (int e = e0; ballot(e < e1) != 0ull; e += U * stride) {
         int j[U]; float a[U]; float v[U];
 #pragma unroll

@@ -30,7 +30,7 @@ gsr_status_t fail(gsr_status_t st, const char* fmt, ...);
 // ---- tunables (gsr_set_option) ----------------------------------------------------------
 struct Options {
     int64_t hub_threshold = 512;  // rows longer than this are reduced in two passes
-    int64_t hub_chunk = 256;      // neighbours per first-pass partial
+    int64_t hub_chunk = 64;       // neighbours per first-pass partial
     int64_t max_workgroups = 0;   // 0: derive from the device (multiple of 8)
     int64_t profile = 0;          // bit i set: time kernel class i with HIP events
     int64_t debug_skip = 0;       // timing experiments only: bit 0 gather, 1 matrix products, 2 GS/emit, 3 epilogue memory

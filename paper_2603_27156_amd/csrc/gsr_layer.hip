@@ -183,13 +183,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
     }
 }
 
-// dW_i[e] = sum over workgroup partials, ascending
-__global__ void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems, float* __restrict__ out) {
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= elems) return;
+// dW_i[e] = sum over workgroup partials.  A block owns 64 entries; its 16 thread rows each sum a
+// contiguous sixteenth of the partials in ascending order, then the 16 sums are added in order.
+__global__ __launch_bounds__(1024) void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems,
+                                                    float* __restrict__ out) {
+    __shared__ float red[16][64];
+    const int e = blockIdx.x * 64 + (threadIdx.x & 63), seg = threadIdx.x >> 6;
+    const int per = (nparts + 15) / 16, p0 = seg * per, p1 = min(nparts, p0 + per);
     float acc = 0.f;
-    for (int p = 0; p < nparts; ++p) acc += partial[(size_t)p * elems + e];
-    out[e] = acc;
+    if (e < elems)
+        for (int p = p0; p < p1; ++p) acc += partial[(size_t)p * elems + e];
+    red[seg][threadIdx.x & 63] = acc;
+    __syncthreads();
+    if (seg == 0 && e < elems) {
+        float s = red[0][threadIdx.x];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) s += red[q][threadIdx.x];
+        out[e] = s;
+    }
 }
 
 // ---- block: data gradient ---------------------------------------------------------------------------
@@ -606,7 +617,7 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         const unsigned nparts = launch_block<DG, T>(x, 2, i - 1, wi, y.grp(i - 1), y.ld, out_slot, dy.grp(i - 1), dy.ld);
         {
             ProfScope prof(KC_DW_REDUCE, x.s);
-            hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 255) / 256), dim3(256), 0, x.s, (const float*)x.dw_partial(),
+            hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 63) / 64), dim3(1024), 0, x.s, (const float*)x.dw_partial(),
                                (int)nparts, DG * DG, dw_out + (size_t)(i - 1) * DG * DG);
         }
         if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, i - 1, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1);

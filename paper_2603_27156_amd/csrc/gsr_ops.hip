@@ -28,8 +28,12 @@ __global__ __launch_bounds__(256) void k_group_sparse(const T* __restrict__ x, i
     for (int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; row < n; row += nwaves) {
         const bool real = lane < dg;
         const float v = real ? to_float(x[row * ld + lane]) : -__builtin_huge_valf();
-        uint64_t mask;
-        const bool sel = topk_select<64>(v, k, lane, 0, &mask);
+        const float xs[1] = {v};
+        bool sels[1];
+        uint64_t masks[1];
+        topk_select_multi<64, 1>(xs, k, lane, 0, sels, masks);
+        const bool sel = sels[0];
+        const uint64_t mask = masks[0];
         float scale = 1.f;
         if (norm == GSR_NORM_RMS) {
             const float ss = sub_sum<64>(real ? v * v : 0.f);

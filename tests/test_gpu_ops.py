@@ -127,7 +127,7 @@ def test_spmm_dense_and_transpose():
 @pytest.mark.parametrize("dg,k,hub_threshold", [(64, 16, 512), (32, 8, 512), (64, 16, 6), (32, 8, 5)])
 def test_spmm_compressed(dg, k, hub_threshold):
     gsr.gsr_set_option("hub_threshold", hub_threshold)
-    gsr.gsr_set_option("hub_chunk", 4 if hub_threshold < 100 else 256)
+    gsr.gsr_set_option("hub_chunk", 4 if hub_threshold < 100 else 64)
     try:
         w = synth.scaled(synth.workload(2), 6001)
         rng = np.random.Generator(np.random.PCG64(1))
@@ -150,7 +150,7 @@ def test_spmm_compressed(dg, k, hub_threshold):
             gsr.gsr_spmm_compressed(gg, torch.from_numpy(Vp).to(dev()), torch.from_numpy(bad).to(dev()), dg)
     finally:
         gsr.gsr_set_option("hub_threshold", 512)
-        gsr.gsr_set_option("hub_chunk", 256)
+        gsr.gsr_set_option("hub_chunk", 64)
 
 
 def test_forward_block_example_of_the_paper():
