@@ -49,7 +49,6 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override L")
     ap.add_argument("--max-workgroups", type=int, default=0, help="override the persistent grid (multiple of 8)")
-    ap.add_argument("--debug-skip", type=int, default=0, help="timing experiments: leave kernel parts out (wrong results)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events in the timed region")
     args = ap.parse_args()
@@ -76,8 +75,6 @@ def main() -> int:
         w = synth.workload(idx, l=args.layers, dtype=w.dtype, name=w.name)
     if args.max_workgroups:
         gsr.gsr_set_option("max_workgroups", args.max_workgroups)
-    if args.debug_skip:
-        gsr.gsr_set_option("debug_skip", args.debug_skip)
     t_gen = time.time()
     inp = synth.make_inputs(w, 0)
     g = gsr.gsr_graph_create(inp.rowptr, inp.colidx)

@@ -361,42 +361,86 @@ __device__ __forceinline__ int stage_edges(const CsrView& g, int eb, int e_b, co
     return e_b - eb < 64 ? e_b - eb : 64;
 }
 
-// H[r][col] += a_ij * V[j][t] for every edge in [e_a, e_b) and every recorded slot t of j.
-// Lane = (edge of a group, slot): 64 / KP edges per load instruction, KP = k rounded up to a power
-// of two; the record of j is k values plus their k column bytes.  The LDS read-add-writes of one
-// group are issued edge by edge (LDS float atomics are far slower than a read and a write), so no
-// instruction carries two contributions to the same word and the order of additions is fixed.
+// One staged edge of a record gather: where neighbour j's k values start, a_ij, and j's column mask.
+struct RecEdge {
+    uint32_t off0;   // j * k
+    float a;
+    uint32_t mlo, mhi;
+};
+
+// H[r][c] += a_ij * V[j][slot of c] for every edge in [e_a, e_b): lane c of a (sub-)wave owns
+// column c.  The record of j is its k kept values in ascending column order plus a DG-bit column
+// mask, so lane c finds its value at popcount(mask below c) if bit c is set.  All 64 lanes load
+// from inside the 4k-byte record (lanes whose column is absent read a neighbouring slot and
+// contribute 0), so the loads of a batch of edges are unconditional and in flight together.  The
+// edges of one row are summed in a register; the sum goes to the LDS tile when the row changes.
+// With two rows per wave (DG = 32) the half-waves take alternate edges and flush one after the
+// other.  n * k must stay below 2^32.
 template <int DG, typename T>
 __device__ __forceinline__ void range_gather_records(const CsrView& g, const T* __restrict__ vals,
-                                                     const uint8_t* __restrict__ idx, int k, int kpl, int e_a, int e_b,
-                                                     const int* s_rp, EdgeRec* ebuf, float* st_h, int lane) {
-    constexpr int LR = DG + 1, GB = 8;
-    const int epg = 64 >> kpl, q = lane >> kpl, t = lane & ((1 << kpl) - 1);
+                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
+                                                     int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, float* st_h,
+                                                     int lane) {
+    using M = typename MaskOf<DG>::type;
+    constexpr int LR = DG + 1, G = 64 / DG, GB = 16;
+    const int c = lane % DG, sub = lane / DG;
+    const uint32_t bit_lo = c < 32 ? 1u << c : 0u, bit_hi = c >= 32 ? 1u << (c - 32) : 0u;
+    const uint32_t below_lo = c < 32 ? bit_lo - 1u : 0xFFFFFFFFu, below_hi = c >= 32 ? bit_hi - 1u : 0u;
+    float acc = 0.f;
+    int cur = 16;                      // row being summed; 16 = the dump row
+    auto flush = [&](int next) {
+#pragma unroll
+        for (int s2 = 0; s2 < G; ++s2)
+            if (s2 == sub && next != cur) st_h[cur * LR + c] += acc;
+        if (next != cur) { acc = 0.f; cur = next; }
+    };
     for (int eb = e_a; eb < e_b; eb += 64) {
-        const int cnt = stage_edges(g, eb, e_b, s_rp, ebuf, lane);
-        const int ngroups = (cnt + epg - 1) >> (6 - kpl);
-        for (int g0 = 0; g0 < ngroups; g0 += GB) {
+        // stage up to 64 edges: lane l takes edge eb + l
+        const int e = eb + lane;
+        const bool eok = e < e_b;
+        const int j = eok ? g.ci[e] : 0;
+        RecEdge me;
+        me.a = eok ? g.av[e] : 0.f;
+        me.off0 = (uint32_t)j * (uint32_t)k;
+        const M m = masks[j];
+        me.mlo = (uint32_t)m;
+        if constexpr (DG == 64) me.mhi = (uint32_t)(m >> 32);
+        else me.mhi = 0u;
+        int r = 0;
+#pragma unroll
+        for (int step = 8; step >= 1; step >>= 1)
+            if (s_rp[r + step] <= e) r += step;
+        wave_sync();          // readers of the previous chunk are done
+        ebuf[lane] = me;
+        rbuf[lane] = (uint8_t)r;
+        wave_sync();
+        const int cnt = e_b - eb < 64 ? e_b - eb : 64;
+        const int nit = (cnt + G - 1) / G;
+        for (int i0 = 0; i0 < nit; i0 += GB) {
             float v[GB];
-            int dst[GB];
+            int rr[GB];
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
-                // loads are unconditional (index clamped to a staged edge); what must not count adds 0
-                // into the dump words behind the tile
-                const int ei = (g0 + u) * epg + q;
-                const bool ok = ei < cnt && t < k;
-                const EdgeRec er = ebuf[ei < cnt ? ei : cnt - 1];
-                const size_t off = (size_t)er.j * k + (t < k ? t : 0);
-                const float val = to_float(vals[off]);
-                const int col = (int)idx[off];
-                v[u] = ok ? er.a * val : 0.f;
-                dst[u] = ok ? er.r * LR + col : 16 * LR + lane;
+                const int ei = (i0 + u) * G + sub;
+                const bool ok = ei < cnt;
+                const int eu = ok ? ei : cnt - 1;
+                const RecEdge er = ebuf[eu];
+                const bool hit = ((er.mlo & bit_lo) | (er.mhi & bit_hi)) != 0u;
+                int pos = __popc(er.mlo & below_lo) + __popc(er.mhi & below_hi);
+                pos = pos < k ? pos : k - 1;
+                const float val = to_float(vals[er.off0 + (uint32_t)pos]);
+                v[u] = (ok && hit) ? er.a * val : 0.f;
+                const int rrow = (int)rbuf[eu];
+                rr[u] = ok ? rrow : -1;
             }
 #pragma unroll
-            for (int u = 0; u < GB; ++u)
-                for (int qq = 0; qq < epg; ++qq)
-                    if (qq == q) st_h[dst[u]] += v[u];
+            for (int u = 0; u < GB; ++u) {
+                flush(rr[u] >= 0 ? rr[u] : cur);
+                acc += v[u];
+            }
         }
     }
+    flush(16);
 }
 
 // Q[r][c] += a_ij * X[j][c] for every edge in [e_a, e_b): lane c of a (sub-)wave owns column c and
@@ -405,7 +449,7 @@ __device__ __forceinline__ void range_gather_records(const CsrView& g, const T* 
 // other, so two partial sums of the same row never meet in one instruction.
 template <int DG, typename T>
 __device__ __forceinline__ void range_gather_dense(const CsrView& g, const T* __restrict__ x, int64_t ld, int e_a, int e_b,
-                                                   const int* s_rp, EdgeRec* ebuf, float* st, int lane, int dbg = 0) {
+                                                   const int* s_rp, EdgeRec* ebuf, float* st, int lane) {
     constexpr int LR = DG + 1, G = 64 / DG, GB = 16;
     const int c = lane % DG, sub = lane / DG;
     float acc = 0.f;

@@ -223,8 +223,6 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     for (int s = 0; s < cfg->c && s < 8; ++s) {
         w.rec_vals[s] = off;
         off += align_up(n * (size_t)cfg->k * b);
-        w.rec_idx[s] = off;
-        off += align_up(n * (size_t)cfg->k);
         w.rec_mask[s] = off;
         off += align_up(n * (dg == 32 ? 4 : 8));
     }
@@ -268,6 +266,8 @@ gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool
     if (cfg->norm != GSR_NORM_NONE && cfg->norm != GSR_NORM_RMS) return fail(GSR_ERR_UNSUPPORTED, "norm %d", cfg->norm);
     if (cfg->layout != GSR_LAYOUT_ROW_MAJOR && cfg->layout != GSR_LAYOUT_GROUP_PLANAR)
         return fail(GSR_ERR_UNSUPPORTED, "layout %d", cfg->layout);
+    if ((uint64_t)cfg->n * (uint64_t)cfg->k >= ((uint64_t)1 << 32))
+        return fail(GSR_ERR_UNSUPPORTED, "n * k = %llu does not fit 32-bit record offsets", (unsigned long long)cfg->n * cfg->k);
     if (need_l && cfg->l < 1) return fail(GSR_ERR_INVALID_ARG, "layers L=%d", cfg->l);
     if (!(cfg->eps >= 0.f)) return fail(GSR_ERR_INVALID_ARG, "eps must be >= 0");
     return GSR_OK;
@@ -294,8 +294,6 @@ gsr_status_t gsr_set_option(const char* key, int64_t value) {
     } else if (!strcmp(key, "max_workgroups")) {
         if (value < 0 || value % 8 != 0) return fail(GSR_ERR_INVALID_ARG, "max_workgroups must be a multiple of 8");
         o.max_workgroups = value;
-    } else if (!strcmp(key, "debug_skip")) {
-        o.debug_skip = value;
     } else if (!strcmp(key, "profile")) {
         if (value < 0 || value >= ((int64_t)1 << KC_COUNT)) return fail(GSR_ERR_INVALID_ARG, "profile mask out of range");
         o.profile = value;

@@ -33,7 +33,6 @@ struct Options {
     int64_t hub_chunk = 64;       // neighbours per first-pass partial
     int64_t max_workgroups = 0;   // 0: derive from the device (multiple of 8)
     int64_t profile = 0;          // bit i set: time kernel class i with HIP events
-    int64_t debug_skip = 0;       // timing experiments only: bit 0 gather, 1 matrix products, 2 GS/emit, 3 epilogue memory
 };
 Options& options();
 
@@ -102,7 +101,6 @@ gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool
 // Workspace carving shared by gsr_workspace_size and the layer / step calls.
 struct LayerWs {
     size_t rec_vals[8];  // per slot: compressed values  [n][k] of T
-    size_t rec_idx[8];   // per slot: column of each value [n][k] of uint8
     size_t rec_mask[8];  // per slot: column bit mask    [n] of uint32 (dg=32) / uint64 (dg=64)
     size_t y0;           // Y_0 plane [n][dg] of T (C > 2)
     size_t dw_partial;   // [grid][dg*dg] float

@@ -22,12 +22,11 @@ namespace gsr {
 CsrView make_view(const gsr_graph_t* g, bool transpose);
 
 // Compressed record of a row ("CBSR" of Section 4.3): the k kept values in ascending column
-// order (already RMS-scaled), their k column bytes, and the row's column bit mask.
+// order (already RMS-scaled) and the row's column bit mask.
 template <int DG, typename T>
 struct Record {
     using M = typename MaskOf<DG>::type;
     T* vals;        // [n][k]
-    uint8_t* idx;   // [n][k]
     M* mask;        // [n]
 };
 
@@ -54,7 +53,6 @@ __device__ __forceinline__ void emit_records(const float (&yq)[R], const bool (&
         if (ok[r] && sel[r]) {
             const size_t at = (size_t)row[r] * k + rank_in_mask<DG>(mask[r], wave_mask, sub);
             out.vals[at] = from_float<T>(x[r] * scale);
-            out.idx[at] = (uint8_t)c;
         }
         if (ok[r] && c == 0) out.mask[row[r]] = mask[r];
     }
@@ -64,8 +62,9 @@ __device__ __forceinline__ void emit_records(const float (&yq)[R], const bool (&
 template <int DG, int TILES>
 struct WaveLds {
     float st[TILES][16 * (DG + 1) + 64];   // tile + 64 dump words for contributions that must not count
-    EdgeRec ebuf[64];
-    int rp[32];
+    EdgeRec ebuf[64];                      // 64 staged edges (RecEdge has the same size)
+    int rp[20];                            // row pointers of the tile's 17 row boundaries
+    uint8_t rbuf[64];                      // tile row of every staged edge
 };
 
 // ---- block: forward / inverse (+ weight gradient) ------------------------------------------------
@@ -74,7 +73,7 @@ struct BlockArgs {
     CsrView g;
     int n, tiles;
     Record<DG, T> in;       // record of Y_{i-1}
-    int k, kpl;             // kpl = log2 of k rounded up to a power of two
+    int k;
     const float* hub_part;  // first-pass partial rows of split rows
     const float* w;         // W_i [DG][DG]
     T* plane;               // X_i on entry / Y_i on return (or the reverse), row stride ld
@@ -85,7 +84,6 @@ struct BlockArgs {
     const T* dy;            // dY_i, row stride ldg            (WITH_DW)
     int64_t ldg;
     float* dw_partial;      // [gridDim.x][DG*DG]              (WITH_DW)
-    int dbg;                // timing experiments: parts to leave out (results are then wrong)
 };
 
 template <int DG, typename T, int SIGN, bool WITH_DW>
@@ -111,9 +109,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         wave_sync();
         const bool has_hub = tile_begin(a.g, r0, a.n, L.rp, lane);
         zero_tile<DG>(st_h, lane);
-        if (!(a.dbg & 1)) tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
-            range_gather_records<DG, T>(a.g, a.in.vals, a.in.idx, a.k, a.kpl, __builtin_amdgcn_readfirstlane(e_a),
-                                        __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st_h, lane);
+        tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
+            range_gather_records<DG, T>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
+                                        __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
+                                        st_h, lane);
         });
         if constexpr (WITH_DW) {
             float gy[RPW];
@@ -127,7 +126,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
             for (int it = 0; it < RPW; ++it) st_g[(it * G + sub) * LR + c] = gy[it];
         }
         wave_sync();
-        if (!(a.dbg & 2)) {
+        {
             f32x4 acc[DG / 16];
             mfma_tile<DG>(st_h, wl, acc);
             if constexpr (WITH_DW) mfma_outer<DG>(st_h, st_g, dw);
@@ -153,10 +152,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
                 ok[u] = row[u] < a.n;
                 const float o = st_h[r * LR + c];
                 const T yt = from_float<T>(SIGN > 0 ? xv[i0 + u] + o : xv[i0 + u] - o);
-                if (ok[u] && !(a.dbg & 8)) a.plane[(size_t)row[u] * a.ld + c] = yt;
+                if (ok[u]) a.plane[(size_t)row[u] * a.ld + c] = yt;
                 yq[u] = to_float(yt);
             }
-            if (a.out.mask && !(a.dbg & 4)) emit_records<DG, T, ER>(yq, ok, row, c, sub, a.k, a.norm, a.eps, a.out);
+            if (a.out.mask) emit_records<DG, T, ER>(yq, ok, row, c, sub, a.k, a.norm, a.eps, a.out);
         }
     }
     if constexpr (WITH_DW) {
@@ -221,7 +220,6 @@ struct GradArgs {
     T* dst;                 // dY_{i-1} plane(s): ndst planes, dst_gs apart, row stride ldd
     int64_t ldd, dst_gs;
     int ndst;
-    int dbg;
 };
 
 template <int DG, typename T>
@@ -239,19 +237,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
         wave_sync();
         const bool has_hub = tile_begin(a.gt, r0, a.n, L.rp, lane);
         zero_tile<DG>(st, lane);
-        if (!(a.dbg & 1)) tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, [&](int e_a, int e_b) {
+        tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, [&](int e_a, int e_b) {
             range_gather_dense<DG, T>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
-                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st, lane, a.dbg);
+                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st, lane);
         });
         wave_sync();
-        if (!(a.dbg & 2)) {
+        {
             f32x4 acc[DG / 16];
             mfma_tile<DG>(st, wl, acc);      // dH = Q W^T
             wave_sync();
             store_tile<DG>(st, acc);
             wave_sync();
         }
-        if (a.dbg & 8) continue;
         // everything the rows need from memory, issued together
         float zz[RPW];
         bool sel[RPW];
@@ -273,7 +270,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
             const float gdh = st[r * LR + c];
             float dz = sel[it] ? gdh : 0.f;
             touch[it] = sel[it];
-            if (a.norm == GSR_NORM_RMS && !(a.dbg & 4)) {
+            if (a.norm == GSR_NORM_RMS) {
                 // V = Z[I] * rinv, rinv = (mean Z^2 + eps)^-1/2:
                 // dZ_c = [c in I] g_c rinv - Z_c (sum_t g_t Z_{I_t}) rinv^3 / DG
                 const float sq = zz[it] * zz[it];
@@ -461,9 +458,8 @@ struct Ctx {
     int tiles;
     Record<DG, T> rec(int slot) const {
         Record<DG, T> r;
-        if (slot < 0) { r.vals = nullptr; r.idx = nullptr; r.mask = nullptr; return r; }
+        if (slot < 0) { r.vals = nullptr; r.mask = nullptr; return r; }
         r.vals = (T*)(ws + lw.rec_vals[slot]);
-        r.idx = (uint8_t*)(ws + lw.rec_idx[slot]);
         r.mask = (M*)(ws + lw.rec_mask[slot]);
         return r;
     }
@@ -531,11 +527,10 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const f
     BlockArgs<DG, T> a;
     a.g = make_view(x.g, false);
     a.n = (int)x.cfg->n; a.tiles = x.tiles;
-    a.in = x.rec(in_slot); a.k = x.cfg->k; a.kpl = x.kpl();
+    a.in = x.rec(in_slot); a.k = x.cfg->k;
     a.hub_part = x.hub_part(); a.w = w; a.plane = plane; a.ld = ld;
     a.out = x.rec(out_slot);
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
-    a.dbg = (int)options().debug_skip;
     const dim3 block(256);
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
     unsigned grid;
@@ -564,7 +559,6 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
     a.own_mask = x.rec(mask_slot).mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
-    a.dbg = (int)options().debug_skip;
     ProfScope prof(KC_GRAD, x.s);
     static const int per_cu = resident_blocks((const void*)k_grad<DG, T>);
     hipLaunchKernelGGL((k_grad<DG, T>), dim3(persistent_grid(x.g, per_cu)), dim3(256), 0, x.s, a);
