@@ -8,6 +8,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace gsr {
 
@@ -97,6 +98,41 @@ __device__ __forceinline__ float sub_sum(float v) {
     const float lo = read_lane(v, 0) + read_lane(v, 16), hi = read_lane(v, 32) + read_lane(v, 48);
     if constexpr (DG == 64) return lo + hi;
     else return (threadIdx.x & 32) ? hi : lo;
+}
+
+// ---- "quarter layout": lane = (row r = lane % 16, quarter q = lane / 16) ------------------------
+// The four lanes r, r+16, r+32, r+48 share a row of a 16-row tile, each holding a quarter of its
+// columns.  v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even
+// rows of its second, v_permlane32_swap the upper half of the first with the lower half of the
+// second; fed the same register twice they hand every lane its partner quarters.
+
+// q[i] = v of the lane of quarter i in this lane's row
+__device__ __forceinline__ void quarter_all(uint32_t v, uint32_t (&q)[4]) {
+    const auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);        // quarters {0|2}, {1|3} of my half
+    const auto b = __builtin_amdgcn_permlane32_swap(a[0], a[0], false, false);  // quarter 0, quarter 2
+    const auto d = __builtin_amdgcn_permlane32_swap(a[1], a[1], false, false);  // quarter 1, quarter 3
+    q[0] = b[0]; q[1] = d[0]; q[2] = b[1]; q[3] = d[1];
+}
+__device__ __forceinline__ uint32_t quarter_sum(uint32_t v) {
+    const auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    const uint32_t s = a[0] + a[1];
+    const auto b = __builtin_amdgcn_permlane32_swap(s, s, false, false);
+    return b[0] + b[1];
+}
+__device__ __forceinline__ uint32_t quarter_max(uint32_t v) {
+    const auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    const uint32_t s = max(a[0], a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(s, s, false, false);
+    return max(b[0], b[1]);
+}
+// (q0 + q1) + (q2 + q3), the same value in the four lanes
+__device__ __forceinline__ float quarter_sum(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const float s = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const uint32_t su = __float_as_uint(s);
+    const auto b = __builtin_amdgcn_permlane32_swap(su, su, false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
 // ---- GS: exact top-k of a row ----------------------------------------------------------------
@@ -315,12 +351,42 @@ __device__ __forceinline__ float gather_dense(const CsrView& g, const T* __restr
     return acc;
 }
 
-// ---- tile-staged gathers ----------------------------------------------------------------------------
+// ---- tile gathers on the matrix cores ------------------------------------------------------------------
 // A wave owns 16 consecutive rows.  Their neighbour lists are one contiguous edge range, so the
 // dependent chain row pointer -> column index -> neighbour data is walked once per tile, 64 edges
-// per step, instead of once per row: lane l loads edge l of the chunk, finds the row it belongs
-// to, and parks (column, value, row) in LDS.  The neighbour data of many edges is then in flight
-// at once, and every contribution is added into the LDS tile H[row][col] in edge order.
+// per step: lane l loads edge l, finds the tile row it belongs to, and parks (neighbour, a_ij, row)
+// in LDS.  The aggregation itself is the product  H = P * X  of the tile's 16 x E selection
+// matrix (P[r][e] = a_e if edge e belongs to row r, else 0) with the E x DG matrix of neighbour
+// rows, taken four edges at a time by v_mfma_f32_16x16x4_f32:
+//   A operand  lane (i = lane % 16, kk = lane / 16):  P[i][edge kk of the four]
+//   B operand  lane (j = lane % 16, kk = lane / 16):  X[neighbour of edge kk][column of (j, cb)]
+// One MFMA covers 16 columns; the DG / 16 column blocks cb are interleaved, column = CPL * j + cb
+// with CPL = DG / 16, so that a lane's CPL columns are adjacent in memory and arrive in one load
+// of CPL values.  One load instruction thus fetches the rows of four edges, nothing is predicated
+// (edges past the end are staged with a_ij = 0 and neighbour 0) and the sum over a row's edges is
+// taken in edge order inside the accumulators, which hold H as D[4 * (lane / 16) + reg][j].
+using f32x4 = __attribute__((__vector_size__(4 * sizeof(float)))) float;
+typedef uint32_t u32x2a __attribute__((ext_vector_type(2), aligned(4)));
+typedef uint32_t u32x3a __attribute__((ext_vector_type(3), aligned(4)));
+typedef uint32_t u32x4a __attribute__((ext_vector_type(4), aligned(4)));
+
+template <int NW>
+__device__ __forceinline__ void load_words(const void* p, uint32_t (&w)[NW]) {
+    if constexpr (NW == 1) {
+        w[0] = *reinterpret_cast<const uint32_t*>(p);
+    } else if constexpr (NW == 2) {
+        const u32x2a v = *reinterpret_cast<const u32x2a*>(p);
+        w[0] = v[0]; w[1] = v[1];
+    } else if constexpr (NW == 3) {
+        const u32x3a v = *reinterpret_cast<const u32x3a*>(p);
+        w[0] = v[0]; w[1] = v[1]; w[2] = v[2];
+    } else {
+        static_assert(NW == 4, "1 to 4 words");
+        const u32x4a v = *reinterpret_cast<const u32x4a*>(p);
+        w[0] = v[0]; w[1] = v[1]; w[2] = v[2]; w[3] = v[3];
+    }
+}
+
 struct EdgeRec {
     int j;      // neighbour (column of A)
     float a;    // a_ij
@@ -342,23 +408,66 @@ __device__ __forceinline__ bool tile_begin(const CsrView& g, int r0, int n, int*
     return ballot(hub) != 0ull;
 }
 
-// stage up to 64 edges [eb, min(eb+64, e_b)) into ebuf; returns how many
-__device__ __forceinline__ int stage_edges(const CsrView& g, int eb, int e_b, const int* s_rp, EdgeRec* ebuf, int lane) {
-    const int e = eb + lane;
-    const bool ok = e < e_b;
-    EdgeRec me;
-    me.j = ok ? g.ci[e] : 0;
-    me.a = ok ? g.av[e] : 0.f;
+// tile row of edge e: the last row boundary at or below e
+__device__ __forceinline__ int tile_row_of(const int* s_rp, int e) {
     int r = 0;
 #pragma unroll
     for (int step = 8; step >= 1; step >>= 1)
         if (s_rp[r + step] <= e) r += step;
-    me.r = r;
-    me.pad = 0;
-    wave_sync();          // readers of the previous chunk are done
-    ebuf[lane] = me;
-    wave_sync();
-    return e_b - eb < 64 ? e_b - eb : 64;
+    return r;
+}
+
+// Runs `batch(GB, i0)` over the nit groups of four staged edges, eight groups at a time while
+// they last, then four at a time (a batch may overrun nit by up to three groups, which stay
+// inside the 64 staged edges and contribute zero).
+template <typename Batch>
+__device__ __forceinline__ void edge_batches(int nit, Batch batch) {
+    int i0 = 0;
+    for (; i0 + 8 <= nit; i0 += 8) batch(std::integral_constant<int, 8>{}, i0);
+    for (; i0 < nit; i0 += 4) batch(std::integral_constant<int, 4>{}, i0);
+}
+
+// acc += P * X over the edges [e_a, e_b) of ordinary rows; X is a dense plane, row stride ld.
+template <int DG, typename T>
+__device__ __forceinline__ void gather_dense_mfma(const CsrView& g, const T* __restrict__ x, int64_t ld, int e_a, int e_b,
+                                                  const int* s_rp, EdgeRec* ebuf, int lane, f32x4 (&acc)[DG / 16]) {
+    constexpr int CPL = DG / 16, NW = CPL * (int)sizeof(T) / 4;
+    const int i16 = lane & 15, kk = lane >> 4;
+    const T* xl = x + CPL * i16;
+    const uint32_t ldu = (uint32_t)ld;
+    for (int eb = e_a; eb < e_b; eb += 64) {
+        const int e = eb + lane;
+        const bool ok = e < e_b;
+        EdgeRec me;
+        me.j = ok ? g.ci[e] : 0;
+        me.a = ok ? g.av[e] : 0.f;
+        me.r = tile_row_of(s_rp, e);
+        me.pad = 0;
+        wave_sync();          // readers of the previous chunk are done
+        ebuf[lane] = me;
+        wave_sync();
+        const int cnt = e_b - eb < 64 ? e_b - eb : 64;
+        edge_batches((cnt + 3) >> 2, [&](auto gbc, int i0) {
+            constexpr int GB = decltype(gbc)::value;
+            uint32_t w[GB][NW];
+            float p[GB];
+#pragma unroll
+            for (int u = 0; u < GB; ++u) {
+                const EdgeRec er = ebuf[4 * (i0 + u) + kk];
+                load_words<NW>(xl + (size_t)(uint32_t)er.j * ldu, w[u]);
+                p[u] = er.r == i16 ? er.a : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < GB; ++u)
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) {
+                    float b;
+                    if constexpr (sizeof(T) == 4) b = __uint_as_float(w[u][cb]);
+                    else b = __uint_as_float((cb & 1) ? (w[u][cb >> 1] & 0xFFFF0000u) : (w[u][cb >> 1] << 16));
+                    acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], b, acc[cb], 0, 0, 0);
+                }
+        });
+    }
 }
 
 // One staged edge of a record gather: where neighbour j's k values start, a_ij, and j's column mask.
@@ -368,157 +477,131 @@ struct RecEdge {
     uint32_t mlo, mhi;
 };
 
-// H[r][c] += a_ij * V[j][slot of c] for every edge in [e_a, e_b): lane c of a (sub-)wave owns
-// column c.  The record of j is its k kept values in ascending column order plus a DG-bit column
-// mask, so lane c finds its value at popcount(mask below c) if bit c is set.  All 64 lanes load
-// from inside the 4k-byte record (lanes whose column is absent read a neighbouring slot and
-// contribute 0), so the loads of a batch of edges are unconditional and in flight together.  The
-// edges of one row are summed in a register; the sum goes to the LDS tile when the row changes.
-// With two rows per wave (DG = 32) the half-waves take alternate edges and flush one after the
-// other.  n * k must stay below 2^32.
+// acc += P * scatter(V, I) over the edges [e_a, e_b) of ordinary rows (Section 4.1, eq. (10)).
+// The record of neighbour j is its k kept values in ascending column order plus a DG-bit column
+// mask.  A lane's CPL adjacent columns occupy adjacent slots of the record, starting at
+// popcount(mask below its first column): the lane loads CPL values from there (the tail of the
+// window may belong to the next record, or to the padding that follows the last one) and deals
+// them out to the columns whose mask bit is set.  16-bit values are loaded from the even slot at
+// or below the start.  n * k must stay below 2^32.
 template <int DG, typename T>
-__device__ __forceinline__ void range_gather_records(const CsrView& g, const T* __restrict__ vals,
-                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
-                                                     int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, float* st_h,
-                                                     int lane) {
+__device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* __restrict__ vals,
+                                                    const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
+                                                    int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, int lane,
+                                                    f32x4 (&acc)[DG / 16]) {
     using M = typename MaskOf<DG>::type;
-    constexpr int LR = DG + 1, G = 64 / DG, GB = 16;
-    const int c = lane % DG, sub = lane / DG;
-    const uint32_t bit_lo = c < 32 ? 1u << c : 0u, bit_hi = c >= 32 ? 1u << (c - 32) : 0u;
-    const uint32_t below_lo = c < 32 ? bit_lo - 1u : 0xFFFFFFFFu, below_hi = c >= 32 ? bit_hi - 1u : 0u;
-    float acc = 0.f;
-    int cur = 16;                      // row being summed; 16 = the dump row
-    auto flush = [&](int next) {
-#pragma unroll
-        for (int s2 = 0; s2 < G; ++s2)
-            if (s2 == sub && next != cur) st_h[cur * LR + c] += acc;
-        if (next != cur) { acc = 0.f; cur = next; }
-    };
+    constexpr int CPL = DG / 16, NW = sizeof(T) == 4 ? CPL : CPL / 2 + 1;
+    const int i16 = lane & 15, kk = lane >> 4, bp = CPL * i16;
+    const uint32_t sh = bp & 31;
+    const bool upper = bp >= 32;
+    const uint32_t below_lo = upper ? 0xFFFFFFFFu : (1u << sh) - 1u, below_hi = upper ? (1u << sh) - 1u : 0u;
     for (int eb = e_a; eb < e_b; eb += 64) {
-        // stage up to 64 edges: lane l takes edge eb + l
         const int e = eb + lane;
-        const bool eok = e < e_b;
-        const int j = eok ? g.ci[e] : 0;
+        const bool ok = e < e_b;
+        const int j = ok ? g.ci[e] : 0;
         RecEdge me;
-        me.a = eok ? g.av[e] : 0.f;
+        me.a = ok ? g.av[e] : 0.f;
         me.off0 = (uint32_t)j * (uint32_t)k;
         const M m = masks[j];
         me.mlo = (uint32_t)m;
         if constexpr (DG == 64) me.mhi = (uint32_t)(m >> 32);
         else me.mhi = 0u;
-        int r = 0;
-#pragma unroll
-        for (int step = 8; step >= 1; step >>= 1)
-            if (s_rp[r + step] <= e) r += step;
+        const int r = tile_row_of(s_rp, e);
         wave_sync();          // readers of the previous chunk are done
         ebuf[lane] = me;
         rbuf[lane] = (uint8_t)r;
         wave_sync();
         const int cnt = e_b - eb < 64 ? e_b - eb : 64;
-        const int nit = (cnt + G - 1) / G;
-        for (int i0 = 0; i0 < nit; i0 += GB) {
-            float v[GB];
-            int rr[GB];
+        edge_batches((cnt + 3) >> 2, [&](auto gbc, int i0) {
+            constexpr int GB = decltype(gbc)::value;
+            uint32_t w[GB][NW];
+            uint32_t nib[GB];     // mask bits of this lane's CPL columns (bit 31: odd 16-bit start)
+            float p[GB];
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
-                const int ei = (i0 + u) * G + sub;
-                const bool ok = ei < cnt;
-                const int eu = ok ? ei : cnt - 1;
-                const RecEdge er = ebuf[eu];
-                const bool hit = ((er.mlo & bit_lo) | (er.mhi & bit_hi)) != 0u;
-                int pos = __popc(er.mlo & below_lo) + __popc(er.mhi & below_hi);
-                pos = pos < k ? pos : k - 1;
-                const float val = to_float(vals[er.off0 + (uint32_t)pos]);
-                v[u] = (ok && hit) ? er.a * val : 0.f;
-                const int rrow = (int)rbuf[eu];
-                rr[u] = ok ? rrow : -1;
+                const int ei = 4 * (i0 + u) + kk;
+                const RecEdge er = ebuf[ei];
+                const uint32_t word = upper ? er.mhi : er.mlo;
+                const uint32_t at = er.off0 + (uint32_t)__popc(er.mlo & below_lo) + (uint32_t)__popc(er.mhi & below_hi);
+                nib[u] = (word >> sh) & ((1u << CPL) - 1u);
+                if constexpr (sizeof(T) == 4) {
+                    load_words<NW>(vals + (size_t)at, w[u]);
+                } else {
+                    load_words<NW>(vals + (size_t)(at & ~1u), w[u]);
+                    nib[u] |= at << 31;
+                }
+                p[u] = (int)rbuf[ei] == i16 ? er.a : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
-                flush(rr[u] >= 0 ? rr[u] : cur);
-                acc += v[u];
+                float q[CPL];     // the window: slot start + t
+                if constexpr (sizeof(T) == 4) {
+#pragma unroll
+                    for (int t = 0; t < CPL; ++t) q[t] = __uint_as_float(w[u][t]);
+                } else {
+                    const uint32_t shift = (nib[u] >> 31) * 16u;
+#pragma unroll
+                    for (int t = 0; t < CPL / 2; ++t) {
+                        const uint32_t pair = __builtin_amdgcn_alignbit(w[u][t + 1], w[u][t], shift);
+                        q[2 * t] = __uint_as_float(pair << 16);
+                        q[2 * t + 1] = __uint_as_float(pair & 0xFFFF0000u);
+                    }
+                }
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) {
+                    const bool bit = (nib[u] >> cb) & 1u;
+                    const float b = bit ? q[0] : 0.f;
+#pragma unroll
+                    for (int t = 0; t + 1 < CPL - cb; ++t) q[t] = bit ? q[t + 1] : q[t];
+                    acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], b, acc[cb], 0, 0, 0);
+                }
             }
-        }
+        });
     }
-    flush(16);
 }
 
-// Q[r][c] += a_ij * X[j][c] for every edge in [e_a, e_b): lane c of a (sub-)wave owns column c and
-// sums the edges of one row in a register; the sum goes to the LDS tile when the row changes.
-// With two rows per wave (DG = 32) the half-waves take alternate edges and flush one after the
-// other, so two partial sums of the same row never meet in one instruction.
-template <int DG, typename T>
-__device__ __forceinline__ void range_gather_dense(const CsrView& g, const T* __restrict__ x, int64_t ld, int e_a, int e_b,
-                                                   const int* s_rp, EdgeRec* ebuf, float* st, int lane) {
-    constexpr int LR = DG + 1, G = 64 / DG, GB = 16;
-    const int c = lane % DG, sub = lane / DG;
-    float acc = 0.f;
-    int cur = 16;                      // row being summed; 16 = the dump row
-    auto flush = [&](int next) {
-#pragma unroll
-        for (int s2 = 0; s2 < G; ++s2)
-            if (s2 == sub && next != cur) st[cur * LR + c] += acc;
-        if (next != cur) { acc = 0.f; cur = next; }
-    };
-    for (int eb = e_a; eb < e_b; eb += 64) {
-        const int cnt = stage_edges(g, eb, e_b, s_rp, ebuf, lane);
-        const int nit = (cnt + G - 1) / G;
-        for (int i0 = 0; i0 < nit; i0 += GB) {
-            float v[GB];
-            int rr[GB];
-#pragma unroll
-            for (int u = 0; u < GB; ++u) {
-                const int ei = (i0 + u) * G + sub;
-                const bool ok = ei < cnt;
-                const EdgeRec er = ebuf[ok ? ei : cnt - 1];
-                const float val = to_float(x[(size_t)er.j * ld + c]);
-                v[u] = ok ? er.a * val : 0.f;
-                rr[u] = ok ? er.r : -1;
-            }
-#pragma unroll
-            for (int u = 0; u < GB; ++u) {
-                flush(rr[u] >= 0 ? rr[u] : cur);
-                acc += v[u];
-            }
-        }
+// sum of the first-pass partial rows of every split row of the tile into st
+template <int DG>
+__device__ __forceinline__ void hub_rows_fill(const CsrView& g, const float* __restrict__ hub_part, int r0, const int* s_rp,
+                                              float* st, int lane) {
+    for (int r = 0; r < 16; ++r) {
+        const bool hub = (s_rp[r + 1] - s_rp[r]) > g.hub_threshold;
+        if (hub && lane < DG) st[r * (DG + 1) + lane] = hub_row_sum<DG>(g, hub_part, r0 + r, lane);
     }
-    flush(16);
 }
 
-// Walks the tile's rows: maximal runs of ordinary rows go through `range(e_a, e_b)`, split rows
-// receive the sum of their first-pass partial rows.  st must be zero on entry; it is 16 rows of
-// DG+1 floats followed by 64 dump words.
+// H of the tile into st (16 rows of DG+1 floats): maximal runs of ordinary rows go through
+// `range(e_a, e_b)`, which accumulates into acc; split rows receive the sum of their first-pass
+// partial rows afterwards.
 template <int DG, typename Range>
 __device__ __forceinline__ void tile_gather(const CsrView& g, const float* __restrict__ hub_part, bool has_hub, int r0,
-                                            const int* s_rp, float* st, int lane, Range range) {
-    constexpr int LR = DG + 1;
+                                            const int* s_rp, float* st, int lane, f32x4 (&acc)[DG / 16], Range range) {
+    constexpr int CPL = DG / 16, LR = DG + 1;
+#pragma unroll
+    for (int cb = 0; cb < CPL; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
     if (!has_hub) {
         range(s_rp[0], s_rp[16]);
-        return;
-    }
-    int run = 0;
-    for (int r = 0; r <= 16; ++r) {
-        const bool hub = r < 16 && (s_rp[r + 1] - s_rp[r]) > g.hub_threshold;
-        if (r == 16 || hub) {
-            if (s_rp[r] > s_rp[run]) range(s_rp[run], s_rp[r]);
-            run = r + 1;
+    } else {
+        int run = 0;
+        for (int r = 0; r <= 16; ++r) {
+            const bool hub = r < 16 && (s_rp[r + 1] - s_rp[r]) > g.hub_threshold;
+            if (r == 16 || hub) {
+                if (s_rp[r] > s_rp[run]) range(s_rp[run], s_rp[r]);
+                run = r + 1;
+            }
         }
-        if (hub && lane < DG) st[r * LR + lane] = hub_row_sum<DG>(g, hub_part, r0 + r, lane);
     }
-}
-
-template <int DG>
-__device__ __forceinline__ void zero_tile(float* st, int lane) {
 #pragma unroll
-    for (int i = lane; i < 16 * (DG + 1); i += 64) st[i] = 0.f;
+    for (int cb = 0; cb < CPL; ++cb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) st[(4 * (lane >> 4) + r) * LR + CPL * (lane & 15) + cb] = acc[cb][r];
+    if (has_hub) hub_rows_fill<DG>(g, hub_part, r0, s_rp, st, lane);
 }
 
 // ---- 16-row MFMA tiles -------------------------------------------------------------------------
 // A wave multiplies its 16 x DG tile (staged in LDS, row stride DG+1) by a DG x DG matrix with
 // v_mfma_f32_16x16x4_f32:
 //   A[i][kk]: lane = kk*16 + i;  B[kk][j]: lane = kk*16 + j;  D[4*(lane/16)+r][lane%16] in reg r.
-using f32x4 = __attribute__((__vector_size__(4 * sizeof(float)))) float;
-
 // The DG x DG weight matrix sits in LDS (row stride DG + 8, which spreads the four k-rows of a
 // B operand over different banks), loaded once per workgroup; transposed = true stores W^T.
 template <int DG>

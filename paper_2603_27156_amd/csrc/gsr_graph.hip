@@ -222,7 +222,7 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     size_t off = 0;
     for (int s = 0; s < cfg->c && s < 8; ++s) {
         w.rec_vals[s] = off;
-        off += align_up(n * (size_t)cfg->k * b);
+        off += align_up(n * (size_t)cfg->k * b + 16);   // the record gather loads up to 16 bytes past a record
         w.rec_mask[s] = off;
         off += align_up(n * (dg == 32 ? 4 : 8));
     }

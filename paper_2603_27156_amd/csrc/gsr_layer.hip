@@ -30,32 +30,118 @@ struct Record {
     M* mask;        // [n]
 };
 
-// GS of R rows held in row layout (yq[r] = this lane's column of row r) and their records.
-template <int DG, typename T, int R>
-__device__ __forceinline__ void emit_records(const float (&yq)[R], const bool (&ok)[R], const int (&row)[R], int c, int sub,
-                                             int k, int norm, float eps, const Record<DG, T>& out) {
+// GS of the 16 rows of an LDS tile and their records (Section 4.1; record layout of Section 4.3).
+// st holds the rows as they read back from memory (16 x (DG+1) floats, rows past the end zero).
+// Lane (r, q) takes the quarter q of row r into registers, so the 16 searches for the k-th largest
+// key run side by side in vector registers: interval bisection on an order-preserving integer
+// image of the values, count = own compares + the three partner quarters.  Invariant per row: at
+// least k keys are >= lo and fewer than k are >= hi; hi starts just above the row maximum, lo four
+// binades below it (0 when a count says that is too high).  A row closes when a candidate splits
+// off exactly k keys or the interval is down to one value (a tie at the k-th position); ties go
+// to the lowest columns, -0 equals +0.  The kept values (RMS-scaled) are compacted in LDS in
+// column order and leave as one contiguous block, since rows r0..r0+15 are adjacent in [n][k].
+// st is overwritten.
+template <int DG, typename T>
+__device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int norm, float eps, const Record<DG, T>& out,
+                                          int lane) {
     using M = typename MaskOf<DG>::type;
-    float x[R];
-    bool sel[R];
-    M mask[R];
+    constexpr int QW = DG / 4, LR = DG + 1;
+    constexpr int KS = sizeof(T) == 2 ? 16 : 0;   // bf16 values: the low 16 key bits are zero
+    const int r = lane & 15, q = lane >> 4;
+    float x[QW];
+    uint32_t key[QW];
 #pragma unroll
-    for (int r = 0; r < R; ++r) x[r] = ok[r] ? yq[r] : 0.f;
-    topk_select_multi<DG, R>(x, k, c, sub, sel, mask);
+    for (int j = 0; j < QW; ++j) x[j] = st[r * LR + q * QW + j];
+    uint32_t top = 0u;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-        float scale = 1.f;
-        if (norm == GSR_NORM_RMS) {
-            const float sq = x[r] * x[r];
-            const float ss = sub_sum<DG>(sq);
-            scale = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + eps);
-        }
-        const uint64_t wave_mask = ballot(sel[r]);
-        if (ok[r] && sel[r]) {
-            const size_t at = (size_t)row[r] * k + rank_in_mask<DG>(mask[r], wave_mask, sub);
-            out.vals[at] = from_float<T>(x[r] * scale);
-        }
-        if (ok[r] && c == 0) out.mask[row[r]] = mask[r];
+    for (int j = 0; j < QW; ++j) {
+        const uint32_t u = __float_as_uint(x[j]);
+        uint32_t kk = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+        kk = kk == 0x7FFFFFFFu ? 0x80000000u : kk;          // -0 -> +0
+        key[j] = kk >> KS;
+        top = max(top, key[j]);
     }
+    top = quarter_max(top);
+    auto count_ge = [&](uint32_t t) {
+        uint32_t cnt = 0u;
+#pragma unroll
+        for (int j = 0; j < QW; ++j) cnt += key[j] >= t ? 1u : 0u;
+        return quarter_sum(cnt);
+    };
+    constexpr uint32_t span = (4u << 23) >> KS;
+    const uint32_t uk = (uint32_t)k;
+    uint32_t lo = top > span ? top - span : 0u, hi = top + 1u;
+    {
+        const uint32_t cnt = count_ge(lo);
+        lo = (cnt >= uk && k < DG) ? lo : 0u;
+        uint32_t open = (cnt != uk && k < DG && r0 + r < n) ? 1u : 0u;
+        for (int round = 0; round < 33 && ballot(open != 0u) != 0ull; ++round) {
+            const uint32_t mid = lo + ((hi - lo) >> 1);
+            const uint32_t c2 = count_ge(mid);
+            lo = c2 >= uk ? mid : lo;
+            hi = c2 >= uk ? hi : mid;
+            open = (c2 == uk || hi - lo <= 1u) ? 0u : open;
+        }
+    }
+    // column sets of this quarter: above the threshold, at the threshold
+    uint32_t mgt = 0u, meq = 0u;
+#pragma unroll
+    for (int j = 0; j < QW; ++j) {
+        mgt |= key[j] > lo ? 1u << j : 0u;
+        meq |= key[j] == lo ? 1u << j : 0u;
+    }
+    uint32_t msel;
+    {
+        const uint32_t cg = __popc(mgt), ce = __popc(meq);
+        uint32_t all[4];
+        quarter_all(cg | ce << 8, all);
+        const int need = k - (int)((all[0] & 255u) + (all[1] & 255u) + (all[2] & 255u) + (all[3] & 255u));
+        int before = 0;   // ties in lower quarters
+#pragma unroll
+        for (int i = 0; i < 3; ++i) before += i < q ? (int)(all[i] >> 8) : 0;
+        int take = min(max(need - before, 0), (int)ce);
+        if (ballot(take != (int)ce) == 0ull) {
+            msel = mgt | meq;
+        } else {
+            msel = mgt;
+#pragma unroll
+            for (int j = 0; j < QW; ++j) {
+                const uint32_t s = ((meq >> j) & 1u) & (take > 0 ? 1u : 0u);
+                msel |= s << j;
+                take -= (int)s;
+            }
+        }
+    }
+    uint32_t all[4];
+    quarter_all(msel | (uint32_t)__popc(msel) << 16, all);
+    int slot = r * k;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) slot += i < q ? (int)(all[i] >> 16) : 0;
+    M mask;
+    if constexpr (DG == 64)
+        mask = (M)(all[0] & 0xFFFFu) | (M)(all[1] & 0xFFFFu) << 16 | (M)(all[2] & 0xFFFFu) << 32 | (M)(all[3] & 0xFFFFu) << 48;
+    else
+        mask = (all[0] & 0xFFu) | (all[1] & 0xFFu) << 8 | (all[2] & 0xFFu) << 16 | (all[3] & 0xFFu) << 24;
+    float scale = 1.f;
+    if (norm == GSR_NORM_RMS) {
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < QW; ++j) ss += x[j] * x[j];
+        ss = quarter_sum(ss);
+        scale = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + eps);
+    }
+    wave_sync();   // every lane holds its quarter: the tile can be reused for the compacted values
+#pragma unroll
+    for (int j = 0; j < QW; ++j) {
+        const uint32_t bit = (msel >> j) & 1u;
+        st[bit ? slot : 16 * LR + lane] = x[j] * scale;      // dropped columns go to the dump words
+        slot += (int)bit;
+    }
+    wave_sync();
+    const int rows = min(16, n - r0), total = rows * k;
+    T* dst = out.vals + (size_t)r0 * k;
+    for (int i = lane; i < total; i += 64) dst[i] = from_float<T>(st[i]);
+    if (q == 0 && r < rows) out.mask[r0 + r] = mask;
 }
 
 // per-wave LDS: tile(s) of 16 x (DG+1) floats, 64 staged edges, 17 row pointers
@@ -88,7 +174,7 @@ struct BlockArgs {
 
 template <int DG, typename T, int SIGN, bool WITH_DW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
-    constexpr int G = 64 / DG, LR = DG + 1, NT = WITH_DW ? 2 : 1, RPW = 16 / G, ER = 4;
+    constexpr int G = 64 / DG, LR = DG + 1, NT = WITH_DW ? 2 : 1, RPW = 16 / G;
     __shared__ WaveLds<DG, NT> lds[4];
     const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
     WaveLds<DG, NT>& L = lds[wave];
@@ -108,11 +194,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         const int r0 = t * 16;
         wave_sync();
         const bool has_hub = tile_begin(a.g, r0, a.n, L.rp, lane);
-        zero_tile<DG>(st_h, lane);
-        tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
-            range_gather_records<DG, T>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
-                                        __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
-                                        st_h, lane);
+        f32x4 hacc[DG / 16];
+        tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, hacc, [&](int e_a, int e_b) {
+            gather_records_mfma<DG, T>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
+                                       __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
+                                       lane, hacc);
         });
         if constexpr (WITH_DW) {
             float gy[RPW];
@@ -141,21 +227,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
             xv[it] = to_float(a.plane[(size_t)(row < a.n ? row : a.n - 1) * a.ld + c]);
         }
 #pragma unroll
-        for (int i0 = 0; i0 < RPW; i0 += ER) {
-            float yq[ER];
-            bool ok[ER];
-            int row[ER];
-#pragma unroll
-            for (int u = 0; u < ER; ++u) {
-                const int r = (i0 + u) * G + sub;
-                row[u] = r0 + r;
-                ok[u] = row[u] < a.n;
-                const float o = st_h[r * LR + c];
-                const T yt = from_float<T>(SIGN > 0 ? xv[i0 + u] + o : xv[i0 + u] - o);
-                if (ok[u]) a.plane[(size_t)row[u] * a.ld + c] = yt;
-                yq[u] = to_float(yt);
-            }
-            if (a.out.mask) emit_records<DG, T, ER>(yq, ok, row, c, sub, a.k, a.norm, a.eps, a.out);
+        for (int it = 0; it < RPW; ++it) {
+            const int r = it * G + sub, row = r0 + r;
+            const float o = st_h[r * LR + c];
+            const T yt = from_float<T>(SIGN > 0 ? xv[it] + o : xv[it] - o);
+            if (row < a.n) a.plane[(size_t)row * a.ld + c] = yt;
+            st_h[r * LR + c] = row < a.n ? to_float(yt) : 0.f;
+        }
+        if (a.out.mask) {
+            wave_sync();
+            emit_tile<DG, T>(st_h, r0, a.n, a.k, a.norm, a.eps, a.out, lane);
         }
     }
     if constexpr (WITH_DW) {
@@ -236,10 +317,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
         const int r0 = t * 16;
         wave_sync();
         const bool has_hub = tile_begin(a.gt, r0, a.n, L.rp, lane);
-        zero_tile<DG>(st, lane);
-        tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, [&](int e_a, int e_b) {
-            range_gather_dense<DG, T>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
-                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, st, lane);
+        f32x4 qacc[DG / 16];
+        tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, qacc, [&](int e_a, int e_b) {
+            gather_dense_mfma<DG, T>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
+                                     __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, lane, qacc);
         });
         wave_sync();
         {
@@ -316,27 +397,39 @@ struct SumArgs {
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
-    constexpr int G = 64 / DG, ER = 4;
+    constexpr int G = 64 / DG, LR = DG + 1, RPW = 16 / G;
+    __shared__ float tile[4][16 * LR + 64];
     const int lane = lane_id(), c = lane % DG, sub = lane / DG;
-    const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    for (int r0 = ((blockIdx.x * blockDim.x + threadIdx.x) >> 6) * (G * ER); r0 < a.n; r0 += nwaves * G * ER) {
-        float yq[ER];
-        bool ok[ER];
-        int row[ER];
+    float* st = tile[threadIdx.x >> 6];
+    const int nwaves = (gridDim.x * blockDim.x) >> 6, tiles = (a.n + 15) / 16;
+    for (int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; t < tiles; t += nwaves) {
+        const int r0 = t * 16;
+        float s[RPW];
 #pragma unroll
-        for (int u = 0; u < ER; ++u) {
-            row[u] = r0 + u * G + sub;
-            ok[u] = row[u] < a.n;
-            float s = 0.f;
-            if (ok[u]) {
-                s = to_float(a.src[(size_t)row[u] * a.ld + c]);
-                for (int j = 1; j < a.nsrc; ++j) s += to_float(a.src[(size_t)j * a.src_gs + (size_t)row[u] * a.ld + c]);
-            }
-            const T st = from_float<T>(s);
-            if (ok[u] && a.y0) a.y0[(size_t)row[u] * DG + c] = st;
-            yq[u] = to_float(st);
+        for (int it = 0; it < RPW; ++it) {
+            const int row = r0 + it * G + sub;
+            s[it] = to_float(a.src[(size_t)(row < a.n ? row : a.n - 1) * a.ld + c]);
         }
-        emit_records<DG, T, ER>(yq, ok, row, c, sub, a.k, a.norm, a.eps, a.out);
+        for (int j = 1; j < a.nsrc; ++j) {
+            float v[RPW];
+#pragma unroll
+            for (int it = 0; it < RPW; ++it) {
+                const int row = r0 + it * G + sub;
+                v[it] = to_float(a.src[(size_t)j * a.src_gs + (size_t)(row < a.n ? row : a.n - 1) * a.ld + c]);
+            }
+#pragma unroll
+            for (int it = 0; it < RPW; ++it) s[it] += v[it];
+        }
+        wave_sync();
+#pragma unroll
+        for (int it = 0; it < RPW; ++it) {
+            const int r = it * G + sub, row = r0 + r;
+            const T yt = from_float<T>(s[it]);
+            if (row < a.n && a.y0) a.y0[(size_t)row * DG + c] = yt;
+            st[r * LR + c] = row < a.n ? to_float(yt) : 0.f;
+        }
+        wave_sync();
+        emit_tile<DG, T>(st, r0, a.n, a.k, a.norm, a.eps, a.out, lane);
     }
 }
 
