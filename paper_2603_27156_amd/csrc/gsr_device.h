@@ -61,6 +61,9 @@ __device__ __forceinline__ void lds_add(float* p, float v) {
     __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
+// (a & m) | (b & ~m)
+__device__ __forceinline__ uint32_t bit_select(uint32_t m, uint32_t a, uint32_t b) { return (a & m) | (b & ~m); }
+
 __device__ __forceinline__ uint64_t ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 
 // bits of a wave-wide ballot that belong to this lane's row
@@ -417,18 +420,24 @@ __device__ __forceinline__ int tile_row_of(const int* s_rp, int e) {
     return r;
 }
 
-// Runs `batch(GB, i0)` over the nit groups of four staged edges, eight groups at a time while
-// they last, then four at a time (a batch may overrun nit by up to three groups, which stay
-// inside the 64 staged edges and contribute zero).
-template <typename Batch>
+// Runs `batch(GB, i0)` over the nit <= 16 groups of four staged edges: all sixteen at once if
+// MAXB allows, else eight at a time while they last, then four at a time (a batch may overrun
+// nit by up to three groups, which stay inside the 64 staged edges and contribute zero).
+template <int MAXB, typename Batch>
 __device__ __forceinline__ void edge_batches(int nit, Batch batch) {
     int i0 = 0;
+    if constexpr (MAXB >= 16) {
+        if (nit > 12) {
+            batch(std::integral_constant<int, 16>{}, 0);
+            return;
+        }
+    }
     for (; i0 + 8 <= nit; i0 += 8) batch(std::integral_constant<int, 8>{}, i0);
     for (; i0 < nit; i0 += 4) batch(std::integral_constant<int, 4>{}, i0);
 }
 
 // acc += P * X over the edges [e_a, e_b) of ordinary rows; X is a dense plane, row stride ld.
-template <int DG, typename T>
+template <int DG, typename T, int MAXB>
 __device__ __forceinline__ void gather_dense_mfma(const CsrView& g, const T* __restrict__ x, int64_t ld, int e_a, int e_b,
                                                   const int* s_rp, EdgeRec* ebuf, int lane, f32x4 (&acc)[DG / 16]) {
     constexpr int CPL = DG / 16, NW = CPL * (int)sizeof(T) / 4;
@@ -447,7 +456,7 @@ __device__ __forceinline__ void gather_dense_mfma(const CsrView& g, const T* __r
         ebuf[lane] = me;
         wave_sync();
         const int cnt = e_b - eb < 64 ? e_b - eb : 64;
-        edge_batches((cnt + 3) >> 2, [&](auto gbc, int i0) {
+        edge_batches<MAXB>((cnt + 3) >> 2, [&](auto gbc, int i0) {
             constexpr int GB = decltype(gbc)::value;
             uint32_t w[GB][NW];
             float p[GB];
@@ -484,7 +493,7 @@ struct RecEdge {
 // window may belong to the next record, or to the padding that follows the last one) and deals
 // them out to the columns whose mask bit is set.  16-bit values are loaded from the even slot at
 // or below the start.  n * k must stay below 2^32.
-template <int DG, typename T>
+template <int DG, typename T, int MAXB>
 __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* __restrict__ vals,
                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
                                                     int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, int lane,
@@ -512,7 +521,7 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
         rbuf[lane] = (uint8_t)r;
         wave_sync();
         const int cnt = e_b - eb < 64 ? e_b - eb : 64;
-        edge_batches((cnt + 3) >> 2, [&](auto gbc, int i0) {
+        edge_batches<MAXB>((cnt + 3) >> 2, [&](auto gbc, int i0) {
             constexpr int GB = decltype(gbc)::value;
             uint32_t w[GB][NW];
             uint32_t nib[GB];     // mask bits of this lane's CPL columns (bit 31: odd 16-bit start)
@@ -534,25 +543,27 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
             }
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
-                float q[CPL];     // the window: slot start + t
+                uint32_t q[CPL];  // the window (float bits): slot start + t
                 if constexpr (sizeof(T) == 4) {
 #pragma unroll
-                    for (int t = 0; t < CPL; ++t) q[t] = __uint_as_float(w[u][t]);
+                    for (int t = 0; t < CPL; ++t) q[t] = w[u][t];
                 } else {
                     const uint32_t shift = (nib[u] >> 31) * 16u;
 #pragma unroll
                     for (int t = 0; t < CPL / 2; ++t) {
                         const uint32_t pair = __builtin_amdgcn_alignbit(w[u][t + 1], w[u][t], shift);
-                        q[2 * t] = __uint_as_float(pair << 16);
-                        q[2 * t + 1] = __uint_as_float(pair & 0xFFFF0000u);
+                        q[2 * t] = pair << 16;
+                        q[2 * t + 1] = pair & 0xFFFF0000u;
                     }
                 }
+                // a set column takes the head of the window and advances it; all-ones / all-zero
+                // words from a signed bit extract drive bitwise selects, no condition codes
 #pragma unroll
                 for (int cb = 0; cb < CPL; ++cb) {
-                    const bool bit = (nib[u] >> cb) & 1u;
-                    const float b = bit ? q[0] : 0.f;
+                    const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)nib[u], cb, 1);
+                    const float b = __uint_as_float(q[0] & m);
 #pragma unroll
-                    for (int t = 0; t + 1 < CPL - cb; ++t) q[t] = bit ? q[t + 1] : q[t];
+                    for (int t = 0; t + 1 < CPL - cb; ++t) q[t] = bit_select(m, q[t + 1], q[t]);
                     acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], b, acc[cb], 0, 0, 0);
                 }
             }

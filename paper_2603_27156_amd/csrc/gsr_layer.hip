@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         const bool has_hub = tile_begin(a.g, r0, a.n, L.rp, lane);
         f32x4 hacc[DG / 16];
         tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, hacc, [&](int e_a, int e_b) {
-            gather_records_mfma<DG, T>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
+            gather_records_mfma<DG, T, WITH_DW ? 16 : 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
                                        __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
                                        lane, hacc);
         });
@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
         const bool has_hub = tile_begin(a.gt, r0, a.n, L.rp, lane);
         f32x4 qacc[DG / 16];
         tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, qacc, [&](int e_a, int e_b) {
-            gather_dense_mfma<DG, T>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
+            gather_dense_mfma<DG, T, 16>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, lane, qacc);
         });
         wave_sync();
@@ -330,53 +330,58 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
             store_tile<DG>(st, acc);
             wave_sync();
         }
-        // everything the rows need from memory, issued together
-        float zz[RPW];
-        bool sel[RPW];
+        // epilogue in batches of HB rows per lane: everything a batch needs from memory is issued
+        // together
+        constexpr int HB = RPW < 8 ? RPW : 8;
+#pragma unroll 1
+        for (int h0 = 0; h0 < RPW; h0 += HB) {
+            float zz[HB];
+            bool sel[HB];
 #pragma unroll
-        for (int it = 0; it < RPW; ++it) {
-            const int row = r0 + it * G + sub;
-            const bool ok = row < a.n;
-            const int rowc = ok ? row : a.n - 1;
-            sel[it] = ok && ((a.own_mask[rowc] >> c) & 1);
-            const float zv = a.norm == GSR_NORM_RMS ? to_float(a.z[(size_t)rowc * a.ldz + c]) : 0.f;
-            zz[it] = ok ? zv : 0.f;
-        }
-        float dzv[RPW];
-        bool touch[RPW];
-#pragma unroll
-        for (int it = 0; it < RPW; ++it) {
-            const int r = it * G + sub, row = r0 + r;
-            const bool ok = row < a.n;
-            const float gdh = st[r * LR + c];
-            float dz = sel[it] ? gdh : 0.f;
-            touch[it] = sel[it];
-            if (a.norm == GSR_NORM_RMS) {
-                // V = Z[I] * rinv, rinv = (mean Z^2 + eps)^-1/2:
-                // dZ_c = [c in I] g_c rinv - Z_c (sum_t g_t Z_{I_t}) rinv^3 / DG
-                const float sq = zz[it] * zz[it];
-                const float ss = sub_sum<DG>(sq);
-                const float rinv = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + a.eps);
-                const float pr = sel[it] ? gdh * zz[it] : 0.f;
-                const float dot = sub_sum<DG>(pr);
-                const float coef = dot * (rinv * rinv * rinv) * (1.0f / (float)DG);
-                dz = (sel[it] ? gdh * rinv : 0.f) - zz[it] * coef;
-                touch[it] = ok;
+            for (int u = 0; u < HB; ++u) {
+                const int row = r0 + (h0 + u) * G + sub;
+                const bool ok = row < a.n;
+                const int rowc = ok ? row : a.n - 1;
+                sel[u] = ok && ((a.own_mask[rowc] >> c) & 1);
+                const float zv = a.norm == GSR_NORM_RMS ? to_float(a.z[(size_t)rowc * a.ldz + c]) : 0.f;
+                zz[u] = ok ? zv : 0.f;
             }
-            dzv[it] = dz;
-        }
-        for (int j = 0; j < a.ndst; ++j) {
-            T* plane = a.dst + (size_t)j * a.dst_gs;
-            float old[RPW];
+            float dzv[HB];
+            bool touch[HB];
 #pragma unroll
-            for (int it = 0; it < RPW; ++it) {
-                const int row = r0 + it * G + sub;
-                old[it] = to_float(plane[(size_t)(row < a.n ? row : a.n - 1) * a.ldd + c]);
+            for (int u = 0; u < HB; ++u) {
+                const int r = (h0 + u) * G + sub, row = r0 + r;
+                const bool ok = row < a.n;
+                const float gdh = st[r * LR + c];
+                float dz = sel[u] ? gdh : 0.f;
+                touch[u] = sel[u];
+                if (a.norm == GSR_NORM_RMS) {
+                    // V = Z[I] * rinv, rinv = (mean Z^2 + eps)^-1/2:
+                    // dZ_c = [c in I] g_c rinv - Z_c (sum_t g_t Z_{I_t}) rinv^3 / DG
+                    const float sq = zz[u] * zz[u];
+                    const float ss = sub_sum<DG>(sq);
+                    const float rinv = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + a.eps);
+                    const float pr = sel[u] ? gdh * zz[u] : 0.f;
+                    const float dot = sub_sum<DG>(pr);
+                    const float coef = dot * (rinv * rinv * rinv) * (1.0f / (float)DG);
+                    dz = (sel[u] ? gdh * rinv : 0.f) - zz[u] * coef;
+                    touch[u] = ok;
+                }
+                dzv[u] = dz;
             }
+            for (int j = 0; j < a.ndst; ++j) {
+                T* plane = a.dst + (size_t)j * a.dst_gs;
+                float old[HB];
 #pragma unroll
-            for (int it = 0; it < RPW; ++it) {
-                const int row = r0 + it * G + sub;
-                if (touch[it]) plane[(size_t)row * a.ldd + c] = from_float<T>(old[it] + dzv[it]);
+                for (int u = 0; u < HB; ++u) {
+                    const int row = r0 + (h0 + u) * G + sub;
+                    old[u] = to_float(plane[(size_t)(row < a.n ? row : a.n - 1) * a.ldd + c]);
+                }
+#pragma unroll
+                for (int u = 0; u < HB; ++u) {
+                    const int row = r0 + (h0 + u) * G + sub;
+                    if (touch[u]) plane[(size_t)row * a.ldd + c] = from_float<T>(old[u] + dzv[u]);
+                }
             }
         }
     }
