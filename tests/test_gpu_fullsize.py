@@ -1,0 +1,238 @@
+"""GPU parity at the full size of the benchmarked workloads, in the launch configuration the
+benchmark times (persistent grids over all compute units, hub rows split in two passes).
+
+The top-k selection of GS is a discontinuous function of its input: where the k-th and (k+1)-th
+largest entries of a row differ by less than the rounding difference between float32 accumulation
+(GPU) and float64 accumulation rounded to float32 (oracle), the two sides may keep different
+columns, and both selections are valid.  Such a row changes the rows that aggregate it.  The tests
+therefore compare every element at the float32 bar outside the rows such a flip can reach
+(a flip needs a deviation of at least half the row's top-k gap), and bound how many rows lie
+inside."""
+import time
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import oracle
+import paper_2603_27156_amd as gsr
+from paper_2603_27156_amd import synth
+from gpu_util import Case, violations, rel_norm, BF16_REL
+from test_gpu_layer import run_step
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+PLANAR = gsr.GSR_LAYOUT_GROUP_PLANAR
+_cases = {}
+
+
+def case(name) -> Case:
+    if name not in _cases:
+        t = time.time()
+        if name == "cfg1":
+            w = synth.workload(1)
+        elif name == "cfg2":
+            w = synth.workload(2)
+        elif name == "cfg2-bf16":
+            w = synth.workload(2, dtype="bf16")
+        _cases[name] = Case(w, 0, PLANAR)
+        print(f"[case] {name} n={w.n} D={w.d} C={w.c} k={w.k} built in {time.time() - t:.1f}s", flush=True)
+    return _cases[name]
+
+
+def adjacency(c: Case):
+    n = c.w.n
+    return sp.csr_matrix((np.ones(len(c.og.ci), dtype=np.int32), c.og.ci, c.og.rp), shape=(n, n))
+
+
+def row_gap(z, k):
+    """Gap between the k-th and (k+1)-th largest entry of every row."""
+    if k >= z.shape[1]:
+        return np.full(z.shape[0], np.inf)
+    s = -np.sort(-z, axis=1)
+    return s[:, k - 1] - s[:, k]
+
+
+def audit_layer_forward(c: Case, X, Y, Y_ref, tag):
+    """Element-wise comparison of a layer output with the oracle's, group by group.
+
+    Group i is X_i + f_i(Y_{i-1}).  A row of Y_{i-1} can select different columns on the two
+    sides only if its two versions differ by at least half its top-k gap; a row of group i can
+    leave the tolerance only if it aggregates such a row, or a row of group i-1 that already left
+    it.  Every other row must agree at the float32 bar.  Returns the fraction of rows outside the
+    tolerance; asserts that each of them is explained."""
+    w = c.w
+    dg, C = w.dg, w.c
+    A = adjacency(c)
+    if C > 2:
+        # Y_0 as the kernel forms it (float32, planes added in order) and as the oracle does
+        z_gpu = X[:, dg:2 * dg].astype(np.float32)
+        for j in range(2, C):
+            z_gpu = z_gpu + X[:, j * dg:(j + 1) * dg].astype(np.float32)
+        z_gpu = z_gpu.astype(np.float64)
+        z_ref = oracle.round_store(X[:, dg:].reshape(w.n, C - 1, dg).sum(axis=1), c.ocfg.sm)
+    else:
+        z_gpu = z_ref = X[:, dg:2 * dg]
+    prev_bad = np.zeros(w.n, dtype=bool)
+    total_bad = np.zeros(w.n, dtype=bool)
+    for i in range(C):
+        dev = np.abs(z_gpu - z_ref).max(axis=1)
+        may_flip = row_gap(z_ref, w.k) <= 2.0 * dev + 1e-30 * (dev > 0)
+        may_flip &= dev > 0
+        allowed = (A @ (may_flip | prev_bad).astype(np.int32)) > 0
+        sl = slice(i * dg, (i + 1) * dg)
+        bad, worst = violations(Y[:, sl], Y_ref[:, sl])
+        rows = bad.any(axis=1)
+        print(f"[{tag}] group {i}: rows that may flip {int(may_flip.sum())}, reachable {int(allowed.sum())}, "
+              f"outside tolerance {int(rows.sum())}, unexplained {int((rows & ~allowed).sum())}", flush=True)
+        assert not (rows & ~allowed).any(), f"group {i}: rows outside tolerance that no flipped selection explains"
+        assert allowed.mean() < 2e-2
+        prev_bad = rows
+        total_bad |= rows
+        z_gpu, z_ref = Y[:, sl], Y_ref[:, sl]
+    return float(total_bad.mean())
+
+
+def test_cfg1_full_size_layer():
+    c = case("cfg1")
+    w = c.w
+    X = c.x0_on_grid()
+    for l in range(2):
+        X = oracle.layer_forward(c.og, c.ocfg, c.inp.weights[l], X)
+    W = c.inp.weights[2]
+    Wd = torch.from_numpy(W).to(c.dev)
+    Y_ref = oracle.layer_forward(c.og, c.ocfg, W, X)
+    y = c.to_dev(X)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y)
+    frac = audit_layer_forward(c, X, c.to_host(y), Y_ref, "cfg1 fwd")
+    assert frac < 1e-3
+
+    rng = np.random.default_rng(5)
+    dY = (rng.standard_normal((w.n, w.d)) * 1e-3).astype(np.float32).astype(np.float64)
+    Xb_ref, dX_ref, dW_ref = oracle.layer_backward(c.og, c.ocfg, W, Y_ref, dY)
+    yb, dyb = c.to_dev(Y_ref), c.to_dev(dY)
+    dW = torch.empty((w.c, w.dg, w.dg), dtype=torch.float32, device=c.dev)
+    gsr.gsr_layer_backward(c.gg, c.gcfg, Wd, yb, dyb, dW)
+    for name, got, ref in (("X rebuilt", c.to_host(yb), Xb_ref), ("dX", c.to_host(dyb), dX_ref)):
+        bad, worst = violations(got, ref)
+        print(f"[cfg1 bwd] {name}: bad rows {int(bad.any(axis=1).sum())} of {w.n}, worst {worst:.2f}, "
+              f"rel {rel_norm(got, ref):.2e}", flush=True)
+        assert bad.any(axis=1).mean() < 2e-3
+        assert rel_norm(got, ref) < 1e-3
+    print(f"[cfg1 bwd] dW rel {rel_norm(dW.cpu().numpy(), dW_ref):.2e}", flush=True)
+    assert rel_norm(dW.cpu().numpy(), dW_ref) < 1e-4
+
+
+def test_cfg2_full_size_layer_forward_and_properties():
+    c = case("cfg2")
+    w = c.w
+    X = c.x0_on_grid()
+    W = c.inp.weights[0]
+    Wd = torch.from_numpy(W).to(c.dev)
+    t = time.time()
+    Y_ref = oracle.layer_forward(c.og, c.ocfg, W, X)
+    print(f"[cfg2] oracle layer forward {time.time() - t:.1f}s", flush=True)
+    y = c.to_dev(X)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y)
+    Y = c.to_host(y)
+    frac = audit_layer_forward(c, X, Y, Y_ref, "cfg2 fwd")
+    assert frac < 5e-3
+    assert rel_norm(Y, Y_ref) < 1e-3
+
+    # bit-identical reruns, and inverse(forward(X)) returns X outside the rows a recomputed
+    # selection flipped
+    y2 = c.to_dev(X)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y2)
+    assert torch.equal(y, y2)
+    gsr.gsr_layer_inverse(c.gg, c.gcfg, Wd, y2)
+    Xr = c.to_host(y2)
+    bad, worst = violations(Xr, X, rtol=1e-4, atol=1e-4)
+    print(f"[cfg2] inverse(forward(X)): bad rows {int(bad.any(axis=1).sum())}, worst {worst:.2f}", flush=True)
+    assert bad.any(axis=1).mean() < 5e-3
+
+    # backward fused with the inverse, from the oracle's Y: the inverse recomputes GS on rebuilt
+    # activations, so a few selections flip on either side; bounded in count and in norm
+    rng = np.random.default_rng(5)
+    dY = (rng.standard_normal((w.n, w.d)) * 1e-3).astype(np.float32).astype(np.float64)
+    Xb_ref, dX_ref, dW_ref = oracle.layer_backward(c.og, c.ocfg, W, Y_ref, dY)
+    yb, dyb = c.to_dev(Y_ref), c.to_dev(dY)
+    dW = torch.empty((w.c, w.dg, w.dg), dtype=torch.float32, device=c.dev)
+    gsr.gsr_layer_backward(c.gg, c.gcfg, Wd, yb, dyb, dW)
+    for name, got, ref, frac, rel in (("X rebuilt", c.to_host(yb), Xb_ref, 5e-3, 1e-3),
+                                      ("dX", c.to_host(dyb), dX_ref, 2e-2, 1e-2)):
+        bad, worst = violations(got, ref)
+        print(f"[cfg2 bwd] {name}: bad rows {int(bad.any(axis=1).sum())} of {w.n}, rel {rel_norm(got, ref):.2e}",
+              flush=True)
+        assert bad.any(axis=1).mean() < frac, name
+        assert rel_norm(got, ref) < rel, name
+    print(f"[cfg2 bwd] dW rel {rel_norm(dW.cpu().numpy(), dW_ref):.2e}", flush=True)
+    assert rel_norm(dW.cpu().numpy(), dW_ref) < 1e-3
+
+
+def test_cfg2_full_size_step_equals_chain_of_layers():
+    c = case("cfg2")
+    w = c.w
+    L = 2
+    a = run_step(c, l=L, raw=True)
+    b = run_step(c, l=L, raw=True)
+    for key in a:
+        assert torch.equal(a[key], b[key]), key
+    x = c.to_dev(c.inp.x0)
+    Wd = torch.from_numpy(np.ascontiguousarray(c.inp.weights[:L])).to(c.dev)
+    for l in range(L):
+        gsr.gsr_layer_forward(c.gg, c.gcfg, Wd[l], x)
+    assert torch.equal(x, a["XL"])
+    yh = a["yhat"].cpu().numpy().astype(np.float32)
+    gy = (np.float32(2.0) * (yh - c.inp.target) / np.float32(w.n)).astype(np.float32)
+    dy = c.to_dev((gy[:, None] * c.inp.w_out[None, :]).astype(np.float32))
+    dW = torch.empty_like(Wd)
+    for l in reversed(range(L)):
+        gsr.gsr_layer_backward(c.gg, c.gcfg, Wd[l], x, dy, dW[l])
+    assert torch.equal(x, a["X0rec"]) and torch.equal(dW, a["dW"]) and torch.equal(dy, a["dX0"])
+    # the head against the oracle's head on the same X^L is covered at small size; here the loss
+    # only has to be finite and the rebuilt input close to X0 for all but flipped rows
+    assert np.isfinite(float(a["loss"].item()))
+    bad, worst = violations(c.to_host(a["X0rec"]), c.x0_on_grid(), rtol=1e-4, atol=1e-4)
+    print(f"[cfg2 step L={L}] X0 rebuilt: bad rows {int(bad.any(axis=1).sum())}, worst {worst:.2f}", flush=True)
+    assert bad.any(axis=1).mean() < 2e-2
+
+
+def test_cfg1_full_size_step():
+    c = case("cfg1")
+    w = c.w
+    L = 6
+    t = time.time()
+    ref = oracle.step(c.og, c.ocfg, L, c.x0_on_grid(), c.inp.weights[:L], c.inp.w_out, c.inp.b_out, c.inp.target)
+    print(f"[cfg1 step L={L}] oracle {time.time() - t:.1f}s", flush=True)
+    out = run_step(c, l=L)
+    for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+        bad, worst = violations(out[key], ref[key])
+        rows = bad.reshape(bad.shape[0], -1).any(axis=1) if bad.ndim > 1 else bad
+        print(f"[cfg1 step L={L}] {key}: rel {rel_norm(out[key], ref[key]):.2e}, bad {rows.mean():.2e}, worst {worst:.1f}",
+              flush=True)
+    assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
+    for key, rel, frac in (("yhat", 1e-3, 2e-2), ("XL", 1e-3, 2e-2), ("X0rec", 3e-2, 1e-1), ("dX0", 5e-2, 2e-1)):
+        bad, _ = violations(out[key], ref[key])
+        rows = bad.reshape(bad.shape[0], -1).any(axis=1)
+        assert rel_norm(out[key], ref[key]) < rel, key
+        assert rows.mean() < frac, key
+    assert rel_norm(out["dW"], ref["dW"]) < 2e-2
+    assert rel_norm(out["dwout"], ref["dwout"]) < 1e-3
+
+
+def test_cfg2_bf16_full_size_layer():
+    c = case("cfg2-bf16")
+    w = c.w
+    X = c.x0_on_grid()
+    W = c.inp.weights[0]
+    Y_ref = oracle.layer_forward(c.og, c.ocfg, W, X)
+    y = c.to_dev(X)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, torch.from_numpy(W).to(c.dev), y)
+    Y = c.to_host(y)
+    print(f"[cfg2 bf16] layer forward rel {rel_norm(Y, Y_ref):.2e}", flush=True)
+    assert rel_norm(Y, Y_ref) <= BF16_REL
+    # rows no bf16 rounding tie can reach agree to one bf16 ulp
+    err = np.abs(Y - Y_ref) / np.maximum(np.abs(Y_ref), 1e-3)
+    print(f"[cfg2 bf16] elements beyond 2^-7 relative: {(err > 2.0 ** -7).mean():.2e}", flush=True)
+    assert (err > 2.0 ** -7).mean() < 5e-2
