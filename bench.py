@@ -140,8 +140,9 @@ def main() -> int:
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
-        ws_n = min(w.n, 200_000)
-        sw = synth.scaled(w, ws_n, l=2) if ws_n < w.n else synth.workload(idx, l=min(w.l, 2), dtype=w.dtype)
+        # bounded sample: the first layers of the same recipe, at most 1M nodes (10-30 s of CPU work)
+        ws_n, ws_l = min(w.n, 1_000_000), min(w.l, 4 if w.c <= 4 else 2)
+        sw = synth.scaled(w, ws_n, l=ws_l) if ws_n < w.n else synth.workload(idx, l=ws_l, dtype=w.dtype)
         sinp = synth.make_inputs(sw, 0)
         og = oracle.graph_build(sinp.rowptr, sinp.colidx)
         ocfg = oracle.Cfg(sw.d, sw.c, sw.k, oracle.NORM_RMS if sw.norm == "rms" else oracle.NORM_NONE, 1e-5,
