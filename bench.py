@@ -23,6 +23,15 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
+# HBM bytes per launch read from hardware counters (two rocprofv3 --pmc passes over this script,
+# FETCH_SIZE then WRITE_SIZE, KiB per dispatch averaged over the launches of a step), each scaled
+# by what the same counter reads for the plain plane copy of known size in the same run
+# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Only the workload the passes were taken on has entries.
+MEASURED_TRAFFIC = {
+    "cfg2-1M": {"grad": 2.0 * 711.9e6 + 384.0e6, "block_forward": 2.0 * 319.5e6 + 310.0e6,
+                "block_backward": 2.0 * 395.8e6 + 318.4e6},
+}
+
 
 def algorithmic_bytes(n, nnz, dg, k, c, b, rms):
     """Bytes each kernel class must move per launch, every array touched once (neighbour gathers
@@ -132,7 +141,8 @@ def main() -> int:
         dom = max(cand, key=lambda k: cand[k]["ms_per_step"])
         achieved = ab[dom] / (cand[dom]["avg_us"] * 1e-6) / 1e9
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dom),
                     "algorithmic_bytes_per_launch": ab[dom], "avg_launch_us": cand[dom]["avg_us"]}
         for k in cand:
             kernels[k]["algorithmic_GBps"] = ab[k] / (cand[k]["avg_us"] * 1e-6) / 1e9
