@@ -164,14 +164,16 @@ def layer_inverse(g: Graph, cfg: Cfg, W, Y):
     return X
 
 
-def layer_backward(g: Graph, cfg: Cfg, W, Y, dY):
-    """Inverse interleaved with backward.  Returns (X, dX, dW[C,dg,dg])."""
+def layer_backward(g: Graph, cfg: Cfg, W, Y, dY, I_saved=None):
+    """Inverse interleaved with backward.  Returns (X, dX, dW[C,dg,dg]).  I_saved [C, n, k]
+    int32: indices kept from the forward pass, used instead of selecting again."""
     X = _f64(Y).copy()
     dX = _f64(dY).copy()
     W = _f64(W)
     dW = np.zeros((cfg.c, cfg.dg, cfg.dg), dtype=np.float64)
     lib().orc_layer_backward(C.c_int64(g.n), _p(g.rp), _p(g.ci), _p(g.av), _p(g.trp), _p(g.tci), _p(g.tav),
-                             *_cfg_args(cfg), _p(W), _p(X), _p(dX), _p(dW))
+                             *_cfg_args(cfg), _p(W), _p(X), _p(dX), _p(dW),
+                             _p(np.ascontiguousarray(I_saved, dtype=np.int32)) if I_saved is not None else None)
     return X, dX, dW
 
 
@@ -204,7 +206,8 @@ def head(X, w, b, target, sm: int = STORE_F64):
 
 def step(g: Graph, cfg: Cfg, L: int, X0, W, w_out, b_out, target, variant: int = 0,
          want=("yhat", "XL", "X0rec", "dW", "dwout", "dX0")):
-    """One training step.  variant 0: inverse interleaved with backward; 1: stored activations.
+    """One training step.  variant 0: inverse interleaved with backward; 1: stored activations;
+    2: as 0 with the indices of the forward sweep kept and reused (Section 4.2).
     Returns dict(loss, yhat, XL, X0rec, dW [L,C,dg,dg], dwout, dbout, dX0)."""
     X0 = _f64(X0)
     n, d = X0.shape

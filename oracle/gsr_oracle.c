@@ -210,6 +210,25 @@ void orc_gs(const double* Z, int64_t ldz, int64_t n, int dg, int k, int norm, do
     }
 }
 
+/* The values of GS when the indices are given (kept from an earlier application, Section 4.2):
+ * V[row][t] = Z[row][I[row][t]] (times the RMS scale of the present row), no selection. */
+void orc_gs_given(const double* Z, int64_t ldz, int64_t n, int dg, int k, int norm, double eps, int sm,
+                  const int32_t* I, double* V, double* r) {
+#pragma omp parallel for schedule(static)
+    for (int64_t row = 0; row < n; ++row) {
+        const double* z = Z + row * ldz;
+        double scale = 1.0, rr = 1.0;
+        if (norm == ORC_NORM_RMS) {
+            double ss = 0.0;
+            for (int c = 0; c < dg; ++c) ss += z[c] * z[c];
+            rr = sqrt(ss / (double)dg + eps);
+            scale = 1.0 / rr;
+        }
+        if (r) r[row] = rr;
+        for (int t = 0; t < k; ++t) V[row * k + t] = store(z[I[row * k + t]] * scale, sm);
+    }
+}
+
 /* H = A * scatter(V, I): row i gathers, from every stored neighbour j, the k values of j
  * at the columns j recorded (Section 4.1, eq. (10)). */
 void orc_aggregate(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
@@ -236,13 +255,19 @@ typedef struct {
     double eps;
 } blk_t;
 
-/* f(Z) = (A scatter(GS(Z))) W.   Z has row stride ldz.  Outputs O (n x dg, dense) and,
- * when the pointers are given, what the backward needs: I, r, H. */
+/* f(Z) = (A scatter(GS(Z))) W.   Z has row stride ldz.  Outputs O (n x dg, dense) and what
+ * the backward needs: I, r, H.  With I_given the selection is not made again: the values
+ * are taken at the given indices (and I is not written). */
 static void block_f(const blk_t* b, const double* Z, int64_t ldz, const double* W,
-                    double* O, int32_t* I, double* r, double* H) {
+                    double* O, int32_t* I, double* r, double* H, const int32_t* I_given) {
     int64_t n = b->n; int dg = b->dg, k = b->k;
     double* V = (double*)malloc((size_t)n * k * sizeof(double));
-    orc_gs(Z, ldz, n, dg, k, b->norm, b->eps, b->sm, V, I, r);
+    if (I_given) {
+        orc_gs_given(Z, ldz, n, dg, k, b->norm, b->eps, b->sm, I_given, V, r);
+        I = (int32_t*)I_given;
+    } else {
+        orc_gs(Z, ldz, n, dg, k, b->norm, b->eps, b->sm, V, I, r);
+    }
     orc_aggregate(n, b->rp, b->ci, b->av, V, I, k, dg, H);
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n; ++i) {
@@ -360,7 +385,7 @@ void orc_layer_forward(int64_t n, const int64_t* rp, const int32_t* ci, const fl
         block_f(&b, Z, ldz, W + (int64_t)(i - 1) * dg * dg, O,
                 keep_I ? keep_I + (int64_t)(i - 1) * n * k : I,
                 keep_r ? keep_r + (int64_t)(i - 1) * n : r,
-                keep_H ? keep_H + (int64_t)(i - 1) * n * dg : H);
+                keep_H ? keep_H + (int64_t)(i - 1) * n * dg : H, 0);
 #pragma omp parallel for schedule(static)
         for (int64_t row = 0; row < n; ++row)
             for (int c = 0; c < dg; ++c) {
@@ -387,7 +412,7 @@ void orc_layer_inverse(int64_t n, const int64_t* rp, const int32_t* ci, const fl
         const double* Z; int64_t ldz;
         if (i == 1) { group_sum(n, D, C, sm, Y, Y0); Z = Y0; ldz = dg; }
         else { Z = Y + (i - 2) * dg; ldz = D; }
-        block_f(&b, Z, ldz, W + (int64_t)(i - 1) * dg * dg, O, I, r, H);
+        block_f(&b, Z, ldz, W + (int64_t)(i - 1) * dg * dg, O, I, r, H, 0);
 #pragma omp parallel for schedule(static)
         for (int64_t row = 0; row < n; ++row)
             for (int c = 0; c < dg; ++c) {
@@ -400,11 +425,13 @@ void orc_layer_inverse(int64_t n, const int64_t* rp, const int32_t* ci, const fl
 
 /* Backward of one layer interleaved with its inverse (Algorithm 2's structure applied to
  * eq. (6)/(7)).  In: Y (layer output) and dY (gradient w.r.t. it), both n x D.  Out, in
- * place: X (layer input, rebuilt) and dX; dW [C][dg][dg]. */
+ * place: X (layer input, rebuilt) and dX; dW [C][dg][dg].  I_saved (or NULL): the indices
+ * [C][n][k] the forward pass of this layer selected (Section 4.2 keeps them); with them the
+ * inverse takes the values at those indices instead of selecting again. */
 void orc_layer_backward(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
                         const int64_t* trp, const int32_t* tci, const float* tav,
                         int D, int C, int k, int norm, double eps, int sm,
-                        const double* W, double* Y, double* dY, double* dW) {
+                        const double* W, double* Y, double* dY, double* dW, const int32_t* I_saved) {
     int dg = D / C;
     blk_t b = mk_blk(n, rp, ci, av, trp, tci, tav, dg, k, norm, eps, sm);
     double* Y0 = (double*)malloc((size_t)n * dg * sizeof(double));
@@ -418,7 +445,8 @@ void orc_layer_backward(int64_t n, const int64_t* rp, const int32_t* ci, const f
         if (i == 1) { group_sum(n, D, C, sm, Y, Y0); Z = Y0; ldz = dg; }
         else { Z = Y + (i - 2) * dg; ldz = D; }
         const double* Wi = W + (int64_t)(i - 1) * dg * dg;
-        block_f(&b, Z, ldz, Wi, O, I, r, H);                   /* recompute f_i(Y_{i-1}) */
+        const int32_t* Ii = I_saved ? I_saved + (int64_t)(i - 1) * n * k : I;
+        block_f(&b, Z, ldz, Wi, O, I, r, H, I_saved ? Ii : 0); /* recompute f_i(Y_{i-1}) */
 #pragma omp parallel for schedule(static)
         for (int64_t row = 0; row < n; ++row)
             for (int c = 0; c < dg; ++c) {
@@ -426,9 +454,9 @@ void orc_layer_backward(int64_t n, const int64_t* rp, const int32_t* ci, const f
                 *y = store(*y - O[row * dg + c], sm);          /* X_i rebuilt */
             }
         /* dY_i is complete here (its own slice of dY plus what block i+1 added). */
-        if (i == 1) block_backward(&b, Z, ldz, Wi, I, r, H, dY + (i - 1) * dg, D,
+        if (i == 1) block_backward(&b, Z, ldz, Wi, Ii, r, H, dY + (i - 1) * dg, D,
                                    dW + (int64_t)(i - 1) * dg * dg, dY0, dg);
-        else block_backward(&b, Z, ldz, Wi, I, r, H, dY + (i - 1) * dg, D,
+        else block_backward(&b, Z, ldz, Wi, Ii, r, H, dY + (i - 1) * dg, D,
                             dW + (int64_t)(i - 1) * dg * dg, dY + (i - 2) * dg, D);
     }
     /* dX_i = dY_i (residual path); groups 2..C also receive dY_0 (they formed Y_0). */
@@ -509,7 +537,9 @@ void orc_head(int64_t n, int D, int sm, const double* X, const double* w, double
 /* One training step over L layers (no parameter update): forward, head + loss, then the
  * backward sweep.  variant 0: inverse recomputation interleaved with backward, nothing kept
  * per layer (memory independent of L).  variant 1: every layer input stored, plain
- * back-propagation (memory grows with L; small cases only).
+ * back-propagation (memory grows with L; small cases only).  variant 2: as variant 0, but
+ * the indices every block selected in the forward sweep are kept (O(L N k), Section 4.2)
+ * and reused by the inverse instead of selecting again on the rebuilt activations.
  * Outputs (any may be NULL except loss): yhat [n], XL [n*D], X0rec [n*D] (variant 0: the
  * rebuilt input), dW [L*C*dg*dg], dwout [D], dbout [1], dX0 [n*D]. */
 int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
@@ -527,6 +557,12 @@ int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
     double* X = (double*)malloc(plane * sizeof(double));
     double* G = (double*)malloc(plane * sizeof(double));
     double* stored = variant == 1 ? (double*)malloc(plane * (size_t)L * sizeof(double)) : 0;
+    size_t per_layer_I = (size_t)C * n * k;
+    int32_t* saved_I = variant == 2 ? (int32_t*)malloc(per_layer_I * (size_t)L * sizeof(int32_t)) : 0;
+    double* tmp_r = variant == 2 ? (double*)malloc((size_t)C * n * sizeof(double)) : 0;
+    double* tmp_H = variant == 2 ? (double*)malloc((size_t)C * n * dg * sizeof(double)) : 0;
+    double* tmp_Y0 = variant == 2 ? (double*)malloc((size_t)n * dg * sizeof(double)) : 0;
+    if (variant == 2 && (!saved_I || !tmp_r || !tmp_H || !tmp_Y0)) return -1;
     double* dw_tmp = (double*)malloc((size_t)D * sizeof(double));
     double* dW_tmp = (double*)malloc((size_t)C * dg * dg * sizeof(double));
     if (!trp || !tci || !tav || !X || !G || !dw_tmp || !dW_tmp || (variant == 1 && !stored)) return -1;
@@ -534,8 +570,12 @@ int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
     for (size_t p = 0; p < plane; ++p) X[p] = store(X0[p], sm);
     for (int l = 0; l < L; ++l) {
         if (stored) memcpy(stored + plane * l, X, plane * sizeof(double));
-        orc_layer_forward(n, rp, ci, av, D, C, k, norm, eps, sm,
-                          W + (int64_t)l * C * dg * dg, X, 0, 0, 0, 0);
+        if (variant == 2)
+            orc_layer_forward(n, rp, ci, av, D, C, k, norm, eps, sm,
+                              W + (int64_t)l * C * dg * dg, X, saved_I + per_layer_I * l, tmp_r, tmp_H, tmp_Y0);
+        else
+            orc_layer_forward(n, rp, ci, av, D, C, k, norm, eps, sm,
+                              W + (int64_t)l * C * dg * dg, X, 0, 0, 0, 0);
     }
     if (XL) memcpy(XL, X, plane * sizeof(double));
     double db = 0.0;
@@ -549,12 +589,13 @@ int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
                                       Wl, stored + plane * l, G, dW_tmp);
         else
             orc_layer_backward(n, rp, ci, av, trp, tci, tav, D, C, k, norm, eps, sm,
-                               Wl, X, G, dW_tmp);
+                               Wl, X, G, dW_tmp, variant == 2 ? saved_I + per_layer_I * l : 0);
         if (dW) memcpy(dW + (int64_t)l * C * dg * dg, dW_tmp, (size_t)C * dg * dg * sizeof(double));
     }
     if (X0rec) memcpy(X0rec, variant == 1 ? stored : X, plane * sizeof(double));
     if (dX0) memcpy(dX0, G, plane * sizeof(double));
     free(trp); free(tci); free(tav); free(X); free(G); free(stored); free(dw_tmp); free(dW_tmp);
+    free(saved_I); free(tmp_r); free(tmp_H); free(tmp_Y0);
     return 0;
 }
 
