@@ -76,6 +76,12 @@ typedef struct gsr_config {
     int32_t norm;   /* gsr_norm_t */
     float eps;      /* RMS epsilon */
     int32_t layout; /* gsr_layout_t of caller-side N x D planes */
+    int32_t save_indices; /* gsr_step only.  0: GS is applied again to the rebuilt activations during
+                             the inverse and nothing is kept per layer (workspace independent of L).
+                             1: the column set every block selected in the forward sweep is kept
+                             (Section 4.2: selective save of the indices, O(L N k) bits) and reused by
+                             the inverse, which is then continuous in its input; the workspace grows
+                             by (L+1) * C * N * (D/C)/8 bytes. */
 } gsr_config_t;
 
 const char* gsr_last_error(void);
@@ -156,7 +162,7 @@ gsr_status_t gsr_spmm_compressed(const gsr_graph_t* g, const void* vals, const i
  *
  * Bytes of device workspace the layer / step calls need for (cfg, g).  gsr_step's figure
  * includes its activation and gradient arena and does not grow with cfg->l (the reversible
- * scheme's memory is independent of depth, Sections 1 and 2). */
+ * scheme's memory is independent of depth, Sections 1 and 2) unless cfg->save_indices is set. */
 gsr_status_t gsr_workspace_size(const gsr_config_t* cfg, const gsr_graph_t* g, size_t* layer_bytes,
                                 size_t* step_bytes);
 
@@ -180,7 +186,7 @@ gsr_status_t gsr_layer_backward(const gsr_graph_t* g, const gsr_config_t* cfg, c
 
 /* One training step over cfg->l layers (Algorithm 1 then Algorithm 2; no parameter update):
  * forward sweep, scalar linear head + mean-squared-error loss, backward sweep with inverse
- * recomputation.  Nothing is kept per layer.
+ * recomputation.  Nothing is kept per layer, except the column masks when cfg->save_indices is set.
  *   x0        device N x D (cfg->dtype, cfg->layout), read only
  *   w_all     device L x C x dg x dg float32
  *   w_out     device D float32;  b_out: device 1 float32;  target: device N float32

@@ -42,7 +42,8 @@ class GsrError(RuntimeError):
 
 class gsr_config_t(C.Structure):
     _fields_ = [("n", C.c_int64), ("d", C.c_int32), ("c", C.c_int32), ("l", C.c_int32), ("k", C.c_int32),
-                ("dtype", C.c_int32), ("norm", C.c_int32), ("eps", C.c_float), ("layout", C.c_int32)]
+                ("dtype", C.c_int32), ("norm", C.c_int32), ("eps", C.c_float), ("layout", C.c_int32),
+                ("save_indices", C.c_int32)]
 
 
 _lib = None
@@ -120,13 +121,15 @@ class Config:
     norm: int = GSR_NORM_NONE
     eps: float = 1e-5
     layout: int = GSR_LAYOUT_ROW_MAJOR
+    save_indices: int = 0
 
     @property
     def dg(self) -> int:
         return self.d // self.c
 
     def c_struct(self) -> gsr_config_t:
-        return gsr_config_t(self.n, self.d, self.c, self.l, self.k, self.dtype, self.norm, self.eps, self.layout)
+        return gsr_config_t(self.n, self.d, self.c, self.l, self.k, self.dtype, self.norm, self.eps, self.layout,
+                            self.save_indices)
 
 
 class Graph:

@@ -249,6 +249,9 @@ StepWs carve_step(const gsr_config_t* cfg, const gsr_graph_t* g) {
     off += align_up((size_t)g->grid * ((size_t)cfg->d + 2) * sizeof(float));
     w.layer = off;
     off += carve_layer(cfg, g).total;
+    w.masks = off;
+    if (cfg->save_indices)
+        off += align_up(((size_t)(cfg->l > 0 ? cfg->l : 0) + 1) * (size_t)cfg->c * n * (size_t)(cfg->d / cfg->c / 8));
     w.total = off;
     return w;
 }
@@ -270,6 +273,7 @@ gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool
         return fail(GSR_ERR_UNSUPPORTED, "n * k = %llu does not fit 32-bit record offsets", (unsigned long long)cfg->n * cfg->k);
     if (need_l && cfg->l < 1) return fail(GSR_ERR_INVALID_ARG, "layers L=%d", cfg->l);
     if (!(cfg->eps >= 0.f)) return fail(GSR_ERR_INVALID_ARG, "eps must be >= 0");
+    if (cfg->save_indices != 0 && cfg->save_indices != 1) return fail(GSR_ERR_INVALID_ARG, "save_indices must be 0 or 1");
     return GSR_OK;
 }
 

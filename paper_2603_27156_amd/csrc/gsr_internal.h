@@ -112,6 +112,7 @@ struct StepWs {
     size_t grad;  // [C][n][dg] of T
     size_t head;  // [grid][D + 2] float
     size_t layer; // LayerWs starts here
+    size_t masks; // [L+1][C][n] column masks kept from the forward sweep (cfg->save_indices), else unused
     size_t total;
 };
 LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g);

@@ -30,28 +30,12 @@ struct Record {
     M* mask;        // [n]
 };
 
-// GS of the 16 rows of an LDS tile and their records (Section 4.1; record layout of Section 4.3).
-// st holds the rows as they read back from memory (16 x (DG+1) floats, rows past the end zero).
-// Lane (r, q) takes the quarter q of row r into registers, so the 16 searches for the k-th largest
-// key run side by side in vector registers: interval bisection on an order-preserving integer
-// image of the values, count = own compares + the three partner quarters.  Invariant per row: at
-// least k keys are >= lo and fewer than k are >= hi; hi starts just above the row maximum, lo four
-// binades below it (0 when a count says that is too high).  A row closes when a candidate splits
-// off exactly k keys or the interval is down to one value (a tie at the k-th position); ties go
-// to the lowest columns, -0 equals +0.  The kept values (RMS-scaled) are compacted in LDS in
-// column order and leave as one contiguous block, since rows r0..r0+15 are adjacent in [n][k].
-// st is overwritten.
-template <int DG, typename T>
-__device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int norm, float eps, const Record<DG, T>& out,
-                                          int lane) {
-    using M = typename MaskOf<DG>::type;
-    constexpr int QW = DG / 4, LR = DG + 1;
-    constexpr int KS = sizeof(T) == 2 ? 16 : 0;   // bf16 values: the low 16 key bits are zero
-    const int r = lane & 15, q = lane >> 4;
-    float x[QW];
+// Bits of the quarter's columns that belong to the row's k largest entries (x: the quarter's QW
+// values; valid: the row exists; q: the quarter).  All four lanes of a row must call it together.
+template <int DG, int KS>
+__device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int k, bool valid, int q) {
+    constexpr int QW = DG / 4;
     uint32_t key[QW];
-#pragma unroll
-    for (int j = 0; j < QW; ++j) x[j] = st[r * LR + q * QW + j];
     uint32_t top = 0u;
 #pragma unroll
     for (int j = 0; j < QW; ++j) {
@@ -74,7 +58,7 @@ __device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int n
     {
         const uint32_t cnt = count_ge(lo);
         lo = (cnt >= uk && k < DG) ? lo : 0u;
-        uint32_t open = (cnt != uk && k < DG && r0 + r < n) ? 1u : 0u;
+        uint32_t open = (cnt != uk && k < DG && valid) ? 1u : 0u;
         for (int round = 0; round < 33 && ballot(open != 0u) != 0ull; ++round) {
             const uint32_t mid = lo + ((hi - lo) >> 1);
             const uint32_t c2 = count_ge(mid);
@@ -112,6 +96,39 @@ __device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int n
             }
         }
     }
+    return msel;
+}
+
+// GS of the 16 rows of an LDS tile and their records (Section 4.1; record layout of Section 4.3).
+// st holds the rows as they read back from memory (16 x (DG+1) floats, rows past the end zero).
+// Lane (r, q) takes the quarter q of row r into registers, so the 16 searches for the k-th largest
+// key run side by side in vector registers: interval bisection on an order-preserving integer
+// image of the values, count = own compares + the three partner quarters.  Invariant per row: at
+// least k keys are >= lo and fewer than k are >= hi; hi starts just above the row maximum, lo four
+// binades below it (0 when a count says that is too high).  A row closes when a candidate splits
+// off exactly k keys or the interval is down to one value (a tie at the k-th position); ties go
+// to the lowest columns, -0 equals +0.  The kept values (RMS-scaled) are compacted in LDS in
+// column order and leave as one contiguous block, since rows r0..r0+15 are adjacent in [n][k].
+// With `given` the column set is not searched for: out.mask already holds the set an earlier
+// application selected (Section 4.2 keeps the indices of the forward pass) and only the values
+// are taken, from the present rows.  st is overwritten.
+template <int DG, typename T>
+__device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int norm, float eps, const Record<DG, T>& out,
+                                          bool given, int lane) {
+    using M = typename MaskOf<DG>::type;
+    constexpr int QW = DG / 4, LR = DG + 1;
+    constexpr int KS = sizeof(T) == 2 ? 16 : 0;   // bf16 values: the low 16 key bits are zero
+    const int r = lane & 15, q = lane >> 4;
+    float x[QW];
+#pragma unroll
+    for (int j = 0; j < QW; ++j) x[j] = st[r * LR + q * QW + j];
+    uint32_t msel;
+    if (given) {
+        const M m = out.mask[r0 + r < n ? r0 + r : n - 1];
+        msel = (uint32_t)(m >> (QW * q)) & ((1u << QW) - 1u);
+    } else {
+        msel = select_quarter<DG, KS>(x, k, r0 + r < n, q);
+    }
     uint32_t all[4];
     quarter_all(msel | (uint32_t)__popc(msel) << 16, all);
     int slot = r * k;
@@ -141,7 +158,7 @@ __device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int n
     const int rows = min(16, n - r0), total = rows * k;
     T* dst = out.vals + (size_t)r0 * k;
     for (int i = lane; i < total; i += 64) dst[i] = from_float<T>(st[i]);
-    if (q == 0 && r < rows) out.mask[r0 + r] = mask;
+    if (!given && q == 0 && r < rows) out.mask[r0 + r] = mask;
 }
 
 // per-wave LDS: tile(s) of 16 x (DG+1) floats, 64 staged edges, 17 row pointers
@@ -165,6 +182,7 @@ struct BlockArgs {
     T* plane;               // X_i on entry / Y_i on return (or the reverse), row stride ld
     int64_t ld;
     Record<DG, T> out;      // record of the row written (out.mask == NULL: none)
+    bool out_given;         // out.mask holds the column sets to use (kept from the forward sweep)
     int norm;
     float eps;
     const T* dy;            // dY_i, row stride ldg            (WITH_DW)
@@ -236,7 +254,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         }
         if (a.out.mask) {
             wave_sync();
-            emit_tile<DG, T>(st_h, r0, a.n, a.k, a.norm, a.eps, a.out, lane);
+            emit_tile<DG, T>(st_h, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane);
         }
     }
     if constexpr (WITH_DW) {
@@ -398,6 +416,7 @@ struct SumArgs {
     int k, norm;
     float eps;
     Record<DG, T> out;
+    bool out_given;         // out.mask holds the column sets to use
 };
 
 template <int DG, typename T>
@@ -434,7 +453,7 @@ __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
             st[r * LR + c] = row < a.n ? to_float(yt) : 0.f;
         }
         wave_sync();
-        emit_tile<DG, T>(st, r0, a.n, a.k, a.norm, a.eps, a.out, lane);
+        emit_tile<DG, T>(st, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane);
     }
 }
 
@@ -554,11 +573,14 @@ struct Ctx {
     char* ws;
     LayerWs lw;
     int tiles;
-    Record<DG, T> rec(int slot) const {
+    M* saved;       // [L+1][C][n] column masks kept from the forward sweep, or NULL
+    // Record slot `slot` of layer `layer`: the values always live in the slot (they are rebuilt),
+    // the mask in the slot, or in the kept store when indices are saved.
+    Record<DG, T> rec(int slot, int layer = 0) const {
         Record<DG, T> r;
         if (slot < 0) { r.vals = nullptr; r.mask = nullptr; return r; }
         r.vals = (T*)(ws + lw.rec_vals[slot]);
-        r.mask = (M*)(ws + lw.rec_mask[slot]);
+        r.mask = saved ? saved + ((size_t)layer * cfg->c + slot) * (size_t)cfg->n : (M*)(ws + lw.rec_mask[slot]);
         return r;
     }
     int kpl() const {
@@ -587,24 +609,25 @@ static unsigned persistent_grid(const gsr_graph_t* g, int per_cu) {
 }
 
 template <int DG, typename T>
-static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0, int slot) {
+static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0,
+                       const Record<DG, T>& out, bool out_given = false) {
     SumArgs<DG, T> a;
     a.n = (int)x.cfg->n; a.src = src; a.ld = ld; a.src_gs = gs; a.nsrc = nsrc; a.y0 = y0;
     a.k = x.cfg->k; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
-    a.out = x.rec(slot);
+    a.out = out; a.out_given = out_given;
     ProfScope prof(KC_SUM, x.s);
     hipLaunchKernelGGL((k_sum<DG, T>), dim3((unsigned)x.g->grid * 2), dim3(256), 0, x.s, a);
 }
 
 template <int DG, typename T>
-static void launch_hub_records(const Ctx<DG, T>& x, int slot) {
+static void launch_hub_records(const Ctx<DG, T>& x, const Record<DG, T>& in) {
     const HubPlan& h = x.g->a.hub;
     if (h.n_chunks == 0) return;
     HubChunks hc{h.ce0, h.ce1, h.n_chunks};
     ProfScope prof(KC_HUB, x.s);
     hipLaunchKernelGGL((k_hub_records<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
-                       make_view(x.g, false), hc, (const T*)x.rec(slot).vals,
-                       (const typename MaskOf<DG>::type*)x.rec(slot).mask, x.cfg->k, x.hub_part());
+                       make_view(x.g, false), hc, (const T*)in.vals, (const typename MaskOf<DG>::type*)in.mask, x.cfg->k,
+                       x.hub_part());
 }
 
 template <int DG, typename T>
@@ -619,15 +642,15 @@ static void launch_hub_dense(const Ctx<DG, T>& x, const T* plane, int64_t ld) {
 
 // mode 0: forward (+), 1: inverse (-), 2: inverse (-) with dW
 template <int DG, typename T>
-static unsigned launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const float* w, T* plane, int64_t ld, int out_slot,
-                         const T* dy, int64_t ldg) {
-    launch_hub_records<DG, T>(x, in_slot);
+static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>& in, const float* w, T* plane, int64_t ld,
+                             const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg) {
+    launch_hub_records<DG, T>(x, in);
     BlockArgs<DG, T> a;
     a.g = make_view(x.g, false);
     a.n = (int)x.cfg->n; a.tiles = x.tiles;
-    a.in = x.rec(in_slot); a.k = x.cfg->k;
+    a.in = in; a.k = x.cfg->k;
     a.hub_part = x.hub_part(); a.w = w; a.plane = plane; a.ld = ld;
-    a.out = x.rec(out_slot);
+    a.out = out; a.out_given = out_given;
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
     const dim3 block(256);
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
@@ -649,28 +672,30 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, int in_slot, const f
 }
 
 template <int DG, typename T>
-static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const float* w, int mask_slot, const T* z,
+static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const float* w,
+                        const typename MaskOf<DG>::type* own_mask, const T* z,
                         int64_t ldz, T* dst, int64_t ldd, int64_t dst_gs, int ndst) {
     launch_hub_dense<DG, T>(x, dy, ldg);
     GradArgs<DG, T> a;
     a.gt = make_view(x.g, true);
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
-    a.own_mask = x.rec(mask_slot).mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
+    a.own_mask = own_mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
     ProfScope prof(KC_GRAD, x.s);
     static const int per_cu = resident_blocks((const void*)k_grad<DG, T>);
     hipLaunchKernelGGL((k_grad<DG, T>), dim3(persistent_grid(x.g, per_cu)), dim3(256), 0, x.s, a);
 }
 
-// eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of
-// the previous layer's Y_2, emitted when that plane was written).
+// eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of the
+// previous layer's Y_2, emitted when that plane was written).  `layer`: index of the layer inside
+// a step (selects the kept masks when indices are saved; 0 otherwise).
 template <int DG, typename T>
-static void layer_forward_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& p, bool slot0_ready) {
+static void layer_forward_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& p, bool slot0_ready, int layer = 0) {
     const int C = x.cfg->c;
-    if (!slot0_ready) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, 0);
+    if (!slot0_ready) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, x.rec(0, layer));
     for (int i = 1; i <= C; ++i) {
-        const int out_slot = i < C ? i : (C == 2 ? 0 : -1);
-        launch_block<DG, T>(x, 0, i - 1, w + (size_t)(i - 1) * DG * DG, p.grp(i - 1), p.ld, out_slot, nullptr, 0);
+        const Record<DG, T> out = i < C ? x.rec(i, layer) : (C == 2 ? x.rec(0, layer + 1) : x.rec(-1));
+        launch_block<DG, T>(x, 0, x.rec(i - 1, layer), w + (size_t)(i - 1) * DG * DG, p.grp(i - 1), p.ld, out, false, nullptr, 0);
     }
 }
 
@@ -678,23 +703,27 @@ static void layer_forward_impl(const Ctx<DG, T>& x, const float* w, const Planes
 template <int DG, typename T>
 static void layer_inverse_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& p) {
     const int C = x.cfg->c;
-    for (int i = 1; i < C; ++i) launch_sum<DG, T>(x, p.grp(i - 1), p.ld, p.gs, 1, nullptr, i);
+    for (int i = 1; i < C; ++i) launch_sum<DG, T>(x, p.grp(i - 1), p.ld, p.gs, 1, nullptr, x.rec(i));
     for (int i = C; i >= 1; --i) {
-        if (i == 1 && C > 2) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, 0);
-        const int out_slot = (i == 2 && C == 2) ? 0 : -1;
-        launch_block<DG, T>(x, 1, i - 1, w + (size_t)(i - 1) * DG * DG, p.grp(i - 1), p.ld, out_slot, nullptr, 0);
+        if (i == 1 && C > 2) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, x.rec(0));
+        const Record<DG, T> out = (i == 2 && C == 2) ? x.rec(0) : x.rec(-1);
+        launch_block<DG, T>(x, 1, x.rec(i - 1), w + (size_t)(i - 1) * DG * DG, p.grp(i - 1), p.ld, out, false, nullptr, 0);
     }
 }
 
 // Backward fused with the inverse.  slots_ready: slots 1..C-1 already hold the records of
 // Y_1..Y_{C-1} of this layer (left by the forward sweep, or by the layer above while it rebuilt
-// its input).  On return slots 1..C-1 hold the records of X_1..X_{C-1}, i.e. of the layer below.
+// its input).  On return slots 1..C-1 hold the records of X_1..X_{C-1}, i.e. of the layer below
+// (not written for the lowest layer of a step, `layer` = 0 with `in_step`).  When indices are
+// saved, every record written here takes its column set from the kept masks of the layer it
+// belongs to instead of selecting again.
 template <int DG, typename T>
 static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& y, const Planes<T>& dy, float* dw_out,
-                                bool slots_ready) {
+                                bool slots_ready, int layer = 0, bool in_step = false) {
     const int C = x.cfg->c;
+    const bool given = x.saved != nullptr;
     if (!slots_ready)
-        for (int i = 1; i < C; ++i) launch_sum<DG, T>(x, y.grp(i - 1), y.ld, y.gs, 1, nullptr, i);
+        for (int i = 1; i < C; ++i) launch_sum<DG, T>(x, y.grp(i - 1), y.ld, y.gs, 1, nullptr, x.rec(i, layer), given);
     for (int i = C; i >= 1; --i) {
         const float* wi = w + (size_t)(i - 1) * DG * DG;
         const T* z;      // rows of Y_{i-1}
@@ -702,18 +731,25 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         if (i >= 2) { z = y.grp(i - 2); ldz = y.ld; }
         else if (C == 2) { z = y.grp(1); ldz = y.ld; }      // Y_0 = X_2, rebuilt just before
         else {
-            launch_sum<DG, T>(x, y.grp(1), y.ld, y.gs, C - 1, x.y0(), 0);
+            launch_sum<DG, T>(x, y.grp(1), y.ld, y.gs, C - 1, x.y0(), x.rec(0, layer), given);
             z = x.y0(); ldz = DG;
         }
-        const int out_slot = i < C ? i : (C == 2 ? 0 : -1);
-        const unsigned nparts = launch_block<DG, T>(x, 2, i - 1, wi, y.grp(i - 1), y.ld, out_slot, dy.grp(i - 1), dy.ld);
+        Record<DG, T> out = x.rec(-1);
+        if (i < C) {
+            if (!(in_step && layer == 0)) out = x.rec(i, given ? layer - 1 : 0);      // record of Y_i of the layer below
+        } else if (C == 2) {
+            out = x.rec(0, layer);                                                     // X_2 = Y_0 of this layer
+        }
+        const unsigned nparts =
+            launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld);
         {
             ProfScope prof(KC_DW_REDUCE, x.s);
             hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 63) / 64), dim3(1024), 0, x.s, (const float*)x.dw_partial(),
                                (int)nparts, DG * DG, dw_out + (size_t)(i - 1) * DG * DG);
         }
-        if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, i - 1, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1);
-        else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, 0, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1);
+        const typename MaskOf<DG>::type* own = x.rec(i - 1, layer).mask;
+        if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, own, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1);
+        else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, own, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1);
     }
 }
 
@@ -722,6 +758,7 @@ static Ctx<DG, T> make_ctx(const gsr_graph_t* g, const gsr_config_t* cfg, void* 
     Ctx<DG, T> x;
     x.g = g; x.cfg = cfg; x.s = s; x.ws = (char*)ws; x.lw = carve_layer(cfg, g);
     x.tiles = (int)((cfg->n + 15) / 16);
+    x.saved = nullptr;
     return x;
 }
 
@@ -765,6 +802,7 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
     const StepWs sw = carve_step(cfg, g);
     char* base = (char*)ws;
     Ctx<DG, T> x = make_ctx<DG, T>(g, cfg, base + sw.layer, s);
+    if (cfg->save_indices) x.saved = (typename MaskOf<DG>::type*)(base + sw.masks);
     const int C = cfg->c, L = cfg->l;
     const int64_t n = cfg->n;
     const Planes<T> act{(T*)(base + sw.act), (int64_t)DG, n * DG};
@@ -778,7 +816,7 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
     };
     copy(in, act);
     const size_t wl = (size_t)C * DG * DG;
-    for (int l = 0; l < L; ++l) layer_forward_impl<DG, T>(x, w_all + l * wl, act, C == 2 && l > 0);
+    for (int l = 0; l < L; ++l) layer_forward_impl<DG, T>(x, w_all + l * wl, act, C == 2 && l > 0, l);
     if (xl_out) copy(act, caller_planes<T>(xl_out, cfg));
     HeadArgs<T> h;
     h.n = (int)n; h.d = cfg->d; h.dg = DG; h.act = act.base; h.grad = grad.base; h.ld = act.ld; h.gs = act.gs;
@@ -789,7 +827,7 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
         hipLaunchKernelGGL(k_head_reduce, dim3((cfg->d + 2 + 255) / 256), dim3(256), 0, s, (const float*)h.partial, g->grid,
                            cfg->d, (int)n, dw_out, db_out, loss_out);
     }
-    for (int l = L - 1; l >= 0; --l) layer_backward_impl<DG, T>(x, w_all + l * wl, act, grad, dw_all + l * wl, true);
+    for (int l = L - 1; l >= 0; --l) layer_backward_impl<DG, T>(x, w_all + l * wl, act, grad, dw_all + l * wl, true, l, true);
     if (dx0_out) copy(grad, caller_planes<T>(dx0_out, cfg));
     if (x0_rebuilt_out) copy(act, caller_planes<T>(x0_rebuilt_out, cfg));
     GSR_HIP_CHECK(hipGetLastError());
