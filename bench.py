@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the GSR-GNN training step (forward + inverse recomputation + backward) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg2-bf16] [--layers L]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg2-bf16|cfg4] [--layers L] [--save-indices]
 
 A "step" is one gsr_step call: L grouped reversible layers forward, head + loss, and the backward
 sweep that rebuilds every layer input instead of storing it.  Inputs are synthetic (seeded circuit
@@ -58,6 +58,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override L")
     ap.add_argument("--max-workgroups", type=int, default=0, help="override the persistent grid (multiple of 8)")
+    ap.add_argument("--save-indices", action="store_true",
+                    help="keep the forward sweep's column masks for the inverse (memory grows with L)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events in the timed region")
     args = ap.parse_args()
@@ -94,7 +96,7 @@ def main() -> int:
     tdt = torch.bfloat16 if bf16 else torch.float32
     cfg = gsr.Config(n=w.n, d=w.d, c=w.c, k=w.k, l=w.l, dtype=gsr.GSR_BF16 if bf16 else gsr.GSR_F32,
                      norm=gsr.GSR_NORM_RMS if w.norm == "rms" else gsr.GSR_NORM_NONE, eps=1e-5,
-                     layout=gsr.GSR_LAYOUT_GROUP_PLANAR)
+                     layout=gsr.GSR_LAYOUT_GROUP_PLANAR, save_indices=1 if args.save_indices else 0)
     f32 = dict(dtype=torch.float32, device=dev)
     x0 = torch.from_numpy(inp.x0).to(dev).to(tdt).view(w.n, w.c, w.dg).permute(1, 0, 2).contiguous()
     W = torch.from_numpy(inp.weights).to(dev)
@@ -158,7 +160,8 @@ def main() -> int:
         ocfg = oracle.Cfg(sw.d, sw.c, sw.k, oracle.NORM_RMS if sw.norm == "rms" else oracle.NORM_NONE, 1e-5,
                           oracle.STORE_BF16 if bf16 else oracle.STORE_F32)
         tc = time.perf_counter()
-        oracle.step(og, ocfg, sw.l, sinp.x0, sinp.weights, sinp.w_out, 0.0, sinp.target, want=())
+        oracle.step(og, ocfg, sw.l, sinp.x0, sinp.weights, sinp.w_out, 0.0, sinp.target,
+                    variant=2 if args.save_indices else 0, want=())
         tc = time.perf_counter() - tc
         cpu_baseline = {"value": sw.n * sw.l / tc, "unit": "node-layers/s", "cores": oracle.num_threads(),
                         "kind": "oracle", "seconds": tc,
@@ -170,7 +173,8 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16-storage/f32-accumulate" if bf16 else "f32",
         "data": "synthetic",
         "config": {"workload": w.name, "n": w.n, "nnz": info["nnz"], "max_degree": info["max_degree"], "d": w.d,
-                   "c": w.c, "k": w.k, "l": w.l, "norm": w.norm, "hub_rows": info["n_hub_rows"]},
+                   "c": w.c, "k": w.k, "l": w.l, "norm": w.norm, "hub_rows": info["n_hub_rows"],
+                   "save_indices": bool(args.save_indices)},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
         "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()), "workspace_bytes": int(ws_bytes),
         "loss": float(loss.item()), "x0_rebuild_max_abs_err": rebuilt_err, "setup_seconds": t_gen,
