@@ -33,6 +33,18 @@ __device__ __forceinline__ bf16_t from_float<bf16_t>(float v) {
     return r;
 }
 
+// Streaming accesses: data touched once per kernel (activation and gradient planes) is loaded and
+// stored with the non-temporal hint, so that it does not push the neighbour records and gradient
+// rows that many tiles gather out of the caches.
+__device__ __forceinline__ float load_stream(const float* p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ bf16_t load_stream(const bf16_t* p) {
+    bf16_t r;
+    r.bits = __builtin_nontemporal_load(&p->bits);
+    return r;
+}
+__device__ __forceinline__ void store_stream(float* p, float v) { __builtin_nontemporal_store(v, p); }
+__device__ __forceinline__ void store_stream(bf16_t* p, bf16_t v) { __builtin_nontemporal_store(v.bits, &p->bits); }
+
 // value as it will read back after a store of type T
 template <typename T>
 __device__ __forceinline__ float stored(float v) { return to_float(from_float<T>(v)); }
@@ -420,9 +432,10 @@ __device__ __forceinline__ int tile_row_of(const int* s_rp, int e) {
     return r;
 }
 
-// Runs `batch(GB, i0)` over the nit <= 16 groups of four staged edges: all sixteen at once if
-// MAXB allows, else eight at a time while they last, then four at a time (a batch may overrun
-// nit by up to three groups, which stay inside the 64 staged edges and contribute zero).
+// Runs `batch(GB, i0)` over the nit <= 16 groups of four staged edges in as few batches as
+// possible: all sixteen at once if MAXB allows, else eight, then the rest as one batch of eight
+// or four (a batch may overrun nit by up to three groups, which stay inside the 64 staged edges
+// and contribute zero).
 template <int MAXB, typename Batch>
 __device__ __forceinline__ void edge_batches(int nit, Batch batch) {
     int i0 = 0;
@@ -432,8 +445,12 @@ __device__ __forceinline__ void edge_batches(int nit, Batch batch) {
             return;
         }
     }
-    for (; i0 + 8 <= nit; i0 += 8) batch(std::integral_constant<int, 8>{}, i0);
-    for (; i0 < nit; i0 += 4) batch(std::integral_constant<int, 4>{}, i0);
+    if (nit > 8) {
+        batch(std::integral_constant<int, 8>{}, 0);
+        i0 = 8;
+    }
+    if (nit - i0 > 4) batch(std::integral_constant<int, 8>{}, i0);
+    else if (nit - i0 > 0) batch(std::integral_constant<int, 4>{}, i0);
 }
 
 // acc += P * X over the edges [e_a, e_b) of ordinary rows; X is a dense plane, row stride ld.
@@ -448,8 +465,8 @@ __device__ __forceinline__ void gather_dense_mfma(const CsrView& g, const T* __r
         const int e = eb + lane;
         const bool ok = e < e_b;
         EdgeRec me;
-        me.j = ok ? g.ci[e] : 0;
-        me.a = ok ? g.av[e] : 0.f;
+        me.j = ok ? __builtin_nontemporal_load(g.ci + e) : 0;
+        me.a = ok ? __builtin_nontemporal_load(g.av + e) : 0.f;
         me.r = tile_row_of(s_rp, e);
         me.pad = 0;
         wave_sync();          // readers of the previous chunk are done
@@ -507,9 +524,9 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
     for (int eb = e_a; eb < e_b; eb += 64) {
         const int e = eb + lane;
         const bool ok = e < e_b;
-        const int j = ok ? g.ci[e] : 0;
+        const int j = ok ? __builtin_nontemporal_load(g.ci + e) : 0;
         RecEdge me;
-        me.a = ok ? g.av[e] : 0.f;
+        me.a = ok ? __builtin_nontemporal_load(g.av + e) : 0.f;
         me.off0 = (uint32_t)j * (uint32_t)k;
         const M m = masks[j];
         me.mlo = (uint32_t)m;

@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
 #pragma unroll
             for (int it = 0; it < RPW; ++it) {
                 const int row = r0 + it * G + sub;
-                const float g = to_float(a.dy[(size_t)(row < a.n ? row : a.n - 1) * a.ldg + c]);
+                const float g = to_float(load_stream(a.dy + (size_t)(row < a.n ? row : a.n - 1) * a.ldg + c));
                 gy[it] = row < a.n ? g : 0.f;
             }
 #pragma unroll
@@ -242,14 +242,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
 #pragma unroll
         for (int it = 0; it < RPW; ++it) {
             const int row = r0 + it * G + sub;
-            xv[it] = to_float(a.plane[(size_t)(row < a.n ? row : a.n - 1) * a.ld + c]);
+            xv[it] = to_float(load_stream(a.plane + (size_t)(row < a.n ? row : a.n - 1) * a.ld + c));
         }
 #pragma unroll
         for (int it = 0; it < RPW; ++it) {
             const int r = it * G + sub, row = r0 + r;
             const float o = st_h[r * LR + c];
             const T yt = from_float<T>(SIGN > 0 ? xv[it] + o : xv[it] - o);
-            if (row < a.n) a.plane[(size_t)row * a.ld + c] = yt;
+            if (row < a.n) store_stream(a.plane + (size_t)row * a.ld + c, yt);
             st_h[r * LR + c] = row < a.n ? to_float(yt) : 0.f;
         }
         if (a.out.mask) {
@@ -321,10 +321,15 @@ struct GradArgs {
     int ndst;
 };
 
+// Waves per workgroup of k_grad (they share one copy of W^T in LDS).  Measured at 1M rows, Dg = 64:
+// 4 and 8 waves (16 resident waves per compute unit either way) take the same time; 6 and 10
+// waves, which would allow 18 and 20 resident waves, are 20 % and 10 % slower.
+constexpr int GRAD_WAVES = 4;
+
 template <int DG, typename T>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
+__global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
     constexpr int G = 64 / DG, LR = DG + 1, RPW = 16 / G;
-    __shared__ WaveLds<DG, 1> lds[4];
+    __shared__ WaveLds<DG, 1> lds[GRAD_WAVES];
     const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
     WaveLds<DG, 1>& L = lds[wave];
     float* st = L.st[0];
@@ -361,7 +366,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
                 const bool ok = row < a.n;
                 const int rowc = ok ? row : a.n - 1;
                 sel[u] = ok && ((a.own_mask[rowc] >> c) & 1);
-                const float zv = a.norm == GSR_NORM_RMS ? to_float(a.z[(size_t)rowc * a.ldz + c]) : 0.f;
+                const float zv = a.norm == GSR_NORM_RMS ? to_float(load_stream(a.z + (size_t)rowc * a.ldz + c)) : 0.f;
                 zz[u] = ok ? zv : 0.f;
             }
             float dzv[HB];
@@ -393,12 +398,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
 #pragma unroll
                 for (int u = 0; u < HB; ++u) {
                     const int row = r0 + (h0 + u) * G + sub;
-                    old[u] = to_float(plane[(size_t)(row < a.n ? row : a.n - 1) * a.ldd + c]);
+                    old[u] = to_float(load_stream(plane + (size_t)(row < a.n ? row : a.n - 1) * a.ldd + c));
                 }
 #pragma unroll
                 for (int u = 0; u < HB; ++u) {
                     const int row = r0 + (h0 + u) * G + sub;
-                    if (touch[u]) plane[(size_t)row * a.ldd + c] = from_float<T>(old[u] + dzv[u]);
+                    if (touch[u]) store_stream(plane + (size_t)row * a.ldd + c, from_float<T>(old[u] + dzv[u]));
                 }
             }
         }
@@ -432,14 +437,14 @@ __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
 #pragma unroll
         for (int it = 0; it < RPW; ++it) {
             const int row = r0 + it * G + sub;
-            s[it] = to_float(a.src[(size_t)(row < a.n ? row : a.n - 1) * a.ld + c]);
+            s[it] = to_float(load_stream(a.src + (size_t)(row < a.n ? row : a.n - 1) * a.ld + c));
         }
         for (int j = 1; j < a.nsrc; ++j) {
             float v[RPW];
 #pragma unroll
             for (int it = 0; it < RPW; ++it) {
                 const int row = r0 + it * G + sub;
-                v[it] = to_float(a.src[(size_t)j * a.src_gs + (size_t)(row < a.n ? row : a.n - 1) * a.ld + c]);
+                v[it] = to_float(load_stream(a.src + (size_t)j * a.src_gs + (size_t)(row < a.n ? row : a.n - 1) * a.ld + c));
             }
 #pragma unroll
             for (int it = 0; it < RPW; ++it) s[it] += v[it];
@@ -449,7 +454,7 @@ __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
         for (int it = 0; it < RPW; ++it) {
             const int r = it * G + sub, row = r0 + r;
             const T yt = from_float<T>(s[it]);
-            if (row < a.n && a.y0) a.y0[(size_t)row * DG + c] = yt;
+            if (row < a.n && a.y0) store_stream(a.y0 + (size_t)row * DG + c, yt);
             st[r * LR + c] = row < a.n ? to_float(yt) : 0.f;
         }
         wave_sync();
@@ -596,9 +601,9 @@ struct Ctx {
 // Workgroups of 256 threads one CU keeps resident for a kernel, and the persistent grid that
 // fills the chip with them: a multiple of 8 (one share per XCD), never above g->grid, which
 // sizes the per-workgroup partial buffers.
-static int resident_blocks(const void* kernel) {
+static int resident_blocks(const void* kernel, int threads = 256) {
     int nb = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, 256, 0) != hipSuccess || nb < 1) nb = 1;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kernel, threads, 0) != hipSuccess || nb < 1) nb = 1;
     return nb;
 }
 static unsigned persistent_grid(const gsr_graph_t* g, int per_cu) {
@@ -682,8 +687,8 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     a.own_mask = own_mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
     ProfScope prof(KC_GRAD, x.s);
-    static const int per_cu = resident_blocks((const void*)k_grad<DG, T>);
-    hipLaunchKernelGGL((k_grad<DG, T>), dim3(persistent_grid(x.g, per_cu)), dim3(256), 0, x.s, a);
+    static const int per_cu = resident_blocks((const void*)k_grad<DG, T>, 64 * GRAD_WAVES);
+    hipLaunchKernelGGL((k_grad<DG, T>), dim3(persistent_grid(x.g, per_cu)), dim3(64 * GRAD_WAVES), 0, x.s, a);
 }
 
 // eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of the
