@@ -402,6 +402,62 @@ __device__ __forceinline__ void load_words(const void* p, uint32_t (&w)[NW]) {
     }
 }
 
+// ---- tile register layout ---------------------------------------------------------------------------
+// What the MFMA leaves in a wave's accumulators for a 16 x DG tile when the A operand takes tile
+// row 4 (i % 4) + i / 4 as its row i and the B operand takes column CPL j + cb as column j of
+// block cb (CPL = DG / 16): lane (g = lane / 16, j = lane % 16) holds, in acc[cb][reg],
+//     tile row 4 reg + g,  column CPL j + cb.
+// For a fixed reg the 16 lanes of a group cover one whole row with CPL adjacent elements each, so
+// a row moves between registers and memory with one fully coalesced access of CPL elements per
+// lane, four rows per instruction.  Sums over a row are sums over the 16 lanes of a group.
+template <int CPL, typename T>
+__device__ __forceinline__ void load_cols(const T* p, float (&v)[CPL]) {       // non-temporal
+    constexpr int NW = CPL * (int)sizeof(T) / 4;
+    uint32_t w[NW];
+    if constexpr (NW == 1) {
+        w[0] = __builtin_nontemporal_load(reinterpret_cast<const uint32_t*>(p));
+    } else if constexpr (NW == 2) {
+        const u32x2a t = __builtin_nontemporal_load(reinterpret_cast<const u32x2a*>(p));
+        w[0] = t[0]; w[1] = t[1];
+    } else {
+        const u32x4a t = __builtin_nontemporal_load(reinterpret_cast<const u32x4a*>(p));
+        w[0] = t[0]; w[1] = t[1]; w[2] = t[2]; w[3] = t[3];
+    }
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        if constexpr (sizeof(T) == 4) v[c] = __uint_as_float(w[c]);
+        else v[c] = __uint_as_float((c & 1) ? (w[c >> 1] & 0xFFFF0000u) : (w[c >> 1] << 16));
+    }
+}
+// v must hold values representable in T (as stored<T>() returns them)
+template <int CPL, typename T>
+__device__ __forceinline__ void store_cols(T* p, const float (&v)[CPL]) {      // non-temporal
+    constexpr int NW = CPL * (int)sizeof(T) / 4;
+    uint32_t w[NW];
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        if constexpr (sizeof(T) == 4) w[i] = __float_as_uint(v[i]);
+        else w[i] = (__float_as_uint(v[2 * i]) >> 16) | (__float_as_uint(v[2 * i + 1]) & 0xFFFF0000u);
+    }
+    if constexpr (NW == 1) {
+        __builtin_nontemporal_store(w[0], reinterpret_cast<uint32_t*>(p));
+    } else if constexpr (NW == 2) {
+        u32x2a t; t[0] = w[0]; t[1] = w[1];
+        __builtin_nontemporal_store(t, reinterpret_cast<u32x2a*>(p));
+    } else {
+        u32x4a t; t[0] = w[0]; t[1] = w[1]; t[2] = w[2]; t[3] = w[3];
+        __builtin_nontemporal_store(t, reinterpret_cast<u32x4a*>(p));
+    }
+}
+// sum over the 16 lanes of this lane's group, the same value in all of them
+__device__ __forceinline__ float group16_sum(float v) {
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror
+    v = dpp_add<0x140>(v);   // row_mirror
+    return v;
+}
+
 struct EdgeRec {
     int j;      // neighbour (column of A)
     float a;    // a_ij
@@ -630,11 +686,11 @@ __device__ __forceinline__ void tile_gather(const CsrView& g, const float* __res
 // A wave multiplies its 16 x DG tile (staged in LDS, row stride DG+1) by a DG x DG matrix with
 // v_mfma_f32_16x16x4_f32:
 //   A[i][kk]: lane = kk*16 + i;  B[kk][j]: lane = kk*16 + j;  D[4*(lane/16)+r][lane%16] in reg r.
-// The DG x DG weight matrix sits in LDS (row stride DG + 8, which spreads the four k-rows of a
+// The DG x DG weight matrix sits in LDS (odd row stride DG + 1, which spreads the four k-rows of a
 // B operand over different banks), loaded once per workgroup; transposed = true stores W^T.
 template <int DG>
 struct WLds {
-    static constexpr int WP = DG + 8;
+    static constexpr int WP = DG + 1;
     float w[DG * WP];
 };
 
@@ -647,30 +703,24 @@ __device__ __forceinline__ void load_w_lds(const float* __restrict__ w, bool tra
     __syncthreads();
 }
 
-// acc = tile (16 x DG, LDS, row stride DG+1) * B (DG x DG, LDS)
+// acc = tile (16 x DG, LDS, row stride DG+1) * B (DG x DG, LDS), left in the tile register
+// layout: acc[cb][reg] = product[row 4 reg + lane / 16][column CPL (lane % 16) + cb].
 template <int DG>
 __device__ __forceinline__ void mfma_tile(const float* st, const WLds<DG>& wl, f32x4 (&acc)[DG / 16]) {
-    const int lane = lane_id();
+    constexpr int CPL = DG / 16;
+    const int lane = lane_id(), i = lane & 15, kk = lane >> 4;
+    const int arow = 4 * (i & 3) + (i >> 2);
 #pragma unroll
-    for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < CPL; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < DG / 4; ++s) {
-        const float a = st[(lane & 15) * (DG + 1) + 4 * s + (lane >> 4)];
+        const float a = st[arow * (DG + 1) + 4 * s + kk];
 #pragma unroll
-        for (int cb = 0; cb < DG / 16; ++cb) {
-            const float b = wl.w[(4 * s + (lane >> 4)) * WLds<DG>::WP + 16 * cb + (lane & 15)];
+        for (int cb = 0; cb < CPL; ++cb) {
+            const float b = wl.w[(4 * s + kk) * WLds<DG>::WP + CPL * i + cb];
             acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc[cb], 0, 0, 0);
         }
     }
-}
-
-template <int DG>
-__device__ __forceinline__ void store_tile(float* st, const f32x4 (&acc)[DG / 16]) {
-    const int lane = lane_id();
-#pragma unroll
-    for (int cb = 0; cb < DG / 16; ++cb)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) st[(4 * (lane >> 4) + r) * (DG + 1) + 16 * cb + (lane & 15)] = acc[cb][r];
 }
 
 // dW += H^T dY over the 16 rows of the tile: D[m][o] += sum_n H[n][m] dY[n][o]

@@ -192,9 +192,9 @@ struct BlockArgs {
 
 template <int DG, typename T, int SIGN, bool WITH_DW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
-    constexpr int G = 64 / DG, LR = DG + 1, NT = WITH_DW ? 2 : 1, RPW = 16 / G;
+    constexpr int LR = DG + 1, NT = WITH_DW ? 2 : 1, CPL = DG / 16;
     __shared__ WaveLds<DG, NT> lds[4];
-    const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
+    const int lane = lane_id(), wave = threadIdx.x >> 6, tg = lane >> 4, tj = lane & 15;
     WaveLds<DG, NT>& L = lds[wave];
     float* st_h = L.st[0];
     float* st_g = L.st[NT - 1];
@@ -219,38 +219,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
                                        lane, hacc);
         });
         if constexpr (WITH_DW) {
-            float gy[RPW];
+            // dY_i rows into the second tile (rows past the end zero)
 #pragma unroll
-            for (int it = 0; it < RPW; ++it) {
-                const int row = r0 + it * G + sub;
-                const float g = to_float(load_stream(a.dy + (size_t)(row < a.n ? row : a.n - 1) * a.ldg + c));
-                gy[it] = row < a.n ? g : 0.f;
+            for (int reg = 0; reg < 4; ++reg) {
+                const int rr = 4 * reg + tg, row = r0 + rr;
+                float gy[CPL];
+                load_cols<CPL, T>(a.dy + (size_t)(row < a.n ? row : a.n - 1) * a.ldg + CPL * tj, gy);
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) st_g[rr * LR + CPL * tj + cb] = row < a.n ? gy[cb] : 0.f;
             }
-#pragma unroll
-            for (int it = 0; it < RPW; ++it) st_g[(it * G + sub) * LR + c] = gy[it];
         }
         wave_sync();
-        {
-            f32x4 acc[DG / 16];
-            mfma_tile<DG>(st_h, wl, acc);
-            if constexpr (WITH_DW) mfma_outer<DG>(st_h, st_g, dw);
-            wave_sync();
-            store_tile<DG>(st_h, acc);
-            wave_sync();
-        }
-        float xv[RPW];
+        f32x4 acc[CPL];
+        mfma_tile<DG>(st_h, wl, acc);                      // O = H W_i in the tile register layout
+        if constexpr (WITH_DW) mfma_outer<DG>(st_h, st_g, dw);
+        wave_sync();                                       // H has been read: the tile is free
+        // residual: four rows per instruction, CPL adjacent elements per lane
 #pragma unroll
-        for (int it = 0; it < RPW; ++it) {
-            const int row = r0 + it * G + sub;
-            xv[it] = to_float(load_stream(a.plane + (size_t)(row < a.n ? row : a.n - 1) * a.ld + c));
-        }
+        for (int reg = 0; reg < 4; ++reg) {
+            const int rr = 4 * reg + tg, row = r0 + rr;
+            const bool ok = row < a.n;
+            T* p = a.plane + (size_t)(ok ? row : a.n - 1) * a.ld + CPL * tj;
+            float y[CPL];
+            load_cols<CPL, T>(p, y);
 #pragma unroll
-        for (int it = 0; it < RPW; ++it) {
-            const int r = it * G + sub, row = r0 + r;
-            const float o = st_h[r * LR + c];
-            const T yt = from_float<T>(SIGN > 0 ? xv[it] + o : xv[it] - o);
-            if (row < a.n) store_stream(a.plane + (size_t)row * a.ld + c, yt);
-            st_h[r * LR + c] = row < a.n ? to_float(yt) : 0.f;
+            for (int cb = 0; cb < CPL; ++cb) y[cb] = stored<T>(SIGN > 0 ? y[cb] + acc[cb][reg] : y[cb] - acc[cb][reg]);
+            if (ok) store_cols<CPL, T>(p, y);
+#pragma unroll
+            for (int cb = 0; cb < CPL; ++cb) st_h[rr * LR + CPL * tj + cb] = ok ? y[cb] : 0.f;
         }
         if (a.out.mask) {
             wave_sync();
@@ -328,9 +324,9 @@ constexpr int GRAD_WAVES = 4;
 
 template <int DG, typename T>
 __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
-    constexpr int G = 64 / DG, LR = DG + 1, RPW = 16 / G;
+    constexpr int CPL = DG / 16;
     __shared__ WaveLds<DG, 1> lds[GRAD_WAVES];
-    const int lane = lane_id(), c = lane % DG, sub = lane / DG, wave = threadIdx.x >> 6;
+    const int lane = lane_id(), wave = threadIdx.x >> 6, tg = lane >> 4, tj = lane & 15;
     WaveLds<DG, 1>& L = lds[wave];
     float* st = L.st[0];
     __shared__ WLds<DG> wl;
@@ -346,65 +342,44 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, lane, qacc);
         });
         wave_sync();
-        {
-            f32x4 acc[DG / 16];
-            mfma_tile<DG>(st, wl, acc);      // dH = Q W^T
-            wave_sync();
-            store_tile<DG>(st, acc);
-            wave_sync();
-        }
-        // epilogue in batches of HB rows per lane: everything a batch needs from memory is issued
-        // together
-        constexpr int HB = RPW < 8 ? RPW : 8;
-#pragma unroll 1
-        for (int h0 = 0; h0 < RPW; h0 += HB) {
-            float zz[HB];
-            bool sel[HB];
+        f32x4 acc[CPL];
+        mfma_tile<DG>(st, wl, acc);          // dH = Q W^T in the tile register layout
+        // epilogue on registers: row 4 reg + tg, columns CPL tj + cb
 #pragma unroll
-            for (int u = 0; u < HB; ++u) {
-                const int row = r0 + (h0 + u) * G + sub;
-                const bool ok = row < a.n;
-                const int rowc = ok ? row : a.n - 1;
-                sel[u] = ok && ((a.own_mask[rowc] >> c) & 1);
-                const float zv = a.norm == GSR_NORM_RMS ? to_float(load_stream(a.z + (size_t)rowc * a.ldz + c)) : 0.f;
-                zz[u] = ok ? zv : 0.f;
-            }
-            float dzv[HB];
-            bool touch[HB];
+        for (int reg = 0; reg < 4; ++reg) {
+            const int row = r0 + 4 * reg + tg;
+            const bool ok = row < a.n;
+            const int rowc = ok ? row : a.n - 1;
+            const uint32_t bits = ok ? (uint32_t)(a.own_mask[rowc] >> (CPL * tj)) & ((1u << CPL) - 1u) : 0u;
+            float dz[CPL];
+            if (a.norm == GSR_NORM_RMS) {
+                // V = Z[I] * rinv, rinv = (mean Z^2 + eps)^-1/2:
+                // dZ_c = [c in I] g_c rinv - Z_c (sum_t g_t Z_{I_t}) rinv^3 / DG
+                float z[CPL];
+                load_cols<CPL, T>(a.z + (size_t)rowc * a.ldz + CPL * tj, z);
+                float ss = 0.f, dot = 0.f;
 #pragma unroll
-            for (int u = 0; u < HB; ++u) {
-                const int r = (h0 + u) * G + sub, row = r0 + r;
-                const bool ok = row < a.n;
-                const float gdh = st[r * LR + c];
-                float dz = sel[u] ? gdh : 0.f;
-                touch[u] = sel[u];
-                if (a.norm == GSR_NORM_RMS) {
-                    // V = Z[I] * rinv, rinv = (mean Z^2 + eps)^-1/2:
-                    // dZ_c = [c in I] g_c rinv - Z_c (sum_t g_t Z_{I_t}) rinv^3 / DG
-                    const float sq = zz[u] * zz[u];
-                    const float ss = sub_sum<DG>(sq);
-                    const float rinv = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + a.eps);
-                    const float pr = sel[u] ? gdh * zz[u] : 0.f;
-                    const float dot = sub_sum<DG>(pr);
-                    const float coef = dot * (rinv * rinv * rinv) * (1.0f / (float)DG);
-                    dz = (sel[u] ? gdh * rinv : 0.f) - zz[u] * coef;
-                    touch[u] = ok;
+                for (int cb = 0; cb < CPL; ++cb) {
+                    ss += z[cb] * z[cb];
+                    dot += ((bits >> cb) & 1u) ? acc[cb][reg] * z[cb] : 0.f;
                 }
-                dzv[u] = dz;
+                ss = group16_sum(ss);
+                dot = group16_sum(dot);
+                const float rinv = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + a.eps);
+                const float coef = dot * (rinv * rinv * rinv) * (1.0f / (float)DG);
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) dz[cb] = (((bits >> cb) & 1u) ? acc[cb][reg] * rinv : 0.f) - z[cb] * coef;
+            } else {
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) dz[cb] = ((bits >> cb) & 1u) ? acc[cb][reg] : 0.f;
             }
             for (int j = 0; j < a.ndst; ++j) {
-                T* plane = a.dst + (size_t)j * a.dst_gs;
-                float old[HB];
+                T* p = a.dst + (size_t)j * a.dst_gs + (size_t)rowc * a.ldd + CPL * tj;
+                float g[CPL];
+                load_cols<CPL, T>(p, g);
 #pragma unroll
-                for (int u = 0; u < HB; ++u) {
-                    const int row = r0 + (h0 + u) * G + sub;
-                    old[u] = to_float(load_stream(plane + (size_t)(row < a.n ? row : a.n - 1) * a.ldd + c));
-                }
-#pragma unroll
-                for (int u = 0; u < HB; ++u) {
-                    const int row = r0 + (h0 + u) * G + sub;
-                    if (touch[u]) store_stream(plane + (size_t)row * a.ldd + c, from_float<T>(old[u] + dzv[u]));
-                }
+                for (int cb = 0; cb < CPL; ++cb) g[cb] = stored<T>(g[cb] + dz[cb]);
+                if (ok) store_cols<CPL, T>(p, g);
             }
         }
     }
@@ -426,36 +401,41 @@ struct SumArgs {
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
-    constexpr int G = 64 / DG, LR = DG + 1, RPW = 16 / G;
+    constexpr int LR = DG + 1, CPL = DG / 16;
     __shared__ float tile[4][16 * LR + 64];
-    const int lane = lane_id(), c = lane % DG, sub = lane / DG;
+    const int lane = lane_id(), tg = lane >> 4, tj = lane & 15;
     float* st = tile[threadIdx.x >> 6];
     const int nwaves = (gridDim.x * blockDim.x) >> 6, tiles = (a.n + 15) / 16;
     for (int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; t < tiles; t += nwaves) {
         const int r0 = t * 16;
-        float s[RPW];
+        float y[4][CPL];
 #pragma unroll
-        for (int it = 0; it < RPW; ++it) {
-            const int row = r0 + it * G + sub;
-            s[it] = to_float(load_stream(a.src + (size_t)(row < a.n ? row : a.n - 1) * a.ld + c));
+        for (int reg = 0; reg < 4; ++reg) {
+            const int row = r0 + 4 * reg + tg;
+            load_cols<CPL, T>(a.src + (size_t)(row < a.n ? row : a.n - 1) * a.ld + CPL * tj, y[reg]);
         }
         for (int j = 1; j < a.nsrc; ++j) {
-            float v[RPW];
+            float v[4][CPL];
 #pragma unroll
-            for (int it = 0; it < RPW; ++it) {
-                const int row = r0 + it * G + sub;
-                v[it] = to_float(load_stream(a.src + (size_t)j * a.src_gs + (size_t)(row < a.n ? row : a.n - 1) * a.ld + c));
+            for (int reg = 0; reg < 4; ++reg) {
+                const int row = r0 + 4 * reg + tg;
+                load_cols<CPL, T>(a.src + (size_t)j * a.src_gs + (size_t)(row < a.n ? row : a.n - 1) * a.ld + CPL * tj, v[reg]);
             }
 #pragma unroll
-            for (int it = 0; it < RPW; ++it) s[it] += v[it];
-        }
-        wave_sync();
+            for (int reg = 0; reg < 4; ++reg)
 #pragma unroll
-        for (int it = 0; it < RPW; ++it) {
-            const int r = it * G + sub, row = r0 + r;
-            const T yt = from_float<T>(s[it]);
-            if (row < a.n && a.y0) store_stream(a.y0 + (size_t)row * DG + c, yt);
-            st[r * LR + c] = row < a.n ? to_float(yt) : 0.f;
+                for (int cb = 0; cb < CPL; ++cb) y[reg][cb] += v[reg][cb];
+        }
+        wave_sync();          // the previous tile's records have left the scratch
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) {
+            const int rr = 4 * reg + tg, row = r0 + rr;
+            const bool ok = row < a.n;
+#pragma unroll
+            for (int cb = 0; cb < CPL; ++cb) y[reg][cb] = stored<T>(y[reg][cb]);
+            if (ok && a.y0) store_cols<CPL, T>(a.y0 + (size_t)row * DG + CPL * tj, y[reg]);
+#pragma unroll
+            for (int cb = 0; cb < CPL; ++cb) st[rr * LR + CPL * tj + cb] = ok ? y[reg][cb] : 0.f;
         }
         wave_sync();
         emit_tile<DG, T>(st, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane);
@@ -781,6 +761,9 @@ static gsr_status_t layer_call(LayerOp op, const gsr_graph_t* g, const gsr_confi
     return GSR_OK;
 }
 
+// rows are moved in pieces of up to 16 bytes
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
 static gsr_status_t layer_dispatch(LayerOp op, const gsr_graph_t* g, const gsr_config_t* cfg, const float* w, void* y, void* dy,
                                    float* dw, void* ws, size_t ws_bytes, void* stream) {
     GSR_TRY(validate_config(cfg, g, false));
@@ -789,6 +772,8 @@ static gsr_status_t layer_dispatch(LayerOp op, const gsr_graph_t* g, const gsr_c
     if (op == OP_BWD && !g->has_transpose) return fail(GSR_ERR_UNSUPPORTED, "graph has no transpose");
     const size_t need = carve_layer(cfg, g).total;
     if (ws_bytes < need) return fail(GSR_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < %zu bytes", ws_bytes, need);
+    if (!aligned16(y) || !aligned16(dy) || ((uintptr_t)ws & 255))
+        return fail(GSR_ERR_INVALID_ARG, "planes must be 16-byte aligned and the workspace 256-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const int dg = cfg->d / cfg->c;
     if (cfg->dtype == GSR_F32) {
@@ -872,6 +857,7 @@ gsr_status_t gsr_step(const gsr_graph_t* g, const gsr_config_t* cfg, const void*
     const size_t need = carve_step(cfg, g).total;
     if (workspace_bytes < need) return fail(GSR_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < %zu bytes", workspace_bytes, need);
     if (cfg->n == 0) return fail(GSR_ERR_INVALID_ARG, "empty graph");
+    if ((uintptr_t)workspace & 255) return fail(GSR_ERR_INVALID_ARG, "the workspace must be 256-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     const int dg = cfg->d / cfg->c;
 #define GSR_STEP(DGV, TV)                                                                                            \
