@@ -723,22 +723,22 @@ __device__ __forceinline__ void mfma_tile(const float* st, const WLds<DG>& wl, f
     }
 }
 
-// dW += H^T dY over the 16 rows of the tile: D[m][o] += sum_n H[n][m] dY[n][o]
+// dW += H^T dY over the 16 rows of the tile: D[m][o] += sum_n H[n][m] dY[n][o].  H comes from the
+// LDS tile; dY is held in the tile register layout (gy[reg][cb] = dY[row 4 reg + lane / 16]
+// [column CPL (lane % 16) + cb]), which is the B operand as it stands.  The result has its
+// columns interleaved the same way: acc[mb][ob][r] = dW[16 mb + 4 (lane / 16) + r][CPL (lane % 16) + ob].
 template <int DG>
-__device__ __forceinline__ void mfma_outer(const float* st_h, const float* st_g, f32x4 (&acc)[DG / 16][DG / 16]) {
+__device__ __forceinline__ void mfma_outer(const float* st_h, const float (&gy)[4][DG / 16], f32x4 (&acc)[DG / 16][DG / 16]) {
     const int lane = lane_id();
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         const int nrow = 4 * ks + (lane >> 4);
-        float bop[DG / 16];
-#pragma unroll
-        for (int ob = 0; ob < DG / 16; ++ob) bop[ob] = st_g[nrow * (DG + 1) + 16 * ob + (lane & 15)];
 #pragma unroll
         for (int mb = 0; mb < DG / 16; ++mb) {
             const float a = st_h[nrow * (DG + 1) + 16 * mb + (lane & 15)];
 #pragma unroll
             for (int ob = 0; ob < DG / 16; ++ob)
-                acc[mb][ob] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, bop[ob], acc[mb][ob], 0, 0, 0);
+                acc[mb][ob] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, gy[ks][ob], acc[mb][ob], 0, 0, 0);
         }
     }
 }

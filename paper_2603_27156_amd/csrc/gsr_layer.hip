@@ -192,12 +192,11 @@ struct BlockArgs {
 
 template <int DG, typename T, int SIGN, bool WITH_DW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
-    constexpr int LR = DG + 1, NT = WITH_DW ? 2 : 1, CPL = DG / 16;
-    __shared__ WaveLds<DG, NT> lds[4];
+    constexpr int LR = DG + 1, CPL = DG / 16;
+    __shared__ WaveLds<DG, 1> lds[4];
     const int lane = lane_id(), wave = threadIdx.x >> 6, tg = lane >> 4, tj = lane & 15;
-    WaveLds<DG, NT>& L = lds[wave];
+    WaveLds<DG, 1>& L = lds[wave];
     float* st_h = L.st[0];
-    float* st_g = L.st[NT - 1];
     __shared__ WLds<DG> wl;
     load_w_lds<DG>(a.w, false, wl);
     f32x4 dw[WITH_DW ? DG / 16 : 1][WITH_DW ? DG / 16 : 1];
@@ -218,21 +217,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
                                        __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
                                        lane, hacc);
         });
+        float gy[WITH_DW ? 4 : 1][CPL];
         if constexpr (WITH_DW) {
-            // dY_i rows into the second tile (rows past the end zero)
+            // dY_i of the tile's rows in the tile register layout (rows past the end zero)
 #pragma unroll
             for (int reg = 0; reg < 4; ++reg) {
-                const int rr = 4 * reg + tg, row = r0 + rr;
-                float gy[CPL];
-                load_cols<CPL, T>(a.dy + (size_t)(row < a.n ? row : a.n - 1) * a.ldg + CPL * tj, gy);
+                const int row = r0 + 4 * reg + tg;
+                load_cols<CPL, T>(a.dy + (size_t)(row < a.n ? row : a.n - 1) * a.ldg + CPL * tj, gy[reg]);
 #pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) st_g[rr * LR + CPL * tj + cb] = row < a.n ? gy[cb] : 0.f;
+                for (int cb = 0; cb < CPL; ++cb) gy[reg][cb] = row < a.n ? gy[reg][cb] : 0.f;
             }
         }
         wave_sync();
         f32x4 acc[CPL];
         mfma_tile<DG>(st_h, wl, acc);                      // O = H W_i in the tile register layout
-        if constexpr (WITH_DW) mfma_outer<DG>(st_h, st_g, dw);
+        if constexpr (WITH_DW) mfma_outer<DG>(st_h, gy, dw);
         wave_sync();                                       // H has been read: the tile is free
         // residual: four rows per instruction, CPL adjacent elements per lane
 #pragma unroll
@@ -266,7 +265,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
                     for (int ob = 0; ob < DG / 16; ++ob)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            const int m = 16 * mb + 4 * (lane >> 4) + r, o = 16 * ob + (lane & 15);
+                            const int m = 16 * mb + 4 * (lane >> 4) + r, o = CPL * (lane & 15) + ob;
                             if (w == 0) red[m * DG + o] = dw[mb][ob][r];
                             else red[m * DG + o] += dw[mb][ob][r];
                         }
