@@ -211,22 +211,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         const int r0 = t * 16;
         wave_sync();
         const bool has_hub = tile_begin(a.g, r0, a.n, L.rp, lane);
+        // The tile's own rows (X_i, and dY_i for the weight gradient) are requested first, in the
+        // tile register layout, and arrive while the neighbour records are gathered.
+        float xy[4][CPL], gy[WITH_DW ? 4 : 1][CPL];
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) {
+            const int row = r0 + 4 * reg + tg;
+            const size_t rowc = (size_t)(row < a.n ? row : a.n - 1);
+            load_cols<CPL, T>(a.plane + rowc * a.ld + CPL * tj, xy[reg]);
+            if constexpr (WITH_DW) load_cols<CPL, T>(a.dy + rowc * a.ldg + CPL * tj, gy[reg]);
+        }
         f32x4 hacc[DG / 16];
         tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, hacc, [&](int e_a, int e_b) {
-            gather_records_mfma<DG, T, WITH_DW ? 16 : 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
-                                       __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
-                                       lane, hacc);
+            gather_records_mfma<DG, T, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
+                                          __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
+                                          lane, hacc);
         });
-        float gy[WITH_DW ? 4 : 1][CPL];
         if constexpr (WITH_DW) {
-            // dY_i of the tile's rows in the tile register layout (rows past the end zero)
 #pragma unroll
-            for (int reg = 0; reg < 4; ++reg) {
-                const int row = r0 + 4 * reg + tg;
-                load_cols<CPL, T>(a.dy + (size_t)(row < a.n ? row : a.n - 1) * a.ldg + CPL * tj, gy[reg]);
+            for (int reg = 0; reg < 4; ++reg)
 #pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) gy[reg][cb] = row < a.n ? gy[reg][cb] : 0.f;
-            }
+                for (int cb = 0; cb < CPL; ++cb) gy[reg][cb] = r0 + 4 * reg + tg < a.n ? gy[reg][cb] : 0.f;   // rows past the end
         }
         wave_sync();
         f32x4 acc[CPL];
@@ -240,9 +245,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
             const bool ok = row < a.n;
             T* p = a.plane + (size_t)(ok ? row : a.n - 1) * a.ld + CPL * tj;
             float y[CPL];
-            load_cols<CPL, T>(p, y);
 #pragma unroll
-            for (int cb = 0; cb < CPL; ++cb) y[cb] = stored<T>(SIGN > 0 ? y[cb] + acc[cb][reg] : y[cb] - acc[cb][reg]);
+            for (int cb = 0; cb < CPL; ++cb) y[cb] = stored<T>(SIGN > 0 ? xy[reg][cb] + acc[cb][reg] : xy[reg][cb] - acc[cb][reg]);
             if (ok) store_cols<CPL, T>(p, y);
 #pragma unroll
             for (int cb = 0; cb < CPL; ++cb) st_h[rr * LR + CPL * tj + cb] = ok ? y[cb] : 0.f;
@@ -335,6 +339,16 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
         const int r0 = t * 16;
         wave_sync();
         const bool has_hub = tile_begin(a.gt, r0, a.n, L.rp, lane);
+        // what the epilogue needs of the tile's own rows is requested first
+        typename MaskOf<DG>::type own[4];
+        float z[4][CPL];
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) {
+            const int row = r0 + 4 * reg + tg;
+            const size_t rowc = (size_t)(row < a.n ? row : a.n - 1);
+            own[reg] = a.own_mask[rowc];
+            if (a.norm == GSR_NORM_RMS) load_cols<CPL, T>(a.z + rowc * a.ldz + CPL * tj, z[reg]);
+        }
         f32x4 qacc[DG / 16];
         tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, qacc, [&](int e_a, int e_b) {
             gather_dense_mfma<DG, T, 16>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
@@ -349,25 +363,23 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
             const int row = r0 + 4 * reg + tg;
             const bool ok = row < a.n;
             const int rowc = ok ? row : a.n - 1;
-            const uint32_t bits = ok ? (uint32_t)(a.own_mask[rowc] >> (CPL * tj)) & ((1u << CPL) - 1u) : 0u;
+            const uint32_t bits = ok ? (uint32_t)(own[reg] >> (CPL * tj)) & ((1u << CPL) - 1u) : 0u;
             float dz[CPL];
             if (a.norm == GSR_NORM_RMS) {
                 // V = Z[I] * rinv, rinv = (mean Z^2 + eps)^-1/2:
                 // dZ_c = [c in I] g_c rinv - Z_c (sum_t g_t Z_{I_t}) rinv^3 / DG
-                float z[CPL];
-                load_cols<CPL, T>(a.z + (size_t)rowc * a.ldz + CPL * tj, z);
                 float ss = 0.f, dot = 0.f;
 #pragma unroll
                 for (int cb = 0; cb < CPL; ++cb) {
-                    ss += z[cb] * z[cb];
-                    dot += ((bits >> cb) & 1u) ? acc[cb][reg] * z[cb] : 0.f;
+                    ss += z[reg][cb] * z[reg][cb];
+                    dot += ((bits >> cb) & 1u) ? acc[cb][reg] * z[reg][cb] : 0.f;
                 }
                 ss = group16_sum(ss);
                 dot = group16_sum(dot);
                 const float rinv = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + a.eps);
                 const float coef = dot * (rinv * rinv * rinv) * (1.0f / (float)DG);
 #pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) dz[cb] = (((bits >> cb) & 1u) ? acc[cb][reg] * rinv : 0.f) - z[cb] * coef;
+                for (int cb = 0; cb < CPL; ++cb) dz[cb] = (((bits >> cb) & 1u) ? acc[cb][reg] * rinv : 0.f) - z[reg][cb] * coef;
             } else {
 #pragma unroll
                 for (int cb = 0; cb < CPL; ++cb) dz[cb] = ((bits >> cb) & 1u) ? acc[cb][reg] : 0.f;
