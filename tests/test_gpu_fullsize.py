@@ -263,3 +263,65 @@ def test_cfg1_full_depth_step_with_saved_indices():
     assert np.isclose(saved["loss"], ref["loss"], rtol=1e-3)
     for key, bound in (("yhat", 1e-2), ("XL", 1e-2), ("X0rec", 1e-5), ("dW", 5e-2), ("dwout", 1e-2), ("dX0", 1e-1)):
         assert rel_norm(saved[key], ref[key]) <= bound, key
+
+
+def test_cfg4_full_size_sampled_rows_and_properties():
+    """cfg4 (8M nodes, D 256, C 8, k 8, bf16 storage, int64 row pointers) in the launch
+    configuration the benchmark uses.  The oracle cannot run a layer on 8M x 256 doubles inside
+    the test budget, so block 1 of the first layer is checked on sampled rows, each computed by
+    the oracle's operators from its own neighbourhood (GS of the neighbours' Y_0 rows, aggregation
+    over the row's stored edges, weight product in float64); reruns must be bit-identical and
+    inverse(forward(X)) must return X to bf16 rounding."""
+    w = synth.workload(4)
+    t = time.time()
+    inp = synth.make_inputs(w, 0)
+    assert inp.rowptr.dtype == np.int64
+    gg = gsr.gsr_graph_create(inp.rowptr, inp.colidx)
+    og = oracle.graph_build(inp.rowptr, inp.colidx)
+    print(f"[cfg4] n={w.n} nnz={og.nnz} built in {time.time() - t:.1f}s", flush=True)
+    dev = torch.device("cuda:0")
+    dg, C, k = w.dg, w.c, w.k
+    cfg = gsr.Config(n=w.n, d=w.d, c=C, k=k, l=1, dtype=gsr.GSR_BF16, norm=gsr.GSR_NORM_RMS, eps=1e-5, layout=PLANAR)
+    x = torch.from_numpy(inp.x0).to(dev).to(torch.bfloat16).view(w.n, C, dg).permute(1, 0, 2).contiguous()
+    W = inp.weights[0]
+    Wd = torch.from_numpy(W).to(dev)
+    y = x.clone()
+    gsr.gsr_layer_forward(gg, cfg, Wd, y)
+    y2 = x.clone()
+    gsr.gsr_layer_forward(gg, cfg, Wd, y2)
+    assert torch.equal(y, y2)
+    gsr.gsr_layer_inverse(gg, cfg, Wd, y2)
+    diff = (y2.float() - x.float()).abs().amax(dim=(0, 2))           # per row
+    frac = float((diff > 0.05).float().mean().item())
+    print(f"[cfg4] inverse(forward(X)): rows off by more than 0.05: {frac:.2e}", flush=True)
+    assert frac < 4e-2          # bf16 near-ties re-selected differently; everything else to rounding
+
+    # sampled rows of block 1: the two first tiles (they hold the split rows) and 3,000 random rows
+    rng = np.random.default_rng(11)
+    S = np.unique(np.concatenate([np.arange(32), rng.integers(0, w.n, 3000)]))
+    deg = og.rp[S + 1] - og.rp[S]
+    cols = np.concatenate([og.ci[og.rp[i]:og.rp[i + 1]] for i in S])
+    vals = np.concatenate([og.av[og.rp[i]:og.rp[i + 1]] for i in S])
+    nodes, inv = np.unique(cols, return_inverse=True)                # neighbourhood of the sample (holds S: self-loops)
+    xs = synth.to_bf16_grid(inp.x0[nodes]).astype(np.float64)
+    y0 = oracle.round_store(xs[:, dg:].reshape(len(nodes), C - 1, dg).sum(axis=1), oracle.STORE_BF16)
+    V, I, _ = oracle.gs(y0, k, oracle.NORM_RMS, 1e-5, oracle.STORE_BF16)
+    # a CSR over the neighbourhood's local numbering with the sampled rows' edges only
+    pos = np.searchsorted(nodes, S)
+    rp = np.zeros(len(nodes) + 1, dtype=np.int64)
+    rp[pos + 1] = deg
+    rp = np.cumsum(rp)
+    order = np.argsort(pos, kind="stable")                           # S is sorted, so pos is: identity
+    assert np.array_equal(order, np.arange(len(S)))
+    sub = oracle.graph_from_csr(rp, inv.astype(np.int32), vals)
+    H = oracle.aggregate(sub, V, I, dg)[pos]
+    ref = oracle.round_store(xs[pos, :dg] + H @ W[0].astype(np.float64), oracle.STORE_BF16)
+    got = y[0].index_select(0, torch.from_numpy(S).to(dev)).float().cpu().numpy().astype(np.float64)
+    rel = rel_norm(got, ref)
+    ulp_off = np.abs(got - ref) > 2.0 ** -7 * np.maximum(np.abs(ref), 2.0 ** -6)
+    print(f"[cfg4] block 1 on {len(S)} sampled rows (max degree {int(deg.max())}): rel {rel:.2e}, "
+          f"elements off by more than one bf16 ulp {ulp_off.mean():.2e}", flush=True)
+    assert rel <= BF16_REL
+    assert ulp_off.mean() < 2e-2
+    del x, y, y2
+    torch.cuda.empty_cache()
