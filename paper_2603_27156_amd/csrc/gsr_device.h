@@ -1,9 +1,12 @@
 // Device-side building blocks for gfx950 (wave64): storage conversion, sub-wave reductions,
 // the exact top-k select of the GS operator, neighbour gathers and 16x16x4 float32 MFMA tiles.
 //
-// Thread layout used everywhere ("row layout"): a row of a group has DG = 32 or 64 columns;
-// lane c of a (sub-)wave owns column c.  With DG = 64 a wave holds one row, with DG = 32 it
-// holds two rows (lanes 0..31 and 32..63, `sub` = lane / DG).
+// Three thread layouts appear.  "Row layout" (operators exposed on their own, first pass over split
+// rows, head): a row of a group has DG = 32 or 64 columns and lane c of a (sub-)wave owns column
+// c; with DG = 64 a wave holds one row, with DG = 32 two (lanes 0..31 and 32..63, `sub` = lane /
+// DG).  "Tile register layout" (layer kernels: what the MFMA leaves in the accumulators for a
+// 16-row tile; four rows per memory instruction) and "quarter layout" (GS of a 16-row tile: lane
+// = (row, quarter of its columns)) are described where they are introduced below.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -33,18 +36,6 @@ __device__ __forceinline__ bf16_t from_float<bf16_t>(float v) {
     return r;
 }
 
-// Streaming accesses: data touched once per kernel (activation and gradient planes) is loaded and
-// stored with the non-temporal hint, so that it does not push the neighbour records and gradient
-// rows that many tiles gather out of the caches.
-__device__ __forceinline__ float load_stream(const float* p) { return __builtin_nontemporal_load(p); }
-__device__ __forceinline__ bf16_t load_stream(const bf16_t* p) {
-    bf16_t r;
-    r.bits = __builtin_nontemporal_load(&p->bits);
-    return r;
-}
-__device__ __forceinline__ void store_stream(float* p, float v) { __builtin_nontemporal_store(v, p); }
-__device__ __forceinline__ void store_stream(bf16_t* p, bf16_t v) { __builtin_nontemporal_store(v.bits, &p->bits); }
-
 // value as it will read back after a store of type T
 template <typename T>
 __device__ __forceinline__ float stored(float v) { return to_float(from_float<T>(v)); }
@@ -64,13 +55,6 @@ __device__ __forceinline__ int lane_id() { return threadIdx.x & 63; }
 __device__ __forceinline__ void wave_sync() {
     asm volatile("" ::: "memory");
     __builtin_amdgcn_wave_barrier();
-}
-
-// LDS += v without a return value (ds_add_f32).  Only used where no two lanes of the same
-// instruction address the same word and one wave owns the buffer: the additions then happen in
-// program order and the result does not depend on timing.
-__device__ __forceinline__ void lds_add(float* p, float v) {
-    __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
 // (a & m) | (b & ~m)
@@ -155,35 +139,12 @@ __device__ __forceinline__ float quarter_sum(float v) {
 // signed value.  The row's k-th largest value is found by bisection on an order-preserving
 // 32-bit image of the floats, one bit per round: count = popcount(ballot(key >= candidate)).
 // As soon as a candidate splits off exactly k entries the search is over.  Ties at the
-// threshold go to the lowest columns, -0 equals +0.  Returns whether this lane's column is kept
-// and the row's column bit mask.
-template <int DG>
-__device__ __forceinline__ bool topk_select(float x, int k, int c, int sub, typename MaskOf<DG>::type* mask_out) {
-    using M = typename MaskOf<DG>::type;
-    uint32_t u = __float_as_uint(x);
-    if (u == 0x80000000u) u = 0u;
-    const uint32_t key = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-    uint32_t thr = 0u;
-    bool done = (k >= DG);
-    for (int bit = 31; bit >= 0; --bit) {
-        if (ballot(!done) == 0ull) break;
-        const uint32_t cand = thr | (1u << bit);
-        const int cnt = popc<DG>(sub_bits<DG>(ballot(key >= cand), sub));
-        if (cnt >= k) thr = cand;
-        done = done || (cnt == k);
-    }
-    const M gt = sub_bits<DG>(ballot(key > thr), sub);
-    const M eq = sub_bits<DG>(ballot(key == thr), sub);
-    const int need = k - popc<DG>(gt);
-    const M below = ((M)1 << c) - 1;
-    const bool sel = (key > thr) || (key == thr && popc<DG>(eq & below) < need);
-    *mask_out = sub_bits<DG>(ballot(sel), sub);
-    return sel;
-}
-
-// The same search for R rows at once (independent bisections interleaved so that their
-// dependent ballot -> popcount -> compare chains overlap).  With one row per wave (DG = 64) every
-// quantity of the search is wave-uniform and lives in scalar registers.
+// threshold go to the lowest columns, -0 equals +0.  Row layout (lane c of a (sub-)wave owns
+// column c), R rows at once: the independent bisections are interleaved so that their dependent
+// ballot -> popcount -> compare chains overlap.  sel[r]: this lane's column of row r is kept;
+// mask_out[r]: the row's column bit mask.  With one row per wave (DG = 64) every quantity of the
+// search is wave-uniform and lives in scalar registers.  (The layer kernels select in the
+// quarter layout instead, 16 rows at once in vector registers.)
 template <int DG, int R>
 __device__ __forceinline__ void topk_select_multi(const float (&x)[R], int k, int c, int sub, bool (&sel)[R],
                                                   typename MaskOf<DG>::type (&mask_out)[R]) {
@@ -271,14 +232,6 @@ __device__ __forceinline__ void topk_select_multi(const float (&x)[R], int k, in
             mask_out[r] = sub_bits<DG>(ballot(sel[r]), sub);
         }
     }
-}
-
-// number of set bits of this row's mask below this lane's column
-template <int DG>
-__device__ __forceinline__ int rank_in_mask(typename MaskOf<DG>::type m, uint64_t wave_mask, int sub) {
-    const int below = __builtin_amdgcn_mbcnt_hi((uint32_t)(wave_mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)wave_mask, 0));
-    if constexpr (DG == 64) return below;
-    else return sub ? below - __popc((uint32_t)wave_mask) : below;
 }
 
 // ---- CSR views -------------------------------------------------------------------------------
@@ -807,17 +760,6 @@ __device__ __forceinline__ float row_records(const CsrView& g, const T* __restri
     if (ok) { e0 = g.rp[row]; e1 = g.rp[row + 1]; }
     const bool hub = (e1 - e0) > g.hub_threshold;
     float acc = gather_records<DG, T>(g, vals, masks, k, e0, hub ? e0 : e1, c);
-    if (hub) acc = hub_row_sum<DG>(g, hub_part, row, c);
-    return acc;
-}
-
-template <int DG, typename T>
-__device__ __forceinline__ float row_dense(const CsrView& g, const T* __restrict__ x, int64_t ld,
-                                           const float* __restrict__ hub_part, int row, bool ok, int c) {
-    int e0 = 0, e1 = 0;
-    if (ok) { e0 = g.rp[row]; e1 = g.rp[row + 1]; }
-    const bool hub = (e1 - e0) > g.hub_threshold;
-    float acc = gather_dense<DG, T>(g, x, ld, e0, hub ? e0 : e1, c);
     if (hub) acc = hub_row_sum<DG>(g, hub_part, row, c);
     return acc;
 }

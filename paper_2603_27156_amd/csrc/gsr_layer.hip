@@ -579,11 +579,6 @@ struct Ctx {
         r.mask = saved ? saved + ((size_t)layer * cfg->c + slot) * (size_t)cfg->n : (M*)(ws + lw.rec_mask[slot]);
         return r;
     }
-    int kpl() const {
-        int l = 0;
-        while ((1 << l) < cfg->k) ++l;
-        return l;
-    }
     T* y0() const { return (T*)(ws + lw.y0); }
     float* dw_partial() const { return (float*)(ws + lw.dw_partial); }
     float* hub_part() const { return (float*)(ws + lw.hub_partial); }
