@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the GSR-GNN training step (forward + inverse recomputation + backward) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg2-bf16|cfg4] [--layers L] [--save-indices]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg2-bf16|cfg4|dense] [--layers L] [--k K] [--save-indices]
 
 A "step" is one gsr_step call: L grouped reversible layers forward, head + loss, and the backward
 sweep that rebuilds every layer input instead of storing it.  Inputs are synthetic (seeded circuit
@@ -57,9 +57,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override L")
+    ap.add_argument("--k", type=int, default=0, help="override k (sweep over the paper's K = 4 ... 64)")
     ap.add_argument("--max-workgroups", type=int, default=0, help="override the persistent grid (multiple of 8)")
     ap.add_argument("--save-indices", action="store_true",
                     help="keep the forward sweep's column masks for the inverse (memory grows with L)")
+    ap.add_argument("--hub-threshold", type=int, default=0, help="rows longer than this are reduced in two passes")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events in the timed region")
     args = ap.parse_args()
@@ -78,14 +80,18 @@ def main() -> int:
     gsr.lib()
     dev = torch.device("cuda:0")
 
-    idx = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg2-bf16": 2, "cfg4": 4}[args.workload]
+    idx = {"cfg0": 0, "cfg1": 1, "cfg2": 2, "cfg2-bf16": 2, "cfg4": 4, "dense": 5}[args.workload]
     w = synth.workload(idx)
     if args.workload == "cfg2-bf16":
         w = synth.workload(2, dtype="bf16", name="cfg2-1M-bf16")
     if args.layers > 0:
         w = synth.workload(idx, l=args.layers, dtype=w.dtype, name=w.name)
+    if args.k > 0:
+        w = synth.workload(idx, l=w.l, dtype=w.dtype, name=f"{w.name}-k{args.k}", k=args.k)
     if args.max_workgroups:
         gsr.gsr_set_option("max_workgroups", args.max_workgroups)
+    if args.hub_threshold:
+        gsr.gsr_set_option("hub_threshold", args.hub_threshold)
     t_gen = time.time()
     inp = synth.make_inputs(w, 0)
     g = gsr.gsr_graph_create(inp.rowptr, inp.colidx)

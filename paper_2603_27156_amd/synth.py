@@ -58,6 +58,11 @@ WORKLOADS = {
                    256, 4, 448, 16, "rms", "f32"),
     4: GsrWorkload("cfg4-8M", 8_000_000, 4_000, (0.25, 0.25, 0.25, 0.25), 1.1, 8, 50_000,
                    256, 8, 112, 8, "rms", "bf16", True),
+    # Shaped like the graphs of the paper's Table 1 / Table 2 (about 50k nodes, 12M edges: mean degree
+    # about 246; 100 layers, 384 channels): the regime where the neighbour gather dominates.  Used for
+    # the sweep over k.  384 channels as 6 groups of 64 (the paper runs C = 2).
+    5: GsrWorkload("dense-50k", 49_600, 50, tuple([1.0 / 245.0] * 245), None, 0, 0,
+                   384, 6, 100, 16, "rms", "f32"),
 }
 
 
