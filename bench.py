@@ -155,6 +155,37 @@ def main() -> int:
         for k in cand:
             kernels[k]["algorithmic_GBps"] = ab[k] / (cand[k]["avg_us"] * 1e-6) / 1e9
 
+    # the operators exposed on their own, on one group plane of the same workload (outside the timed step)
+    operators = None
+    if w.dg in (32, 64) and not args.no_profile:
+        def avg_us(f, reps=5):
+            f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps * 1e3
+        plane = x0[0].float().contiguous()                         # [n, dg]
+        row, nnz = w.dg * 4, info["nnz"]
+        csr = nnz * 8 + w.n * 4
+        t_spmm = avg_us(lambda: gsr.gsr_spmm(g, plane))
+        t_gs = avg_us(lambda: gsr.gsr_group_sparse(plane, w.k, cfg.norm))
+        vv, ii = gsr.gsr_group_sparse(plane, w.k, cfg.norm)
+        t_agg = avg_us(lambda: gsr.gsr_spmm_compressed(g, vv, ii, w.dg))
+        def entry(us, nbytes):
+            return {"avg_us": us, "algorithmic_GBps": nbytes / (us * 1e-6) / 1e9, "frac_of_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        operators = {
+            "gsr_spmm": entry(t_spmm, w.n * 2 * row + csr),
+            "gsr_group_sparse": entry(t_gs, w.n * (row + w.k * 8)),
+            "gsr_spmm_compressed": entry(t_agg, w.n * (w.k * 8 + row) + csr),
+            "note": "float32, one group plane [n, dg]; compulsory bytes; gsr_spmm_compressed includes the conversion of "
+                    "(V, I int32) into records, its index check and one host synchronisation",
+        }
+        del plane, vv, ii
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
@@ -181,7 +212,7 @@ def main() -> int:
         "config": {"workload": w.name, "n": w.n, "nnz": info["nnz"], "max_degree": info["max_degree"], "d": w.d,
                    "c": w.c, "k": w.k, "l": w.l, "norm": w.norm, "hub_rows": info["n_hub_rows"],
                    "save_indices": bool(args.save_indices)},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "kernels": kernels, "operators": operators,
         "peak_hbm_bytes": int(torch.cuda.max_memory_allocated()), "workspace_bytes": int(ws_bytes),
         "loss": float(loss.item()), "x0_rebuild_max_abs_err": rebuilt_err, "setup_seconds": t_gen,
     }

@@ -420,6 +420,11 @@ gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const v
         if (symmetric) g->at = g->a;
         else st = upload_csr(t, n, options().hub_threshold, options().hub_chunk, &g->at);
     }
+    if (st == GSR_OK) {
+        const size_t chunks = (size_t)std::max(std::max(g->a.hub.n_chunks, g->at.hub.n_chunks), 1);
+        e = hipMalloc((void**)&g->scratch, chunks * 64 * sizeof(float));
+        if (e != hipSuccess) st = fail(GSR_ERR_HIP, "hipMalloc: %s", hipGetErrorString(e));
+    }
     if (st == GSR_OK && (flags & GSR_GRAPH_GCN_NORM)) st = gsr_graph_normalize(g, GSR_ADJ_GCN_SYM, stream);
     if (st == GSR_OK) {
         e = hipStreamSynchronize((hipStream_t)stream);
@@ -472,6 +477,7 @@ gsr_status_t gsr_graph_destroy(gsr_graph_t* g) {
     if (!g) return GSR_OK;
     if (!g->symmetric) free_csr(g->at);
     free_csr(g->a);
+    if (g->scratch) (void)hipFree(g->scratch);
     delete g;
     return GSR_OK;
 }

@@ -91,6 +91,7 @@ struct gsr_graph {
     int device = 0;
     int num_cus = 256;
     int grid = 512;          // workgroups of the persistent row-tile kernels (multiple of 8)
+    float* scratch = nullptr; // device [max(chunks of A, chunks of A^T, 1)][64]: first-pass sums of split rows for gsr_spmm
 };
 
 namespace gsr {

@@ -21,146 +21,6 @@ namespace gsr {
 
 CsrView make_view(const gsr_graph_t* g, bool transpose);
 
-// Compressed record of a row ("CBSR" of Section 4.3): the k kept values in ascending column
-// order (already RMS-scaled) and the row's column bit mask.
-template <int DG, typename T>
-struct Record {
-    using M = typename MaskOf<DG>::type;
-    T* vals;        // [n][k]
-    M* mask;        // [n]
-};
-
-// Bits of the quarter's columns that belong to the row's k largest entries (x: the quarter's QW
-// values; valid: the row exists; q: the quarter).  All four lanes of a row must call it together.
-template <int DG, int KS>
-__device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int k, bool valid, int q) {
-    constexpr int QW = DG / 4;
-    uint32_t key[QW];
-    uint32_t top = 0u;
-#pragma unroll
-    for (int j = 0; j < QW; ++j) {
-        const uint32_t u = __float_as_uint(x[j]);
-        uint32_t kk = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
-        kk = kk == 0x7FFFFFFFu ? 0x80000000u : kk;          // -0 -> +0
-        key[j] = kk >> KS;
-        top = max(top, key[j]);
-    }
-    top = quarter_max(top);
-    auto count_ge = [&](uint32_t t) {
-        uint32_t cnt = 0u;
-#pragma unroll
-        for (int j = 0; j < QW; ++j) cnt += key[j] >= t ? 1u : 0u;
-        return quarter_sum(cnt);
-    };
-    constexpr uint32_t span = (4u << 23) >> KS;
-    const uint32_t uk = (uint32_t)k;
-    uint32_t lo = top > span ? top - span : 0u, hi = top + 1u;
-    {
-        const uint32_t cnt = count_ge(lo);
-        lo = (cnt >= uk && k < DG) ? lo : 0u;
-        uint32_t open = (cnt != uk && k < DG && valid) ? 1u : 0u;
-        for (int round = 0; round < 33 && ballot(open != 0u) != 0ull; ++round) {
-            const uint32_t mid = lo + ((hi - lo) >> 1);
-            const uint32_t c2 = count_ge(mid);
-            lo = c2 >= uk ? mid : lo;
-            hi = c2 >= uk ? hi : mid;
-            open = (c2 == uk || hi - lo <= 1u) ? 0u : open;
-        }
-    }
-    // column sets of this quarter: above the threshold, at the threshold
-    uint32_t mgt = 0u, meq = 0u;
-#pragma unroll
-    for (int j = 0; j < QW; ++j) {
-        mgt |= key[j] > lo ? 1u << j : 0u;
-        meq |= key[j] == lo ? 1u << j : 0u;
-    }
-    uint32_t msel;
-    {
-        const uint32_t cg = __popc(mgt), ce = __popc(meq);
-        uint32_t all[4];
-        quarter_all(cg | ce << 8, all);
-        const int need = k - (int)((all[0] & 255u) + (all[1] & 255u) + (all[2] & 255u) + (all[3] & 255u));
-        int before = 0;   // ties in lower quarters
-#pragma unroll
-        for (int i = 0; i < 3; ++i) before += i < q ? (int)(all[i] >> 8) : 0;
-        int take = min(max(need - before, 0), (int)ce);
-        if (ballot(take != (int)ce) == 0ull) {
-            msel = mgt | meq;
-        } else {
-            msel = mgt;
-#pragma unroll
-            for (int j = 0; j < QW; ++j) {
-                const uint32_t s = ((meq >> j) & 1u) & (take > 0 ? 1u : 0u);
-                msel |= s << j;
-                take -= (int)s;
-            }
-        }
-    }
-    return msel;
-}
-
-// GS of the 16 rows of an LDS tile and their records (Section 4.1; record layout of Section 4.3).
-// st holds the rows as they read back from memory (16 x (DG+1) floats, rows past the end zero).
-// Lane (r, q) takes the quarter q of row r into registers, so the 16 searches for the k-th largest
-// key run side by side in vector registers: interval bisection on an order-preserving integer
-// image of the values, count = own compares + the three partner quarters.  Invariant per row: at
-// least k keys are >= lo and fewer than k are >= hi; hi starts just above the row maximum, lo four
-// binades below it (0 when a count says that is too high).  A row closes when a candidate splits
-// off exactly k keys or the interval is down to one value (a tie at the k-th position); ties go
-// to the lowest columns, -0 equals +0.  The kept values (RMS-scaled) are compacted in LDS in
-// column order and leave as one contiguous block, since rows r0..r0+15 are adjacent in [n][k].
-// With `given` the column set is not searched for: out.mask already holds the set an earlier
-// application selected (Section 4.2 keeps the indices of the forward pass) and only the values
-// are taken, from the present rows.  st is overwritten.
-template <int DG, typename T>
-__device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int norm, float eps, const Record<DG, T>& out,
-                                          bool given, int lane) {
-    using M = typename MaskOf<DG>::type;
-    constexpr int QW = DG / 4, LR = DG + 1;
-    constexpr int KS = sizeof(T) == 2 ? 16 : 0;   // bf16 values: the low 16 key bits are zero
-    const int r = lane & 15, q = lane >> 4;
-    float x[QW];
-#pragma unroll
-    for (int j = 0; j < QW; ++j) x[j] = st[r * LR + q * QW + j];
-    uint32_t msel;
-    if (given) {
-        const M m = out.mask[r0 + r < n ? r0 + r : n - 1];
-        msel = (uint32_t)(m >> (QW * q)) & ((1u << QW) - 1u);
-    } else {
-        msel = select_quarter<DG, KS>(x, k, r0 + r < n, q);
-    }
-    uint32_t all[4];
-    quarter_all(msel | (uint32_t)__popc(msel) << 16, all);
-    int slot = r * k;
-#pragma unroll
-    for (int i = 0; i < 3; ++i) slot += i < q ? (int)(all[i] >> 16) : 0;
-    M mask;
-    if constexpr (DG == 64)
-        mask = (M)(all[0] & 0xFFFFu) | (M)(all[1] & 0xFFFFu) << 16 | (M)(all[2] & 0xFFFFu) << 32 | (M)(all[3] & 0xFFFFu) << 48;
-    else
-        mask = (all[0] & 0xFFu) | (all[1] & 0xFFu) << 8 | (all[2] & 0xFFu) << 16 | (all[3] & 0xFFu) << 24;
-    float scale = 1.f;
-    if (norm == GSR_NORM_RMS) {
-        float ss = 0.f;
-#pragma unroll
-        for (int j = 0; j < QW; ++j) ss += x[j] * x[j];
-        ss = quarter_sum(ss);
-        scale = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + eps);
-    }
-    wave_sync();   // every lane holds its quarter: the tile can be reused for the compacted values
-#pragma unroll
-    for (int j = 0; j < QW; ++j) {
-        const uint32_t bit = (msel >> j) & 1u;
-        st[bit ? slot : 16 * LR + lane] = x[j] * scale;      // dropped columns go to the dump words
-        slot += (int)bit;
-    }
-    wave_sync();
-    const int rows = min(16, n - r0), total = rows * k;
-    T* dst = out.vals + (size_t)r0 * k;
-    for (int i = lane; i < total; i += 64) dst[i] = from_float<T>(st[i]);
-    if (!given && q == 0 && r < rows) out.mask[r0 + r] = mask;
-}
-
 // per-wave LDS: tile(s) of 16 x (DG+1) floats, 64 staged edges, 17 row pointers
 template <int DG, int TILES>
 struct WaveLds {

@@ -64,70 +64,180 @@ __global__ __launch_bounds__(256) void k_spmm_dense(CsrView g, int64_t n, const 
     }
 }
 
+// ---- the same operators on 16-row tiles (the forms the layer kernels use) -------------------------
+// One wave per tile in a persistent sweep; neighbour data gathered as MFMA products (see
+// gsr_device.h), results stored straight from the accumulators: lane (g, j) holds rows
+// 4 g + reg and the CPL adjacent columns CPL j .. CPL j + CPL - 1, so every store instruction
+// writes four whole rows.
+struct TileLds {
+    EdgeRec ebuf[64];
+    int rp[20];
+    uint8_t rbuf[64];
+};
+
+template <int W>
+__device__ __forceinline__ void store_acc_rows(const f32x4 (&acc)[W / 16], const CsrView& g, const float* __restrict__ hub_part,
+                                               bool has_hub, int r0, int n, const int* s_rp, float* __restrict__ y,
+                                               int64_t ldy, int lane) {
+    constexpr int CPL = W / 16;
+#pragma unroll
+    for (int reg = 0; reg < 4; ++reg) {
+        const int rr = 4 * (lane >> 4) + reg, row = r0 + rr;
+        float v[CPL];
+#pragma unroll
+        for (int cb = 0; cb < CPL; ++cb) v[cb] = acc[cb][reg];
+        const bool split = has_hub && (s_rp[rr + 1] - s_rp[rr]) > g.hub_threshold;     // written below instead
+        if (row < n && !split) store_cols<CPL, float>(y + (size_t)row * ldy + CPL * (lane & 15), v);
+    }
+    if (has_hub) {
+        for (int r = 0; r < 16; ++r) {
+            const bool hub = (s_rp[r + 1] - s_rp[r]) > g.hub_threshold;
+            if (hub && lane < W) y[(size_t)(r0 + r) * ldy + lane] = hub_row_sum<W>(g, hub_part, r0 + r, lane);
+        }
+    }
+}
+
+template <int W>
+__global__ __launch_bounds__(256) void k_spmm_tile(CsrView g, int n, int tiles, const float* __restrict__ x, int64_t ldx,
+                                                   float* __restrict__ y, int64_t ldy, const float* __restrict__ hub_part) {
+    __shared__ TileLds lds[4];
+    TileLds& L = lds[threadIdx.x >> 6];
+    const int lane = lane_id();
+    const TileSweep ts = tile_sweep(tiles);
+    for (int t = ts.first; t < ts.end; t += ts.step) {
+        const int r0 = t * 16;
+        wave_sync();
+        const bool has_hub = tile_begin(g, r0, n, L.rp, lane);
+        f32x4 acc[W / 16];
+#pragma unroll
+        for (int cb = 0; cb < W / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        tile_ranges(g, has_hub, L.rp, [&](int e_a, int e_b) {
+            gather_dense_mfma<W, float, 16>(g, x, ldx, __builtin_amdgcn_readfirstlane(e_a), __builtin_amdgcn_readfirstlane(e_b),
+                                            L.rp, L.ebuf, lane, acc);
+        });
+        store_acc_rows<W>(acc, g, hub_part, has_hub, r0, n, L.rp, y, ldy, lane);
+    }
+}
+
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_aggregate_tile(CsrView g, int n, int tiles, const T* __restrict__ vals,
+                                                        const typename MaskOf<DG>::type* __restrict__ masks, int k,
+                                                        const float* __restrict__ hub_part, float* __restrict__ h_out) {
+    __shared__ TileLds lds[4];
+    TileLds& L = lds[threadIdx.x >> 6];
+    const int lane = lane_id();
+    const TileSweep ts = tile_sweep(tiles);
+    for (int t = ts.first; t < ts.end; t += ts.step) {
+        const int r0 = t * 16;
+        wave_sync();
+        const bool has_hub = tile_begin(g, r0, n, L.rp, lane);
+        f32x4 acc[DG / 16];
+#pragma unroll
+        for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        tile_ranges(g, has_hub, L.rp, [&](int e_a, int e_b) {
+            gather_records_mfma<DG, T, 8>(g, vals, masks, k, __builtin_amdgcn_readfirstlane(e_a),
+                                          __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
+                                          lane, acc);
+        });
+        store_acc_rows<DG>(acc, g, hub_part, has_hub, r0, n, L.rp, h_out, DG, lane);
+    }
+}
+
+// GS of 16 rows per wave: rows are read four at a time into an LDS tile, then selected in the
+// quarter layout (emit_tile), values and column numbers leave as contiguous blocks.
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_gs_tile(const T* __restrict__ x, int n, int64_t ld, int k, int norm, float eps,
+                                                 T* __restrict__ vals, int32_t* __restrict__ idx) {
+    constexpr int LR = DG + 1, CPL = DG / 16;
+    struct Wave {
+        float st[16 * LR + 64];
+        int ist[16 * DG];
+    };
+    __shared__ Wave lds[4];
+    Wave& L = lds[threadIdx.x >> 6];
+    const int lane = lane_id(), tg = lane >> 4, tj = lane & 15;
+    const int nwaves = (gridDim.x * blockDim.x) >> 6, tiles = (n + 15) / 16;
+    Record<DG, T> out;
+    out.vals = vals;
+    out.mask = nullptr;
+    for (int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; t < tiles; t += nwaves) {
+        const int r0 = t * 16;
+        float v[4][CPL];
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) {
+            const int row = r0 + 4 * reg + tg;
+            load_cols<CPL, T>(x + (size_t)(row < n ? row : n - 1) * ld + CPL * tj, v[reg]);
+        }
+        wave_sync();          // the previous tile's results have left the scratch
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg)
+#pragma unroll
+            for (int cb = 0; cb < CPL; ++cb)
+                L.st[(4 * reg + tg) * LR + CPL * tj + cb] = r0 + 4 * reg + tg < n ? v[reg][cb] : 0.f;
+        wave_sync();
+        emit_tile<DG, T>(L.st, r0, n, k, norm, eps, out, false, lane, idx, L.ist);
+    }
+}
+
 // ---- (V, I int32, any slot order) -> record (values in ascending column order + column mask) -----
+// kp lanes per row (kp: the power of two at or above k), 64 / kp rows per wave step, so that the
+// [n][k] arrays are read and written in whole rows.  The row's mask is the OR over its lanes;
+// a column outside [0, DG) or named twice sets *bad (the caller's indices are not trusted).
 template <int DG, typename T>
-__global__ void k_pack_records(int64_t n, int k, const T* __restrict__ v_in, const int32_t* __restrict__ i_in,
-                               T* __restrict__ v_out, typename MaskOf<DG>::type* __restrict__ m_out) {
+__global__ __launch_bounds__(256) void k_pack_records(int64_t n, int k, int kp, const T* __restrict__ v_in,
+                                                      const int32_t* __restrict__ i_in, T* __restrict__ v_out,
+                                                      typename MaskOf<DG>::type* __restrict__ m_out, int* __restrict__ bad) {
     using M = typename MaskOf<DG>::type;
-    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= n) return;
-    M mask = 0;
-    for (int t = 0; t < k; ++t) mask |= (M)1 << i_in[row * k + t];
-    for (int t = 0; t < k; ++t) {
-        const int col = i_in[row * k + t];
-        v_out[row * k + popc<DG>(mask & (((M)1 << col) - 1))] = v_in[row * k + t];
-    }
-    m_out[row] = mask;
-}
-
-template <int DG>
-__global__ void k_check_indices(int64_t n, int k, const int32_t* __restrict__ idx, int* __restrict__ bad) {
-    const int64_t row = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (row >= n) return;
-    uint64_t mask = 0;
-    for (int t = 0; t < k; ++t) {
-        const int col = idx[row * k + t];
-        if (col < 0 || col >= DG || ((mask >> col) & 1)) { *bad = 1; return; }
-        mask |= (uint64_t)1 << col;
-    }
-}
-
-template <int DG, typename T>
-__global__ __launch_bounds__(256) void k_aggregate(CsrView g, int n, const T* __restrict__ vals,
-                                                   const typename MaskOf<DG>::type* __restrict__ masks, int k,
-                                                   const float* __restrict__ hub_part, float* __restrict__ h_out) {
-    constexpr int G = 64 / DG;
-    const int lane = lane_id(), c = lane % DG, sub = lane / DG;
-    const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    for (int r0 = ((blockIdx.x * blockDim.x + threadIdx.x) >> 6) * G; r0 < n; r0 += nwaves * G) {
-        const int row = r0 + sub;
-        const bool ok = row < n;
-        const float acc = row_records<DG, T>(g, vals, masks, k, hub_part, row, ok, c);
-        if (ok) h_out[(size_t)row * DG + c] = acc;
+    const int lane = lane_id(), t = lane % kp, sub = lane / kp, per = 64 / kp;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t r0 = (((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6) * per; r0 < n; r0 += nwaves * per) {
+        const int64_t row = r0 + sub;
+        const bool ok = row < n && t < k;
+        const int col = ok ? i_in[row * k + t] : 0;
+        const bool in_range = col >= 0 && col < DG;
+        const M bit = (ok && in_range) ? (M)1 << col : (M)0;
+        uint32_t lo = (uint32_t)bit, hi = DG == 64 ? (uint32_t)((uint64_t)bit >> 32) : 0u;
+        for (int off = 1; off < kp; off <<= 1) {
+            lo |= (uint32_t)__shfl_xor((int)lo, off, 64);
+            if (DG == 64) hi |= (uint32_t)__shfl_xor((int)hi, off, 64);
+        }
+        const M mask = DG == 64 ? (M)(((uint64_t)hi << 32) | lo) : (M)lo;
+        if (ok && (!in_range || popc<DG>(mask) != k)) *bad = 1;
+        if (ok && in_range) v_out[row * k + popc<DG>(mask & (bit - 1))] = v_in[row * k + t];
+        if (row < n && t == 0) m_out[row] = mask;
     }
 }
 
 template <int DG, typename T>
 static gsr_status_t aggregate_impl(const gsr_graph_t* g, const void* vals, const int32_t* idx, int k, float* h_out,
-                                   void* ws, hipStream_t s) {
+                                   void* ws, int* bad, hipStream_t s) {
     using M = typename MaskOf<DG>::type;
     const int64_t n = g->n;
     char* p = (char*)ws;
     T* v_rec = (T*)p;
-    p += align_up((size_t)n * k * sizeof(T));
+    p += align_up((size_t)n * k * sizeof(T) + 16);          // the record gather loads up to 16 bytes past a record
     M* m_rec = (M*)p;
     p += align_up((size_t)n * sizeof(M));
     float* part = (float*)p;
-    const unsigned rows_blocks = (unsigned)((n + 255) / 256);
-    hipLaunchKernelGGL((k_pack_records<DG, T>), dim3(rows_blocks), dim3(256), 0, s, n, k, (const T*)vals, idx, v_rec, m_rec);
+    // indices come from the caller: reject out-of-range or repeated columns instead of reading wild
+    int kp = 1;
+    while (kp < k) kp <<= 1;
+    const int64_t steps = (n + 64 / kp - 1) / (64 / kp);
+    GSR_HIP_CHECK(hipMemsetAsync(bad, 0, sizeof(int), s));
+    hipLaunchKernelGGL((k_pack_records<DG, T>), dim3((unsigned)std::min<int64_t>((steps + 3) / 4, 16384)), dim3(256), 0, s, n, k,
+                       kp, (const T*)vals, idx, v_rec, m_rec, bad);
+    int bad_h = 0;
+    GSR_HIP_CHECK(hipMemcpyAsync(&bad_h, bad, sizeof(int), hipMemcpyDeviceToHost, s));
+    GSR_HIP_CHECK(hipStreamSynchronize(s));
+    if (bad_h) return fail(GSR_ERR_INVALID_ARG, "idx holds a column outside [0,dg) or a repeated column");
     CsrView v = make_view(g, false);
     if (g->a.hub.n_chunks > 0) {
         HubChunks hc{g->a.hub.ce0, g->a.hub.ce1, g->a.hub.n_chunks};
         hipLaunchKernelGGL((k_hub_records<DG, T>), dim3((unsigned)std::min(g->a.hub.n_chunks, 4096)), dim3(256), 0, s, v, hc,
                            (const T*)v_rec, (const M*)m_rec, k, part);
     }
-    hipLaunchKernelGGL((k_aggregate<DG, T>), dim3((unsigned)g->grid * 2), dim3(256), 0, s, v, (int)n, (const T*)v_rec,
-                       (const M*)m_rec, k, (const float*)part, h_out);
+    hipLaunchKernelGGL((k_aggregate_tile<DG, T>), dim3((unsigned)g->grid), dim3(256), 0, s, v, (int)n, (int)((n + 15) / 16),
+                       (const T*)v_rec, (const M*)m_rec, k, (const float*)part, h_out);
     GSR_HIP_CHECK(hipGetLastError());
     return GSR_OK;
 }
@@ -149,6 +259,26 @@ gsr_status_t gsr_group_sparse(const void* x, int64_t n, int32_t dg, int64_t ld, 
     if (n == 0) return GSR_OK;
     if (!x || !vals_out || !idx_out) return fail(GSR_ERR_INVALID_ARG, "null pointer");
     hipStream_t s = (hipStream_t)stream;
+    // whole groups of 32 or 64 columns with rows that can be moved in aligned pieces: 16 rows per wave
+    const size_t piece = (size_t)(dg / 16) * dtype_size(dtype);
+    if ((dg == 32 || dg == 64) && n < ((int64_t)1 << 31) && ((size_t)ld * dtype_size(dtype)) % piece == 0 &&
+        ((uintptr_t)x % piece) == 0) {
+        const unsigned tb = (unsigned)std::min<int64_t>((n + 63) / 64, 4096);
+        if (dtype == GSR_F32 && dg == 64)
+            hipLaunchKernelGGL((k_gs_tile<64, float>), dim3(tb), dim3(256), 0, s, (const float*)x, (int)n, ld, k, norm, eps,
+                               (float*)vals_out, idx_out);
+        else if (dtype == GSR_F32)
+            hipLaunchKernelGGL((k_gs_tile<32, float>), dim3(tb), dim3(256), 0, s, (const float*)x, (int)n, ld, k, norm, eps,
+                               (float*)vals_out, idx_out);
+        else if (dg == 64)
+            hipLaunchKernelGGL((k_gs_tile<64, bf16_t>), dim3(tb), dim3(256), 0, s, (const bf16_t*)x, (int)n, ld, k, norm, eps,
+                               (bf16_t*)vals_out, idx_out);
+        else
+            hipLaunchKernelGGL((k_gs_tile<32, bf16_t>), dim3(tb), dim3(256), 0, s, (const bf16_t*)x, (int)n, ld, k, norm, eps,
+                               (bf16_t*)vals_out, idx_out);
+        GSR_HIP_CHECK(hipGetLastError());
+        return GSR_OK;
+    }
     const unsigned blocks = (unsigned)std::min<int64_t>((n + 3) / 4, 8192);
     if (dtype == GSR_F32)
         hipLaunchKernelGGL((k_group_sparse<float>), dim3(blocks), dim3(256), 0, s, (const float*)x, n, dg, ld, k, norm, eps,
@@ -167,16 +297,40 @@ gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t
     if (ldx < width || ldy < width) return fail(GSR_ERR_INVALID_ARG, "row stride below width");
     if (g->n == 0) return GSR_OK;
     if (!x || !y) return fail(GSR_ERR_INVALID_ARG, "null pointer");
+    if (transpose && !g->has_transpose) return fail(GSR_ERR_UNSUPPORTED, "graph has no transpose");
+    hipStream_t s = (hipStream_t)stream;
+    const CsrView view = make_view(g, transpose != 0);
+    // 32 or 64 columns with aligned rows: 16-row tiles on the matrix cores; split rows go through a
+    // first pass into the graph's own scratch
+    const size_t piece = (size_t)(width / 16) * sizeof(float);
+    if ((width == 32 || width == 64) && g->n < ((int64_t)1 << 31) && (ldx * sizeof(float)) % piece == 0 &&
+        (ldy * sizeof(float)) % piece == 0 && ((uintptr_t)x % piece) == 0 && ((uintptr_t)y % piece) == 0 && g->scratch) {
+        const HubPlan& h = transpose ? g->at.hub : g->a.hub;
+        const int tiles = (int)((g->n + 15) / 16);
+        if (h.n_chunks > 0) {
+            HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+            const dim3 hg((unsigned)std::min((h.n_chunks + 3) / 4, 4096));
+            if (width == 64) hipLaunchKernelGGL((k_hub_dense<64, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
+            else hipLaunchKernelGGL((k_hub_dense<32, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
+        }
+        if (width == 64)
+            hipLaunchKernelGGL((k_spmm_tile<64>), dim3((unsigned)g->grid), dim3(256), 0, s, view, (int)g->n, tiles, x, ldx, y, ldy,
+                               (const float*)g->scratch);
+        else
+            hipLaunchKernelGGL((k_spmm_tile<32>), dim3((unsigned)g->grid), dim3(256), 0, s, view, (int)g->n, tiles, x, ldx, y, ldy,
+                               (const float*)g->scratch);
+        GSR_HIP_CHECK(hipGetLastError());
+        return GSR_OK;
+    }
     const unsigned blocks = (unsigned)std::min<int64_t>((g->n + 3) / 4, 8192);
-    hipLaunchKernelGGL(k_spmm_dense, dim3(blocks), dim3(256), 0, (hipStream_t)stream, make_view(g, transpose != 0), g->n, x,
-                       ldx, width, y, ldy);
+    hipLaunchKernelGGL(k_spmm_dense, dim3(blocks), dim3(256), 0, s, view, g->n, x, ldx, width, y, ldy);
     GSR_HIP_CHECK(hipGetLastError());
     return GSR_OK;
 }
 
 size_t gsr_spmm_compressed_workspace(const gsr_graph_t* g, int32_t k, int32_t dg) {
     if (!g || k < 1 || dg < 1) return 0;
-    return align_up((size_t)g->n * k * 4) + align_up((size_t)g->n * 8) +
+    return align_up((size_t)g->n * k * 4 + 16) + align_up((size_t)g->n * 8) +
            align_up((size_t)std::max(g->a.hub.n_chunks, 1) * dg * sizeof(float)) + 256;
 }
 
@@ -188,23 +342,17 @@ gsr_status_t gsr_spmm_compressed(const gsr_graph_t* g, const void* vals, const i
     if (dtype != GSR_F32 && dtype != GSR_BF16) return fail(GSR_ERR_UNSUPPORTED, "dtype %d", dtype);
     if (g->n == 0) return GSR_OK;
     if (!vals || !idx || !h_out || !workspace) return fail(GSR_ERR_INVALID_ARG, "null pointer");
+    if ((uint64_t)g->n * (uint64_t)k >= ((uint64_t)1 << 32)) return fail(GSR_ERR_UNSUPPORTED, "n * k does not fit 32 bits");
+    if (((uintptr_t)workspace & 255) || ((uintptr_t)h_out & 15))
+        return fail(GSR_ERR_INVALID_ARG, "the workspace must be 256-byte aligned and h_out 16-byte aligned");
     if (workspace_bytes < gsr_spmm_compressed_workspace(g, k, dg))
         return fail(GSR_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < %zu", workspace_bytes, gsr_spmm_compressed_workspace(g, k, dg));
     hipStream_t s = (hipStream_t)stream;
-    // indices come from the caller: reject out-of-range or repeated columns instead of reading wild
     int* bad = (int*)((char*)workspace + gsr_spmm_compressed_workspace(g, k, dg) - 256);
-    GSR_HIP_CHECK(hipMemsetAsync(bad, 0, sizeof(int), s));
-    const unsigned rows_blocks = (unsigned)((g->n + 255) / 256);
-    if (dg == 32) hipLaunchKernelGGL((k_check_indices<32>), dim3(rows_blocks), dim3(256), 0, s, g->n, k, idx, bad);
-    else hipLaunchKernelGGL((k_check_indices<64>), dim3(rows_blocks), dim3(256), 0, s, g->n, k, idx, bad);
-    int bad_h = 0;
-    GSR_HIP_CHECK(hipMemcpyAsync(&bad_h, bad, sizeof(int), hipMemcpyDeviceToHost, s));
-    GSR_HIP_CHECK(hipStreamSynchronize(s));
-    if (bad_h) return fail(GSR_ERR_INVALID_ARG, "idx holds a column outside [0,dg) or a repeated column");
-    if (dg == 32 && dtype == GSR_F32) return aggregate_impl<32, float>(g, vals, idx, k, h_out, workspace, s);
-    if (dg == 64 && dtype == GSR_F32) return aggregate_impl<64, float>(g, vals, idx, k, h_out, workspace, s);
-    if (dg == 32) return aggregate_impl<32, bf16_t>(g, vals, idx, k, h_out, workspace, s);
-    return aggregate_impl<64, bf16_t>(g, vals, idx, k, h_out, workspace, s);
+    if (dg == 32 && dtype == GSR_F32) return aggregate_impl<32, float>(g, vals, idx, k, h_out, workspace, bad, s);
+    if (dg == 64 && dtype == GSR_F32) return aggregate_impl<64, float>(g, vals, idx, k, h_out, workspace, bad, s);
+    if (dg == 32) return aggregate_impl<32, bf16_t>(g, vals, idx, k, h_out, workspace, bad, s);
+    return aggregate_impl<64, bf16_t>(g, vals, idx, k, h_out, workspace, bad, s);
 }
 
 }  // extern "C"
