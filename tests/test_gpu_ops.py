@@ -124,6 +124,31 @@ def test_spmm_dense_and_transpose():
     assert np.allclose(out, b["OUT"], atol=5e-3)
 
 
+@pytest.mark.parametrize("width,hub_threshold", [(64, 512), (32, 512), (64, 6), (32, 5), (48, 6)])
+def test_spmm_dense_on_a_circuit_graph_with_split_rows(width, hub_threshold):
+    """The tiled path of gsr_spmm (widths 32 and 64) with rows above the threshold reduced in two
+    passes, a ragged last tile, and the row-per-wave path (width 48) on the same graph."""
+    gsr.gsr_set_option("hub_threshold", hub_threshold)
+    gsr.gsr_set_option("hub_chunk", 4 if hub_threshold < 100 else 64)
+    try:
+        w = synth.scaled(synth.workload(2), 6001)
+        rng = np.random.Generator(np.random.PCG64(2))
+        rp, ci = synth.circuit_dag(w, rng)
+        og = oracle.graph_build(rp, ci)
+        gg = gsr.gsr_graph_create(rp, ci)
+        X = rng.standard_normal((w.n, width)).astype(np.float32)
+        want = oracle.spmm(og, X)
+        xt = torch.from_numpy(X).to(dev())
+        assert_close("A X", gsr.gsr_spmm(gg, xt).cpu().numpy(), want)
+        assert_close("A^T X", gsr.gsr_spmm(gg, xt, transpose=True).cpu().numpy(), want)     # the matrix is symmetric
+        wide = torch.zeros((w.n, 2 * width + 16), dtype=torch.float32, device=dev())       # a column slice: row stride > width
+        wide[:, 16:16 + width] = xt
+        assert_close("A X (strided)", gsr.gsr_spmm(gg, wide[:, 16:16 + width]).cpu().numpy(), want)
+    finally:
+        gsr.gsr_set_option("hub_threshold", 512)
+        gsr.gsr_set_option("hub_chunk", 64)
+
+
 @pytest.mark.parametrize("dg,k,hub_threshold", [(64, 16, 512), (32, 8, 512), (64, 16, 6), (32, 8, 5)])
 def test_spmm_compressed(dg, k, hub_threshold):
     gsr.gsr_set_option("hub_threshold", hub_threshold)
@@ -148,6 +173,10 @@ def test_spmm_compressed(dg, k, hub_threshold):
         bad[17, 0] = dg
         with pytest.raises(gsr.GsrError):
             gsr.gsr_spmm_compressed(gg, torch.from_numpy(Vp).to(dev()), torch.from_numpy(bad).to(dev()), dg)
+        twice = Ip.copy()
+        twice[w.n - 1, 1] = twice[w.n - 1, 0]                            # a column named twice
+        with pytest.raises(gsr.GsrError):
+            gsr.gsr_spmm_compressed(gg, torch.from_numpy(Vp).to(dev()), torch.from_numpy(twice).to(dev()), dg)
     finally:
         gsr.gsr_set_option("hub_threshold", 512)
         gsr.gsr_set_option("hub_chunk", 64)
