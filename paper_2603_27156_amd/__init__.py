@@ -40,6 +40,11 @@ class GsrError(RuntimeError):
         self.status = status
 
 
+def gsr_last_error() -> str:
+    """Message of the last call that returned a status other than GSR_OK."""
+    return lib().gsr_last_error().decode()
+
+
 class gsr_config_t(C.Structure):
     _fields_ = [("n", C.c_int64), ("d", C.c_int32), ("c", C.c_int32), ("l", C.c_int32), ("k", C.c_int32),
                 ("dtype", C.c_int32), ("norm", C.c_int32), ("eps", C.c_float), ("layout", C.c_int32),

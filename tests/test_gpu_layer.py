@@ -247,3 +247,34 @@ def test_bf16_storage_variant():
     assert np.isclose(out["loss"], ref["loss"], rtol=BF16_REL)
     for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
         assert rel_norm(out[key], ref[key]) <= BF16_REL, (key, rel_norm(out[key], ref[key]))
+
+
+def test_layer_calls_reject_what_the_kernels_cannot_take():
+    """Error paths of the layer entry points: nothing is launched, a status and a message come back."""
+    c = case("cfg0", ROW)
+    w = c.w
+    Wd = torch.from_numpy(c.inp.weights[0]).to(c.dev)
+    x = c.to_dev(c.inp.x0)
+    need = gsr.gsr_workspace_size(c.gg, c.gcfg)[0]
+    before = x.clone()
+
+    def status_of(f):
+        with pytest.raises(gsr.GsrError) as e:
+            f()
+        return e.value.status
+
+    # rows are moved in 16-byte pieces: a plane that starts 4 bytes into an allocation is refused
+    flat = torch.zeros(w.n * w.d + 4, dtype=torch.float32, device=c.dev)
+    shifted = flat[1:1 + w.n * w.d].view(w.n, w.d)
+    assert status_of(lambda: gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, shifted)) == gsr.GSR_ERR_INVALID_ARG
+    # workspace: too small, and not 256-byte aligned
+    small = torch.empty(need - 256, dtype=torch.uint8, device=c.dev)
+    assert status_of(lambda: gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, x, workspace=small)) == gsr.GSR_ERR_WORKSPACE_TOO_SMALL
+    odd = torch.empty(need + 512, dtype=torch.uint8, device=c.dev)[64:]
+    assert status_of(lambda: gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, x, workspace=odd)) == gsr.GSR_ERR_INVALID_ARG
+    # configurations outside what is built
+    for bad in (dict(k=w.dg + 1), dict(c=3), dict(d=w.d + 2), dict(n=w.n + 1), dict(norm=7), dict(dtype=9)):
+        cfg = gsr.Config(**{**c.gcfg.__dict__, **bad})
+        assert status_of(lambda: gsr.gsr_layer_forward(c.gg, cfg, Wd, x)) in (gsr.GSR_ERR_UNSUPPORTED, gsr.GSR_ERR_INVALID_ARG)
+    assert torch.equal(x, before)            # none of the refused calls touched the plane
+    assert "" != gsr.gsr_last_error()
