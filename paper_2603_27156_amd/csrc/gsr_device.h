@@ -418,18 +418,24 @@ struct EdgeRec {
     int pad;
 };
 
-// Row pointers of the tile's 17 row boundaries (clamped at n) into s_rp.  Returns whether one of
-// the rows is a split ("hub") row.
-__device__ __forceinline__ bool tile_begin(const CsrView& g, int r0, int n, int* s_rp, int lane) {
+// Row pointer of row r0 + lane (clamped at n) for the 17 row boundaries of a tile, in lanes 0..16.
+// Split from tile_begin so that a kernel can request its other per-tile data before it waits.
+__device__ __forceinline__ int tile_rp_load(const CsrView& g, int r0, int n, int lane) {
     int rpv = 0;
-    if (lane < 17) {
-        const int row = r0 + lane < n ? r0 + lane : n;
-        rpv = g.rp[row];
-        s_rp[lane] = rpv;
-    }
+    if (lane < 17) rpv = g.rp[r0 + lane < n ? r0 + lane : n];
+    return rpv;
+}
+
+// Publishes the tile's row pointers (rpv as tile_rp_load returned it) in s_rp.  Returns whether
+// one of the rows is a split ("hub") row.
+__device__ __forceinline__ bool tile_begin(const CsrView& g, int rpv, int* s_rp, int lane) {
+    if (lane < 17) s_rp[lane] = rpv;
     wave_sync();
     const bool hub = lane < 16 && (s_rp[lane + 1] - rpv) > g.hub_threshold;
     return ballot(hub) != 0ull;
+}
+__device__ __forceinline__ bool tile_begin(const CsrView& g, int r0, int n, int* s_rp, int lane) {
+    return tile_begin(g, tile_rp_load(g, r0, n, lane), s_rp, lane);
 }
 
 // tile row of edge e: the last row boundary at or below e

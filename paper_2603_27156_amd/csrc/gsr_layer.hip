@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
     for (int t = ts.first; t < ts.end; t += ts.step) {
         const int r0 = t * 16;
         wave_sync();
-        const bool has_hub = tile_begin(a.g, r0, a.n, L.rp, lane);
+        const int rpv = tile_rp_load(a.g, r0, a.n, lane);
         // The tile's own rows (X_i, and dY_i for the weight gradient) are requested first, in the
         // tile register layout, and arrive while the neighbour records are gathered.
         float xy[4][CPL], gy[WITH_DW ? 4 : 1][CPL];
@@ -81,6 +81,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
             load_cols<CPL, T>(a.plane + rowc * a.ld + CPL * tj, xy[reg]);
             if constexpr (WITH_DW) load_cols<CPL, T>(a.dy + rowc * a.ldg + CPL * tj, gy[reg]);
         }
+        const bool has_hub = tile_begin(a.g, rpv, L.rp, lane);
         f32x4 hacc[DG / 16];
         tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, hacc, [&](int e_a, int e_b) {
             gather_records_mfma<DG, T, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
@@ -198,7 +199,7 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
     for (int t = ts.first; t < ts.end; t += ts.step) {
         const int r0 = t * 16;
         wave_sync();
-        const bool has_hub = tile_begin(a.gt, r0, a.n, L.rp, lane);
+        const int rpv = tile_rp_load(a.gt, r0, a.n, lane);
         // what the epilogue needs of the tile's own rows is requested first
         typename MaskOf<DG>::type own[4];
         float z[4][CPL];
@@ -209,6 +210,7 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
             own[reg] = a.own_mask[rowc];
             if (a.norm == GSR_NORM_RMS) load_cols<CPL, T>(a.z + rowc * a.ldz + CPL * tj, z[reg]);
         }
+        const bool has_hub = tile_begin(a.gt, rpv, L.rp, lane);
         f32x4 qacc[DG / 16];
         tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, qacc, [&](int e_a, int e_b) {
             gather_dense_mfma<DG, T, 16>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
