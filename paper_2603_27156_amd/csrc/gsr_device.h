@@ -411,6 +411,39 @@ __device__ __forceinline__ float group16_sum(float v) {
     return v;
 }
 
+// ---- bf16 operands for the gathers of the bf16-storage variant --------------------------------------
+// With 16-bit stored values the product P * X runs on v_mfma_f32_16x16x16_bf16: sixteen edges per
+// instruction instead of four.  The K index is permuted so that nothing has to move between
+// lanes: K slot 4 kk + u of lane group kk is edge kk of staged group u (u = 0..3), which is what
+// the lane already holds after four loads.  X is exact in bf16; a_ij is split into two bf16 terms
+// (a = hi + lo + O(2^-17 a)), one MFMA each, float32 accumulation.
+typedef short bf16x4 __attribute__((ext_vector_type(4)));
+
+// upper halves of four float32 words as four bf16
+__device__ __forceinline__ bf16x4 pack_upper4(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3) {
+    const uint32_t lo = __builtin_amdgcn_perm(w1, w0, 0x07060302u), hi = __builtin_amdgcn_perm(w3, w2, 0x07060302u);
+    return __builtin_bit_cast(bf16x4, (uint64_t)lo | ((uint64_t)hi << 32));
+}
+// lower halves of four words as four bf16
+__device__ __forceinline__ bf16x4 pack_lower4(uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3) {
+    const uint32_t lo = __builtin_amdgcn_perm(w1, w0, 0x05040100u), hi = __builtin_amdgcn_perm(w3, w2, 0x05040100u);
+    return __builtin_bit_cast(bf16x4, (uint64_t)lo | ((uint64_t)hi << 32));
+}
+// the selection operand of four groups as three bf16 terms: p = hi + mid + lo exactly
+__device__ __forceinline__ void split_p4(const float* p, bf16x4& hi, bf16x4& mid, bf16x4& lo) {
+    uint32_t h[4], m[4], l[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        h[u] = __float_as_uint(p[u]) & 0xFFFF0000u;
+        const float r1 = p[u] - __uint_as_float(h[u]);
+        m[u] = __float_as_uint(r1) & 0xFFFF0000u;
+        l[u] = __float_as_uint(r1 - __uint_as_float(m[u]));
+    }
+    hi = pack_upper4(h[0], h[1], h[2], h[3]);
+    mid = pack_upper4(m[0], m[1], m[2], m[3]);
+    lo = pack_upper4(l[0], l[1], l[2], l[3]);
+}
+
 struct EdgeRec {
     int j;      // neighbour (column of A)
     float a;    // a_ij
@@ -498,15 +531,28 @@ __device__ __forceinline__ void gather_dense_mfma(const CsrView& g, const T* __r
                 load_words<NW>(xl + (size_t)(uint32_t)er.j * ldu, w[u]);
                 p[u] = er.r == i16 ? er.a : 0.f;
             }
+            if constexpr (sizeof(T) == 4) {
 #pragma unroll
-            for (int u = 0; u < GB; ++u)
+                for (int u = 0; u < GB; ++u)
 #pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) {
-                    float b;
-                    if constexpr (sizeof(T) == 4) b = __uint_as_float(w[u][cb]);
-                    else b = __uint_as_float((cb & 1) ? (w[u][cb >> 1] & 0xFFFF0000u) : (w[u][cb >> 1] << 16));
-                    acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], b, acc[cb], 0, 0, 0);
+                    for (int cb = 0; cb < CPL; ++cb)
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], __uint_as_float(w[u][cb]), acc[cb], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int u = 0; u < GB; u += 4) {
+                    bf16x4 ph, pm, pl;
+                    split_p4(p + u, ph, pm, pl);
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) {
+                        const int d = cb >> 1;
+                        const bf16x4 b = (cb & 1) ? pack_upper4(w[u][d], w[u + 1][d], w[u + 2][d], w[u + 3][d])
+                                                  : pack_lower4(w[u][d], w[u + 1][d], w[u + 2][d], w[u + 3][d]);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ph, b, acc[cb], 0, 0, 0);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pm, b, acc[cb], 0, 0, 0);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl, b, acc[cb], 0, 0, 0);
+                    }
                 }
+            }
         });
     }
 }
@@ -573,6 +619,7 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
                 }
                 p[u] = (int)rbuf[ei] == i16 ? er.a : 0.f;
             }
+            uint32_t bq[sizeof(T) == 4 ? 1 : GB][CPL];   // dealt-out values (float bits) of the 16-bit variant
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
                 uint32_t q[CPL];  // the window (float bits): slot start + t
@@ -593,10 +640,25 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
 #pragma unroll
                 for (int cb = 0; cb < CPL; ++cb) {
                     const uint32_t m = (uint32_t)__builtin_amdgcn_sbfe((int)nib[u], cb, 1);
-                    const float b = __uint_as_float(q[0] & m);
+                    const uint32_t b = q[0] & m;
 #pragma unroll
                     for (int t = 0; t + 1 < CPL - cb; ++t) q[t] = bit_select(m, q[t + 1], q[t]);
-                    acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], b, acc[cb], 0, 0, 0);
+                    if constexpr (sizeof(T) == 4) acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], __uint_as_float(b), acc[cb], 0, 0, 0);
+                    else bq[u][cb] = b;
+                }
+            }
+            if constexpr (sizeof(T) != 4) {
+#pragma unroll
+                for (int u = 0; u < GB; u += 4) {
+                    bf16x4 ph, pm, pl;
+                    split_p4(p + u, ph, pm, pl);
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) {
+                        const bf16x4 b = pack_upper4(bq[u][cb], bq[u + 1][cb], bq[u + 2][cb], bq[u + 3][cb]);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ph, b, acc[cb], 0, 0, 0);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pm, b, acc[cb], 0, 0, 0);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl, b, acc[cb], 0, 0, 0);
+                    }
                 }
             }
         });
