@@ -935,6 +935,48 @@ __device__ __forceinline__ TileSweep tile_sweep(int tiles) {
     return t;
 }
 
+// Dynamic form of the sweep.  Tiles differ a lot in cost (a few rows have hundreds of neighbours),
+// and with a fixed assignment the kernel ends when the unluckiest wave does.  Here the tiles of an
+// XCD's eighth are dealt to nq = TILE_NQ queues (queue q owns tiles t0 + q + nq v); a wave serves
+// queue (its slot mod nq) and draws the queue's next tile from a counter, so a wave that drew
+// long rows draws fewer tiles.  The active window still moves through the rows in order.  Many
+// queues rather than one keep the atomics on different addresses: one counter for the 512 waves
+// of an XCD serialises and costs more than the balance gains.  The next draw is requested at
+// the start of a tile and read at its end.  Counters come in two sets: a launch counts in one
+// and clears the other for the launch after it (launches on one stream do not overlap), so no
+// separate clearing step is needed.  Which wave processes which tile varies between runs;
+// kernels that sum over the tiles a wave has seen must keep the fixed sweep.
+constexpr int TILE_NQ = 64, TILE_QSTRIDE = 32;              // counters sit 128 bytes apart
+constexpr int TILE_COUNTERS = 8 * TILE_NQ * TILE_QSTRIDE;   // ints per set (the host allocates kTileCounters)
+struct TileDraws {
+    int* ctr;      // this wave's queue counter
+    int base;      // first tile of the queue
+    int nq;        // queues in use: TILE_NQ, or the number of waves of the XCD if that is smaller
+    int end;       // one past the XCD's last tile
+};
+__device__ __forceinline__ TileDraws tile_draws(int tiles, int* set_now, int* set_next) {
+    const int xcd = blockIdx.x & 7;
+    const int slot = (blockIdx.x >> 3) * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int waves = (gridDim.x >> 3) * (blockDim.x >> 6);
+    TileDraws d;
+    d.nq = waves < TILE_NQ ? waves : TILE_NQ;
+    const int q = slot % d.nq, at = (xcd * TILE_NQ + q) * TILE_QSTRIDE;
+    d.ctr = set_now + at;
+    d.base = (int)((int64_t)tiles * xcd / 8) + q;
+    d.end = (int)((int64_t)tiles * (xcd + 1) / 8);
+    if (lane_id() == 0) set_next[at] = 0;
+    return d;
+}
+// requests a draw; the value is valid in lane 0 once the wave waits for it (tile_drawn)
+__device__ __forceinline__ int tile_request(const TileDraws& d) {
+    int v = 0;
+    if (lane_id() == 0) v = atomicAdd(d.ctr, 1);
+    return v;
+}
+__device__ __forceinline__ int tile_drawn(const TileDraws& d, int requested) {
+    return d.base + d.nq * __builtin_amdgcn_readfirstlane(requested);
+}
+
 // ---- first pass over the chunks of very long rows ------------------------------------------------
 // One wave per chunk.  With DG = 32 the two half-waves take alternate neighbours of the chunk and
 // their sums are added (lower half first).  part[chunk][DG] receives the un-scaled partial row.

@@ -215,6 +215,15 @@ static void transpose_host(int64_t n, const HostCsr& a, HostCsr* t) {
         }
 }
 
+// The two sets of tile counters of a graph alternate between launches: the one a launch counts in
+// was cleared by the launch before it (both are clear when the graph is created).
+void next_draw_sets(const gsr_graph_t* g, int** now, int** next) {
+    gsr_graph_t* m = const_cast<gsr_graph_t*>(g);
+    *now = m->draws + (size_t)m->draws_turn * kTileCounters;
+    m->draws_turn ^= 1;
+    *next = m->draws + (size_t)m->draws_turn * kTileCounters;
+}
+
 LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     LayerWs w;
     memset(&w, 0, sizeof(w));
@@ -423,6 +432,9 @@ gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const v
     if (st == GSR_OK) {
         const size_t chunks = (size_t)std::max(std::max(g->a.hub.n_chunks, g->at.hub.n_chunks), 1);
         e = hipMalloc((void**)&g->scratch, chunks * 64 * sizeof(float));
+        const size_t draw_bytes = (size_t)2 * kTileCounters * sizeof(int);
+        if (e == hipSuccess) e = hipMalloc((void**)&g->draws, draw_bytes);
+        if (e == hipSuccess) e = hipMemset(g->draws, 0, draw_bytes);
         if (e != hipSuccess) st = fail(GSR_ERR_HIP, "hipMalloc: %s", hipGetErrorString(e));
     }
     if (st == GSR_OK && (flags & GSR_GRAPH_GCN_NORM)) st = gsr_graph_normalize(g, GSR_ADJ_GCN_SYM, stream);
@@ -478,6 +490,7 @@ gsr_status_t gsr_graph_destroy(gsr_graph_t* g) {
     if (!g->symmetric) free_csr(g->at);
     free_csr(g->a);
     if (g->scratch) (void)hipFree(g->scratch);
+    if (g->draws) (void)hipFree(g->draws);
     delete g;
     return GSR_OK;
 }

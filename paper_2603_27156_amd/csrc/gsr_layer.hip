@@ -48,6 +48,8 @@ struct BlockArgs {
     const T* dy;            // dY_i, row stride ldg            (WITH_DW)
     int64_t ldg;
     float* dw_partial;      // [gridDim.x][DG*DG]              (WITH_DW)
+    int* draws_now;         // tile counters of this launch and of the next one (not WITH_DW)
+    int* draws_next;
 };
 
 template <int DG, typename T, int SIGN, bool WITH_DW>
@@ -66,8 +68,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
 #pragma unroll
             for (int ob = 0; ob < DG / 16; ++ob) dw[mb][ob] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    // the weight gradient sums over the tiles a wave has seen: fixed sweep there, drawn tiles otherwise
     const TileSweep ts = tile_sweep(a.tiles);
-    for (int t = ts.first; t < ts.end; t += ts.step) {
+    TileDraws td;
+    int t = ts.first, t_end = ts.end;
+    if constexpr (!WITH_DW) {
+        td = tile_draws(a.tiles, a.draws_now, a.draws_next);
+        t = tile_drawn(td, tile_request(td));
+        t_end = td.end;
+    }
+    while (t < t_end) {
+        int requested = 0;
+        if constexpr (!WITH_DW) requested = tile_request(td);
         const int r0 = t * 16;
         wave_sync();
         const int rpv = tile_rp_load(a.g, r0, a.n, lane);
@@ -116,6 +128,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
             wave_sync();
             emit_tile<DG, T>(st_h, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane);
         }
+        if constexpr (WITH_DW) t += ts.step;
+        else t = tile_drawn(td, requested);
     }
     if constexpr (WITH_DW) {
         // workgroup partial of dW_i: the four waves add their accumulators in wave order
@@ -179,6 +193,8 @@ struct GradArgs {
     T* dst;                 // dY_{i-1} plane(s): ndst planes, dst_gs apart, row stride ldd
     int64_t ldd, dst_gs;
     int ndst;
+    int* draws_now;         // tile counters of this launch and of the next one
+    int* draws_next;
 };
 
 // Waves per workgroup of k_grad (they share one copy of W^T in LDS).  Measured at 1M rows, Dg = 64:
@@ -195,8 +211,10 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
     float* st = L.st[0];
     __shared__ WLds<DG> wl;
     load_w_lds<DG>(a.w, true, wl);
-    const TileSweep ts = tile_sweep(a.tiles);
-    for (int t = ts.first; t < ts.end; t += ts.step) {
+    TileDraws td = tile_draws(a.tiles, a.draws_now, a.draws_next);
+    int t = tile_drawn(td, tile_request(td));
+    while (t < td.end) {
+        const int requested = tile_request(td);
         const int r0 = t * 16;
         wave_sync();
         const int rpv = tile_rp_load(a.gt, r0, a.n, lane);
@@ -255,6 +273,7 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
                 if (ok) store_cols<CPL, T>(p, g);
             }
         }
+        t = tile_drawn(td, requested);
     }
 }
 
@@ -505,6 +524,8 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     a.hub_part = x.hub_part(); a.w = w; a.plane = plane; a.ld = ld;
     a.out = out; a.out_given = out_given;
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
+    if (mode != 2) next_draw_sets(x.g, &a.draws_now, &a.draws_next);
+    else a.draws_now = a.draws_next = nullptr;
     const dim3 block(256);
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
     unsigned grid;
@@ -534,6 +555,7 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
     a.own_mask = own_mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
+    next_draw_sets(x.g, &a.draws_now, &a.draws_next);
     ProfScope prof(KC_GRAD, x.s);
     static const int per_cu = resident_blocks((const void*)k_grad<DG, T>, 64 * GRAD_WAVES);
     hipLaunchKernelGGL((k_grad<DG, T>), dim3(persistent_grid(x.g, per_cu)), dim3(64 * GRAD_WAVES), 0, x.s, a);

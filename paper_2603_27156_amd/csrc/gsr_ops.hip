@@ -7,6 +7,8 @@
 
 namespace gsr {
 
+static_assert(TILE_COUNTERS == kTileCounters, "host and device disagree on the size of a counter set");
+
 CsrView make_view(const gsr_graph_t* g, bool transpose);
 CsrView make_view(const gsr_graph_t* g, bool transpose) {
     const Csr& c = transpose ? g->at : g->a;
@@ -99,12 +101,14 @@ __device__ __forceinline__ void store_acc_rows(const f32x4 (&acc)[W / 16], const
 
 template <int W>
 __global__ __launch_bounds__(256) void k_spmm_tile(CsrView g, int n, int tiles, const float* __restrict__ x, int64_t ldx,
-                                                   float* __restrict__ y, int64_t ldy, const float* __restrict__ hub_part) {
+                                                   float* __restrict__ y, int64_t ldy, const float* __restrict__ hub_part,
+                                                   int* draws_now, int* draws_next) {
     __shared__ TileLds lds[4];
     TileLds& L = lds[threadIdx.x >> 6];
     const int lane = lane_id();
-    const TileSweep ts = tile_sweep(tiles);
-    for (int t = ts.first; t < ts.end; t += ts.step) {
+    const TileDraws td = tile_draws(tiles, draws_now, draws_next);
+    for (int t = tile_drawn(td, tile_request(td)); t < td.end;) {
+        const int requested = tile_request(td);
         const int r0 = t * 16;
         wave_sync();
         const bool has_hub = tile_begin(g, r0, n, L.rp, lane);
@@ -116,18 +120,21 @@ __global__ __launch_bounds__(256) void k_spmm_tile(CsrView g, int n, int tiles, 
                                             L.rp, L.ebuf, lane, acc);
         });
         store_acc_rows<W>(acc, g, hub_part, has_hub, r0, n, L.rp, y, ldy, lane);
+        t = tile_drawn(td, requested);
     }
 }
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_aggregate_tile(CsrView g, int n, int tiles, const T* __restrict__ vals,
                                                         const typename MaskOf<DG>::type* __restrict__ masks, int k,
-                                                        const float* __restrict__ hub_part, float* __restrict__ h_out) {
+                                                        const float* __restrict__ hub_part, float* __restrict__ h_out,
+                                                        int* draws_now, int* draws_next) {
     __shared__ TileLds lds[4];
     TileLds& L = lds[threadIdx.x >> 6];
     const int lane = lane_id();
-    const TileSweep ts = tile_sweep(tiles);
-    for (int t = ts.first; t < ts.end; t += ts.step) {
+    const TileDraws td = tile_draws(tiles, draws_now, draws_next);
+    for (int t = tile_drawn(td, tile_request(td)); t < td.end;) {
+        const int requested = tile_request(td);
         const int r0 = t * 16;
         wave_sync();
         const bool has_hub = tile_begin(g, r0, n, L.rp, lane);
@@ -140,6 +147,7 @@ __global__ __launch_bounds__(256) void k_aggregate_tile(CsrView g, int n, int ti
                                           lane, acc);
         });
         store_acc_rows<DG>(acc, g, hub_part, has_hub, r0, n, L.rp, h_out, DG, lane);
+        t = tile_drawn(td, requested);
     }
 }
 
@@ -236,8 +244,10 @@ static gsr_status_t aggregate_impl(const gsr_graph_t* g, const void* vals, const
         hipLaunchKernelGGL((k_hub_records<DG, T>), dim3((unsigned)std::min(g->a.hub.n_chunks, 4096)), dim3(256), 0, s, v, hc,
                            (const T*)v_rec, (const M*)m_rec, k, part);
     }
+    int *dn, *dx;
+    next_draw_sets(g, &dn, &dx);
     hipLaunchKernelGGL((k_aggregate_tile<DG, T>), dim3((unsigned)g->grid), dim3(256), 0, s, v, (int)n, (int)((n + 15) / 16),
-                       (const T*)v_rec, (const M*)m_rec, k, (const float*)part, h_out);
+                       (const T*)v_rec, (const M*)m_rec, k, (const float*)part, h_out, dn, dx);
     GSR_HIP_CHECK(hipGetLastError());
     return GSR_OK;
 }
@@ -313,12 +323,14 @@ gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t
             if (width == 64) hipLaunchKernelGGL((k_hub_dense<64, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
             else hipLaunchKernelGGL((k_hub_dense<32, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
         }
+        int *dn, *dx;
+        next_draw_sets(g, &dn, &dx);
         if (width == 64)
             hipLaunchKernelGGL((k_spmm_tile<64>), dim3((unsigned)g->grid), dim3(256), 0, s, view, (int)g->n, tiles, x, ldx, y, ldy,
-                               (const float*)g->scratch);
+                               (const float*)g->scratch, dn, dx);
         else
             hipLaunchKernelGGL((k_spmm_tile<32>), dim3((unsigned)g->grid), dim3(256), 0, s, view, (int)g->n, tiles, x, ldx, y, ldy,
-                               (const float*)g->scratch);
+                               (const float*)g->scratch, dn, dx);
         GSR_HIP_CHECK(hipGetLastError());
         return GSR_OK;
     }

@@ -278,3 +278,22 @@ def test_layer_calls_reject_what_the_kernels_cannot_take():
         assert status_of(lambda: gsr.gsr_layer_forward(c.gg, cfg, Wd, x)) in (gsr.GSR_ERR_UNSUPPORTED, gsr.GSR_ERR_INVALID_ARG)
     assert torch.equal(x, before)            # none of the refused calls touched the plane
     assert "" != gsr.gsr_last_error()
+
+
+@pytest.mark.parametrize("workgroups", [8, 24, 136])
+def test_small_and_odd_grids(workgroups):
+    """The persistent kernels take whatever grid they are given (a multiple of 8): fewer waves than
+    tile queues, and wave counts that do not divide the number of tiles."""
+    gsr.gsr_set_option("max_workgroups", workgroups)
+    try:
+        w = synth.scaled(synth.workload(2), 5003, l=2)
+        c = Case(w, 0, PLANAR)
+        ref = oracle.step(c.og, c.ocfg, w.l, c.x0_on_grid(), c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target)
+        out = run_step(c)
+        for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+            assert_close(key, out[key], ref[key])
+        X = np.random.default_rng(1).standard_normal((w.n, w.dg)).astype(np.float32)
+        got = gsr.gsr_spmm(c.gg, torch.from_numpy(X).to(c.dev)).cpu().numpy()
+        assert_close("A X", got, oracle.spmm(c.og, X))
+    finally:
+        gsr.gsr_set_option("max_workgroups", 0)
