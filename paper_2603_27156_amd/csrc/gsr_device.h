@@ -978,38 +978,70 @@ __device__ __forceinline__ int tile_drawn(const TileDraws& d, int requested) {
 }
 
 // ---- first pass over the chunks of very long rows ------------------------------------------------
-// One wave per chunk.  With DG = 32 the two half-waves take alternate neighbours of the chunk and
-// their sums are added (lower half first).  part[chunk][DG] receives the un-scaled partial row.
+// One wave per chunk, through the same matrix-core gathers as a tile: the chunk is treated as a
+// tile whose row 0 owns every edge, so all of a chunk's neighbours are in flight at once (a chain
+// of one row pointer, the edges, the masks and the values instead of one such chain per edge).
+// part[chunk][DG] receives the un-scaled partial row.
 struct HubChunks {
     const int32_t* ce0;
     const int32_t* ce1;
     int32_t n_chunks;
 };
 
+struct HubLds {
+    EdgeRec ebuf[64];
+    int rp[20];
+    uint8_t rbuf[64];
+};
+// row pointers of the pretended tile: row 0 spans [e0, e1), rows 1..15 are empty
+__device__ __forceinline__ void hub_chunk_begin(HubLds& L, int e0, int e1, int lane) {
+    wave_sync();
+    if (lane < 17) L.rp[lane] = lane == 0 ? e0 : e1;
+    wave_sync();
+}
+template <int DG>
+__device__ __forceinline__ void hub_chunk_store(const f32x4 (&acc)[DG / 16], float* __restrict__ part, int lane) {
+    constexpr int CPL = DG / 16;
+    if (lane < 16) {
+#pragma unroll
+        for (int cb = 0; cb < CPL; ++cb) part[CPL * lane + cb] = acc[cb][0];
+    }
+}
+
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_hub_records(CsrView g, HubChunks h, const T* __restrict__ vals,
                                                      const typename MaskOf<DG>::type* __restrict__ masks, int k,
                                                      float* __restrict__ part) {
-    constexpr int G = 64 / DG;
-    const int lane = lane_id(), c = lane % DG, sub = lane / DG;
+    __shared__ HubLds lds[4];
+    const int lane = lane_id();
+    HubLds& L = lds[threadIdx.x >> 6];
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     for (int q = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; q < h.n_chunks; q += nwaves) {
-        float acc = gather_records<DG, T>(g, vals, masks, k, h.ce0[q] + sub, h.ce1[q], c, G);
-        if constexpr (G == 2) acc = __shfl(acc, c, 64) + __shfl(acc, c + 32, 64);
-        if (sub == 0) part[(size_t)q * DG + c] = acc;
+        const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
+        hub_chunk_begin(L, e0, e1, lane);
+        f32x4 acc[DG / 16];
+#pragma unroll
+        for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        gather_records_mfma<DG, T, 16>(g, vals, masks, k, e0, e1, L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf, lane, acc);
+        hub_chunk_store<DG>(acc, part + (size_t)q * DG, lane);
     }
 }
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_hub_dense(CsrView g, HubChunks h, const T* __restrict__ x, int64_t ld,
                                                    float* __restrict__ part) {
-    constexpr int G = 64 / DG;
-    const int lane = lane_id(), c = lane % DG, sub = lane / DG;
+    __shared__ HubLds lds[4];
+    const int lane = lane_id();
+    HubLds& L = lds[threadIdx.x >> 6];
     const int nwaves = (gridDim.x * blockDim.x) >> 6;
     for (int q = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; q < h.n_chunks; q += nwaves) {
-        float acc = gather_dense<DG, T>(g, x, ld, h.ce0[q] + sub, h.ce1[q], c, G);
-        if constexpr (G == 2) acc = __shfl(acc, c, 64) + __shfl(acc, c + 32, 64);
-        if (sub == 0) part[(size_t)q * DG + c] = acc;
+        const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
+        hub_chunk_begin(L, e0, e1, lane);
+        f32x4 acc[DG / 16];
+#pragma unroll
+        for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        gather_dense_mfma<DG, T, 16>(g, x, ld, e0, e1, L.rp, L.ebuf, lane, acc);
+        hub_chunk_store<DG>(acc, part + (size_t)q * DG, lane);
     }
 }
 
