@@ -259,8 +259,19 @@ __device__ __forceinline__ int find_hub(const CsrView& g, int row) {
 template <int DG>
 __device__ __forceinline__ float hub_row_sum(const CsrView& g, const float* __restrict__ part, int row, int c) {
     const int h = find_hub(g, row);
+    // sixteen partial rows in flight at a time; added in chunk order, so the sum does not depend
+    // on the unrolling
+    const int q1 = g.hub_cptr[h + 1];
+    int q = g.hub_cptr[h];
     float acc = 0.f;
-    for (int q = g.hub_cptr[h]; q < g.hub_cptr[h + 1]; ++q) acc += part[(size_t)q * DG + c];
+    for (; q + 16 <= q1; q += 16) {
+        float v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = part[(size_t)(q + u) * DG + c];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) acc += v[u];
+    }
+    for (; q < q1; ++q) acc += part[(size_t)q * DG + c];
     return acc;
 }
 
