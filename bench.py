@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # by what the same counter reads for the plain plane copy of known size in the same run
 # (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Only the workload the passes were taken on has entries.
 MEASURED_TRAFFIC = {
-    "cfg2-1M": {"grad": 2.0 * 729.1e6 + 416.9e6, "block_forward": 2.0 * 299.8e6 + 314.2e6,
-                "block_backward": 2.0 * 354.8e6 + 291.4e6},
+    "cfg2-1M": {"grad": 2.0 * 656.2e6 + 386.1e6, "block_forward": 2.0 * 248.3e6 + 320.5e6,
+                "block_backward": 2.0 * 355.8e6 + 291.4e6},
 }
 
 
