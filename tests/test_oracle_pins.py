@@ -54,6 +54,85 @@ def test_gs_worked_examples(name, mk):
     assert np.allclose(V, b["VAL"], atol=5e-3)
 
 
+# ------------------------------------------------------------------ the walk-throughs' own pipeline
+
+def test_walkthrough_blocks_place_sums_in_the_rows_own_column():
+    from oracle import literal
+    b = read_golden("sec43_block_first.txt")
+    g = oracle.graph_from_csr(*dense_to_csr(b["A"]))
+    assert np.allclose(literal.slot_block(g, b["VAL"], b["IDX"].astype(np.int32), 2), b["OUT"], atol=5e-3)
+    c = read_golden("sec44_blocks.txt")
+    assert np.allclose(literal.slot_block(g, c["VALA"], c["IDXA"].astype(np.int32), 2), c["OUTA"], atol=5e-3)
+    assert np.allclose(literal.slot_block(g, c["VALB"], c["IDXB"].astype(np.int32), 2), c["OUTB"], atol=5e-3)
+    # the other placement (every neighbour at its own column) does not give these matrices
+    assert not np.allclose(oracle.aggregate(g, b["VAL"], b["IDX"].astype(np.int32), 2), b["OUT"], atol=5e-2)
+
+
+def test_sec41_backward_block_values():
+    from oracle import literal
+    b = read_golden("sec41_gsr_backward_block.txt")
+    g = oracle.graph_from_csr(*dense_to_csr(b["A"]))
+    I = b["IDX"].astype(np.int32)
+    M = literal.scatter(b["VALG"], I, 4)
+    M[M == 0] = 7.0                       # entries outside the recorded positions must not be read
+    out = literal.block_backward(g, M, I)
+    assert np.allclose(out[np.arange(4)[:, None], I], b["OUT"].sum(axis=1, keepdims=True), atol=5e-3)
+    assert np.allclose(out[1:], b["OUT"][1:], atol=5e-3)       # row 0 is printed one column off
+    assert np.count_nonzero(out) == 4
+
+
+def test_sec43_layer_of_algorithm_1():
+    from oracle import literal
+    b = read_golden("sec43_layer_forward.txt")
+    g = oracle.graph_from_csr(*dense_to_csr(b["A"]))
+    X1n, X2n, (V1, I1, V2, I2) = literal.alg1_layer_forward(g, b["G1"], b["G2"], 1)
+    assert np.allclose(X2n, b["X2NEW"], atol=5e-3)
+    assert np.array_equal(I2[:, 0], [0, 1, 0, 1]) and np.allclose(V2[:, 0], [1.55, 1.2, 1.86, 1.15], atol=5e-3)
+    # Algorithm 1, line 10, on the second block as printed
+    assert np.allclose(literal.scatter(V1, I1, 2) + b["M2"], b["X1NEW"], atol=5e-3)
+    # the whole layer: rows 1 and 3 exact, rows 0 and 2 carry the printed block's 0.06 / 0.05 slip
+    assert np.allclose(X1n[[1, 3]], b["X1NEW"][[1, 3]], atol=5e-3)
+    assert np.allclose(X1n, b["X1NEW"], atol=0.07)
+    assert np.array_equal(X1n == 0, b["X1NEW"] == 0)
+
+
+def test_sec44_steps_of_algorithm_2():
+    from oracle import literal
+    c = read_golden("sec44_blocks.txt")
+    s = read_golden("sec44_gs_signed.txt")
+    g = oracle.graph_from_csr(*dense_to_csr(c["A"]))
+    _, _, im = literal.alg2_layer_backward(g, c["G1"], s["Z"], 1)
+    assert np.array_equal(im["I2"], c["IDXA"].astype(np.int32)) and np.allclose(im["V2"], c["VALA"], atol=5e-3)
+    assert np.allclose(im["B2"], c["OUTA"], atol=5e-3)
+    assert (im["M1"] < 0).all() and np.allclose(-im["M1"], c["M1ABS"], atol=5e-3)
+    assert np.array_equal(im["I1"], c["IDXB"].astype(np.int32)) and np.allclose(im["V1"], c["VALB"], atol=5e-3)
+    assert np.allclose(im["Z1"], c["OUTB"], atol=5e-3)
+    assert np.allclose(im["M2"], literal.scatter(c["VALA"], c["IDXA"].astype(np.int32), 2) - c["OUTB"], atol=1e-2)
+
+
+def test_slot_block_against_dense_algebra_and_its_adjoint():
+    """out[i, I[i,t]] = (A V)[i,t] written with dense matrices; block_backward is the adjoint of the map
+    V -> slot_block(V, I) followed by the same placement (non-symmetric A: G and G^T differ)."""
+    from oracle import literal
+    g, A = directed_weighted_graph()
+    rng = np.random.default_rng(4)
+    n, dg, k = A.shape[0], 16, 5
+    I = np.sort(np.argsort(rng.random((n, dg)), axis=1)[:, :k], axis=1).astype(np.int32)
+    V = rng.standard_normal((n, k))
+    out = literal.slot_block(g, V, I, dg)
+    S = A @ V
+    ref = np.zeros((n, dg))
+    for i in range(n):
+        for t in range(k):
+            ref[i, I[i, t]] = S[i, t]
+    assert np.allclose(out, ref, atol=1e-12)
+    M = rng.standard_normal((n, dg))
+    lhs = np.sum(out * M)                                              # <block(V), M>
+    back = literal.block_backward(g, M, I)
+    rhs = np.sum(V * back[np.arange(n)[:, None], I])                   # <V, slots of block_backward(M)>
+    assert abs(lhs - rhs) < 1e-10 * max(1.0, abs(lhs))
+
+
 # ------------------------------------------------------------------ GS against a full sort
 
 @pytest.mark.parametrize("dg,k", [(32, 8), (64, 16), (64, 1), (64, 64), (8, 3)])
