@@ -208,6 +208,36 @@ gsr_status_t gsr_step(const gsr_graph_t* g, const gsr_config_t* cfg, const void*
                       void* x0_rebuilt_out, void* xl_out, void* workspace, size_t workspace_bytes,
                       void* stream);
 
+/* ---- the two-group pipeline as the walk-throughs of Sections 4.3 and 4.4 print it ----
+ *
+ * Its block differs from eq. (10): a row's slot-wise sums over its neighbours stand in the row's
+ * OWN recorded columns, block(V, I)[i, I[i,t]] = sum_j a_ij V[j,t] (the printed block results of
+ * Sections 4.3 and 4.4), and Algorithm 1 / 2 use it without weights.  float32 only; planes are
+ * device n x dg with row stride ld elements, dg in [1, 64], 1 <= k <= dg.  workspace: device,
+ * 256-byte aligned, at least gsr_walkthrough_workspace(g, k) bytes.  The products run through
+ * gsr_spmm, so its note on overlapping calls applies.
+ *
+ * gsr_slot_block: out = block(vals, idx) (transpose = 1: sums over A^T).  vals: device n x k
+ * float32, idx: device n x k int32; a column outside [0, dg) places nothing. */
+size_t gsr_walkthrough_workspace(const gsr_graph_t* g, int32_t k);
+gsr_status_t gsr_slot_block(const gsr_graph_t* g, const float* vals, const int32_t* idx, int32_t k, int32_t dg,
+                            int32_t transpose, float* out, int64_t ld, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/* One pass of the loop body of Algorithm 1, in place: x1 is the group that enters the first
+ * GS-Op.  (V1, I1) = GS(x1); x2 += block(V1, I1); (V2, I2) = GS(x2); x1 = scatter(V1, I1) +
+ * block(V2, I2). */
+gsr_status_t gsr_alg1_layer_forward(const gsr_graph_t* g, int32_t dg, int32_t k, float* x1_inout, float* x2_inout,
+                                    int64_t ld, void* workspace, size_t workspace_bytes, void* stream);
+
+/* One pass of the loop body of Algorithm 2, in place, step by step as printed: (V2, I2) = GS(g2);
+ * M1 = g1 - block(V2, I2); (V1, I1) = GS(M1); M2 = scatter(V2, I2) - block(V1, I1);
+ * g1 = backward_block(M1, I1), g2 = backward_block(M2, I2), where backward_block(M, I) reads M
+ * only at the recorded positions, sums over A^T and places at the row's recorded positions
+ * (Section 4.1, eq. (11)). */
+gsr_status_t gsr_alg2_layer_backward(const gsr_graph_t* g, int32_t dg, int32_t k, float* g1_inout, float* g2_inout,
+                                     int64_t ld, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -30,7 +30,7 @@ EXPORTED = [
     "gsr_profile_class_name", "gsr_graph_create", "gsr_graph_normalize", "gsr_graph_info",
     "gsr_graph_export", "gsr_graph_destroy", "gsr_group_sparse", "gsr_spmm", "gsr_spmm_compressed_workspace",
     "gsr_spmm_compressed", "gsr_workspace_size", "gsr_layer_forward", "gsr_layer_inverse", "gsr_layer_backward",
-    "gsr_step",
+    "gsr_step", "gsr_walkthrough_workspace", "gsr_slot_block", "gsr_alg1_layer_forward", "gsr_alg2_layer_backward",
 ]
 
 
@@ -67,6 +67,8 @@ def lib():
         l.gsr_profile_class_name.restype = C.c_char_p
         l.gsr_spmm_compressed_workspace.restype = C.c_size_t
         l.gsr_spmm_compressed_workspace.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        l.gsr_walkthrough_workspace.restype = C.c_size_t
+        l.gsr_walkthrough_workspace.argtypes = [C.c_void_p, C.c_int32]
         _lib = l
     return _lib
 
@@ -234,6 +236,49 @@ def gsr_spmm(g: Graph, x, transpose: bool = False):
     _check(lib().gsr_spmm(g.ptr, _dp(x), C.c_int64(x.stride(0) if n > 1 else width), C.c_int32(width), _dp(y),
                           C.c_int64(width), C.c_int32(1 if transpose else 0), _stream()))
     return y
+
+
+def _walkthrough_ws(g: Graph, k: int, device):
+    import torch
+    nbytes = lib().gsr_walkthrough_workspace(g.ptr, C.c_int32(k))
+    return torch.empty(max(1, nbytes), dtype=torch.uint8, device=device), nbytes
+
+
+def gsr_slot_block(g: Graph, vals, idx, dg: int, transpose: bool = False):
+    """The block of the Section 4.3 / 4.4 walk-throughs: out[i, idx[i,t]] = sum_j a_ij vals[j,t] -> float32 [n, dg]."""
+    import torch
+    assert vals.is_cuda and idx.is_cuda and vals.dtype == torch.float32 and idx.dtype == torch.int32
+    assert vals.is_contiguous() and idx.is_contiguous()
+    n, k = vals.shape
+    out = torch.empty((n, dg), dtype=torch.float32, device=vals.device)
+    ws, nbytes = _walkthrough_ws(g, k, vals.device)
+    _check(lib().gsr_slot_block(g.ptr, _dp(vals), _dp(idx), C.c_int32(k), C.c_int32(dg), C.c_int32(1 if transpose else 0),
+                                _dp(out), C.c_int64(dg), _dp(ws), C.c_size_t(nbytes), _stream()))
+    return out
+
+
+def gsr_alg1_layer_forward(g: Graph, x1, x2, k: int):
+    """One pass of the loop body of Algorithm 1 on the planes x1, x2 (float32 [n, dg], updated in place)."""
+    import torch
+    for x in (x1, x2):
+        assert x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.stride(1) == 1
+    assert x1.shape == x2.shape and x1.stride(0) == x2.stride(0)
+    n, dg = x1.shape
+    ws, nbytes = _walkthrough_ws(g, k, x1.device)
+    _check(lib().gsr_alg1_layer_forward(g.ptr, C.c_int32(dg), C.c_int32(k), _dp(x1), _dp(x2),
+                                        C.c_int64(x1.stride(0) if n > 1 else dg), _dp(ws), C.c_size_t(nbytes), _stream()))
+
+
+def gsr_alg2_layer_backward(g: Graph, g1, g2, k: int):
+    """One pass of the loop body of Algorithm 2 on the gradient planes g1, g2 (float32 [n, dg], in place)."""
+    import torch
+    for x in (g1, g2):
+        assert x.is_cuda and x.dtype == torch.float32 and x.dim() == 2 and x.stride(1) == 1
+    assert g1.shape == g2.shape and g1.stride(0) == g2.stride(0)
+    n, dg = g1.shape
+    ws, nbytes = _walkthrough_ws(g, k, g1.device)
+    _check(lib().gsr_alg2_layer_backward(g.ptr, C.c_int32(dg), C.c_int32(k), _dp(g1), _dp(g2),
+                                         C.c_int64(g1.stride(0) if n > 1 else dg), _dp(ws), C.c_size_t(nbytes), _stream()))
 
 
 def gsr_spmm_compressed(g: Graph, vals, idx, dg: int):
