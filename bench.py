@@ -177,12 +177,24 @@ def main() -> int:
         t_agg = avg_us(lambda: gsr.gsr_spmm_compressed(g, vv, ii, w.dg))
         def entry(us, nbytes):
             return {"avg_us": us, "algorithmic_GBps": nbytes / (us * 1e-6) / 1e9, "frac_of_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        # the two-group pipeline of the Section 4.3 / 4.4 walk-throughs on two such planes
+        pa, pb = plane.clone(), x0[1].float().contiguous()
+        t_slot = avg_us(lambda: gsr.gsr_slot_block(g, vv.float(), ii, w.dg))
+        t_alg1 = avg_us(lambda: gsr.gsr_alg1_layer_forward(g, pa, pb, w.k), reps=3)
+        pa.mul_(1e-3 / max(float(pa.abs().max()), 1e-30)); pb.mul_(1e-3 / max(float(pb.abs().max()), 1e-30))
+        t_alg2 = avg_us(lambda: gsr.gsr_alg2_layer_backward(g, pa, pb, w.k), reps=3)
+        del pa, pb
         operators = {
+            "gsr_slot_block": entry(t_slot, w.n * (w.k * 8 + row) + csr),
+            "gsr_alg1_layer_forward": entry(t_alg1, w.n * 4 * row + 2 * csr),
+            "gsr_alg2_layer_backward": entry(t_alg2, w.n * 4 * row + 4 * csr),
             "gsr_spmm": entry(t_spmm, w.n * 2 * row + csr),
             "gsr_group_sparse": entry(t_gs, w.n * (row + w.k * 8)),
             "gsr_spmm_compressed": entry(t_agg, w.n * (w.k * 8 + row) + csr),
             "note": "float32, one group plane [n, dg]; compulsory bytes; gsr_spmm_compressed includes the conversion of "
-                    "(V, I int32) into records, its index check and one host synchronisation",
+                    "(V, I int32) into records, its index check and one host synchronisation; gsr_slot_block / gsr_alg1 / "
+                    "gsr_alg2: the pipeline as the walk-throughs of Sections 4.3 / 4.4 print it (two planes, no weights), "
+                    "bytes = both planes read and written once plus the edge lists of its 2 / 4 products",
         }
         del plane, vv, ii
 

@@ -34,26 +34,46 @@ __global__ __launch_bounds__(256) void k_slots_prepare(int64_t n, int k, int W, 
 }
 
 // out[i][c] = beta * base[i][c] + sign * sum_t [idx_own[i][t] == c] S[i][t] + gamma * sum_t [idx_b[i][t] == c] Vb[i][t]
-// One thread per element; indices are only compared, never used as addresses.  out may alias base.
+// A workgroup builds 64 rows in LDS: the base rows arrive coalesced, then one thread per row adds the
+// row's slots in slot order (so repeated columns add up in a fixed order; a column outside [0, dg)
+// is skipped), then the rows leave coalesced.  out may alias base.  Measured at 1M rows, dg 64, k 16:
+// 185 - 270 us; staging the slots in LDS too and splitting a row over four threads was not faster.
+constexpr int COMBINE_ROWS = 64;
 __global__ __launch_bounds__(256) void k_slots_combine(int64_t n, int dg, int k, int W, float* out, int64_t ld_out, float beta,
                                                        const float* base, int64_t ld_base, float sign,
                                                        const float* __restrict__ S, const int32_t* __restrict__ idx_own,
                                                        float gamma, const float* __restrict__ Vb,
                                                        const int32_t* __restrict__ idx_b) {
-    const int64_t total = n * dg;
-    for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t i = e / dg;
-        const int c = (int)(e - i * dg);
-        float v = beta != 0.f ? beta * base[i * ld_base + c] : 0.f;
-        float s = 0.f;
-        for (int t = 0; t < k; ++t) s += idx_own[i * k + t] == c ? S[i * W + t] : 0.f;
-        v += sign * s;
-        if (Vb) {
-            float b = 0.f;
-            for (int t = 0; t < k; ++t) b += idx_b[i * k + t] == c ? Vb[i * k + t] : 0.f;
-            v += gamma * b;
+    __shared__ float tile[COMBINE_ROWS * 65];
+    const int64_t groups = (n + COMBINE_ROWS - 1) / COMBINE_ROWS;
+    for (int64_t gidx = blockIdx.x; gidx < groups; gidx += gridDim.x) {
+        const int64_t r0 = gidx * COMBINE_ROWS;
+        const int rows = (int)(n - r0 < COMBINE_ROWS ? n - r0 : COMBINE_ROWS);
+        __syncthreads();
+        for (int e = threadIdx.x; e < rows * dg; e += 256) {
+            const int r = e / dg, c = e - r * dg;
+            tile[r * 65 + c] = beta != 0.f ? beta * base[(r0 + r) * ld_base + c] : 0.f;
         }
-        out[i * ld_out + c] = v;
+        __syncthreads();
+        if ((int)threadIdx.x < rows) {
+            const int r = threadIdx.x;
+            const int64_t i = r0 + r;
+            for (int t = 0; t < k; ++t) {
+                const int c = idx_own[i * k + t];
+                if ((unsigned)c < (unsigned)dg) tile[r * 65 + c] += sign * S[i * W + t];
+            }
+            if (Vb) {
+                for (int t = 0; t < k; ++t) {
+                    const int c = idx_b[i * k + t];
+                    if ((unsigned)c < (unsigned)dg) tile[r * 65 + c] += gamma * Vb[i * k + t];
+                }
+            }
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < rows * dg; e += 256) {
+            const int r = e / dg, c = e - r * dg;
+            out[(r0 + r) * ld_out + c] = tile[r * 65 + c];
+        }
     }
 }
 
@@ -95,7 +115,7 @@ static gsr_status_t lit_product(const Lit& x, const float* vals, const float* de
 }
 static void lit_combine(const Lit& x, float* out, int64_t ld_out, float beta, const float* base, int64_t ld_base, float sign,
                         const int32_t* idx_own, float gamma, const float* vb, const int32_t* idx_b) {
-    hipLaunchKernelGGL(k_slots_combine, dim3(blocks_for(x.n * x.dg)), dim3(256), 0, x.s, x.n, x.dg, x.k, x.W, out, ld_out, beta,
+    hipLaunchKernelGGL(k_slots_combine, dim3((unsigned)std::min<int64_t>((x.n + COMBINE_ROWS - 1) / COMBINE_ROWS, 65536)), dim3(256), 0, x.s, x.n, x.dg, x.k, x.W, out, ld_out, beta,
                        base, ld_base, sign, (const float*)x.S, idx_own, gamma, vb, idx_b);
 }
 
