@@ -325,3 +325,39 @@ def test_cfg4_full_size_sampled_rows_and_properties():
     assert ulp_off.mean() < 2e-2
     del x, y, y2
     torch.cuda.empty_cache()
+
+
+def test_cfg2_full_size_walkthrough_layers():
+    """Algorithms 1 and 2 as the walk-throughs print them, on two planes of the 1M-node workload.  Rows whose
+    second selection could differ between float32 and float64 sums (and the rows that aggregate them) are
+    counted; everything else is compared element by element."""
+    from oracle import literal
+    c = case("cfg2")
+    w = c.w
+    X = c.x0_on_grid()
+    dg, k = w.dg, w.k
+    X1, X2 = np.ascontiguousarray(X[:, :dg]), np.ascontiguousarray(X[:, dg:2 * dg])
+    x1 = torch.from_numpy(X1.astype(np.float32)).to(c.dev)
+    x2 = torch.from_numpy(X2.astype(np.float32)).to(c.dev)
+    gsr.gsr_alg1_layer_forward(c.gg, x1, x2, k)
+    t = time.time()
+    w1, w2, _ = literal.alg1_layer_forward(c.og, X1, X2, k)
+    print(f"[walkthrough] oracle Alg. 1 layer {time.time() - t:.1f}s", flush=True)
+    for name, got, want, frac in (("x2", x2.cpu().numpy(), w2, 1e-5), ("x1", x1.cpu().numpy(), w1, 2e-3)):
+        bad, worst = violations(got, want)
+        print(f"[walkthrough alg1] {name}: rows outside tolerance {int(bad.any(axis=1).sum())} of {w.n}, "
+              f"rel {rel_norm(got, want):.2e}", flush=True)
+        assert bad.any(axis=1).mean() <= frac and rel_norm(got, want) < 1e-3
+    assert (np.count_nonzero(x1.cpu().numpy(), axis=1) <= 2 * k).all()
+    rng = np.random.default_rng(9)
+    G1 = (rng.standard_normal((w.n, dg)) * 1e-3).astype(np.float32)
+    G2 = (rng.standard_normal((w.n, dg)) * 1e-3).astype(np.float32)
+    g1, g2 = torch.from_numpy(G1).to(c.dev), torch.from_numpy(G2).to(c.dev)
+    gsr.gsr_alg2_layer_backward(c.gg, g1, g2, k)
+    v1, v2, _ = literal.alg2_layer_backward(c.og, G1, G2, k)
+    for name, got, want in (("g1", g1.cpu().numpy(), v1), ("g2", g2.cpu().numpy(), v2)):
+        bad, worst = violations(got, want)
+        print(f"[walkthrough alg2] {name}: rows outside tolerance {int(bad.any(axis=1).sum())} of {w.n}, "
+              f"rel {rel_norm(got, want):.2e}", flush=True)
+        assert bad.any(axis=1).mean() < 2e-3 and rel_norm(got, want) < 1e-2
+        assert (np.count_nonzero(got, axis=1) <= k).all()
