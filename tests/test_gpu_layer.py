@@ -297,3 +297,42 @@ def test_small_and_odd_grids(workgroups):
         assert_close("A X", got, oracle.spmm(c.og, X))
     finally:
         gsr.gsr_set_option("max_workgroups", 0)
+
+
+@pytest.mark.parametrize("name,layout", [("cfg1s", PLANAR), ("cfg2s", ROW)])
+def test_directed_graph_with_mean_aggregation(name, layout):
+    """A non-symmetric adjacency with caller-supplied values: every node averages over its fan-in and itself
+    (A = D^-1 (A_dir + I)), so the forward aggregates over G and the backward over G^T, which differ (Section 3)."""
+    import scipy.sparse as sp
+    c = Case(workloads()[name], 0, layout)
+    w = c.w
+    n = w.n
+    D = sp.csr_matrix((np.ones(len(c.inp.colidx), dtype=np.float64), c.inp.colidx, c.inp.rowptr.astype(np.int64)), shape=(n, n))
+    D = ((D + sp.identity(n, format="csr")) > 0).astype(np.float64).tocsr()
+    D.sort_indices()
+    deg = np.diff(D.indptr)
+    av = (1.0 / np.repeat(deg, deg)).astype(np.float32)
+    assert (D != D.T).nnz > 0
+    c.og = oracle.graph_from_csr(D.indptr.astype(np.int64), D.indices.astype(np.int32), av)
+    c.gg = gsr.gsr_graph_create(D.indptr.astype(np.int64), D.indices.astype(np.int32), vals=av, flags=0)
+    W = c.inp.weights[0]
+    Wd = torch.from_numpy(W).to(c.dev)
+    X = c.x0_on_grid()
+    Y_ref = oracle.layer_forward(c.og, c.ocfg, W, X)
+    y = c.to_dev(X)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y)
+    assert_close("Y", c.to_host(y), Y_ref)
+    rng = np.random.default_rng(17)
+    dY = (rng.standard_normal((n, w.d)) * 1e-3).astype(np.float32).astype(np.float64)
+    Xb_ref, dX_ref, dW_ref = oracle.layer_backward(c.og, c.ocfg, W, Y_ref, dY)
+    yb, dyb = c.to_dev(Y_ref), c.to_dev(dY)
+    dW = torch.empty((w.c, w.dg, w.dg), dtype=torch.float32, device=c.dev)
+    gsr.gsr_layer_backward(c.gg, c.gcfg, Wd, yb, dyb, dW)
+    assert_close("X rebuilt (backward)", c.to_host(yb), Xb_ref)
+    assert_close("dX", c.to_host(dyb), dX_ref)
+    assert_close("dW", dW.cpu().numpy(), dW_ref)
+    ref = oracle.step(c.og, c.ocfg, w.l, X, c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target)
+    out = run_step(c)
+    assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
+    for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+        assert_close(key, out[key], ref[key])
