@@ -238,6 +238,18 @@ gsr_status_t gsr_alg1_layer_forward(const gsr_graph_t* g, int32_t dg, int32_t k,
 gsr_status_t gsr_alg2_layer_backward(const gsr_graph_t* g, int32_t dg, int32_t k, float* g1_inout, float* g2_inout,
                                      int64_t ld, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- parameter updates (Section 5 trains for 250 epochs; the optimiser is not named) ----
+ *
+ * Element-wise, in place, float32 device arrays of `count` elements; apply them to w_all, w_out and
+ * b_out with the gradients gsr_step returned to make a full training step.
+ * gsr_sgd_update:   w <- w - lr * (dw + weight_decay * w)
+ * gsr_adam_update:  g = dw + weight_decay * w;  m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ *                   w <- w - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)   (Kingma & Ba, Algorithm 1);
+ *                   m, v: device state of `count` floats, zero before step t = 1; t counts from 1. */
+gsr_status_t gsr_sgd_update(float* w, const float* dw, int64_t count, float lr, float weight_decay, void* stream);
+gsr_status_t gsr_adam_update(float* w, const float* dw, float* m, float* v, int64_t count, int64_t t, float lr,
+                             float beta1, float beta2, float eps, float weight_decay, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,6 +31,7 @@ EXPORTED = [
     "gsr_graph_export", "gsr_graph_destroy", "gsr_group_sparse", "gsr_spmm", "gsr_spmm_compressed_workspace",
     "gsr_spmm_compressed", "gsr_workspace_size", "gsr_layer_forward", "gsr_layer_inverse", "gsr_layer_backward",
     "gsr_step", "gsr_walkthrough_workspace", "gsr_slot_block", "gsr_alg1_layer_forward", "gsr_alg2_layer_backward",
+    "gsr_sgd_update", "gsr_adam_update",
 ]
 
 
@@ -279,6 +280,24 @@ def gsr_alg2_layer_backward(g: Graph, g1, g2, k: int):
     ws, nbytes = _walkthrough_ws(g, k, g1.device)
     _check(lib().gsr_alg2_layer_backward(g.ptr, C.c_int32(dg), C.c_int32(k), _dp(g1), _dp(g2),
                                          C.c_int64(g1.stride(0) if n > 1 else dg), _dp(ws), C.c_size_t(nbytes), _stream()))
+
+
+def gsr_sgd_update(w, dw, lr: float, weight_decay: float = 0.0):
+    """w <- w - lr * (dw + weight_decay * w), in place (float32 device tensors of one shape)."""
+    import torch
+    assert w.is_cuda and dw.is_cuda and w.dtype == dw.dtype == torch.float32 and w.is_contiguous() and dw.is_contiguous()
+    assert w.numel() == dw.numel()
+    _check(lib().gsr_sgd_update(_dp(w), _dp(dw), C.c_int64(w.numel()), C.c_float(lr), C.c_float(weight_decay), _stream()))
+
+
+def gsr_adam_update(w, dw, m, v, t: int, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+                    weight_decay: float = 0.0):
+    """One Adam step with bias correction, in place; m, v: state tensors (zero before t = 1)."""
+    import torch
+    for x in (w, dw, m, v):
+        assert x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.numel() == w.numel()
+    _check(lib().gsr_adam_update(_dp(w), _dp(dw), _dp(m), _dp(v), C.c_int64(w.numel()), C.c_int64(t), C.c_float(lr),
+                                 C.c_float(beta1), C.c_float(beta2), C.c_float(eps), C.c_float(weight_decay), _stream()))
 
 
 def gsr_spmm_compressed(g: Graph, vals, idx, dg: int):

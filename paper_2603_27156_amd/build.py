@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(HERE, "libgsr.so")
-SOURCES = ["gsr_graph.hip", "gsr_ops.hip", "gsr_layer.hip", "gsr_literal.hip"]
+SOURCES = ["gsr_graph.hip", "gsr_ops.hip", "gsr_layer.hip", "gsr_literal.hip", "gsr_optim.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

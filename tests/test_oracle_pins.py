@@ -524,3 +524,25 @@ def test_storage_rounding_keeps_planes_on_the_grid():
         ref = oracle.layer_forward(g, oracle.Cfg(C * dg, C, k, NORM_RMS), W, X)
         tol = 1e-6 if sm == STORE_F32 else 2e-2
         assert np.allclose(Y, ref, rtol=tol, atol=tol)
+
+
+# ------------------------------------------------------------------ parameter updates
+
+def test_optimiser_closed_forms():
+    from oracle import optim
+    # gradient descent on L = w^2 / 2 (dw = w): w_t = (1 - lr)^t w_0; with weight decay the factor is 1 - lr (1 + wd)
+    w = np.array([2.0, -3.0])
+    for _ in range(10):
+        w = optim.sgd(w, w, 0.1)
+    assert np.allclose(w, 0.9 ** 10 * np.array([2.0, -3.0]), rtol=1e-12)
+    assert np.allclose(optim.sgd(np.array([1.0]), np.array([1.0]), 0.1, wd=0.5), 1 - 0.1 * 1.5)
+    # Adam: the first step moves every parameter by lr against the sign of its gradient, whatever its scale
+    g = np.array([1e-6, -5.0, 300.0])
+    w1, m, v = optim.adam(np.zeros(3), g, np.zeros(3), np.zeros(3), 1, 1e-2, eps=1e-30)
+    assert np.allclose(w1, -1e-2 * np.sign(g), rtol=1e-9)
+    assert np.allclose(m, 0.1 * g) and np.allclose(v, 1e-3 * g * g)
+    # a constant gradient keeps the bias-corrected moments at g and g^2: every step has size lr
+    w = np.zeros(3)
+    for t in range(1, 8):
+        w, m, v = optim.adam(w, g, m if t > 1 else np.zeros(3), v if t > 1 else np.zeros(3), t, 1e-2, eps=1e-30)
+    assert np.allclose(w, -7e-2 * np.sign(g), rtol=1e-9)
