@@ -27,6 +27,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # FETCH_SIZE then WRITE_SIZE, KiB per dispatch averaged over the launches of a step), each scaled
 # by what the same counter reads for the plain plane copy of known size in the same run
 # (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0).  Only the workload the passes were taken on has entries.
+# Share of a SIMD's cycles in which its vector pipe issues / its matrix pipe is busy, from rocprofv3 --pmc runs of
+# the same kernels (profiles/gsr_step_cfg2_sq_counters.md): the block kernels are limited by these, not by HBM.
+MEASURED_PIPES = {
+    "cfg2-1M": {"block_forward": {"valu_busy": 0.51, "mfma_busy": 0.33}, "block_backward": {"valu_busy": 0.36, "mfma_busy": 0.38},
+                "grad": {"valu_busy": 0.18, "mfma_busy": 0.33}},
+}
 MEASURED_TRAFFIC = {
     "cfg2-1M": {"grad": 2.0 * 656.2e6 + 386.1e6, "block_forward": 2.0 * 248.3e6 + 320.5e6,
                 "block_backward": 2.0 * 355.8e6 + 291.4e6},
@@ -62,6 +68,7 @@ def main() -> int:
     ap.add_argument("--save-indices", action="store_true",
                     help="keep the forward sweep's column masks for the inverse (memory grows with L)")
     ap.add_argument("--hub-threshold", type=int, default=0, help="rows longer than this are reduced in two passes")
+    ap.add_argument("--hub-chunk", type=int, default=0, help="neighbours per first-pass partial sum of such rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="no per-kernel events in the timed region")
     args = ap.parse_args()
@@ -92,6 +99,8 @@ def main() -> int:
         gsr.gsr_set_option("max_workgroups", args.max_workgroups)
     if args.hub_threshold:
         gsr.gsr_set_option("hub_threshold", args.hub_threshold)
+    if args.hub_chunk:
+        gsr.gsr_set_option("hub_chunk", args.hub_chunk)
     t_gen = time.time()
     inp = synth.make_inputs(w, 0)
     g = gsr.gsr_graph_create(inp.rowptr, inp.colidx)
@@ -151,7 +160,8 @@ def main() -> int:
         roofline = {"bound": "hbm", "kernel": dom, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": achieved / HBM_PEAK_GBS,
                     "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(dom),
-                    "algorithmic_bytes_per_launch": ab[dom], "avg_launch_us": cand[dom]["avg_us"]}
+                    "algorithmic_bytes_per_launch": ab[dom], "avg_launch_us": cand[dom]["avg_us"],
+                    "pipes": MEASURED_PIPES.get(w.name, {}).get(dom)}
         for k in cand:
             kernels[k]["algorithmic_GBps"] = ab[k] / (cand[k]["avg_us"] * 1e-6) / 1e9
 
