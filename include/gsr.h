@@ -18,7 +18,8 @@
  *     and is asynchronous unless stated.  Calls on one graph / workspace must be ordered:
  *     a graph holds the tile counters its kernels draw work from and the first-pass sums of
  *     its split rows, so two calls that use the same graph must not overlap on different
- *     streams (build one graph per stream for that).
+ *     streams (build one graph per stream for that).  The layer and step calls only launch
+ *     kernels (unless "profile" is set), so they can be captured into a HIP graph and replayed.
  *   - Every call returns a gsr_status_t and never throws or aborts.  gsr_last_error()
  *     gives a thread-local message for the last failure on the calling thread.
  *   - Weights W_i are dg x dg, row-major, "in -> out":  O[n][o] = sum_m H[n][m] W_i[m][o].

@@ -953,29 +953,33 @@ __device__ __forceinline__ TileSweep tile_sweep(int tiles) {
 // long rows draws fewer tiles.  The active window still moves through the rows in order.  Many
 // queues rather than one keep the atomics on different addresses: one counter for the 512 waves
 // of an XCD serialises and costs more than the balance gains.  The next draw is requested at
-// the start of a tile and read at its end.  Counters come in two sets: a launch counts in one
-// and clears the other for the launch after it (launches on one stream do not overlap), so no
-// separate clearing step is needed.  Which wave processes which tile varies between runs;
-// kernels that sum over the tiles a wave has seen must keep the fixed sweep.
+// the start of a tile and read at its end.  A launch leaves the counters as it found them (all
+// zero): every wave signs off when it has drawn its last tile, and the wave that signs off last
+// clears them (tile_finish), so launches need no clearing step and may be replayed from a
+// captured graph in any number.  Which wave processes which tile varies between runs; kernels
+// that sum over the tiles a wave has seen must keep the fixed sweep.
 constexpr int TILE_NQ = 64, TILE_QSTRIDE = 32;              // counters sit 128 bytes apart
-constexpr int TILE_COUNTERS = 8 * TILE_NQ * TILE_QSTRIDE;   // ints per set (the host allocates kTileCounters)
+constexpr int TILE_COUNTERS = 8 * TILE_NQ * TILE_QSTRIDE;   // ints of the counter set (the host allocates kTileCounters)
 struct TileDraws {
     int* ctr;      // this wave's queue counter
     int base;      // first tile of the queue
     int nq;        // queues in use: TILE_NQ, or the number of waves of the XCD if that is smaller
     int end;       // one past the XCD's last tile
+    int* set;      // the whole counter set
+    int* done;     // waves that have signed off
 };
-__device__ __forceinline__ TileDraws tile_draws(int tiles, int* set_now, int* set_next) {
+__device__ __forceinline__ TileDraws tile_draws(int tiles, int* set, int* done) {
     const int xcd = blockIdx.x & 7;
     const int slot = (blockIdx.x >> 3) * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int waves = (gridDim.x >> 3) * (blockDim.x >> 6);
     TileDraws d;
     d.nq = waves < TILE_NQ ? waves : TILE_NQ;
-    const int q = slot % d.nq, at = (xcd * TILE_NQ + q) * TILE_QSTRIDE;
-    d.ctr = set_now + at;
+    const int q = slot % d.nq;
+    d.ctr = set + (xcd * TILE_NQ + q) * TILE_QSTRIDE;
     d.base = (int)((int64_t)tiles * xcd / 8) + q;
     d.end = (int)((int64_t)tiles * (xcd + 1) / 8);
-    if (lane_id() == 0) set_next[at] = 0;
+    d.set = set;
+    d.done = done;
     return d;
 }
 // requests a draw; the value is valid in lane 0 once the wave waits for it (tile_drawn)
@@ -986,6 +990,22 @@ __device__ __forceinline__ int tile_request(const TileDraws& d) {
 }
 __device__ __forceinline__ int tile_drawn(const TileDraws& d, int requested) {
     return d.base + d.nq * __builtin_amdgcn_readfirstlane(requested);
+}
+// Every wave of the grid calls this once, after its last tile_drawn (all its draws have returned).
+// Sign-off in two levels, an XCD's waves on the XCD's counter and the last wave of each XCD on a
+// common one, keeps the atomics on one address few.  d.done: 9 counters, 128 bytes apart.
+__device__ __forceinline__ void tile_finish(const TileDraws& d) {
+    int last = 0;
+    if (lane_id() == 0) {
+        // no fence: this wave's own draws have returned, and nothing but the counters is handed over
+        const int waves = (int)((gridDim.x >> 3) * (blockDim.x >> 6));
+        if (atomicAdd(d.done + (blockIdx.x & 7) * TILE_QSTRIDE, 1) == waves - 1)
+            last = atomicAdd(d.done + 8 * TILE_QSTRIDE, 1) == 7 ? 1 : 0;
+    }
+    if (__builtin_amdgcn_readfirstlane(last)) {
+        for (int i = lane_id(); i < 8 * TILE_NQ; i += 64) d.set[i * TILE_QSTRIDE] = 0;
+        if (lane_id() < 9) d.done[lane_id() * TILE_QSTRIDE] = 0;
+    }
 }
 
 // ---- first pass over the chunks of very long rows ------------------------------------------------

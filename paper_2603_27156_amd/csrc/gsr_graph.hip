@@ -215,13 +215,11 @@ static void transpose_host(int64_t n, const HostCsr& a, HostCsr* t) {
         }
 }
 
-// The two sets of tile counters of a graph alternate between launches: the one a launch counts in
-// was cleared by the launch before it (both are clear when the graph is created).
-void next_draw_sets(const gsr_graph_t* g, int** now, int** next) {
-    gsr_graph_t* m = const_cast<gsr_graph_t*>(g);
-    *now = m->draws + (size_t)m->draws_turn * kTileCounters;
-    m->draws_turn ^= 1;
-    *next = m->draws + (size_t)m->draws_turn * kTileCounters;
+// The tile counters of a graph's dynamic sweeps and, behind them, the nine counters its waves sign off
+// in.  Both are zero between launches (clear when the graph is created; every launch clears them again).
+void tile_counters(const gsr_graph_t* g, int** set, int** done) {
+    *set = g->draws;
+    *done = g->draws + kTileCounters;
 }
 
 LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
@@ -432,7 +430,7 @@ gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const v
     if (st == GSR_OK) {
         const size_t chunks = (size_t)std::max(std::max(g->a.hub.n_chunks, g->at.hub.n_chunks), 1);
         e = hipMalloc((void**)&g->scratch, chunks * 64 * sizeof(float));
-        const size_t draw_bytes = (size_t)2 * kTileCounters * sizeof(int);
+        const size_t draw_bytes = ((size_t)kTileCounters + 9 * 32) * sizeof(int);
         if (e == hipSuccess) e = hipMalloc((void**)&g->draws, draw_bytes);
         if (e == hipSuccess) e = hipMemset(g->draws, 0, draw_bytes);
         if (e != hipSuccess) st = fail(GSR_ERR_HIP, "hipMalloc: %s", hipGetErrorString(e));

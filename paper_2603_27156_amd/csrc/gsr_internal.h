@@ -91,8 +91,7 @@ struct gsr_graph {
     int device = 0;
     int num_cus = 256;
     int grid = 512;          // workgroups of the persistent row-tile kernels (multiple of 8)
-    int* draws = nullptr;     // device: two sets of tile counters for the dynamic sweeps (see tile_draws)
-    int draws_turn = 0;       // which set the next launch counts in
+    int* draws = nullptr;     // device: tile counters of the dynamic sweeps + their sign-off counter (see tile_draws)
     float* scratch = nullptr; // device [max(chunks of A, chunks of A^T, 1)][64]: first-pass sums of split rows for gsr_spmm
 };
 
@@ -122,7 +121,7 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g);
 
 // Tile counters of the dynamic sweeps (device code: tile_draws): 8 XCDs x 64 queues, 128 bytes apart.
 constexpr int kTileCounters = 8 * 64 * 32;
-void next_draw_sets(const gsr_graph_t* g, int** now, int** next);
+void tile_counters(const gsr_graph_t* g, int** set, int** done);
 StepWs carve_step(const gsr_config_t* cfg, const gsr_graph_t* g);
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }

@@ -48,8 +48,8 @@ struct BlockArgs {
     const T* dy;            // dY_i, row stride ldg            (WITH_DW)
     int64_t ldg;
     float* dw_partial;      // [gridDim.x][DG*DG]              (WITH_DW)
-    int* draws_now;         // tile counters of this launch and of the next one (not WITH_DW)
-    int* draws_next;
+    int* draws;             // tile counters of the dynamic sweep and the sign-off counter (not WITH_DW)
+    int* draws_done;
 };
 
 template <int DG, typename T, int SIGN, bool WITH_DW>
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
     TileDraws td;
     int t = ts.first, t_end = ts.end;
     if constexpr (!WITH_DW) {
-        td = tile_draws(a.tiles, a.draws_now, a.draws_next);
+        td = tile_draws(a.tiles, a.draws, a.draws_done);
         t = tile_drawn(td, tile_request(td));
         t_end = td.end;
     }
@@ -131,6 +131,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         if constexpr (WITH_DW) t += ts.step;
         else t = tile_drawn(td, requested);
     }
+    if constexpr (!WITH_DW) tile_finish(td);
     if constexpr (WITH_DW) {
         // workgroup partial of dW_i: the four waves add their accumulators in wave order
         float* red = reinterpret_cast<float*>(lds);
@@ -193,8 +194,8 @@ struct GradArgs {
     T* dst;                 // dY_{i-1} plane(s): ndst planes, dst_gs apart, row stride ldd
     int64_t ldd, dst_gs;
     int ndst;
-    int* draws_now;         // tile counters of this launch and of the next one
-    int* draws_next;
+    int* draws;             // tile counters of the dynamic sweep and the sign-off counter
+    int* draws_done;
 };
 
 // Waves per workgroup of k_grad (they share one copy of W^T in LDS).  Measured at 1M rows, Dg = 64:
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
     float* st = L.st[0];
     __shared__ WLds<DG> wl;
     load_w_lds<DG>(a.w, true, wl);
-    TileDraws td = tile_draws(a.tiles, a.draws_now, a.draws_next);
+    TileDraws td = tile_draws(a.tiles, a.draws, a.draws_done);
     int t = tile_drawn(td, tile_request(td));
     while (t < td.end) {
         const int requested = tile_request(td);
@@ -275,6 +276,7 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
         }
         t = tile_drawn(td, requested);
     }
+    tile_finish(td);
 }
 
 // ---- group sum / record of a plane --------------------------------------------------------------------
@@ -524,8 +526,8 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     a.hub_part = x.hub_part(); a.w = w; a.plane = plane; a.ld = ld;
     a.out = out; a.out_given = out_given;
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
-    if (mode != 2) next_draw_sets(x.g, &a.draws_now, &a.draws_next);
-    else a.draws_now = a.draws_next = nullptr;
+    if (mode != 2) tile_counters(x.g, &a.draws, &a.draws_done);
+    else a.draws = a.draws_done = nullptr;
     const dim3 block(256);
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
     unsigned grid;
@@ -555,7 +557,7 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
     a.own_mask = own_mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
-    next_draw_sets(x.g, &a.draws_now, &a.draws_next);
+    tile_counters(x.g, &a.draws, &a.draws_done);
     ProfScope prof(KC_GRAD, x.s);
     static const int per_cu = resident_blocks((const void*)k_grad<DG, T>, 64 * GRAD_WAVES);
     hipLaunchKernelGGL((k_grad<DG, T>), dim3(persistent_grid(x.g, per_cu)), dim3(64 * GRAD_WAVES), 0, x.s, a);

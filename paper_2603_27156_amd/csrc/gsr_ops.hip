@@ -102,11 +102,11 @@ __device__ __forceinline__ void store_acc_rows(const f32x4 (&acc)[W / 16], const
 template <int W>
 __global__ __launch_bounds__(256) void k_spmm_tile(CsrView g, int n, int tiles, const float* __restrict__ x, int64_t ldx,
                                                    float* __restrict__ y, int64_t ldy, const float* __restrict__ hub_part,
-                                                   int* draws_now, int* draws_next) {
+                                                   int* draws, int* draws_done) {
     __shared__ TileLds lds[4];
     TileLds& L = lds[threadIdx.x >> 6];
     const int lane = lane_id();
-    const TileDraws td = tile_draws(tiles, draws_now, draws_next);
+    const TileDraws td = tile_draws(tiles, draws, draws_done);
     for (int t = tile_drawn(td, tile_request(td)); t < td.end;) {
         const int requested = tile_request(td);
         const int r0 = t * 16;
@@ -122,17 +122,18 @@ __global__ __launch_bounds__(256) void k_spmm_tile(CsrView g, int n, int tiles, 
         store_acc_rows<W>(acc, g, hub_part, has_hub, r0, n, L.rp, y, ldy, lane);
         t = tile_drawn(td, requested);
     }
+    tile_finish(td);
 }
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_aggregate_tile(CsrView g, int n, int tiles, const T* __restrict__ vals,
                                                         const typename MaskOf<DG>::type* __restrict__ masks, int k,
                                                         const float* __restrict__ hub_part, float* __restrict__ h_out,
-                                                        int* draws_now, int* draws_next) {
+                                                        int* draws, int* draws_done) {
     __shared__ TileLds lds[4];
     TileLds& L = lds[threadIdx.x >> 6];
     const int lane = lane_id();
-    const TileDraws td = tile_draws(tiles, draws_now, draws_next);
+    const TileDraws td = tile_draws(tiles, draws, draws_done);
     for (int t = tile_drawn(td, tile_request(td)); t < td.end;) {
         const int requested = tile_request(td);
         const int r0 = t * 16;
@@ -149,6 +150,7 @@ __global__ __launch_bounds__(256) void k_aggregate_tile(CsrView g, int n, int ti
         store_acc_rows<DG>(acc, g, hub_part, has_hub, r0, n, L.rp, h_out, DG, lane);
         t = tile_drawn(td, requested);
     }
+    tile_finish(td);
 }
 
 // GS of 16 rows per wave: rows are read four at a time into an LDS tile, then selected in the
@@ -245,7 +247,7 @@ static gsr_status_t aggregate_impl(const gsr_graph_t* g, const void* vals, const
                            (const T*)v_rec, (const M*)m_rec, k, part);
     }
     int *dn, *dx;
-    next_draw_sets(g, &dn, &dx);
+    tile_counters(g, &dn, &dx);
     hipLaunchKernelGGL((k_aggregate_tile<DG, T>), dim3((unsigned)g->grid), dim3(256), 0, s, v, (int)n, (int)((n + 15) / 16),
                        (const T*)v_rec, (const M*)m_rec, k, (const float*)part, h_out, dn, dx);
     GSR_HIP_CHECK(hipGetLastError());
@@ -324,7 +326,7 @@ gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t
             else hipLaunchKernelGGL((k_hub_dense<32, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
         }
         int *dn, *dx;
-        next_draw_sets(g, &dn, &dx);
+        tile_counters(g, &dn, &dx);
         if (width == 64)
             hipLaunchKernelGGL((k_spmm_tile<64>), dim3((unsigned)g->grid), dim3(256), 0, s, view, (int)g->n, tiles, x, ldx, y, ldy,
                                (const float*)g->scratch, dn, dx);

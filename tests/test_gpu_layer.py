@@ -336,3 +336,73 @@ def test_directed_graph_with_mean_aggregation(name, layout):
     assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
     for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
         assert_close(key, out[key], ref[key])
+
+
+def test_step_captured_in_a_graph_replays_bit_identically():
+    """gsr_step only launches kernels (no allocation, no memset, no host synchronisation), so it can be captured
+    into a HIP graph.  Replays interleaved with eager steps must give the eager results bit for bit."""
+    c = case("cfg2s", PLANAR)
+    w = c.w
+    dv = c.dev
+    f32 = dict(dtype=torch.float32, device=dv)
+    x0 = c.to_dev(c.inp.x0)
+    W = torch.from_numpy(np.ascontiguousarray(c.inp.weights[:w.l])).to(dv)
+    w_out = torch.from_numpy(c.inp.w_out).to(dv)
+    b_out, target = torch.zeros(1, **f32), torch.from_numpy(c.inp.target).to(dv)
+    ws = torch.empty(gsr.gsr_workspace_size(c.gg, c.gcfg)[1], dtype=torch.uint8, device=dv)
+
+    def buffers():
+        return dict(loss=torch.zeros(1, **f32), dW=torch.empty_like(W), dw=torch.empty(w.d, **f32), db=torch.zeros(1, **f32),
+                    dx0=torch.empty_like(x0), x0r=torch.empty_like(x0))
+
+    def step(b):
+        gsr.gsr_step(c.gg, c.gcfg, x0, W, w_out, b_out, target, b["loss"], b["dW"], b["dw"], b["db"], dx0_out=b["dx0"],
+                     x0_rebuilt_out=b["x0r"], workspace=ws)
+
+    eager = buffers()
+    step(eager)
+    torch.cuda.synchronize()
+    want = {k: v.clone() for k, v in eager.items()}
+    captured = buffers()
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            step(captured)
+    for rep in range(3):
+        for v in captured.values():
+            v.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in want:
+            assert torch.equal(captured[k], want[k]), (rep, k)
+        step(eager)                                   # eager work between the replays
+        torch.cuda.synchronize()
+        for k in want:
+            assert torch.equal(eager[k], want[k]), (rep, k)
+
+
+def test_layer_with_an_odd_number_of_launches_replays_from_a_graph():
+    """Three groups: the layer's forward is an odd number of launches that draw tiles from the graph's counters.
+    Every launch leaves the counters clear, so a captured forward can be replayed any number of times."""
+    w = synth.scaled(synth.workload(1), 2001, l=1, d=192, c=3)
+    c = Case(w, 0, PLANAR)
+    W = torch.from_numpy(c.inp.weights[0]).to(c.dev)
+    X = c.x0_on_grid()
+    want = c.to_dev(X)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, W, want)
+    assert_close("Y", c.to_host(want), oracle.layer_forward(c.og, c.ocfg, c.inp.weights[0], X))
+    ws = torch.empty(gsr.gsr_workspace_size(c.gg, c.gcfg)[0], dtype=torch.uint8, device=c.dev)
+    src, y = c.to_dev(X), c.to_dev(X)
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            gsr.gsr_layer_forward(c.gg, c.gcfg, W, y, workspace=ws)
+    for rep in range(4):
+        y.copy_(src)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want), rep
