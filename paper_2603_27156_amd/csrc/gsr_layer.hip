@@ -8,7 +8,7 @@
 //             in place; the GS record of the row just written is emitted in the same pass.  With
 //             WITH_DW it also accumulates dW_i += H^T dY_i, so the recomputed H is consumed
 //             where it is rebuilt.
-//   k_grad    Q = A^T dY_i (dense-row gather); dH = Q W_i^T on the matrix cores; only the k
+//   k_grad    (first: dW_i summed from the workgroup partials the kernel before left;) Q = A^T dY_i (dense-row gather); dH = Q W_i^T on the matrix cores; only the k
 //             positions recorded by I are read; back through the RMS scale; dY_{i-1} += dZ.
 //   k_sum     Y_0 = sum_{j>=2} X_j and/or the GS record of a plane.
 //   k_head    scalar linear head, squared error, dX^L, partial sums for dw_out / db / loss.
@@ -156,26 +156,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
     }
 }
 
-// dW_i[e] = sum over workgroup partials.  A block owns 64 entries; its 16 thread rows each sum a
-// contiguous sixteenth of the partials in ascending order, then the 16 sums are added in order.
-__global__ __launch_bounds__(1024) void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems,
-                                                    float* __restrict__ out) {
-    __shared__ float red[16][64];
-    const int e = blockIdx.x * 64 + (threadIdx.x & 63), seg = threadIdx.x >> 6;
-    const int per = (nparts + 15) / 16, p0 = seg * per, p1 = min(nparts, p0 + per);
-    float acc = 0.f;
-    if (e < elems)
-        for (int p = p0; p < p1; ++p) acc += partial[(size_t)p * elems + e];
-    red[seg][threadIdx.x & 63] = acc;
-    __syncthreads();
-    if (seg == 0 && e < elems) {
-        float s = red[0][threadIdx.x];
-#pragma unroll
-        for (int q = 1; q < 16; ++q) s += red[q][threadIdx.x];
-        out[e] = s;
-    }
-}
-
 // ---- block: data gradient ---------------------------------------------------------------------------
 template <int DG, typename T>
 struct GradArgs {
@@ -196,7 +176,40 @@ struct GradArgs {
     int ndst;
     int* draws;             // tile counters of the dynamic sweep and the sign-off counter
     int* draws_done;
+    // dW_i of the same block, left as workgroup partials by the inverse + dW kernel just before: summed here by
+    // the first workgroups before they start on tiles, which saves a launch per block (dw_out == NULL: nothing to do)
+    const float* dw_partial;
+    int dw_parts;
+    float* dw_out;
 };
+
+// dW_i[e] = sum over the workgroup partials, in a fixed order: a workgroup takes 64 entries at a time; its four
+// waves each sum a contiguous quarter of the partials in ascending order (sixteen loads in flight), then the four
+// sums are added in order.
+template <int ELEMS>
+__device__ __forceinline__ void dw_reduce_slices(const float* __restrict__ partial, int nparts, float* __restrict__ out,
+                                                 float* red /* 256 floats of LDS */) {
+    const int col = threadIdx.x & 63, seg = threadIdx.x >> 6;
+    const int per = (nparts + 3) / 4, p0 = seg * per, p1 = min(nparts, p0 + per);
+    for (int slice = blockIdx.x; slice < ELEMS / 64; slice += gridDim.x) {
+        const float* src = partial + slice * 64 + col;
+        float acc = 0.f;
+        int p = p0;
+        for (; p + 16 <= p1; p += 16) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = src[(size_t)(p + u) * ELEMS];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) acc += v[u];
+        }
+        for (; p < p1; ++p) acc += src[(size_t)p * ELEMS];
+        __syncthreads();
+        red[seg * 64 + col] = acc;
+        __syncthreads();
+        if (seg == 0) out[slice * 64 + col] = ((red[col] + red[64 + col]) + red[128 + col]) + red[192 + col];
+    }
+    __syncthreads();
+}
 
 // Waves per workgroup of k_grad (they share one copy of W^T in LDS).  Measured at 1M rows, Dg = 64:
 // 4 and 8 waves (16 resident waves per compute unit either way) take the same time; 6 and 10
@@ -211,6 +224,8 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
     WaveLds<DG, 1>& L = lds[wave];
     float* st = L.st[0];
     __shared__ WLds<DG> wl;
+    static_assert(GRAD_WAVES == 4 && sizeof(lds) >= 256 * sizeof(float), "dw_reduce_slices expects 256 threads");
+    if (a.dw_out) dw_reduce_slices<DG * DG>(a.dw_partial, a.dw_parts, a.dw_out, reinterpret_cast<float*>(lds));
     load_w_lds<DG>(a.w, true, wl);
     TileDraws td = tile_draws(a.tiles, a.draws, a.draws_done);
     int t = tile_drawn(td, tile_request(td));
@@ -550,13 +565,14 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
 template <int DG, typename T>
 static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const float* w,
                         const typename MaskOf<DG>::type* own_mask, const T* z,
-                        int64_t ldz, T* dst, int64_t ldd, int64_t dst_gs, int ndst) {
+                        int64_t ldz, T* dst, int64_t ldd, int64_t dst_gs, int ndst, int dw_parts, float* dw_out) {
     launch_hub_dense<DG, T>(x, dy, ldg);
     GradArgs<DG, T> a;
     a.gt = make_view(x.g, true);
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
     a.own_mask = own_mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
+    a.dw_partial = x.dw_partial(); a.dw_parts = dw_parts; a.dw_out = dw_out;
     tile_counters(x.g, &a.draws, &a.draws_done);
     ProfScope prof(KC_GRAD, x.s);
     static const int per_cu = resident_blocks((const void*)k_grad<DG, T>, 64 * GRAD_WAVES);
@@ -619,14 +635,10 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         }
         const unsigned nparts =
             launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld);
-        {
-            ProfScope prof(KC_DW_REDUCE, x.s);
-            hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 63) / 64), dim3(1024), 0, x.s, (const float*)x.dw_partial(),
-                               (int)nparts, DG * DG, dw_out + (size_t)(i - 1) * DG * DG);
-        }
+        float* dwi = dw_out + (size_t)(i - 1) * DG * DG;      // summed from the partials by the gradient kernel
         const typename MaskOf<DG>::type* own = x.rec(i - 1, layer).mask;
-        if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, own, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1);
-        else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, own, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1);
+        if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, own, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1, (int)nparts, dwi);
+        else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, own, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1, (int)nparts, dwi);
     }
 }
 
