@@ -1040,14 +1040,11 @@ __device__ __forceinline__ void hub_chunk_store(const f32x4 (&acc)[DG / 16], flo
 }
 
 template <int DG, typename T>
-__global__ __launch_bounds__(256) void k_hub_records(CsrView g, HubChunks h, const T* __restrict__ vals,
-                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k,
-                                                     float* __restrict__ part) {
-    __shared__ HubLds lds[4];
+__device__ __forceinline__ void hub_records_pass(const CsrView& g, const HubChunks& h, const T* __restrict__ vals,
+                                                 const typename MaskOf<DG>::type* __restrict__ masks, int k,
+                                                 float* __restrict__ part, HubLds& L, int first_wave, int nwaves) {
     const int lane = lane_id();
-    HubLds& L = lds[threadIdx.x >> 6];
-    const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    for (int q = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; q < h.n_chunks; q += nwaves) {
+    for (int q = first_wave; q < h.n_chunks; q += nwaves) {
         const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
         hub_chunk_begin(L, e0, e1, lane);
         f32x4 acc[DG / 16];
@@ -1057,15 +1054,11 @@ __global__ __launch_bounds__(256) void k_hub_records(CsrView g, HubChunks h, con
         hub_chunk_store<DG>(acc, part + (size_t)q * DG, lane);
     }
 }
-
 template <int DG, typename T>
-__global__ __launch_bounds__(256) void k_hub_dense(CsrView g, HubChunks h, const T* __restrict__ x, int64_t ld,
-                                                   float* __restrict__ part) {
-    __shared__ HubLds lds[4];
+__device__ __forceinline__ void hub_dense_pass(const CsrView& g, const HubChunks& h, const T* __restrict__ x, int64_t ld,
+                                               float* __restrict__ part, HubLds& L, int first_wave, int nwaves) {
     const int lane = lane_id();
-    HubLds& L = lds[threadIdx.x >> 6];
-    const int nwaves = (gridDim.x * blockDim.x) >> 6;
-    for (int q = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; q < h.n_chunks; q += nwaves) {
+    for (int q = first_wave; q < h.n_chunks; q += nwaves) {
         const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
         hub_chunk_begin(L, e0, e1, lane);
         f32x4 acc[DG / 16];
@@ -1074,6 +1067,36 @@ __global__ __launch_bounds__(256) void k_hub_dense(CsrView g, HubChunks h, const
         gather_dense_mfma<DG, T, 16>(g, x, ld, e0, e1, L.rp, L.ebuf, lane, acc);
         hub_chunk_store<DG>(acc, part + (size_t)q * DG, lane);
     }
+}
+
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_hub_records(CsrView g, HubChunks h, const T* __restrict__ vals,
+                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k,
+                                                     float* __restrict__ part) {
+    __shared__ HubLds lds[4];
+    hub_records_pass<DG, T>(g, h, vals, masks, k, part, lds[threadIdx.x >> 6], (blockIdx.x * blockDim.x + threadIdx.x) >> 6,
+                            (gridDim.x * blockDim.x) >> 6);
+}
+
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_hub_dense(CsrView g, HubChunks h, const T* __restrict__ x, int64_t ld,
+                                                   float* __restrict__ part) {
+    __shared__ HubLds lds[4];
+    hub_dense_pass<DG, T>(g, h, x, ld, part, lds[threadIdx.x >> 6], (blockIdx.x * blockDim.x + threadIdx.x) >> 6,
+                          (gridDim.x * blockDim.x) >> 6);
+}
+
+// Both first passes of one block's backward in one launch: blockIdx.y = 0 takes the records over A (for the
+// inverse), blockIdx.y = 1 the dense gradient rows over A^T (for the data gradient).
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_hub_both(CsrView ga, HubChunks ha, const T* __restrict__ vals,
+                                                  const typename MaskOf<DG>::type* __restrict__ masks, int k,
+                                                  float* __restrict__ part_a, CsrView gt, HubChunks ht,
+                                                  const T* __restrict__ x, int64_t ld, float* __restrict__ part_t) {
+    __shared__ HubLds lds[4];
+    const int first = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nwaves = (gridDim.x * blockDim.x) >> 6;
+    if (blockIdx.y == 0) hub_records_pass<DG, T>(ga, ha, vals, masks, k, part_a, lds[threadIdx.x >> 6], first, nwaves);
+    else hub_dense_pass<DG, T>(gt, ht, x, ld, part_t, lds[threadIdx.x >> 6], first, nwaves);
 }
 
 // Row `row` of A * scatter(V, I): direct gather, or the sum of its first-pass partials.

@@ -240,6 +240,8 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     w.hub_partial = off;
     size_t chunks = (size_t)std::max(g->a.hub.n_chunks, g->at.hub.n_chunks);
     off += align_up(std::max<size_t>(chunks, 1) * dg * sizeof(float));
+    w.hub_partial2 = off;
+    off += align_up(std::max<size_t>(chunks, 1) * dg * sizeof(float));
     w.total = off;
     return w;
 }

@@ -107,6 +107,7 @@ struct LayerWs {
     size_t y0;           // Y_0 plane [n][dg] of T (C > 2)
     size_t dw_partial;   // [grid][dg*dg] float
     size_t hub_partial;  // [max(n_chunks A, n_chunks A^T)][dg] float
+    size_t hub_partial2; // same size: the backward's two first passes of a block run as one launch
     size_t total;
 };
 struct StepWs {

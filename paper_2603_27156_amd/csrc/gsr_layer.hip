@@ -480,6 +480,7 @@ struct Ctx {
     T* y0() const { return (T*)(ws + lw.y0); }
     float* dw_partial() const { return (float*)(ws + lw.dw_partial); }
     float* hub_part() const { return (float*)(ws + lw.hub_partial); }
+    float* hub_part2() const { return (float*)(ws + lw.hub_partial2); }
 };
 
 // Workgroups of 256 threads one CU keeps resident for a kernel, and the persistent grid that
@@ -529,11 +530,26 @@ static void launch_hub_dense(const Ctx<DG, T>& x, const T* plane, int64_t ld) {
                        make_view(x.g, true), hc, plane, ld, x.hub_part());
 }
 
+// Both first passes of a block's backward (records over A into hub_part, dY rows over A^T into hub_part2).
+// Returns false if there is nothing to do.
+template <int DG, typename T>
+static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const T* dy, int64_t ldg) {
+    const HubPlan &ha = x.g->a.hub, &ht = x.g->at.hub;
+    if (ha.n_chunks == 0 && ht.n_chunks == 0) return false;
+    HubChunks ca{ha.ce0, ha.ce1, ha.n_chunks}, ct{ht.ce0, ht.ce1, ht.n_chunks};
+    ProfScope prof(KC_HUB, x.s);
+    const unsigned gx = (unsigned)std::min((std::max(ha.n_chunks, ht.n_chunks) + 3) / 4, 4096);
+    hipLaunchKernelGGL((k_hub_both<DG, T>), dim3(gx, 2), dim3(256), 0, x.s, make_view(x.g, false), ca, (const T*)in.vals,
+                       (const typename MaskOf<DG>::type*)in.mask, x.cfg->k, x.hub_part(), make_view(x.g, true), ct, dy, ldg,
+                       x.hub_part2());
+    return true;
+}
+
 // mode 0: forward (+), 1: inverse (-), 2: inverse (-) with dW
 template <int DG, typename T>
 static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>& in, const float* w, T* plane, int64_t ld,
-                             const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg) {
-    launch_hub_records<DG, T>(x, in);
+                             const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg, bool first_pass_done = false) {
+    if (!first_pass_done) launch_hub_records<DG, T>(x, in);
     BlockArgs<DG, T> a;
     a.g = make_view(x.g, false);
     a.n = (int)x.cfg->n; a.tiles = x.tiles;
@@ -565,11 +581,13 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
 template <int DG, typename T>
 static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const float* w,
                         const typename MaskOf<DG>::type* own_mask, const T* z,
-                        int64_t ldz, T* dst, int64_t ldd, int64_t dst_gs, int ndst, int dw_parts, float* dw_out) {
-    launch_hub_dense<DG, T>(x, dy, ldg);
+                        int64_t ldz, T* dst, int64_t ldd, int64_t dst_gs, int ndst, int dw_parts, float* dw_out,
+                        bool first_pass_done = false) {
+    if (!first_pass_done) launch_hub_dense<DG, T>(x, dy, ldg);
     GradArgs<DG, T> a;
     a.gt = make_view(x.g, true);
-    a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part(); a.w = w;
+    a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = first_pass_done ? x.hub_part2() : x.hub_part();
+    a.w = w;
     a.own_mask = own_mask; a.z = z; a.ldz = ldz; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
     a.dw_partial = x.dw_partial(); a.dw_parts = dw_parts; a.dw_out = dw_out;
@@ -633,12 +651,13 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         } else if (C == 2) {
             out = x.rec(0, layer);                                                     // X_2 = Y_0 of this layer
         }
+        launch_hub_both<DG, T>(x, x.rec(i - 1, layer), dy.grp(i - 1), dy.ld);
         const unsigned nparts =
-            launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld);
+            launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld, true);
         float* dwi = dw_out + (size_t)(i - 1) * DG * DG;      // summed from the partials by the gradient kernel
         const typename MaskOf<DG>::type* own = x.rec(i - 1, layer).mask;
-        if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, own, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1, (int)nparts, dwi);
-        else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, own, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1, (int)nparts, dwi);
+        if (i >= 2) launch_grad<DG, T>(x, dy.grp(i - 1), dy.ld, wi, own, z, ldz, dy.grp(i - 2), dy.ld, dy.gs, 1, (int)nparts, dwi, true);
+        else launch_grad<DG, T>(x, dy.grp(0), dy.ld, wi, own, z, ldz, dy.grp(1), dy.ld, dy.gs, C - 1, (int)nparts, dwi, true);
     }
 }
 
