@@ -104,7 +104,7 @@ gsr_status_t gsr_set_option(const char* key, int64_t value);
  * gsr_profile_read waits for the recorded events and returns the summed duration and number
  * of launches of one class since the last gsr_profile_reset.  Classes: 0 block forward,
  * 1 block inverse, 2 block inverse + weight gradient, 3 data gradient, 4 group sum / record,
- * 5 hub first pass, 6 unused (the dW reduction is part of class 3), 7 head, 8 layout copy.  Not thread-safe. */
+ * 5 hub first pass, 6 dW reduction (on large graphs it is part of class 3), 7 head, 8 layout copy.  Not thread-safe. */
 gsr_status_t gsr_profile_read(int32_t kernel_class, double* total_ms, int64_t* launches);
 gsr_status_t gsr_profile_reset(void);
 const char* gsr_profile_class_name(int32_t kernel_class);
