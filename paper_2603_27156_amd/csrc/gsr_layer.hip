@@ -269,7 +269,7 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
         const bool has_hub = tile_begin(a.gt, rpv, L.rp, lane);
         f32x4 qacc[DG / 16];
         tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, qacc, [&](int e_a, int e_b) {
-            gather_dense_mfma<DG, T, 16>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
+            gather_dense_mfma<DG, T, (sizeof(T) == 4 || DG == 32) ? 16 : 8>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
                                      __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, lane, qacc);
         });
         wave_sync();
