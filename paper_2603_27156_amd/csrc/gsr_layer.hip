@@ -56,7 +56,7 @@ template <int DG, typename T, int SIGN, bool WITH_DW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
     constexpr int LR = DG + 1, CPL = DG / 16;
     __shared__ WaveLds<DG, 1> lds[4];
-    const int lane = lane_id(), wave = threadIdx.x >> 6, tg = lane >> 4, tj = lane & 15;
+    const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tg = lane >> 4, tj = lane & 15;
     WaveLds<DG, 1>& L = lds[wave];
     float* st_h = L.st[0];
     __shared__ WLds<DG> wl;
@@ -242,7 +242,7 @@ template <int DG, typename T>
 __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
     constexpr int CPL = DG / 16;
     __shared__ WaveLds<DG, 1> lds[GRAD_WAVES];
-    const int lane = lane_id(), wave = threadIdx.x >> 6, tg = lane >> 4, tj = lane & 15;
+    const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tg = lane >> 4, tj = lane & 15;
     WaveLds<DG, 1>& L = lds[wave];
     float* st = L.st[0];
     __shared__ WLds<DG> wl;
