@@ -937,7 +937,8 @@ struct TileSweep {
 __device__ __forceinline__ TileSweep tile_sweep(int tiles) {
     const int xcd = blockIdx.x & 7, local_wg = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
     const int waves_per_wg = blockDim.x >> 6;
-    const int slot = local_wg * waves_per_wg + (threadIdx.x >> 6);
+    // the wave index through readfirstlane: everything derived from the tile number then lives in scalar registers
+    const int slot = local_wg * waves_per_wg + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     TileSweep t;
     const int t0 = (int)((int64_t)tiles * xcd / 8), t1 = (int)((int64_t)tiles * (xcd + 1) / 8);
     t.first = t0 + slot;
@@ -970,7 +971,7 @@ struct TileDraws {
 };
 __device__ __forceinline__ TileDraws tile_draws(int tiles, int* set, int* done) {
     const int xcd = blockIdx.x & 7;
-    const int slot = (blockIdx.x >> 3) * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int slot = (blockIdx.x >> 3) * (blockDim.x >> 6) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int waves = (gridDim.x >> 3) * (blockDim.x >> 6);
     TileDraws d;
     d.nq = waves < TILE_NQ ? waves : TILE_NQ;
