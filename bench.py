@@ -34,8 +34,8 @@ MEASURED_PIPES = {
                 "grad": {"valu_busy": 0.18, "mfma_busy": 0.33}},
 }
 MEASURED_TRAFFIC = {
-    "cfg2-1M": {"grad": 2.0 * 656.2e6 + 386.1e6, "block_forward": 2.0 * 248.3e6 + 320.5e6,
-                "block_backward": 2.0 * 355.8e6 + 291.4e6},
+    "cfg2-1M": {"grad": 2.0 * 659.1e6 + 386.3e6, "block_forward": 2.0 * 229.1e6 + 312.3e6,
+                "block_backward": 2.0 * 356.0e6 + 291.4e6},
 }
 
 
