@@ -244,6 +244,10 @@ struct CsrView {
     const int32_t* hub_cptr;
     int32_t n_hub;
     int32_t hub_threshold;
+    // tiles with more than heavy_edges stored entries, ascending (see TileDeal)
+    const int32_t* heavy;
+    int32_t n_heavy;
+    int32_t heavy_edges;
 };
 
 __device__ __forceinline__ int find_hub(const CsrView& g, int row) {
@@ -1007,6 +1011,29 @@ __device__ __forceinline__ void tile_finish(const TileDraws& d) {
         for (int i = lane_id(); i < 8 * TILE_NQ; i += 64) d.set[i * TILE_QSTRIDE] = 0;
         if (lane_id() < 9) d.done[lane_id() * TILE_QSTRIDE] = 0;
     }
+}
+
+// ---- the long tiles first -----------------------------------------------------------------------------
+// A tile with many stored entries takes many times longer than a median one.  Met late in a sweep it makes
+// the kernel's tail; met twice by one wave of a fixed sweep it makes that wave the last.  The layer kernels
+// therefore deal the listed heavy tiles out first, wave w of the grid taking entries w, w + waves, .. of the
+// list, and pass them over in the sweep that follows (a tile is heavy by its row pointers alone, so the sweep
+// needs no flag).  The assignment is the same on every run.
+struct TileDeal {
+    int at;        // this wave's next entry of the list
+    int waves;     // waves of the grid
+    bool on;       // still dealing
+};
+__device__ __forceinline__ TileDeal tile_deal(const CsrView& g) {
+    TileDeal d;
+    d.waves = (int)(gridDim.x * (blockDim.x >> 6));
+    d.at = (int)(blockIdx.x * (blockDim.x >> 6)) + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    d.on = d.at < g.n_heavy;
+    return d;
+}
+// rpv: the tile's row pointers as tile_rp_load returns them
+__device__ __forceinline__ bool tile_is_heavy(const CsrView& g, int rpv) {
+    return __builtin_amdgcn_readlane(rpv, 16) - __builtin_amdgcn_readlane(rpv, 0) > g.heavy_edges;
 }
 
 // ---- first pass over the chunks of very long rows ------------------------------------------------

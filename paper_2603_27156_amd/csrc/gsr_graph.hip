@@ -133,6 +133,7 @@ static void free_csr(Csr& c) {
     if (c.hub.crow) (void)hipFree(c.hub.crow);
     if (c.hub.ce0) (void)hipFree(c.hub.ce0);
     if (c.hub.ce1) (void)hipFree(c.hub.ce1);
+    if (c.heavy) (void)hipFree(c.heavy);
     c = Csr();
 }
 
@@ -145,6 +146,11 @@ static gsr_status_t upload(const std::vector<V>& h, V** d) {
 }
 
 static gsr_status_t upload_csr(const HostCsr& h, int64_t n, int64_t threshold, int64_t chunk, Csr* out) {
+    std::vector<int32_t> heavy;
+    for (int64_t t0 = 0; t0 < n; t0 += 16)
+        if (h.rp[std::min<int64_t>(n, t0 + 16)] - h.rp[t0] > kHeavyTileEdges) heavy.push_back((int32_t)(t0 / 16));
+    out->n_heavy = (int32_t)heavy.size();
+    GSR_TRY(upload(heavy, &out->heavy));
     GSR_TRY(upload(h.rp, &out->rp));
     GSR_TRY(upload(h.ci, &out->ci));
     GSR_TRY(upload(h.av, &out->av));

@@ -71,18 +71,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
     // the weight gradient sums over the tiles a wave has seen: fixed sweep there, drawn tiles otherwise
     const TileSweep ts = tile_sweep(a.tiles);
     TileDraws td;
+    TileDeal deal = tile_deal(a.g);
+    int requested = 0;     // the draw that is outstanding (dynamic sweep)
     int t = ts.first, t_end = ts.end;
     if constexpr (!WITH_DW) {
         td = tile_draws(a.tiles, a.draws, a.draws_done);
-        t = tile_drawn(td, tile_request(td));
+        requested = tile_request(td);
         t_end = td.end;
+        if (!deal.on) t = tile_drawn(td, requested);
     }
+    if (deal.on) { t = a.g.heavy[deal.at]; t_end = a.tiles; }
     while (t < t_end) {
-        int requested = 0;
-        if constexpr (!WITH_DW) requested = tile_request(td);
+        if constexpr (!WITH_DW) {
+            if (!deal.on) requested = tile_request(td);
+        }
         const int r0 = t * 16;
         wave_sync();
         const int rpv = tile_rp_load(a.g, r0, a.n, lane);
+        if (!deal.on && tile_is_heavy(a.g, rpv)) {      // dealt out before the sweep
+            if constexpr (WITH_DW) t += ts.step;
+            else t = tile_drawn(td, requested);
+            continue;
+        }
         // The tile's own rows (X_i, and dY_i for the weight gradient) are requested first, in the
         // tile register layout, and arrive while the neighbour records are gathered.
         float xy[4][CPL], gy[WITH_DW ? 4 : 1][CPL];
@@ -128,8 +138,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
             wave_sync();
             emit_tile<DG, T>(st_h, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane);
         }
-        if constexpr (WITH_DW) t += ts.step;
-        else t = tile_drawn(td, requested);
+        if (deal.on) {
+            deal.at += deal.waves;
+            deal.on = deal.at < a.g.n_heavy;
+            if (deal.on) {
+                t = a.g.heavy[deal.at];
+            } else if constexpr (WITH_DW) {
+                t = ts.first; t_end = ts.end;
+            } else {
+                t = tile_drawn(td, requested); t_end = td.end;
+            }
+        } else {
+            if constexpr (WITH_DW) t += ts.step;
+            else t = tile_drawn(td, requested);
+        }
     }
     if constexpr (!WITH_DW) tile_finish(td);
     if constexpr (WITH_DW) {
@@ -250,12 +272,21 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
     if (a.dw_out) dw_reduce_slices<DG * DG>(a.dw_partial, a.dw_parts, a.dw_out, reinterpret_cast<float*>(lds));
     load_w_lds<DG>(a.w, true, wl);
     TileDraws td = tile_draws(a.tiles, a.draws, a.draws_done);
-    int t = tile_drawn(td, tile_request(td));
-    while (t < td.end) {
-        const int requested = tile_request(td);
+    TileDeal deal = tile_deal(a.gt);
+    int requested = tile_request(td);      // the draw that is outstanding
+    int t_end = td.end;
+    int t = 0;
+    if (deal.on) { t = a.gt.heavy[deal.at]; t_end = a.tiles; }
+    else t = tile_drawn(td, requested);
+    while (t < t_end) {
+        if (!deal.on) requested = tile_request(td);
         const int r0 = t * 16;
         wave_sync();
         const int rpv = tile_rp_load(a.gt, r0, a.n, lane);
+        if (!deal.on && tile_is_heavy(a.gt, rpv)) {    // dealt out before the sweep
+            t = tile_drawn(td, requested);
+            continue;
+        }
         // what the epilogue needs of the tile's own rows is requested first
         typename MaskOf<DG>::type own[4];
         float z[4][CPL];
@@ -311,7 +342,14 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
                 if (ok) store_cols<CPL, T>(p, g);
             }
         }
-        t = tile_drawn(td, requested);
+        if (deal.on) {
+            deal.at += deal.waves;
+            deal.on = deal.at < a.gt.n_heavy;
+            if (deal.on) t = a.gt.heavy[deal.at];
+            else { t = tile_drawn(td, requested); t_end = td.end; }
+        } else {
+            t = tile_drawn(td, requested);
+        }
     }
     tile_finish(td);
 }
