@@ -558,6 +558,17 @@ static unsigned persistent_grid(const gsr_graph_t* g, int per_cu) {
     return (unsigned)grid;
 }
 
+// Whether a launch of `grid` workgroups of four waves deals the heavy tiles out first (TileDeal).  Measured: on the
+// 1M-node workload (15 - 30 tiles per wave) it shortens every layer kernel by 10 - 16 %, and on a 49,600-node
+// graph whose tiles are all heavy the forward kernel by 17 %; on the 100k-node workload (1.5 tiles per wave, 2 %
+// of them just above the threshold) the gradient kernel gets 19 % longer.  So: only with several tiles per wave,
+// or when most tiles are heavy anyway.
+static void heavy_first(CsrView* v, int tiles, unsigned grid) {
+    if ((int64_t)tiles >= (int64_t)4 * 4 * grid || 2 * (int64_t)v->n_heavy >= tiles) return;
+    v->n_heavy = 0;
+    v->heavy_edges = 0x7fffffff;
+}
+
 template <int DG, typename T>
 static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0,
                        const Record<DG, T>& out, bool out_given = false) {
@@ -625,14 +636,17 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     if (mode == 0) {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false>);
         grid = persistent_grid(x.g, per_cu);
+        heavy_first(&a.g, x.tiles, grid);
         hipLaunchKernelGGL((k_block<DG, T, +1, false>), dim3(grid), block, 0, x.s, a);
     } else if (mode == 1) {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false>);
         grid = persistent_grid(x.g, per_cu);
+        heavy_first(&a.g, x.tiles, grid);
         hipLaunchKernelGGL((k_block<DG, T, -1, false>), dim3(grid), block, 0, x.s, a);
     } else {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true>);
         grid = persistent_grid(x.g, per_cu);
+        heavy_first(&a.g, x.tiles, grid);
         hipLaunchKernelGGL((k_block<DG, T, -1, true>), dim3(grid), block, 0, x.s, a);
     }
     return grid;
@@ -654,7 +668,9 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     tile_counters(x.g, &a.draws, &a.draws_done);
     ProfScope prof(KC_GRAD, x.s);
     static const int per_cu = resident_blocks((const void*)k_grad<DG, T>, 64 * GRAD_WAVES);
-    hipLaunchKernelGGL((k_grad<DG, T>), dim3(persistent_grid(x.g, per_cu)), dim3(64 * GRAD_WAVES), 0, x.s, a);
+    const unsigned grid = persistent_grid(x.g, per_cu);
+    heavy_first(&a.gt, x.tiles, grid);
+    hipLaunchKernelGGL((k_grad<DG, T>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
 }
 
 // eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of the
