@@ -1018,7 +1018,7 @@ __device__ __forceinline__ void tile_finish(const TileDraws& d) {
 // the kernel's tail; met twice by one wave of a fixed sweep it makes that wave the last.  The layer kernels
 // therefore deal the listed heavy tiles out first, wave w of the grid taking entries w, w + waves, .. of the
 // list, and pass them over in the sweep that follows (a tile is heavy by its row pointers alone, so the sweep
-// needs no flag).  The assignment is the same on every run.
+// needs no flag; the check sits after the tile's own rows have been requested, which costs a few wasted loads).  The assignment is the same on every run.
 struct TileDeal {
     int at;        // this wave's next entry of the list
     int waves;     // waves of the grid
@@ -1031,9 +1031,17 @@ __device__ __forceinline__ TileDeal tile_deal(const CsrView& g) {
     d.on = d.at < g.n_heavy;
     return d;
 }
-// rpv: the tile's row pointers as tile_rp_load returns them
-__device__ __forceinline__ bool tile_is_heavy(const CsrView& g, int rpv) {
-    return __builtin_amdgcn_readlane(rpv, 16) - __builtin_amdgcn_readlane(rpv, 0) > g.heavy_edges;
+// s_rp: the tile's row pointers as tile_begin published them.  Rows that are split do not count: their
+// neighbours are summed by the first pass.
+__device__ __forceinline__ bool tile_is_heavy(const CsrView& g, int rpv, const int* s_rp, bool has_hub) {
+    int e = __builtin_amdgcn_readlane(rpv, 16) - __builtin_amdgcn_readlane(rpv, 0);   // rpv: as tile_rp_load returned it
+    if (e <= g.heavy_edges) return false;
+    if (has_hub)
+        for (int r = 0; r < 16; ++r) {
+            const int d = s_rp[r + 1] - s_rp[r];
+            e -= d > g.hub_threshold ? d : 0;
+        }
+    return e > g.heavy_edges;
 }
 
 // ---- first pass over the chunks of very long rows ------------------------------------------------

@@ -147,8 +147,14 @@ static gsr_status_t upload(const std::vector<V>& h, V** d) {
 
 static gsr_status_t upload_csr(const HostCsr& h, int64_t n, int64_t threshold, int64_t chunk, Csr* out) {
     std::vector<int32_t> heavy;
-    for (int64_t t0 = 0; t0 < n; t0 += 16)
-        if (h.rp[std::min<int64_t>(n, t0 + 16)] - h.rp[t0] > kHeavyTileEdges) heavy.push_back((int32_t)(t0 / 16));
+    for (int64_t t0 = 0; t0 < n; t0 += 16) {
+        int64_t e = 0;      // stored entries of the tile's rows that are not split
+        for (int64_t r = t0; r < std::min<int64_t>(n, t0 + 16); ++r) {
+            const int64_t d = h.rp[r + 1] - h.rp[r];
+            e += d > threshold ? 0 : d;
+        }
+        if (e > kHeavyTileEdges) heavy.push_back((int32_t)(t0 / 16));
+    }
     out->n_heavy = (int32_t)heavy.size();
     GSR_TRY(upload(heavy, &out->heavy));
     GSR_TRY(upload(h.rp, &out->rp));

@@ -72,7 +72,7 @@ struct HubPlan {
     int32_t* ce1 = nullptr;   // device [n_chunks] one past the last edge
 };
 
-// 16-row tiles with more than this many stored entries (rp[16 t + 16] - rp[16 t]) are listed per matrix; the
+// 16-row tiles with more than this many stored entries in rows that are not split are listed per matrix; the
 // layer kernels deal them out to their waves, one each, before their sweep, so that the long tiles start first
 // and no wave meets several of them.  Measured on the 1M-node workload (median tile 63 entries, 1 % of the tiles
 // around 1,300): inverse + dW kernel 546 us without, 495 - 498 us with 512 / 768 / 1,024, 531 us with 1,100.

@@ -52,7 +52,7 @@ struct BlockArgs {
     int* draws_done;
 };
 
-template <int DG, typename T, int SIGN, bool WITH_DW>
+template <int DG, typename T, int SIGN, bool WITH_DW, bool DEAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
     constexpr int LR = DG + 1, CPL = DG / 16;
     __shared__ WaveLds<DG, 1> lds[4];
@@ -71,7 +71,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
     // the weight gradient sums over the tiles a wave has seen: fixed sweep there, drawn tiles otherwise
     const TileSweep ts = tile_sweep(a.tiles);
     TileDraws td;
-    TileDeal deal = tile_deal(a.g);
+    TileDeal deal{0, 0, false};      // DEAL: the heavy tiles first (a variant of its own: the bookkeeping costs
+    if constexpr (DEAL) deal = tile_deal(a.g);   // 3 % on a graph with 120 short tiles per wave even when it never fires)
     int requested = 0;     // the draw that is outstanding (dynamic sweep)
     int t = ts.first, t_end = ts.end;
     if constexpr (!WITH_DW) {
@@ -80,19 +81,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         t_end = td.end;
         if (!deal.on) t = tile_drawn(td, requested);
     }
-    if (deal.on) { t = a.g.heavy[deal.at]; t_end = a.tiles; }
+    if constexpr (DEAL) {
+        if (deal.on) { t = a.g.heavy[deal.at]; t_end = a.tiles; }
+    }
     while (t < t_end) {
         if constexpr (!WITH_DW) {
-            if (!deal.on) requested = tile_request(td);
+            if (!DEAL || !deal.on) requested = tile_request(td);
         }
         const int r0 = t * 16;
         wave_sync();
         const int rpv = tile_rp_load(a.g, r0, a.n, lane);
-        if (!deal.on && tile_is_heavy(a.g, rpv)) {      // dealt out before the sweep
-            if constexpr (WITH_DW) t += ts.step;
-            else t = tile_drawn(td, requested);
-            continue;
-        }
         // The tile's own rows (X_i, and dY_i for the weight gradient) are requested first, in the
         // tile register layout, and arrive while the neighbour records are gathered.
         float xy[4][CPL], gy[WITH_DW ? 4 : 1][CPL];
@@ -104,6 +102,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
             if constexpr (WITH_DW) load_cols<CPL, T>(a.dy + rowc * a.ldg + CPL * tj, gy[reg]);
         }
         const bool has_hub = tile_begin(a.g, rpv, L.rp, lane);
+        if constexpr (DEAL) {
+            if (!deal.on && tile_is_heavy(a.g, rpv, L.rp, has_hub)) {      // dealt out before the sweep
+                if constexpr (WITH_DW) t += ts.step;
+                else t = tile_drawn(td, requested);
+                continue;
+            }
+        }
         f32x4 hacc[DG / 16];
         tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, hacc, [&](int e_a, int e_b) {
             gather_records_mfma<DG, T, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
@@ -138,7 +143,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
             wave_sync();
             emit_tile<DG, T>(st_h, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane);
         }
-        if (deal.on) {
+        if (DEAL && deal.on) {
             deal.at += deal.waves;
             deal.on = deal.at < a.g.n_heavy;
             if (deal.on) {
@@ -260,7 +265,7 @@ __device__ __forceinline__ void dw_reduce_slices(const float* __restrict__ parti
 // waves, which would allow 18 and 20 resident waves, are 20 % and 10 % slower.
 constexpr int GRAD_WAVES = 4;
 
-template <int DG, typename T>
+template <int DG, typename T, bool DEAL>
 __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
     constexpr int CPL = DG / 16;
     __shared__ WaveLds<DG, 1> lds[GRAD_WAVES];
@@ -272,21 +277,18 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
     if (a.dw_out) dw_reduce_slices<DG * DG>(a.dw_partial, a.dw_parts, a.dw_out, reinterpret_cast<float*>(lds));
     load_w_lds<DG>(a.w, true, wl);
     TileDraws td = tile_draws(a.tiles, a.draws, a.draws_done);
-    TileDeal deal = tile_deal(a.gt);
+    TileDeal deal{0, 0, false};
+    if constexpr (DEAL) deal = tile_deal(a.gt);
     int requested = tile_request(td);      // the draw that is outstanding
     int t_end = td.end;
     int t = 0;
-    if (deal.on) { t = a.gt.heavy[deal.at]; t_end = a.tiles; }
+    if (DEAL && deal.on) { t = a.gt.heavy[deal.at]; t_end = a.tiles; }
     else t = tile_drawn(td, requested);
     while (t < t_end) {
-        if (!deal.on) requested = tile_request(td);
+        if (!DEAL || !deal.on) requested = tile_request(td);
         const int r0 = t * 16;
         wave_sync();
         const int rpv = tile_rp_load(a.gt, r0, a.n, lane);
-        if (!deal.on && tile_is_heavy(a.gt, rpv)) {    // dealt out before the sweep
-            t = tile_drawn(td, requested);
-            continue;
-        }
         // what the epilogue needs of the tile's own rows is requested first
         typename MaskOf<DG>::type own[4];
         float z[4][CPL];
@@ -298,6 +300,12 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
             if (a.norm == GSR_NORM_RMS) load_cols<CPL, T>(a.z + rowc * a.ldz + CPL * tj, z[reg]);
         }
         const bool has_hub = tile_begin(a.gt, rpv, L.rp, lane);
+        if constexpr (DEAL) {
+            if (!deal.on && tile_is_heavy(a.gt, rpv, L.rp, has_hub)) {    // dealt out before the sweep
+                t = tile_drawn(td, requested);
+                continue;
+            }
+        }
         f32x4 qacc[DG / 16];
         tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, qacc, [&](int e_a, int e_b) {
             gather_dense_mfma<DG, T, (sizeof(T) == 4 || DG == 32) ? 16 : 8>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
@@ -342,7 +350,7 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
                 if (ok) store_cols<CPL, T>(p, g);
             }
         }
-        if (deal.on) {
+        if (DEAL && deal.on) {
             deal.at += deal.waves;
             deal.on = deal.at < a.gt.n_heavy;
             if (deal.on) t = a.gt.heavy[deal.at];
@@ -559,14 +567,15 @@ static unsigned persistent_grid(const gsr_graph_t* g, int per_cu) {
 }
 
 // Whether a launch of `grid` workgroups of four waves deals the heavy tiles out first (TileDeal).  Measured: on the
-// 1M-node workload (15 - 30 tiles per wave) it shortens every layer kernel by 10 - 16 %, and on a 49,600-node
-// graph whose tiles are all heavy the forward kernel by 17 %; on the 100k-node workload (1.5 tiles per wave, 2 %
-// of them just above the threshold) the gradient kernel gets 19 % longer.  So: only with several tiles per wave,
-// or when most tiles are heavy anyway.
-static void heavy_first(CsrView* v, int tiles, unsigned grid) {
-    if ((int64_t)tiles >= (int64_t)4 * 4 * grid || 2 * (int64_t)v->n_heavy >= tiles) return;
-    v->n_heavy = 0;
-    v->heavy_edges = 0x7fffffff;
+// 1M-node workload (15 - 30 tiles per wave, 1.6 % of them heavy) it shortens every layer kernel by 10 - 16 %, and
+// on a 49,600-node graph whose tiles are all heavy the forward kernel by 17 %.  On the 100k-node workload (1.5
+// tiles per wave) the gradient kernel gets 19 % longer, and on the 8M-node workload (120 - 240 tiles per wave) all
+// kernels get 6 - 10 % longer: there a late heavy tile is a small part of the kernel, while taking the heavy tiles
+// out of the order of the sweep takes their neighbours out of the cached window.  So: only with a moderate number
+// of tiles per wave, or when most tiles are heavy anyway.
+static bool heavy_first(const CsrView& v, int tiles, unsigned grid) {
+    const int64_t waves = (int64_t)4 * grid;
+    return v.n_heavy > 0 && ((tiles >= 4 * waves && tiles < 64 * waves) || 2 * (int64_t)v.n_heavy >= tiles);
 }
 
 template <int DG, typename T>
@@ -634,20 +643,20 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
     unsigned grid;
     if (mode == 0) {
-        static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false>);
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false, false>);
         grid = persistent_grid(x.g, per_cu);
-        heavy_first(&a.g, x.tiles, grid);
-        hipLaunchKernelGGL((k_block<DG, T, +1, false>), dim3(grid), block, 0, x.s, a);
+        if (heavy_first(a.g, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, +1, false, true>), dim3(grid), block, 0, x.s, a);
+        else hipLaunchKernelGGL((k_block<DG, T, +1, false, false>), dim3(grid), block, 0, x.s, a);
     } else if (mode == 1) {
-        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false>);
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false, false>);
         grid = persistent_grid(x.g, per_cu);
-        heavy_first(&a.g, x.tiles, grid);
-        hipLaunchKernelGGL((k_block<DG, T, -1, false>), dim3(grid), block, 0, x.s, a);
+        if (heavy_first(a.g, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, -1, false, true>), dim3(grid), block, 0, x.s, a);
+        else hipLaunchKernelGGL((k_block<DG, T, -1, false, false>), dim3(grid), block, 0, x.s, a);
     } else {
-        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true>);
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true, false>);
         grid = persistent_grid(x.g, per_cu);
-        heavy_first(&a.g, x.tiles, grid);
-        hipLaunchKernelGGL((k_block<DG, T, -1, true>), dim3(grid), block, 0, x.s, a);
+        if (heavy_first(a.g, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, -1, true, true>), dim3(grid), block, 0, x.s, a);
+        else hipLaunchKernelGGL((k_block<DG, T, -1, true, false>), dim3(grid), block, 0, x.s, a);
     }
     return grid;
 }
@@ -667,10 +676,10 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     a.dw_partial = x.dw_partial(); a.dw_parts = dw_parts; a.dw_out = dw_out;
     tile_counters(x.g, &a.draws, &a.draws_done);
     ProfScope prof(KC_GRAD, x.s);
-    static const int per_cu = resident_blocks((const void*)k_grad<DG, T>, 64 * GRAD_WAVES);
+    static const int per_cu = resident_blocks((const void*)k_grad<DG, T, false>, 64 * GRAD_WAVES);
     const unsigned grid = persistent_grid(x.g, per_cu);
-    heavy_first(&a.gt, x.tiles, grid);
-    hipLaunchKernelGGL((k_grad<DG, T>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
+    if (heavy_first(a.gt, x.tiles, grid)) hipLaunchKernelGGL((k_grad<DG, T, true>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
+    else hipLaunchKernelGGL((k_grad<DG, T, false>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
 }
 
 // eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of the
