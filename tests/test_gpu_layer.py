@@ -406,3 +406,43 @@ def test_layer_with_an_odd_number_of_launches_replays_from_a_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(y, want), rep
+
+
+@pytest.mark.parametrize("workgroups,heavy_share", [(8, 0.3), (8, 1.0), (0, 1.0), (16, 0.05)])
+def test_heavy_tiles_dealt_before_the_sweep(workgroups, heavy_share):
+    """Graphs on which the layer kernels deal the long tiles (more than 512 stored entries) to their waves before
+    the sweep: a few of them among short tiles, all tiles long, more long tiles than waves (several rounds of
+    dealing), and a directed pattern whose transpose has a different set of long tiles."""
+    import scipy.sparse as sp
+    gsr.gsr_set_option("max_workgroups", workgroups)
+    try:
+        rng = np.random.default_rng(11)
+        n, d, C, k = 4000, 128, 2, 16
+        nh = int(n * heavy_share) // 16 * 16
+        rows, cols = [], []
+        for lo, hi, deg in ((0, nh, 48), (nh, n, 3)):
+            if hi > lo:
+                r = np.repeat(np.arange(lo, hi), deg)
+                rows.append(r)
+                cols.append(rng.integers(0, n, size=len(r)))
+        A = sp.csr_matrix((np.ones(sum(len(r) for r in rows)), (np.concatenate(rows), np.concatenate(cols))), shape=(n, n))
+        A = ((A + sp.identity(n, format="csr")) > 0).astype(np.float64).tocsr()
+        A.sort_indices()
+        deg = np.diff(A.indptr)
+        av = (1.0 / np.repeat(deg, deg)).astype(np.float32)
+        tile_edges = np.add.reduceat(deg, np.arange(0, n, 16))
+        assert (tile_edges > 512).sum() >= max(1, nh // 16 - 2) and A.shape[0] == n
+        w = synth.scaled(synth.workload(1), n, l=2)
+        c = Case(w, 0, PLANAR)
+        c.og = oracle.graph_from_csr(A.indptr.astype(np.int64), A.indices.astype(np.int32), av)
+        c.gg = gsr.gsr_graph_create(A.indptr.astype(np.int64), A.indices.astype(np.int32), vals=av, flags=0)
+        ref = oracle.step(c.og, c.ocfg, w.l, c.x0_on_grid(), c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target)
+        out = run_step(c)
+        assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
+        for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+            assert_close(key, out[key], ref[key])
+        again = run_step(c)
+        for key in ("XL", "dW", "dX0"):
+            assert np.array_equal(out[key], again[key]), key          # the dealing is the same on every run
+    finally:
+        gsr.gsr_set_option("max_workgroups", 0)
