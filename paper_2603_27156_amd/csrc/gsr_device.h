@@ -279,61 +279,6 @@ __device__ __forceinline__ float hub_row_sum(const CsrView& g, const float* __re
     return acc;
 }
 
-// One row of  A * scatter(V, I)  (Section 4.1, eq. (10)): for every stored neighbour j of `row`
-// lane c adds a_ij * V[j][slot] if j recorded column c.  The record of j is its k values in
-// ascending column order plus a DG-bit column mask, so slot = popcount(mask below c).
-// e0/e1: edge range to visit (the whole row, or one chunk of a hub row).
-template <int DG, typename T>
-__device__ __forceinline__ float gather_records(const CsrView& g, const T* __restrict__ vals,
-                                                const typename MaskOf<DG>::type* __restrict__ masks, int k,
-                                                int e0, int e1, int c, int stride = 1) {
-    using M = typename MaskOf<DG>::type;
-    const M below = ((M)1 << c) - 1;
-    float acc = 0.f;
-    constexpr int U = 8;
-    for (int e = e0; ballot(e < e1) != 0ull; e += U * stride) {
-        int j[U]; float a[U]; M m[U]; float v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool ok = e + u * stride < e1;
-            j[u] = ok ? g.ci[e + u * stride] : -1;
-            a[u] = ok ? g.av[e + u * stride] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) m[u] = j[u] >= 0 ? masks[j[u]] : (M)0;
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool hit = (m[u] >> c) & 1;
-            v[u] = hit ? to_float(vals[(size_t)j[u] * k + popc<DG>(m[u] & below)]) : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc += a[u] * v[u];
-    }
-    return acc;
-}
-
-// One row of  A * X  for a dense plane X (row stride ld): lane c adds a_ij * X[j][c].
-template <int DG, typename T>
-__device__ __forceinline__ float gather_dense(const CsrView& g, const T* __restrict__ x, int64_t ld,
-                                              int e0, int e1, int c, int stride = 1) {
-    float acc = 0.f;
-    constexpr int U = 8;
-    for (int e = e0; ballot(e < e1) != 0ull; e += U * stride) {
-        int j[U]; float a[U]; float v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool ok = e + u * stride < e1;
-            j[u] = ok ? g.ci[e + u * stride] : -1;
-            a[u] = ok ? g.av[e + u * stride] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = j[u] >= 0 ? to_float(x[(size_t)j[u] * ld + c]) : 0.f;
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc += a[u] * v[u];
-    }
-    return acc;
-}
-
 // ---- tile gathers on the matrix cores ------------------------------------------------------------------
 // A wave owns 16 consecutive rows.  Their neighbour lists are one contiguous edge range, so the
 // dependent chain row pointer -> column index -> neighbour data is walked once per tile, 64 edges
@@ -1133,19 +1078,6 @@ __global__ __launch_bounds__(256) void k_hub_both(CsrView ga, HubChunks ha, cons
     const int first = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nwaves = (gridDim.x * blockDim.x) >> 6;
     if (blockIdx.y == 0) hub_records_pass<DG, T>(ga, ha, vals, masks, k, part_a, lds[threadIdx.x >> 6], first, nwaves);
     else hub_dense_pass<DG, T>(gt, ht, x, ld, part_t, lds[threadIdx.x >> 6], first, nwaves);
-}
-
-// Row `row` of A * scatter(V, I): direct gather, or the sum of its first-pass partials.
-template <int DG, typename T>
-__device__ __forceinline__ float row_records(const CsrView& g, const T* __restrict__ vals,
-                                             const typename MaskOf<DG>::type* __restrict__ masks, int k,
-                                             const float* __restrict__ hub_part, int row, bool ok, int c) {
-    int e0 = 0, e1 = 0;
-    if (ok) { e0 = g.rp[row]; e1 = g.rp[row + 1]; }
-    const bool hub = (e1 - e0) > g.hub_threshold;
-    float acc = gather_records<DG, T>(g, vals, masks, k, e0, hub ? e0 : e1, c);
-    if (hub) acc = hub_row_sum<DG>(g, hub_part, row, c);
-    return acc;
 }
 
 }  // namespace gsr

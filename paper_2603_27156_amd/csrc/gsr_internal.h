@@ -133,6 +133,18 @@ constexpr int kTileCounters = 8 * 64 * 32;
 void tile_counters(const gsr_graph_t* g, int** set, int** done);
 StepWs carve_step(const gsr_config_t* cfg, const gsr_graph_t* g);
 
+// Whether a launch of `grid` workgroups of four waves deals the heavy tiles out first (TileDeal).  Measured: on the
+// 1M-node workload (15 - 30 tiles per wave, 1.6 % of them heavy) it shortens every layer kernel by 10 - 16 %, and
+// on a 49,600-node graph whose tiles are all heavy the forward kernel by 17 %.  On the 100k-node workload (1.5
+// tiles per wave) the gradient kernel gets 19 % longer, and on the 8M-node workload (120 - 240 tiles per wave) all
+// kernels get 6 - 10 % longer: there a late heavy tile is a small part of the kernel, while taking the heavy tiles
+// out of the order of the sweep takes their neighbours out of the cached window.  So: only with a moderate number
+// of tiles per wave, or when most tiles are heavy anyway.
+inline bool heavy_first(int n_heavy, int tiles, unsigned grid) {
+    const int64_t waves = (int64_t)4 * grid;
+    return n_heavy > 0 && ((tiles >= 4 * waves && tiles < 64 * waves) || 2 * (int64_t)n_heavy >= tiles);
+}
+
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 inline size_t dtype_size(int32_t dtype) { return dtype == GSR_BF16 ? 2 : 4; }
 

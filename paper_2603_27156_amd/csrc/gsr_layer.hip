@@ -566,18 +566,6 @@ static unsigned persistent_grid(const gsr_graph_t* g, int per_cu) {
     return (unsigned)grid;
 }
 
-// Whether a launch of `grid` workgroups of four waves deals the heavy tiles out first (TileDeal).  Measured: on the
-// 1M-node workload (15 - 30 tiles per wave, 1.6 % of them heavy) it shortens every layer kernel by 10 - 16 %, and
-// on a 49,600-node graph whose tiles are all heavy the forward kernel by 17 %.  On the 100k-node workload (1.5
-// tiles per wave) the gradient kernel gets 19 % longer, and on the 8M-node workload (120 - 240 tiles per wave) all
-// kernels get 6 - 10 % longer: there a late heavy tile is a small part of the kernel, while taking the heavy tiles
-// out of the order of the sweep takes their neighbours out of the cached window.  So: only with a moderate number
-// of tiles per wave, or when most tiles are heavy anyway.
-static bool heavy_first(const CsrView& v, int tiles, unsigned grid) {
-    const int64_t waves = (int64_t)4 * grid;
-    return v.n_heavy > 0 && ((tiles >= 4 * waves && tiles < 64 * waves) || 2 * (int64_t)v.n_heavy >= tiles);
-}
-
 template <int DG, typename T>
 static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0,
                        const Record<DG, T>& out, bool out_given = false) {
@@ -645,17 +633,17 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     if (mode == 0) {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false, false>);
         grid = persistent_grid(x.g, per_cu);
-        if (heavy_first(a.g, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, +1, false, true>), dim3(grid), block, 0, x.s, a);
+        if (heavy_first(a.g.n_heavy, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, +1, false, true>), dim3(grid), block, 0, x.s, a);
         else hipLaunchKernelGGL((k_block<DG, T, +1, false, false>), dim3(grid), block, 0, x.s, a);
     } else if (mode == 1) {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false, false>);
         grid = persistent_grid(x.g, per_cu);
-        if (heavy_first(a.g, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, -1, false, true>), dim3(grid), block, 0, x.s, a);
+        if (heavy_first(a.g.n_heavy, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, -1, false, true>), dim3(grid), block, 0, x.s, a);
         else hipLaunchKernelGGL((k_block<DG, T, -1, false, false>), dim3(grid), block, 0, x.s, a);
     } else {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true, false>);
         grid = persistent_grid(x.g, per_cu);
-        if (heavy_first(a.g, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, -1, true, true>), dim3(grid), block, 0, x.s, a);
+        if (heavy_first(a.g.n_heavy, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, -1, true, true>), dim3(grid), block, 0, x.s, a);
         else hipLaunchKernelGGL((k_block<DG, T, -1, true, false>), dim3(grid), block, 0, x.s, a);
     }
     return grid;
@@ -678,7 +666,7 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     ProfScope prof(KC_GRAD, x.s);
     static const int per_cu = resident_blocks((const void*)k_grad<DG, T, false>, 64 * GRAD_WAVES);
     const unsigned grid = persistent_grid(x.g, per_cu);
-    if (heavy_first(a.gt, x.tiles, grid)) hipLaunchKernelGGL((k_grad<DG, T, true>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
+    if (heavy_first(a.gt.n_heavy, x.tiles, grid)) hipLaunchKernelGGL((k_grad<DG, T, true>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
     else hipLaunchKernelGGL((k_grad<DG, T, false>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
 }
 

@@ -191,3 +191,44 @@ def test_forward_block_example_of_the_paper():
     i = torch.from_numpy(b["IDX"].astype(np.int32)).to(dev())
     out = gsr.gsr_spmm_compressed(gg, v, i, 32).cpu().numpy()
     assert np.allclose(out[:, :4], b["OUT"], atol=5e-3) and np.all(out[:, 4:] == 0)
+
+
+@pytest.mark.parametrize("workgroups,heavy_share", [(8, 0.3), (8, 1.0), (0, 1.0), (16, 0.05)])
+def test_tile_operators_with_heavy_tiles_dealt_first(workgroups, heavy_share):
+    """gsr_spmm (both directions, widths 32 and 64) and gsr_spmm_compressed on directed graphs whose long tiles
+    (more than 512 stored entries) are dealt to the waves before the sweep: a few among short tiles, all tiles
+    long, more long tiles than waves, and a transpose with a different set of long tiles."""
+    import scipy.sparse as sp
+    gsr.gsr_set_option("max_workgroups", workgroups)
+    try:
+        rng = np.random.default_rng(12)
+        n = 4001                                                     # ragged last tile
+        nh = int(n * heavy_share) // 16 * 16
+        rows, cols = [], []
+        for lo, hi, deg in ((0, nh, 48), (nh, n, 3)):
+            if hi > lo:
+                r = np.repeat(np.arange(lo, hi), deg)
+                rows.append(r)
+                cols.append(rng.integers(0, n, size=len(r)))
+        A = sp.csr_matrix((np.ones(sum(len(r) for r in rows)), (np.concatenate(rows), np.concatenate(cols))), shape=(n, n))
+        A = (A > 0).astype(np.float64).tocsr()
+        A.sort_indices()
+        av = rng.uniform(0.2, 1.0, A.nnz).astype(np.float32)
+        rp, ci = A.indptr.astype(np.int64), A.indices.astype(np.int32)
+        og = oracle.graph_from_csr(rp, ci, av)
+        gg = gsr.gsr_graph_create(rp, ci, vals=av, flags=0)
+        for width in (64, 32):
+            X = rng.standard_normal((n, width)).astype(np.float32)
+            xt = torch.from_numpy(X).to(dev())
+            assert_close("A X", gsr.gsr_spmm(gg, xt).cpu().numpy(), oracle.spmm(og, X))
+            assert_close("A^T X", gsr.gsr_spmm(gg, xt, transpose=True).cpu().numpy(), oracle.spmm(og, X, transpose=True))
+            first = gsr.gsr_spmm(gg, xt)
+            assert torch.equal(first, gsr.gsr_spmm(gg, xt))              # the counters are left clear
+        for dg, k in ((64, 16), (32, 8)):
+            Z = rng.standard_normal((n, dg)).astype(np.float32)
+            V, I, _ = oracle.gs(Z.astype(np.float64), k)
+            got = gsr.gsr_spmm_compressed(gg, torch.from_numpy(V.astype(np.float32)).to(dev()),
+                                          torch.from_numpy(I.astype(np.int32)).to(dev()), dg)
+            assert_close("A scatter(V,I)", got.cpu().numpy(), oracle.aggregate(og, V, I, dg))
+    finally:
+        gsr.gsr_set_option("max_workgroups", 0)
