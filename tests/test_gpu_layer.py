@@ -446,3 +446,38 @@ def test_heavy_tiles_dealt_before_the_sweep(workgroups, heavy_share):
             assert np.array_equal(out[key], again[key]), key          # the dealing is the same on every run
     finally:
         gsr.gsr_set_option("max_workgroups", 0)
+
+
+def _shape_cases():
+    """Seeded draw of shapes the fixed cases do not hit: node counts around tile boundaries, odd group counts,
+    every k from 1 to Dg, both group widths, both normalisations, both layouts and storage types."""
+    rng = np.random.default_rng(2024)
+    ns = [1, 2, 15, 16, 17, 31, 33, 47, 64, 65, 100, 255, 257, 1000, 1023, 2049]
+    out = []
+    for i, n in enumerate(ns):
+        dg = int(rng.choice([32, 64]))
+        c = int(rng.choice([2, 3, 4, 5, 8]))
+        k = int(rng.integers(1, dg + 1))
+        out.append((n, dg, c, k, "rms" if rng.random() < 0.6 else "none", PLANAR if rng.random() < 0.5 else ROW,
+                    "bf16" if i % 5 == 4 else "f32", int(rng.integers(1, 4)), 100 + i))
+    return out
+
+
+@pytest.mark.parametrize("n,dg,c,k,norm,layout,dtype,depth,seed", _shape_cases())
+def test_step_on_drawn_shapes(n, dg, c, k, norm, layout, dtype, depth, seed):
+    print(f"[case] n={n} dg={dg} C={c} k={k} norm={norm} layout={layout} dtype={dtype} L={depth} seed={seed}", flush=True)
+    base = synth.workload(2 if n >= 64 else 0)
+    w = synth.scaled(base, n, levels=max(1, min(n, 6)), d=dg * c, c=c, k=k, norm=norm, dtype=dtype, l=depth,
+                     hubs=min(base.hubs, 2) if n >= 64 else 0)
+    cs = Case(w, seed, layout)
+    ref = oracle.step(cs.og, cs.ocfg, w.l, cs.x0_on_grid(), cs.inp.weights, cs.inp.w_out, cs.inp.b_out, cs.inp.target)
+    out = run_step(cs)
+    if dtype == "bf16":
+        assert np.isclose(out["loss"], ref["loss"], rtol=BF16_REL)
+        for key in ("yhat", "XL", "dW", "dwout", "dX0"):
+            assert rel_norm(out[key], ref[key]) < BF16_REL, key
+        return
+    assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
+    for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+        assert_close(key, out[key], ref[key])
+    assert np.isclose(out["dbout"], ref["dbout"], rtol=1e-4, atol=1e-7)
