@@ -2,9 +2,10 @@
 // Its block places a row's sums in the row's OWN recorded columns,
 //     block(V, I)[i, I[i,t]] = sum_j a_ij V[j,t],
 // i.e. a product of A with the n x k matrix of kept values followed by a scatter to k columns; there
-// are no weights.  The product runs through gsr_spmm (the k slots padded to 32 or 64 columns so that
-// it takes the tiled path on the matrix cores, split rows included); the kernels here prepare its
-// operand and combine its result with the planes.  float32 only.
+// are no weights.  The product runs through gsr_spmm (the k slots padded to 16, 32 or 64 columns so that
+// it takes the tiled path on the matrix cores, split rows included; kept values that fill their width
+// are its operand as they stand); the kernels here prepare its operand otherwise and combine its
+// result with the planes.  float32 only.
 #include "gsr_internal.h"
 
 #include <algorithm>
@@ -80,8 +81,9 @@ __global__ __launch_bounds__(256) void k_slots_combine(int64_t n, int dg, int k,
 struct LiteralWs {
     size_t v1, i1, v2, i2, p, s, total;
 };
+static int slot_width(int k) { return k <= 16 ? 16 : k <= 32 ? 32 : 64; }
 static LiteralWs carve_literal(int64_t n, int k) {
-    const int W = k <= 32 ? 32 : 64;
+    const int W = slot_width(k);
     LiteralWs w;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t at = off; off += align_up(std::max<size_t>(bytes, 1)); return at; };
@@ -109,6 +111,7 @@ static gsr_status_t lit_gs(const Lit& x, const float* plane, int64_t ld, float* 
 // S[:, 0..k) = A (or A^T) * slots, the slots being vals or dense[i, idx[i, t]]
 static gsr_status_t lit_product(const Lit& x, const float* vals, const float* dense, int64_t ld, const int32_t* idx,
                                 bool transpose) {
+    if (vals && x.k == x.W) return gsr_spmm(x.g, vals, x.W, x.W, x.S, x.W, transpose ? 1 : 0, x.s);
     hipLaunchKernelGGL(k_slots_prepare, dim3(blocks_for(x.n * x.W)), dim3(256), 0, x.s, x.n, x.k, x.W, x.dg, vals, dense, ld, idx,
                        x.P);
     return gsr_spmm(x.g, x.P, x.W, x.W, x.S, x.W, transpose ? 1 : 0, x.s);
@@ -131,7 +134,7 @@ static gsr_status_t lit_check(const gsr_graph_t* g, int32_t dg, int32_t k, int64
     const LiteralWs w = carve_literal(g->n, k);
     if (ws_bytes < w.total) return fail(GSR_ERR_WORKSPACE_TOO_SMALL, "workspace %zu < %zu bytes", ws_bytes, w.total);
     char* base = (char*)ws;
-    x->g = g; x->n = g->n; x->dg = dg; x->k = k; x->W = k <= 32 ? 32 : 64; x->s = (hipStream_t)stream;
+    x->g = g; x->n = g->n; x->dg = dg; x->k = k; x->W = slot_width(k); x->s = (hipStream_t)stream;
     x->v1 = (float*)(base + w.v1); x->i1 = (int32_t*)(base + w.i1);
     x->v2 = (float*)(base + w.v2); x->i2 = (int32_t*)(base + w.i2);
     x->P = (float*)(base + w.p); x->S = (float*)(base + w.s);
@@ -168,12 +171,12 @@ gsr_status_t gsr_alg1_layer_forward(const gsr_graph_t* g, int32_t dg, int32_t k,
     Lit x;
     GSR_TRY(lit_check(g, dg, k, ld, x1_inout, x2_inout, workspace, workspace_bytes, &x, stream));
     if (g->n == 0) return GSR_OK;
-    GSR_TRY(lit_gs(x, x1_inout, ld, x.v1, x.i1));                                   // line 5
-    GSR_TRY(lit_product(x, x.v1, nullptr, 0, x.i1, false));                         // line 6
-    lit_combine(x, x2_inout, ld, 1.f, x2_inout, ld, 1.f, x.i1, 0.f, nullptr, nullptr);   // line 7
-    GSR_TRY(lit_gs(x, x2_inout, ld, x.v2, x.i2));                                   // line 8
-    GSR_TRY(lit_product(x, x.v2, nullptr, 0, x.i2, false));                         // line 9
-    lit_combine(x, x1_inout, ld, 0.f, nullptr, 0, 1.f, x.i2, 1.f, x.v1, x.i1);      // line 10
+    GSR_TRY(lit_gs(x, x1_inout, ld, x.v1, x.i1));                                   // (V1, I1) = GS(X1)
+    GSR_TRY(lit_product(x, x.v1, nullptr, 0, x.i1, false));                         // S = A V1
+    lit_combine(x, x2_inout, ld, 1.f, x2_inout, ld, 1.f, x.i1, 0.f, nullptr, nullptr);   // Y2 = X2 + S placed at I1
+    GSR_TRY(lit_gs(x, x2_inout, ld, x.v2, x.i2));                                   // (V2, I2) = GS(Y2)
+    GSR_TRY(lit_product(x, x.v2, nullptr, 0, x.i2, false));                         // S = A V2
+    lit_combine(x, x1_inout, ld, 0.f, nullptr, 0, 1.f, x.i2, 1.f, x.v1, x.i1);      // Y1 = scatter(V1, I1) + S placed at I2
     GSR_HIP_CHECK(hipGetLastError());
     return GSR_OK;
 }
@@ -184,13 +187,13 @@ gsr_status_t gsr_alg2_layer_backward(const gsr_graph_t* g, int32_t dg, int32_t k
     GSR_TRY(lit_check(g, dg, k, ld, g1_inout, g2_inout, workspace, workspace_bytes, &x, stream));
     if (g->n == 0) return GSR_OK;
     if (!g->has_transpose) return fail(GSR_ERR_UNSUPPORTED, "graph has no transpose");
-    GSR_TRY(lit_gs(x, g2_inout, ld, x.v2, x.i2));                                   // line 4
+    GSR_TRY(lit_gs(x, g2_inout, ld, x.v2, x.i2));                                   // (V2, I2) = GS(G2)
     GSR_TRY(lit_product(x, x.v2, nullptr, 0, x.i2, false));
-    lit_combine(x, g1_inout, ld, 1.f, g1_inout, ld, -1.f, x.i2, 0.f, nullptr, nullptr);  // line 5: M1 over g1
-    GSR_TRY(lit_gs(x, g1_inout, ld, x.v1, x.i1));                                   // line 6
+    lit_combine(x, g1_inout, ld, 1.f, g1_inout, ld, -1.f, x.i2, 0.f, nullptr, nullptr);  // M1 = G1 - block(V2, I2), kept in g1
+    GSR_TRY(lit_gs(x, g1_inout, ld, x.v1, x.i1));                                   // (V1, I1) = GS(M1)
     GSR_TRY(lit_product(x, x.v1, nullptr, 0, x.i1, false));
-    lit_combine(x, g2_inout, ld, 0.f, nullptr, 0, -1.f, x.i1, 1.f, x.v2, x.i2);     // line 7: M2 over g2
-    GSR_TRY(lit_product(x, nullptr, g1_inout, ld, x.i1, true));                     // line 8: backward blocks
+    lit_combine(x, g2_inout, ld, 0.f, nullptr, 0, -1.f, x.i1, 1.f, x.v2, x.i2);     // M2 = scatter(V2, I2) - block(V1, I1), kept in g2
+    GSR_TRY(lit_product(x, nullptr, g1_inout, ld, x.i1, true));                     // each M through its block's adjoint, in place
     lit_combine(x, g1_inout, ld, 0.f, nullptr, 0, 1.f, x.i1, 0.f, nullptr, nullptr);
     GSR_TRY(lit_product(x, nullptr, g2_inout, ld, x.i2, true));
     lit_combine(x, g2_inout, ld, 0.f, nullptr, 0, 1.f, x.i2, 0.f, nullptr, nullptr);

@@ -362,7 +362,7 @@ gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t
     // 32 or 64 columns with aligned rows: 16-row tiles on the matrix cores; split rows go through a
     // first pass into the graph's own scratch
     const size_t piece = (size_t)(width / 16) * sizeof(float);
-    if ((width == 32 || width == 64) && g->n < ((int64_t)1 << 31) && (ldx * sizeof(float)) % piece == 0 &&
+    if ((width == 16 || width == 32 || width == 64) && g->n < ((int64_t)1 << 31) && (ldx * sizeof(float)) % piece == 0 &&
         (ldy * sizeof(float)) % piece == 0 && ((uintptr_t)x % piece) == 0 && ((uintptr_t)y % piece) == 0 && g->scratch) {
         const HubPlan& h = transpose ? g->at.hub : g->a.hub;
         const int tiles = (int)((g->n + 15) / 16);
@@ -370,7 +370,8 @@ gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t
             HubChunks hc{h.ce0, h.ce1, h.n_chunks};
             const dim3 hg((unsigned)std::min((h.n_chunks + 3) / 4, 4096));
             if (width == 64) hipLaunchKernelGGL((k_hub_dense<64, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
-            else hipLaunchKernelGGL((k_hub_dense<32, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
+            else if (width == 32) hipLaunchKernelGGL((k_hub_dense<32, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
+            else hipLaunchKernelGGL((k_hub_dense<16, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
         }
         int *dn, *dx;
         tile_counters(g, &dn, &dx);
@@ -380,7 +381,8 @@ gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t
                                (const float*)g->scratch, dn, dx);
         };
         if (width == 64) deal ? launch(k_spmm_tile<64, true>) : launch(k_spmm_tile<64, false>);
-        else deal ? launch(k_spmm_tile<32, true>) : launch(k_spmm_tile<32, false>);
+        else if (width == 32) deal ? launch(k_spmm_tile<32, true>) : launch(k_spmm_tile<32, false>);
+        else deal ? launch(k_spmm_tile<16, true>) : launch(k_spmm_tile<16, false>);
         GSR_HIP_CHECK(hipGetLastError());
         return GSR_OK;
     }

@@ -124,9 +124,9 @@ def test_spmm_dense_and_transpose():
     assert np.allclose(out, b["OUT"], atol=5e-3)
 
 
-@pytest.mark.parametrize("width,hub_threshold", [(64, 512), (32, 512), (64, 6), (32, 5), (48, 6)])
+@pytest.mark.parametrize("width,hub_threshold", [(64, 512), (32, 512), (16, 512), (64, 6), (32, 5), (16, 5), (48, 6)])
 def test_spmm_dense_on_a_circuit_graph_with_split_rows(width, hub_threshold):
-    """The tiled path of gsr_spmm (widths 32 and 64) with rows above the threshold reduced in two
+    """The tiled path of gsr_spmm (widths 16, 32 and 64) with rows above the threshold reduced in two
     passes, a ragged last tile, and the row-per-wave path (width 48) on the same graph."""
     gsr.gsr_set_option("hub_threshold", hub_threshold)
     gsr.gsr_set_option("hub_chunk", 4 if hub_threshold < 100 else 64)
@@ -195,7 +195,7 @@ def test_forward_block_example_of_the_paper():
 
 @pytest.mark.parametrize("workgroups,heavy_share", [(8, 0.3), (8, 1.0), (0, 1.0), (16, 0.05)])
 def test_tile_operators_with_heavy_tiles_dealt_first(workgroups, heavy_share):
-    """gsr_spmm (both directions, widths 32 and 64) and gsr_spmm_compressed on directed graphs whose long tiles
+    """gsr_spmm (both directions, widths 16, 32 and 64) and gsr_spmm_compressed on directed graphs whose long tiles
     (more than 512 stored entries) are dealt to the waves before the sweep: a few among short tiles, all tiles
     long, more long tiles than waves, and a transpose with a different set of long tiles."""
     import scipy.sparse as sp
@@ -217,7 +217,7 @@ def test_tile_operators_with_heavy_tiles_dealt_first(workgroups, heavy_share):
         rp, ci = A.indptr.astype(np.int64), A.indices.astype(np.int32)
         og = oracle.graph_from_csr(rp, ci, av)
         gg = gsr.gsr_graph_create(rp, ci, vals=av, flags=0)
-        for width in (64, 32):
+        for width in (64, 32, 16):
             X = rng.standard_normal((n, width)).astype(np.float32)
             xt = torch.from_numpy(X).to(dev())
             assert_close("A X", gsr.gsr_spmm(gg, xt).cpu().numpy(), oracle.spmm(og, X))
