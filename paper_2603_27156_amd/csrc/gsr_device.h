@@ -989,6 +989,50 @@ __device__ __forceinline__ bool tile_is_heavy(const CsrView& g, int rpv, const i
     return e > g.heavy_edges;
 }
 
+// Per-wave LDS of the tile operators: staged edges, the tile's row pointers, rows of the staged records.
+struct TileLds {
+    EdgeRec ebuf[64];
+    int rp[20];
+    uint8_t rbuf[64];
+};
+
+// The order in which a wave of these kernels visits tiles: its share of the listed heavy tiles first (DEAL, see
+// TileDeal), then tiles drawn from the counters, with the next draw requested a tile ahead.  (Walking one tile
+// further ahead, so that the next tile's row pointers and first edges arrive during the present tile, was
+// measured on the dense product: 233 us against 224, so it is not done.)
+template <bool DEAL>
+struct TileWalk {
+    TileDraws td;
+    TileDeal deal;
+    int requested, t, t_end;
+    __device__ __forceinline__ TileWalk(const CsrView& g, int tiles, int* set, int* done) {
+        td = tile_draws(tiles, set, done);
+        deal = TileDeal{0, 0, false};
+        if constexpr (DEAL) deal = tile_deal(g);
+        requested = tile_request(td);
+        if (DEAL && deal.on) { t = g.heavy[deal.at]; t_end = tiles; }
+        else { t = tile_drawn(td, requested); t_end = td.end; }
+    }
+    __device__ __forceinline__ bool more() const { return t < t_end; }
+    // at the top of a tile: ask for the next draw (while dealing, the one asked for at the start is still out)
+    __device__ __forceinline__ void ahead() { if (!DEAL || !deal.on) requested = tile_request(td); }
+    // in the sweep, a heavy tile has been dealt out already
+    __device__ __forceinline__ bool dealt(const CsrView& g, int rpv, const int* s_rp, bool has_hub) const {
+        if constexpr (DEAL) return !deal.on && tile_is_heavy(g, rpv, s_rp, has_hub);
+        return false;
+    }
+    __device__ __forceinline__ void next(const CsrView& g) {
+        if (DEAL && deal.on) {
+            deal.at += deal.waves;
+            deal.on = deal.at < g.n_heavy;
+            if (deal.on) { t = g.heavy[deal.at]; return; }
+            t_end = td.end;
+        }
+        t = tile_drawn(td, requested);
+    }
+    __device__ __forceinline__ void finish() { tile_finish(td); }
+};
+
 // ---- first pass over the chunks of very long rows ------------------------------------------------
 // One wave per chunk, through the same matrix-core gathers as a tile: the chunk is treated as a
 // tile whose row 0 owns every edge, so all of a chunk's neighbours are in flight at once (a chain
