@@ -485,12 +485,18 @@ __global__ __launch_bounds__(256) void k_head(HeadArgs<T> a) {
     }
 }
 
-__global__ void k_head_reduce(const float* __restrict__ partial, int nparts, int d, int n, float* __restrict__ dw_out,
-                              float* __restrict__ db_out, float* __restrict__ loss_out) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+// One wave per output element: lane l adds partials l, l + 64, .. in that order, then the 64 lane sums are
+// added in a fixed tree.  (One thread per element walking all partials in turn took 240 us whatever the size.)
+__global__ __launch_bounds__(256) void k_head_reduce(const float* __restrict__ partial, int nparts, int d, int n,
+                                                     float* __restrict__ dw_out, float* __restrict__ db_out,
+                                                     float* __restrict__ loss_out) {
+    const int i = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6), lane = lane_id();
     if (i >= d + 2) return;
     float acc = 0.f;
-    for (int p = 0; p < nparts; ++p) acc += partial[(size_t)p * (d + 2) + i];
+    for (int p = lane; p < nparts; p += 64) acc += partial[(size_t)p * (d + 2) + i];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    if (lane != 0) return;
     if (i < d) dw_out[i] = acc;
     else if (i == d) db_out[0] = acc;
     else loss_out[0] = acc / (float)n;
@@ -819,7 +825,7 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
     {
         ProfScope prof(KC_HEAD, s);
         hipLaunchKernelGGL((k_head<T>), dim3((unsigned)g->grid), dim3(256), 0, s, h);
-        hipLaunchKernelGGL(k_head_reduce, dim3((cfg->d + 2 + 255) / 256), dim3(256), 0, s, (const float*)h.partial, g->grid,
+        hipLaunchKernelGGL(k_head_reduce, dim3((cfg->d + 2 + 3) / 4), dim3(256), 0, s, (const float*)h.partial, g->grid,
                            cfg->d, (int)n, dw_out, db_out, loss_out);
     }
     for (int l = L - 1; l >= 0; --l) layer_backward_impl<DG, T>(x, w_all + l * wl, act, grad, dw_all + l * wl, true, l, true);
