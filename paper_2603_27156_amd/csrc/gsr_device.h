@@ -462,7 +462,10 @@ __device__ __forceinline__ void edge_batches(int nit, Batch batch) {
 }
 
 // acc += P * X over the edges [e_a, e_b) of ordinary rows; X is a dense plane, row stride ld.
-template <int DG, typename T, int MAXB>
+// ONE_ROW: every edge belongs to tile row 0 (a chunk of a split row).  The matrix product would then spend
+// fifteen of its sixteen rows on zeros; instead lane (kk, j) adds a_e * X[e][its columns] for the edges kk,
+// kk + 4, .. in ordinary arithmetic into acc[cb][0], and the caller adds the four lane groups up.
+template <int DG, typename T, int MAXB, bool ONE_ROW = false>
 __device__ __forceinline__ void gather_dense_mfma(const CsrView& g, const T* __restrict__ x, int64_t ld, int e_a, int e_b,
                                                   const int* s_rp, EdgeRec* ebuf, int lane, f32x4 (&acc)[DG / 16]) {
     constexpr int CPL = DG / 16, NW = CPL * (int)sizeof(T) / 4;
@@ -489,9 +492,19 @@ __device__ __forceinline__ void gather_dense_mfma(const CsrView& g, const T* __r
             for (int u = 0; u < GB; ++u) {
                 const EdgeRec er = ebuf[4 * (i0 + u) + kk];
                 load_words<NW>(xl + (size_t)(uint32_t)er.j * ldu, w[u]);
-                p[u] = er.r == i16 ? er.a : 0.f;
+                p[u] = (ONE_ROW || er.r == i16) ? er.a : 0.f;
             }
-            if constexpr (sizeof(T) == 4) {
+            if constexpr (ONE_ROW) {
+#pragma unroll
+                for (int u = 0; u < GB; ++u)
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) {
+                        uint32_t bits;
+                        if constexpr (sizeof(T) == 4) bits = w[u][cb];
+                        else bits = (cb & 1) ? (w[u][cb >> 1] & 0xFFFF0000u) : (w[u][cb >> 1] << 16);
+                        acc[cb][0] = __builtin_fmaf(p[u], __uint_as_float(bits), acc[cb][0]);
+                    }
+            } else if constexpr (sizeof(T) == 4) {
 #pragma unroll
                 for (int u = 0; u < GB; ++u)
 #pragma unroll
@@ -531,7 +544,7 @@ struct RecEdge {
 // window may belong to the next record, or to the padding that follows the last one) and deals
 // them out to the columns whose mask bit is set.  16-bit values are loaded from the even slot at
 // or below the start.  n * k must stay below 2^32.
-template <int DG, typename T, int MAXB>
+template <int DG, typename T, int MAXB, bool ONE_ROW = false>
 __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* __restrict__ vals,
                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
                                                     int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, int lane,
@@ -577,7 +590,7 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
                     load_words<NW>(vals + (size_t)(at & ~1u), w[u]);
                     nib[u] |= at << 31;
                 }
-                p[u] = (int)rbuf[ei] == i16 ? er.a : 0.f;
+                p[u] = (ONE_ROW || (int)rbuf[ei] == i16) ? er.a : 0.f;
             }
             uint32_t bq[sizeof(T) == 4 ? 1 : GB][CPL];   // dealt-out values (float bits) of the 16-bit variant
 #pragma unroll
@@ -603,11 +616,12 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
                     const uint32_t b = q[0] & m;
 #pragma unroll
                     for (int t = 0; t + 1 < CPL - cb; ++t) q[t] = bit_select(m, q[t + 1], q[t]);
-                    if constexpr (sizeof(T) == 4) acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], __uint_as_float(b), acc[cb], 0, 0, 0);
+                    if constexpr (ONE_ROW) acc[cb][0] = __builtin_fmaf(p[u], __uint_as_float(b), acc[cb][0]);
+                    else if constexpr (sizeof(T) == 4) acc[cb] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[u], __uint_as_float(b), acc[cb], 0, 0, 0);
                     else bq[u][cb] = b;
                 }
             }
-            if constexpr (sizeof(T) != 4) {
+            if constexpr (sizeof(T) != 4 && !ONE_ROW) {
 #pragma unroll
                 for (int u = 0; u < GB; u += 4) {
                     bf16x4 ph, pm, pl;
@@ -1075,7 +1089,9 @@ __device__ __forceinline__ void hub_records_pass(const CsrView& g, const HubChun
         f32x4 acc[DG / 16];
 #pragma unroll
         for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        gather_records_mfma<DG, T, 16>(g, vals, masks, k, e0, e1, L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf, lane, acc);
+        gather_records_mfma<DG, T, 16, true>(g, vals, masks, k, e0, e1, L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf, lane, acc);
+#pragma unroll
+        for (int cb = 0; cb < DG / 16; ++cb) acc[cb][0] = quarter_sum(acc[cb][0]);
         hub_chunk_store<DG>(acc, part + (size_t)q * DG, lane);
     }
 }
@@ -1089,7 +1105,9 @@ __device__ __forceinline__ void hub_dense_pass(const CsrView& g, const HubChunks
         f32x4 acc[DG / 16];
 #pragma unroll
         for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        gather_dense_mfma<DG, T, 16>(g, x, ld, e0, e1, L.rp, L.ebuf, lane, acc);
+        gather_dense_mfma<DG, T, 16, true>(g, x, ld, e0, e1, L.rp, L.ebuf, lane, acc);
+#pragma unroll
+        for (int cb = 0; cb < DG / 16; ++cb) acc[cb][0] = quarter_sum(acc[cb][0]);
         hub_chunk_store<DG>(acc, part + (size_t)q * DG, lane);
     }
 }

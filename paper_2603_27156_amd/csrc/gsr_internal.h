@@ -29,8 +29,8 @@ gsr_status_t fail(gsr_status_t st, const char* fmt, ...);
 
 // ---- tunables (gsr_set_option) ----------------------------------------------------------
 struct Options {
-    int64_t hub_threshold = 512;  // rows longer than this are reduced in two passes
-    int64_t hub_chunk = 64;       // neighbours per first-pass partial
+    int64_t hub_threshold = 0;    // rows longer than this are reduced in two passes (0: chosen per graph)
+    int64_t hub_chunk = 0;        // neighbours per first-pass partial (0: chosen per graph)
     int64_t max_workgroups = 0;   // 0: derive from the device (multiple of 8)
     int64_t profile = 0;          // bit i set: time kernel class i with HIP events
 };

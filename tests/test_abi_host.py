@@ -67,5 +67,8 @@ def test_options_are_validated():
         gsr.gsr_set_option("no_such_option", 1)
     with pytest.raises(gsr.GsrError):
         gsr.gsr_set_option("max_workgroups", 12)
-    gsr.gsr_set_option("hub_threshold", 512)
+    with pytest.raises(gsr.GsrError):
+        gsr.gsr_set_option("hub_threshold", -1)
+    gsr.gsr_set_option("hub_threshold", 0)        # 0: chosen per graph
+    gsr.gsr_set_option("hub_chunk", 0)
     gsr.gsr_set_option("max_workgroups", 0)

@@ -481,3 +481,33 @@ def test_step_on_drawn_shapes(n, dg, c, k, norm, layout, dtype, depth, seed):
     for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
         assert_close(key, out[key], ref[key])
     assert np.isclose(out["dbout"], ref["dbout"], rtol=1e-4, atol=1e-7)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_graph_of_long_rows_goes_through_the_first_pass(dtype):
+    """A graph whose mean row has more than 64 stored entries (the regime of the paper's Table 1): with the options left
+    at 0 nearly every row is cut into chunks that the first pass sums, in ordinary arithmetic."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(21)
+    n, deg = 1203, 90
+    r = np.repeat(np.arange(n), deg)
+    A = sp.csr_matrix((np.ones(len(r)), (r, rng.integers(0, n, size=len(r)))), shape=(n, n))
+    A = ((A + A.T + sp.identity(n, format="csr")) > 0).astype(np.float64).tocsr()
+    A.sort_indices()
+    d = np.diff(A.indptr)
+    assert A.nnz >= 64 * n and d.min() > 64
+    av = (1.0 / np.sqrt(np.repeat(d, d) * d[A.indices])).astype(np.float32)
+    w = synth.scaled(synth.workload(2), n, l=2, dtype=dtype)
+    c = Case(w, 3, PLANAR)
+    c.og = oracle.graph_from_csr(A.indptr.astype(np.int64), A.indices.astype(np.int32), av)
+    c.gg = gsr.gsr_graph_create(A.indptr.astype(np.int64), A.indices.astype(np.int32), vals=av, flags=0)
+    assert gsr.gsr_graph_info(c.gg)["n_hub_rows"] == n
+    ref = oracle.step(c.og, c.ocfg, w.l, c.x0_on_grid(), c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target)
+    out = run_step(c)
+    if dtype == "bf16":
+        for key in ("yhat", "XL", "dW", "dwout", "dX0"):
+            assert rel_norm(out[key], ref[key]) < BF16_REL, key
+        return
+    assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
+    for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+        assert_close(key, out[key], ref[key])

@@ -145,8 +145,8 @@ def test_spmm_dense_on_a_circuit_graph_with_split_rows(width, hub_threshold):
         wide[:, 16:16 + width] = xt
         assert_close("A X (strided)", gsr.gsr_spmm(gg, wide[:, 16:16 + width]).cpu().numpy(), want)
     finally:
-        gsr.gsr_set_option("hub_threshold", 512)
-        gsr.gsr_set_option("hub_chunk", 64)
+        gsr.gsr_set_option("hub_threshold", 0)
+        gsr.gsr_set_option("hub_chunk", 0)
 
 
 @pytest.mark.parametrize("dg,k,hub_threshold", [(64, 16, 512), (32, 8, 512), (64, 16, 6), (32, 8, 5)])
@@ -178,8 +178,8 @@ def test_spmm_compressed(dg, k, hub_threshold):
         with pytest.raises(gsr.GsrError):
             gsr.gsr_spmm_compressed(gg, torch.from_numpy(Vp).to(dev()), torch.from_numpy(twice).to(dev()), dg)
     finally:
-        gsr.gsr_set_option("hub_threshold", 512)
-        gsr.gsr_set_option("hub_chunk", 64)
+        gsr.gsr_set_option("hub_threshold", 0)
+        gsr.gsr_set_option("hub_chunk", 0)
 
 
 def test_forward_block_example_of_the_paper():

@@ -74,8 +74,8 @@ def test_slot_block_against_oracle(dg, k, hub_threshold):
         assert_close("block", out, literal.slot_block(og, V, I, dg))
         assert np.count_nonzero(out) <= w.n * k
     finally:
-        gsr.gsr_set_option("hub_threshold", 512)
-        gsr.gsr_set_option("hub_chunk", 64)
+        gsr.gsr_set_option("hub_threshold", 0)
+        gsr.gsr_set_option("hub_chunk", 0)
 
 
 def test_slot_block_over_the_transpose_of_a_directed_graph():
