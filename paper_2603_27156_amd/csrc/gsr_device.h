@@ -1048,9 +1048,11 @@ struct TileWalk {
 };
 
 // ---- first pass over the chunks of very long rows ------------------------------------------------
-// One wave per chunk, through the same matrix-core gathers as a tile: the chunk is treated as a
-// tile whose row 0 owns every edge, so all of a chunk's neighbours are in flight at once (a chain
-// of one row pointer, the edges, the masks and the values instead of one such chain per edge).
+// One wave per chunk, through the staging and the wide loads of the tile gathers: the chunk is
+// treated as a tile whose row 0 owns every edge, so all of a chunk's neighbours are in flight at
+// once (a chain of one row pointer, the edges, the masks and the values instead of one such chain
+// per edge).  The sums form in ordinary arithmetic (ONE_ROW of the gathers): lane (kk, j) adds the
+// edges kk, kk + 4, .. for its columns, the four lane groups are added at the end.
 // part[chunk][DG] receives the un-scaled partial row.
 struct HubChunks {
     const int32_t* ce0;
