@@ -639,6 +639,113 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
     }
 }
 
+// The same sums in ordinary arithmetic, for float32 records (Section 4.1, eq. (10)): on this chip float32 matrix
+// instructions do not hide under vector work, and a 16-row product spends fifteen rows of every edge on zeros.
+// The staged edges of a round are cut into four equal runs, one per group of sixteen lanes; a group walks its run
+// in order (rows do not decrease along it), lane j of the group keeping a running sum of its CPL columns for the
+// run's present row and adding it to the row of the LDS tile `st` (zeroed by the caller, row stride DG + 1) when
+// the row changes and at the end of the round.  Two groups never add to one row in the same instruction: inside a
+// round only the last run that holds a row sees it end; the sums left at the end of the round are added group by
+// group.  The order of the additions is fixed by the edge list alone.
+template <int DG, int GB>
+__device__ __forceinline__ void gather_records_rows(const CsrView& g, const float* __restrict__ vals,
+                                                    const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
+                                                    int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, int lane,
+                                                    float* st) {
+    using M = typename MaskOf<DG>::type;
+    constexpr int CPL = DG / 16, LR = DG + 1;
+    const int i16 = lane & 15, kk = lane >> 4, bp = CPL * i16;
+    const uint32_t sh = bp & 31;
+    const bool upper = bp >= 32;
+    const uint32_t below_lo = upper ? 0xFFFFFFFFu : (1u << sh) - 1u, below_hi = upper ? (1u << sh) - 1u : 0u;
+    float* mine = st + bp;
+    for (int eb = e_a; eb < e_b; eb += 64) {
+        const int e = eb + lane;
+        const bool ok = e < e_b;
+        const int j = ok ? __builtin_nontemporal_load(g.ci + e) : 0;
+        RecEdge me;
+        me.a = ok ? __builtin_nontemporal_load(g.av + e) : 0.f;
+        me.off0 = (uint32_t)j * (uint32_t)k;
+        const M m = masks[j];
+        me.mlo = (uint32_t)m;
+        if constexpr (DG == 64) me.mhi = (uint32_t)(m >> 32);
+        else me.mhi = 0u;
+        const int r = tile_row_of(s_rp, e);
+        wave_sync();          // readers of the previous round are done
+        ebuf[lane] = me;
+        rbuf[lane] = (uint8_t)r;
+        wave_sync();
+        const int cnt = e_b - eb < 64 ? e_b - eb : 64;     // wave-uniform
+        const int steps = (cnt + 3) >> 2;                  // edges per run
+        const int first = kk * steps;
+        int cur = (int)rbuf[first < cnt ? first : cnt - 1];
+        float run[CPL];
+#pragma unroll
+        for (int cb = 0; cb < CPL; ++cb) run[cb] = 0.f;
+        for (int s0 = 0; s0 < steps; s0 += GB) {
+            uint32_t w[GB][CPL], nib[GB];
+            float p[GB];
+            int row[GB];
+#pragma unroll
+            for (int u = 0; u < GB; ++u) {
+                const int ei = first + s0 + u;
+                const bool okv = s0 + u < steps && ei < cnt;
+                const int eic = okv ? ei : cnt - 1;
+                const RecEdge er = ebuf[eic];
+                const uint32_t word = upper ? er.mhi : er.mlo;
+                const uint32_t at = er.off0 + (uint32_t)__popc(er.mlo & below_lo) + (uint32_t)__popc(er.mhi & below_hi);
+                nib[u] = (word >> sh) & ((1u << CPL) - 1u);
+                load_words<CPL>(vals + (size_t)at, w[u]);
+                p[u] = okv ? er.a : 0.f;
+                row[u] = okv ? (int)rbuf[eic] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < GB; ++u) {
+                if (row[u] >= 0 && row[u] != cur) {     // the row of this run has ended: its sum joins the tile
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) {
+                        mine[cur * LR + cb] += run[cb];
+                        run[cb] = 0.f;
+                    }
+                    cur = row[u];
+                }
+                uint32_t q[CPL];
+#pragma unroll
+                for (int t = 0; t < CPL; ++t) q[t] = w[u][t];
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) {
+                    const uint32_t mbit = (uint32_t)__builtin_amdgcn_sbfe((int)nib[u], cb, 1);
+                    const uint32_t b = q[0] & mbit;
+#pragma unroll
+                    for (int t = 0; t + 1 < CPL - cb; ++t) q[t] = bit_select(mbit, q[t + 1], q[t]);
+                    run[cb] = __builtin_fmaf(p[u], __uint_as_float(b), run[cb]);
+                }
+            }
+        }
+        // what the runs still hold, one group after the other (neighbouring runs may end in the same row)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            wave_sync();
+            if (kk == gq) {
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) mine[cur * LR + cb] += run[cb];
+            }
+        }
+    }
+}
+
+// H of the tile into st through gather_records_rows: st is cleared, the runs of ordinary rows are added into it,
+// split rows receive the sum of their first-pass partial rows afterwards.
+template <int DG, typename Range>
+__device__ __forceinline__ void tile_gather_rows(const CsrView& g, const float* __restrict__ hub_part, bool has_hub, int r0,
+                                                 const int* s_rp, float* st, int lane, Range range) {
+    for (int i = lane; i < 16 * (DG + 1); i += 64) st[i] = 0.f;
+    wave_sync();
+    tile_ranges(g, has_hub, s_rp, range);
+    wave_sync();
+    if (has_hub) hub_rows_fill<DG>(g, hub_part, r0, s_rp, st, lane);
+}
+
 // sum of the first-pass partial rows of every split row of the tile into st
 template <int DG>
 __device__ __forceinline__ void hub_rows_fill(const CsrView& g, const float* __restrict__ hub_part, int r0, const int* s_rp,

@@ -109,12 +109,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
                 continue;
             }
         }
-        f32x4 hacc[DG / 16];
-        tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, hacc, [&](int e_a, int e_b) {
-            gather_records_mfma<DG, T, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
-                                          __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
-                                          lane, hacc);
-        });
+        // float32 forward: the sums in ordinary arithmetic (329 us against 370 through the matrix cores on the 1M-node
+        // workload).  The inverse kernels keep the matrix product: at two waves per SIMD the row sums' LDS round trips are
+        // not hidden (531 us against 513), and the plain and the fused inverse must rebuild the same bits.
+        if constexpr (sizeof(T) == 4 && SIGN > 0) {
+            tile_gather_rows<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
+                gather_records_rows<DG, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
+                                           __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
+                                           lane, st_h);
+            });
+        } else {
+            f32x4 hacc[DG / 16];
+            tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, hacc, [&](int e_a, int e_b) {
+                gather_records_mfma<DG, T, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
+                                              __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
+                                              lane, hacc);
+            });
+        }
         if constexpr (WITH_DW) {
 #pragma unroll
             for (int reg = 0; reg < 4; ++reg)
