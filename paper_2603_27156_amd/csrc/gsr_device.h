@@ -734,6 +734,71 @@ __device__ __forceinline__ void gather_records_rows(const CsrView& g, const floa
     }
 }
 
+// The same for a dense float32 plane X (row stride ld): st += P * X over the edges [e_a, e_b) of ordinary rows.
+template <int DG, int GB>
+__device__ __forceinline__ void gather_dense_rows(const CsrView& g, const float* __restrict__ x, int64_t ld, int e_a, int e_b,
+                                                  const int* s_rp, EdgeRec* ebuf, int lane, float* st) {
+    constexpr int CPL = DG / 16, LR = DG + 1;
+    const int i16 = lane & 15, kk = lane >> 4;
+    const float* xl = x + CPL * i16;
+    const uint32_t ldu = (uint32_t)ld;
+    float* mine = st + CPL * i16;
+    for (int eb = e_a; eb < e_b; eb += 64) {
+        const int e = eb + lane;
+        const bool ok = e < e_b;
+        EdgeRec me;
+        me.j = ok ? __builtin_nontemporal_load(g.ci + e) : 0;
+        me.a = ok ? __builtin_nontemporal_load(g.av + e) : 0.f;
+        me.r = tile_row_of(s_rp, e);
+        me.pad = 0;
+        wave_sync();          // readers of the previous round are done
+        ebuf[lane] = me;
+        wave_sync();
+        const int cnt = e_b - eb < 64 ? e_b - eb : 64;
+        const int steps = (cnt + 3) >> 2;
+        const int first = kk * steps;
+        int cur = ebuf[first < cnt ? first : cnt - 1].r;
+        float run[CPL];
+#pragma unroll
+        for (int cb = 0; cb < CPL; ++cb) run[cb] = 0.f;
+        for (int s0 = 0; s0 < steps; s0 += GB) {
+            uint32_t w[GB][CPL];
+            float p[GB];
+            int row[GB];
+#pragma unroll
+            for (int u = 0; u < GB; ++u) {
+                const int ei = first + s0 + u;
+                const bool okv = s0 + u < steps && ei < cnt;
+                const EdgeRec er = ebuf[okv ? ei : cnt - 1];
+                load_words<CPL>(xl + (size_t)(uint32_t)er.j * ldu, w[u]);
+                p[u] = okv ? er.a : 0.f;
+                row[u] = okv ? er.r : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < GB; ++u) {
+                if (row[u] >= 0 && row[u] != cur) {
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) {
+                        mine[cur * LR + cb] += run[cb];
+                        run[cb] = 0.f;
+                    }
+                    cur = row[u];
+                }
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) run[cb] = __builtin_fmaf(p[u], __uint_as_float(w[u][cb]), run[cb]);
+            }
+        }
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            wave_sync();
+            if (kk == gq) {
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) mine[cur * LR + cb] += run[cb];
+            }
+        }
+    }
+}
+
 // H of the tile into st through gather_records_rows: st is cleared, the runs of ordinary rows are added into it,
 // split rows receive the sum of their first-pass partial rows afterwards.
 template <int DG, typename Range>
