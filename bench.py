@@ -30,12 +30,12 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 # Share of a SIMD's cycles in which its vector pipe issues / its matrix pipe is busy, from rocprofv3 --pmc runs of
 # the same kernels (profiles/gsr_step_cfg2_sq_counters.md): the block kernels are limited by these, not by HBM.
 MEASURED_PIPES = {
-    "cfg2-1M": {"block_forward": {"valu_busy": 0.58, "mfma_busy": 0.38}, "block_backward": {"valu_busy": 0.40, "mfma_busy": 0.41},
-                "grad": {"valu_busy": 0.20, "mfma_busy": 0.37}},
+    "cfg2-1M": {"block_forward": {"valu_busy": 0.80, "mfma_busy": 0.17}, "block_backward": {"valu_busy": 0.40, "mfma_busy": 0.41},
+                "grad": {"valu_busy": 0.35, "mfma_busy": 0.17}},
 }
 MEASURED_TRAFFIC = {
-    "cfg2-1M": {"grad": 2.0 * 713.9e6 + 386.3e6, "block_forward": 2.0 * 325.9e6 + 314.4e6,
-                "block_backward": 2.0 * 450.8e6 + 291.4e6},
+    "cfg2-1M": {"grad": 2.0 * 700.1e6 + 386.3e6, "block_forward": 2.0 * 318.9e6 + 312.3e6,
+                "block_backward": 2.0 * 450.6e6 + 291.4e6},
 }
 
 
