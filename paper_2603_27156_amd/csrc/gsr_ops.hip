@@ -122,13 +122,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     walk.finish();
 }
 
+// float32 records: the sums of a tile in ordinary arithmetic into an LDS tile (gather_records_rows), rows stored from
+// there; 16-bit records: on the matrix cores, rows stored from the accumulators.
 template <int DG, typename T, bool DEAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k_aggregate_tile(CsrView g, int n, int tiles, const T* __restrict__ vals,
                                                         const typename MaskOf<DG>::type* __restrict__ masks, int k,
                                                         const float* __restrict__ hub_part, float* __restrict__ h_out,
                                                         int* draws, int* draws_done) {
-    __shared__ TileLds lds[4];
-    TileLds& L = lds[threadIdx.x >> 6];
+    constexpr int LR = DG + 1;
+    struct Wave {
+        TileLds t;
+        float st[sizeof(T) == 4 ? 16 * LR : 1];
+    };
+    __shared__ Wave lds[4];
+    Wave& W = lds[threadIdx.x >> 6];
+    TileLds& L = W.t;
     const int lane = lane_id();
     TileWalk<DEAL> walk(g, tiles, draws, draws_done);
     while (walk.more()) {
@@ -138,15 +146,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
         const int rpv = tile_rp_load(g, r0, n, lane);
         const bool has_hub = tile_begin(g, rpv, L.rp, lane);
         if (walk.dealt(g, rpv, L.rp, has_hub)) { walk.next(g); continue; }
-        f32x4 acc[DG / 16];
+        if constexpr (sizeof(T) == 4) {
+            tile_gather_rows<DG>(g, hub_part, has_hub, r0, L.rp, W.st, lane, [&](int e_a, int e_b) {
+                gather_records_rows<DG, 8>(g, vals, masks, k, __builtin_amdgcn_readfirstlane(e_a), __builtin_amdgcn_readfirstlane(e_b),
+                                           L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf, lane, W.st);
+            });
+            wave_sync();
+            const int rows = n - r0 < 16 ? n - r0 : 16;
+            for (int r = 0; r < rows; ++r)
+                if (lane < DG) __builtin_nontemporal_store(W.st[r * LR + lane], h_out + (size_t)(r0 + r) * DG + lane);
+        } else {
+            f32x4 acc[DG / 16];
 #pragma unroll
-        for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        tile_ranges(g, has_hub, L.rp, [&](int e_a, int e_b) {
-            gather_records_mfma<DG, T, 8>(g, vals, masks, k, __builtin_amdgcn_readfirstlane(e_a),
-                                          __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
-                                          lane, acc);
-        });
-        store_acc_rows<DG>(acc, g, hub_part, has_hub, r0, n, L.rp, h_out, DG, lane);
+            for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            tile_ranges(g, has_hub, L.rp, [&](int e_a, int e_b) {
+                gather_records_mfma<DG, T, 8>(g, vals, masks, k, __builtin_amdgcn_readfirstlane(e_a),
+                                              __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
+                                              lane, acc);
+            });
+            store_acc_rows<DG>(acc, g, hub_part, has_hub, r0, n, L.rp, h_out, DG, lane);
+        }
         walk.next(g);
     }
     walk.finish();
