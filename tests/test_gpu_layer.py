@@ -483,11 +483,21 @@ def test_step_on_drawn_shapes(n, dg, c, k, norm, layout, dtype, depth, seed):
     assert np.isclose(out["dbout"], ref["dbout"], rtol=1e-4, atol=1e-7)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_graph_of_long_rows_goes_through_the_first_pass(dtype):
+@pytest.mark.parametrize("dtype,threshold", [("f32", 0), ("bf16", 0), ("f32", 512), ("bf16", 512)])
+def test_graph_of_long_rows_goes_through_the_first_pass(dtype, threshold):
     """A graph whose mean row has more than 64 stored entries (the regime of the paper's Table 1): with the options left
-    at 0 nearly every row is cut into chunks that the first pass sums, in ordinary arithmetic."""
+    at 0 nearly every row is cut into chunks that the first pass sums, in ordinary arithmetic.  With the threshold
+    forced to 512 the same rows stay in their tiles: every tile then holds some 3,000 edges, its rows span several
+    rounds of 64 staged edges and several of a round's four runs."""
     import scipy.sparse as sp
+    gsr.gsr_set_option("hub_threshold", threshold)
+    try:
+        _long_rows_case(dtype, threshold, sp)
+    finally:
+        gsr.gsr_set_option("hub_threshold", 0)
+
+
+def _long_rows_case(dtype, threshold, sp):
     rng = np.random.default_rng(21)
     n, deg = 1203, 90
     r = np.repeat(np.arange(n), deg)
@@ -501,7 +511,7 @@ def test_graph_of_long_rows_goes_through_the_first_pass(dtype):
     c = Case(w, 3, PLANAR)
     c.og = oracle.graph_from_csr(A.indptr.astype(np.int64), A.indices.astype(np.int32), av)
     c.gg = gsr.gsr_graph_create(A.indptr.astype(np.int64), A.indices.astype(np.int32), vals=av, flags=0)
-    assert gsr.gsr_graph_info(c.gg)["n_hub_rows"] == n
+    assert gsr.gsr_graph_info(c.gg)["n_hub_rows"] == (n if threshold == 0 else 0)
     ref = oracle.step(c.og, c.ocfg, w.l, c.x0_on_grid(), c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target)
     out = run_step(c)
     if dtype == "bf16":
