@@ -155,6 +155,16 @@ gsr_status_t gsr_group_sparse(const void* x, int64_t n, int32_t dg, int64_t ld, 
 gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t width, float* y,
                       int64_t ldy, int32_t transpose, void* stream);
 
+/* gsr_spmm for callers that cannot allocate device memory or let a library do it on their behalf: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * results; the scratch gsr_spmm keeps in the graph (the tile counters of its sweep and the first-pass sums of split
+ * rows) lives in a fixed device array of the library instead, 4.1 MiB per GPU, held until the process ends.  The call
+ * allocates and frees nothing and only launches kernels.  Limits: at most 16,384 first-pass chunks (rows above
+ * "hub_threshold" stored entries, cut every "hub_chunk"), else GSR_ERR_UNSUPPORTED; the graph's device must be the
+ * current one.  All calls on one GPU share the array: two that overlap (different streams or threads) race. */
+gsr_status_t gsr_spmm_noalloc(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t width, float* y,
+                              int64_t ldy, int32_t transpose, void* stream);
+
 /* H = A * scatter(V, I): the forward block's aggregation of a compressed embedding, Section
  * 4.1 eq. (10), every neighbour contributing at its own recorded columns.  vals: device n*k
  * of `dtype`; idx: device n*k int32 (distinct per row, any order); dg in {32, 64};

@@ -28,7 +28,8 @@ GSR_ADJ_UNIT, GSR_ADJ_GCN_SYM = 0, 1
 EXPORTED = [
     "gsr_last_error", "gsr_version", "gsr_set_option", "gsr_profile_read", "gsr_profile_reset",
     "gsr_profile_class_name", "gsr_graph_create", "gsr_graph_normalize", "gsr_graph_info",
-    "gsr_graph_export", "gsr_graph_destroy", "gsr_group_sparse", "gsr_spmm", "gsr_spmm_compressed_workspace",
+    "gsr_graph_export", "gsr_graph_destroy", "gsr_group_sparse", "gsr_spmm", "gsr_spmm_noalloc",
+    "gsr_spmm_compressed_workspace",
     "gsr_spmm_compressed", "gsr_workspace_size", "gsr_layer_forward", "gsr_layer_inverse", "gsr_layer_backward",
     "gsr_step", "gsr_walkthrough_workspace", "gsr_slot_block", "gsr_alg1_layer_forward", "gsr_alg2_layer_backward",
     "gsr_sgd_update", "gsr_adam_update",
@@ -237,6 +238,17 @@ def gsr_spmm(g: Graph, x, transpose: bool = False):
     _check(lib().gsr_spmm(g.ptr, _dp(x), C.c_int64(x.stride(0) if n > 1 else width), C.c_int32(width), _dp(y),
                           C.c_int64(width), C.c_int32(1 if transpose else 0), _stream()))
     return y
+
+
+def gsr_spmm_noalloc(g: Graph, x, y, transpose: bool = False) -> None:
+    """gsr_spmm into the caller's y, with the library's scratch in a fixed device array: nothing is allocated."""
+    import torch
+    for t in (x, y):
+        assert t.is_cuda and t.dtype == torch.float32 and t.dim() == 2 and t.stride(1) == 1
+    assert x.shape == y.shape
+    n, width = x.shape
+    _check(lib().gsr_spmm_noalloc(g.ptr, _dp(x), C.c_int64(x.stride(0) if n > 1 else width), C.c_int32(width), _dp(y),
+                                  C.c_int64(y.stride(0) if n > 1 else width), C.c_int32(1 if transpose else 0), _stream()))
 
 
 def _walkthrough_ws(g: Graph, k: int, device):

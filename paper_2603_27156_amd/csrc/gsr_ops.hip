@@ -4,6 +4,7 @@
 #include "gsr_device.h"
 
 #include <algorithm>
+#include <mutex>
 
 namespace gsr {
 
@@ -277,6 +278,91 @@ static gsr_status_t aggregate_impl(const gsr_graph_t* g, const void* vals, const
     return GSR_OK;
 }
 
+
+// ---- gsr_spmm: argument checks and launches shared by its two entry points ------------------------------
+static gsr_status_t spmm_check(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t width, float* y, int64_t ldy,
+                               int32_t transpose) {
+    if (!g) return fail(GSR_ERR_INVALID_ARG, "graph is null");
+    if (width < 1) return fail(GSR_ERR_INVALID_ARG, "width=%d", width);
+    if (ldx < width || ldy < width) return fail(GSR_ERR_INVALID_ARG, "row stride below width");
+    if (g->n == 0) return GSR_OK;
+    if (!x || !y) return fail(GSR_ERR_INVALID_ARG, "null pointer");
+    if (transpose && !g->has_transpose) return fail(GSR_ERR_UNSUPPORTED, "graph has no transpose");
+    return GSR_OK;
+}
+
+// hub_part: first-pass sums of split rows, [chunks][64] floats; draws / done: a clear counter set (tile_draws)
+static gsr_status_t spmm_launch(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t width, float* y, int64_t ldy,
+                                int32_t transpose, float* hub_part, int* draws, int* done, hipStream_t s) {
+    const CsrView view = make_view(g, transpose != 0);
+    // 16, 32 or 64 columns with aligned rows: 16-row tiles on the matrix cores; split rows go through a
+    // first pass into hub_part
+    const size_t piece = (size_t)(width / 16) * sizeof(float);
+    if ((width == 16 || width == 32 || width == 64) && g->n < ((int64_t)1 << 31) && (ldx * sizeof(float)) % piece == 0 &&
+        (ldy * sizeof(float)) % piece == 0 && ((uintptr_t)x % piece) == 0 && ((uintptr_t)y % piece) == 0 && hub_part) {
+        const HubPlan& h = transpose ? g->at.hub : g->a.hub;
+        const int tiles = (int)((g->n + 15) / 16);
+        if (h.n_chunks > 0) {
+            HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+            const dim3 hg((unsigned)std::min((h.n_chunks + 3) / 4, 4096));
+            if (width == 64) hipLaunchKernelGGL((k_hub_dense<64, float>), hg, dim3(256), 0, s, view, hc, x, ldx, hub_part);
+            else if (width == 32) hipLaunchKernelGGL((k_hub_dense<32, float>), hg, dim3(256), 0, s, view, hc, x, ldx, hub_part);
+            else hipLaunchKernelGGL((k_hub_dense<16, float>), hg, dim3(256), 0, s, view, hc, x, ldx, hub_part);
+        }
+        const bool deal = heavy_first(view.n_heavy, tiles, (unsigned)g->grid);
+        auto launch = [&](auto kernel) {
+            hipLaunchKernelGGL(kernel, dim3((unsigned)g->grid), dim3(256), 0, s, view, (int)g->n, tiles, x, ldx, y, ldy,
+                               (const float*)hub_part, draws, done);
+        };
+        if (width == 64) deal ? launch(k_spmm_tile<64, true>) : launch(k_spmm_tile<64, false>);
+        else if (width == 32) deal ? launch(k_spmm_tile<32, true>) : launch(k_spmm_tile<32, false>);
+        else deal ? launch(k_spmm_tile<16, true>) : launch(k_spmm_tile<16, false>);
+        GSR_HIP_CHECK(hipGetLastError());
+        return GSR_OK;
+    }
+    const unsigned blocks = (unsigned)std::min<int64_t>((g->n + 3) / 4, 8192);
+    hipLaunchKernelGGL(k_spmm_dense, dim3(blocks), dim3(256), 0, s, view, g->n, x, ldx, width, y, ldy);
+    GSR_HIP_CHECK(hipGetLastError());
+    return GSR_OK;
+}
+
+// ---- gsr_spmm_noalloc: the scratch of gsr_spmm in a fixed device array -------------------------------------
+// For callers that cannot allocate.  Layout: one counter set of the dynamic tile sweep with its sign-off counters,
+// then the first-pass sums of up to kNoAllocMaxChunks chunks of split rows.  Every GPU the library runs on holds its
+// own copy of the array until the process ends; host code reaches it only through the address that
+// hipGetSymbolAddress returns with that GPU current (the array's name is not a device address on the host).
+constexpr int kNoAllocMaxChunks = 16384;
+constexpr int kNoAllocCounterInts = kTileCounters + 9 * 32;
+constexpr size_t kNoAllocCounterBytes = ((size_t)kNoAllocCounterInts * sizeof(int) + 255) / 256 * 256;
+constexpr size_t kNoAllocBytes = kNoAllocCounterBytes + (size_t)kNoAllocMaxChunks * 64 * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kNoAllocBytes];
+
+constexpr int kNoAllocMaxDevices = 64;
+static std::mutex g_noalloc_mutex;
+static char* g_noalloc_ptr[kNoAllocMaxDevices];      // per device: the address of `scratch` there
+
+// The address of the array on `device` (looked up once per device, with that device current).
+static gsr_status_t noalloc_scratch(int device, char** out) {
+    int cur = -1;
+    GSR_HIP_CHECK(hipGetDevice(&cur));
+    if (cur != device) return fail(GSR_ERR_INVALID_ARG, "the graph was built on device %d, the current device is %d", device, cur);
+    if (device < 0 || device >= kNoAllocMaxDevices) return fail(GSR_ERR_UNSUPPORTED, "device index %d above %d", device, kNoAllocMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+    if (!g_noalloc_ptr[device]) {
+        void* p = nullptr;
+        GSR_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(GSR_ERR_HIP, "hipGetSymbolAddress returned a null address");
+        g_noalloc_ptr[device] = static_cast<char*>(p);
+    }
+    *out = g_noalloc_ptr[device];
+    return GSR_OK;
+}
+
+__global__ void k_clear_ints(int* p, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0;
+}
+
 }  // namespace gsr
 
 using namespace gsr;
@@ -327,45 +413,29 @@ gsr_status_t gsr_group_sparse(const void* x, int64_t n, int32_t dg, int64_t ld, 
 
 gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t width, float* y, int64_t ldy,
                       int32_t transpose, void* stream) {
-    if (!g) return fail(GSR_ERR_INVALID_ARG, "graph is null");
-    if (width < 1) return fail(GSR_ERR_INVALID_ARG, "width=%d", width);
-    if (ldx < width || ldy < width) return fail(GSR_ERR_INVALID_ARG, "row stride below width");
+    GSR_TRY(spmm_check(g, x, ldx, width, y, ldy, transpose));
     if (g->n == 0) return GSR_OK;
-    if (!x || !y) return fail(GSR_ERR_INVALID_ARG, "null pointer");
-    if (transpose && !g->has_transpose) return fail(GSR_ERR_UNSUPPORTED, "graph has no transpose");
+    int *draws, *done;
+    tile_counters(g, &draws, &done);
+    return spmm_launch(g, x, ldx, width, y, ldy, transpose, g->scratch, draws, done, (hipStream_t)stream);
+}
+
+gsr_status_t gsr_spmm_noalloc(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t width, float* y, int64_t ldy,
+                              int32_t transpose, void* stream) {
+    GSR_TRY(spmm_check(g, x, ldx, width, y, ldy, transpose));
+    if (g->n == 0) return GSR_OK;
+    const HubPlan& h = transpose ? g->at.hub : g->a.hub;
+    if (h.n_chunks > kNoAllocMaxChunks)
+        return fail(GSR_ERR_UNSUPPORTED, "gsr_spmm_noalloc: the graph's split rows make %d first-pass chunks, the built-in scratch holds %d",
+                    h.n_chunks, kNoAllocMaxChunks);
+    char* base = nullptr;
+    GSR_TRY(noalloc_scratch(g->device, &base));
     hipStream_t s = (hipStream_t)stream;
-    const CsrView view = make_view(g, transpose != 0);
-    // 32 or 64 columns with aligned rows: 16-row tiles on the matrix cores; split rows go through a
-    // first pass into the graph's own scratch
-    const size_t piece = (size_t)(width / 16) * sizeof(float);
-    if ((width == 16 || width == 32 || width == 64) && g->n < ((int64_t)1 << 31) && (ldx * sizeof(float)) % piece == 0 &&
-        (ldy * sizeof(float)) % piece == 0 && ((uintptr_t)x % piece) == 0 && ((uintptr_t)y % piece) == 0 && g->scratch) {
-        const HubPlan& h = transpose ? g->at.hub : g->a.hub;
-        const int tiles = (int)((g->n + 15) / 16);
-        if (h.n_chunks > 0) {
-            HubChunks hc{h.ce0, h.ce1, h.n_chunks};
-            const dim3 hg((unsigned)std::min((h.n_chunks + 3) / 4, 4096));
-            if (width == 64) hipLaunchKernelGGL((k_hub_dense<64, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
-            else if (width == 32) hipLaunchKernelGGL((k_hub_dense<32, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
-            else hipLaunchKernelGGL((k_hub_dense<16, float>), hg, dim3(256), 0, s, view, hc, x, ldx, g->scratch);
-        }
-        int *dn, *dx;
-        tile_counters(g, &dn, &dx);
-        const bool deal = heavy_first(view.n_heavy, tiles, (unsigned)g->grid);
-        auto launch = [&](auto kernel) {
-            hipLaunchKernelGGL(kernel, dim3((unsigned)g->grid), dim3(256), 0, s, view, (int)g->n, tiles, x, ldx, y, ldy,
-                               (const float*)g->scratch, dn, dx);
-        };
-        if (width == 64) deal ? launch(k_spmm_tile<64, true>) : launch(k_spmm_tile<64, false>);
-        else if (width == 32) deal ? launch(k_spmm_tile<32, true>) : launch(k_spmm_tile<32, false>);
-        else deal ? launch(k_spmm_tile<16, true>) : launch(k_spmm_tile<16, false>);
-        GSR_HIP_CHECK(hipGetLastError());
-        return GSR_OK;
-    }
-    const unsigned blocks = (unsigned)std::min<int64_t>((g->n + 3) / 4, 8192);
-    hipLaunchKernelGGL(k_spmm_dense, dim3(blocks), dim3(256), 0, s, view, g->n, x, ldx, width, y, ldy);
-    GSR_HIP_CHECK(hipGetLastError());
-    return GSR_OK;
+    int* draws = reinterpret_cast<int*>(base);
+    // the array keeps the last call's contents: the counters must read zero when the sweep starts
+    hipLaunchKernelGGL(k_clear_ints, dim3((kNoAllocCounterInts + 255) / 256), dim3(256), 0, s, draws, kNoAllocCounterInts);
+    float* part = reinterpret_cast<float*>(base + kNoAllocCounterBytes);
+    return spmm_launch(g, x, ldx, width, y, ldy, transpose, part, draws, draws + kTileCounters, s);
 }
 
 size_t gsr_spmm_compressed_workspace(const gsr_graph_t* g, int32_t k, int32_t dg) {
