@@ -117,6 +117,15 @@ def gs(Z, k: int, norm: int = NORM_NONE, eps: float = 1e-5, sm: int = STORE_F64)
     return V, I, r
 
 
+def gs_near_tie(Z, k: int, tol: float):
+    """Rows whose top-k boundary is a near-tie: v_k - v_(k+1) <= tol * max|row| in float32 -> bool [n]."""
+    Z = _f64(Z)
+    n, dg = Z.shape
+    out = np.zeros(n, dtype=np.uint8)
+    lib().orc_gs_near_tie(_p(Z), C.c_int64(dg), C.c_int64(n), C.c_int(dg), C.c_int(k), C.c_float(tol), _p(out))
+    return out.astype(bool)
+
+
 def aggregate(g: Graph, V, I, dg: int):
     """A * scatter(V, I) -> [n, dg]."""
     V = _f64(V)
@@ -152,7 +161,7 @@ def layer_forward(g: Graph, cfg: Cfg, W, X):
     Y = _f64(X).copy()
     W = _f64(W)
     lib().orc_layer_forward(C.c_int64(g.n), _p(g.rp), _p(g.ci), _p(g.av), *_cfg_args(cfg), _p(W), _p(Y),
-                            None, None, None, None)
+                            None, None, None, None, None, C.c_float(0.0))
     return Y
 
 
@@ -164,16 +173,18 @@ def layer_inverse(g: Graph, cfg: Cfg, W, Y):
     return X
 
 
-def layer_backward(g: Graph, cfg: Cfg, W, Y, dY, I_saved=None):
+def layer_backward(g: Graph, cfg: Cfg, W, Y, dY, I_saved=None, listed=None):
     """Inverse interleaved with backward.  Returns (X, dX, dW[C,dg,dg]).  I_saved [C, n, k]
-    int32: indices kept from the forward pass, used instead of selecting again."""
+    int32: indices kept from the forward pass, used instead of selecting again; with listed
+    [C, n] (bool) only by the listed rows."""
     X = _f64(Y).copy()
     dX = _f64(dY).copy()
     W = _f64(W)
     dW = np.zeros((cfg.c, cfg.dg, cfg.dg), dtype=np.float64)
     lib().orc_layer_backward(C.c_int64(g.n), _p(g.rp), _p(g.ci), _p(g.av), _p(g.trp), _p(g.tci), _p(g.tav),
                              *_cfg_args(cfg), _p(W), _p(X), _p(dX), _p(dW),
-                             _p(np.ascontiguousarray(I_saved, dtype=np.int32)) if I_saved is not None else None)
+                             _p(np.ascontiguousarray(I_saved, dtype=np.int32)) if I_saved is not None else None,
+                             _p(np.ascontiguousarray(listed, dtype=np.uint8)) if listed is not None else None)
     return X, dX, dW
 
 
@@ -205,10 +216,11 @@ def head(X, w, b, target, sm: int = STORE_F64):
 
 
 def step(g: Graph, cfg: Cfg, L: int, X0, W, w_out, b_out, target, variant: int = 0,
-         want=("yhat", "XL", "X0rec", "dW", "dwout", "dX0")):
+         want=("yhat", "XL", "X0rec", "dW", "dwout", "dX0"), tie_tol: float = 0.0):
     """One training step.  variant 0: inverse interleaved with backward; 1: stored activations;
-    2: as 0 with the indices of the forward sweep kept and reused (Section 4.2).
-    Returns dict(loss, yhat, XL, X0rec, dW [L,C,dg,dg], dwout, dbout, dX0)."""
+    2: as 0 with the indices of the forward sweep kept and reused (Section 4.2); 3: as 2 for the
+    rows that selected at a near-tie (gs_near_tie with tie_tol) only.
+    Returns dict(loss, yhat, XL, X0rec, dW [L,C,dg,dg], dwout, dbout, dX0, n_listed)."""
     X0 = _f64(X0)
     n, d = X0.shape
     W = _f64(W)
@@ -226,15 +238,17 @@ def step(g: Graph, cfg: Cfg, L: int, X0, W, w_out, b_out, target, variant: int =
     )
     loss = C.c_double(0.0)
     db = C.c_double(0.0)
+    n_listed = C.c_int64(0)
     rc = lib().orc_step(C.c_int64(n), _p(g.rp), _p(g.ci), _p(g.av), C.c_int(cfg.d), C.c_int(cfg.c),
                         C.c_int(L), C.c_int(cfg.k), C.c_int(cfg.norm), C.c_double(cfg.eps), C.c_int(cfg.sm),
                         _p(X0), _p(W), _p(w_out), C.c_double(b_out), _p(target), C.c_int(variant),
-                        C.byref(loss), _p(out["yhat"]), _p(out["XL"]), _p(out["X0rec"]), _p(out["dW"]),
+                        C.c_float(tie_tol), C.byref(n_listed), C.byref(loss), _p(out["yhat"]), _p(out["XL"]), _p(out["X0rec"]), _p(out["dW"]),
                         _p(out["dwout"]), C.byref(db), _p(out["dX0"]))
     if rc != 0:
         raise MemoryError("orc_step failed")
     out["loss"] = loss.value
     out["dbout"] = db.value
+    out["n_listed"] = n_listed.value
     return out
 
 

@@ -229,6 +229,43 @@ void orc_gs_given(const double* Z, int64_t ldz, int64_t n, int dg, int k, int no
     }
 }
 
+/* Which rows select at a near-tie (for keeping only those rows' indices, a selective form of
+ * Section 4.2's save-for-backward).  With v_k the k-th and v_{k+1} the (k+1)-th largest value of
+ * the row (by the selection rule of orc_gs; equal when the boundary is an exact tie), the row is
+ * listed iff  k < dg  and  v_k - v_{k+1} <= tol * max_c |z_c|.  The comparison is an integer decision
+ * taken by floating point, so it is made in float32 arithmetic on the float32 images of the values
+ * (exact for float32 / bf16 storage): one rounded subtraction, one rounded product. */
+void orc_gs_near_tie(const double* Z, int64_t ldz, int64_t n, int dg, int k, float tol,
+                     unsigned char* listed) {
+#pragma omp parallel for schedule(static)
+    for (int64_t row = 0; row < n; ++row) {
+        const double* z = Z + row * ldz;
+        listed[row] = 0;
+        if (k >= dg) continue;
+        unsigned char taken[1024];
+        for (int c = 0; c < dg; ++c) taken[c] = 0;
+        double picked[2] = {0.0, 0.0};
+        for (int t = 0; t <= k; ++t) {         /* k + 1 rounds: the k-th and (k+1)-th picks */
+            int best = -1;
+            for (int c = 0; c < dg; ++c) {
+                if (taken[c]) continue;
+                if (best < 0 || z[c] > z[best]) best = c;
+            }
+            taken[best] = 1;
+            if (t == k - 1) picked[0] = z[best];
+            if (t == k) picked[1] = z[best];
+        }
+        float amax = 0.0f;
+        for (int c = 0; c < dg; ++c) {
+            float a = fabsf((float)z[c]);
+            if (a > amax) amax = a;
+        }
+        float gap = (float)picked[0] - (float)picked[1];
+        float bar = tol * amax;
+        listed[row] = gap <= bar ? 1 : 0;
+    }
+}
+
 /* H = A * scatter(V, I): row i gathers, from every stored neighbour j, the k values of j
  * at the columns j recorded (Section 4.1, eq. (10)). */
 void orc_aggregate(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
@@ -256,17 +293,27 @@ typedef struct {
 } blk_t;
 
 /* f(Z) = (A scatter(GS(Z))) W.   Z has row stride ldz.  Outputs O (n x dg, dense) and what
- * the backward needs: I, r, H.  With I_given the selection is not made again: the values
- * are taken at the given indices (and I is not written). */
+ * the backward needs: I, r, H.  With I_given and no `listed` the selection is not made again:
+ * the values are taken at the given indices (and I is not written).  With I_given and `listed`
+ * (one flag per row) only the listed rows take the given indices; every other row selects
+ * again, and I receives the indices in use. */
 static void block_f(const blk_t* b, const double* Z, int64_t ldz, const double* W,
-                    double* O, int32_t* I, double* r, double* H, const int32_t* I_given) {
+                    double* O, int32_t* I, double* r, double* H, const int32_t* I_given,
+                    const unsigned char* listed) {
     int64_t n = b->n; int dg = b->dg, k = b->k;
     double* V = (double*)malloc((size_t)n * k * sizeof(double));
-    if (I_given) {
+    if (I_given && !listed) {
         orc_gs_given(Z, ldz, n, dg, k, b->norm, b->eps, b->sm, I_given, V, r);
         I = (int32_t*)I_given;
     } else {
         orc_gs(Z, ldz, n, dg, k, b->norm, b->eps, b->sm, V, I, r);
+        if (I_given) {
+            for (int64_t row = 0; row < n; ++row) {
+                if (!listed[row]) continue;
+                memcpy(I + row * k, I_given + row * k, (size_t)k * sizeof(int32_t));
+                orc_gs_given(Z + row * ldz, ldz, 1, dg, k, b->norm, b->eps, b->sm, I + row * k, V + row * k, 0);
+            }
+        }
     }
     orc_aggregate(n, b->rp, b->ci, b->av, V, I, k, dg, H);
 #pragma omp parallel for schedule(static)
@@ -366,11 +413,13 @@ static blk_t mk_blk(int64_t n, const int64_t* rp, const int32_t* ci, const float
 /* Forward of one layer, in place: X (n x D) becomes Y = concat(Y_1..Y_C), eq. (6).
  * W: C matrices dg x dg (in -> out).  When keep_* are given (variant "stored"), the block
  * inputs' indices / scales / aggregates are kept for a later backward: I [C][n][k],
- * r [C][n], H [C][n][dg], and Y0 [n][dg]. */
+ * r [C][n], H [C][n][dg], and Y0 [n][dg].  keep_tie [C][n] (or NULL) receives, per block, which
+ * rows selected at a near-tie (orc_gs_near_tie with tie_tol). */
 void orc_layer_forward(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
                        int D, int C, int k, int norm, double eps, int sm,
                        const double* W, double* X,
-                       int32_t* keep_I, double* keep_r, double* keep_H, double* keep_Y0) {
+                       int32_t* keep_I, double* keep_r, double* keep_H, double* keep_Y0,
+                       unsigned char* keep_tie, float tie_tol) {
     int dg = D / C;
     blk_t b = mk_blk(n, rp, ci, av, 0, 0, 0, dg, k, norm, eps, sm);
     double* Y0 = keep_Y0 ? keep_Y0 : (double*)malloc((size_t)n * dg * sizeof(double));
@@ -385,7 +434,8 @@ void orc_layer_forward(int64_t n, const int64_t* rp, const int32_t* ci, const fl
         block_f(&b, Z, ldz, W + (int64_t)(i - 1) * dg * dg, O,
                 keep_I ? keep_I + (int64_t)(i - 1) * n * k : I,
                 keep_r ? keep_r + (int64_t)(i - 1) * n : r,
-                keep_H ? keep_H + (int64_t)(i - 1) * n * dg : H, 0);
+                keep_H ? keep_H + (int64_t)(i - 1) * n * dg : H, 0, 0);
+        if (keep_tie) orc_gs_near_tie(Z, ldz, n, dg, k, tie_tol, keep_tie + (int64_t)(i - 1) * n);
 #pragma omp parallel for schedule(static)
         for (int64_t row = 0; row < n; ++row)
             for (int c = 0; c < dg; ++c) {
@@ -412,7 +462,7 @@ void orc_layer_inverse(int64_t n, const int64_t* rp, const int32_t* ci, const fl
         const double* Z; int64_t ldz;
         if (i == 1) { group_sum(n, D, C, sm, Y, Y0); Z = Y0; ldz = dg; }
         else { Z = Y + (i - 2) * dg; ldz = D; }
-        block_f(&b, Z, ldz, W + (int64_t)(i - 1) * dg * dg, O, I, r, H, 0);
+        block_f(&b, Z, ldz, W + (int64_t)(i - 1) * dg * dg, O, I, r, H, 0, 0);
 #pragma omp parallel for schedule(static)
         for (int64_t row = 0; row < n; ++row)
             for (int c = 0; c < dg; ++c) {
@@ -427,11 +477,14 @@ void orc_layer_inverse(int64_t n, const int64_t* rp, const int32_t* ci, const fl
  * eq. (6)/(7)).  In: Y (layer output) and dY (gradient w.r.t. it), both n x D.  Out, in
  * place: X (layer input, rebuilt) and dX; dW [C][dg][dg].  I_saved (or NULL): the indices
  * [C][n][k] the forward pass of this layer selected (Section 4.2 keeps them); with them the
- * inverse takes the values at those indices instead of selecting again. */
+ * inverse takes the values at those indices instead of selecting again.  With `listed`
+ * ([C][n] flags, or NULL) only the listed rows do; every other row selects again on its rebuilt
+ * values (I_saved then needs to be valid for the listed rows only). */
 void orc_layer_backward(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
                         const int64_t* trp, const int32_t* tci, const float* tav,
                         int D, int C, int k, int norm, double eps, int sm,
-                        const double* W, double* Y, double* dY, double* dW, const int32_t* I_saved) {
+                        const double* W, double* Y, double* dY, double* dW, const int32_t* I_saved,
+                        const unsigned char* listed) {
     int dg = D / C;
     blk_t b = mk_blk(n, rp, ci, av, trp, tci, tav, dg, k, norm, eps, sm);
     double* Y0 = (double*)malloc((size_t)n * dg * sizeof(double));
@@ -445,8 +498,9 @@ void orc_layer_backward(int64_t n, const int64_t* rp, const int32_t* ci, const f
         if (i == 1) { group_sum(n, D, C, sm, Y, Y0); Z = Y0; ldz = dg; }
         else { Z = Y + (i - 2) * dg; ldz = D; }
         const double* Wi = W + (int64_t)(i - 1) * dg * dg;
-        const int32_t* Ii = I_saved ? I_saved + (int64_t)(i - 1) * n * k : I;
-        block_f(&b, Z, ldz, Wi, O, I, r, H, I_saved ? Ii : 0); /* recompute f_i(Y_{i-1}) */
+        const int32_t* Ii = (I_saved && !listed) ? I_saved + (int64_t)(i - 1) * n * k : I;
+        block_f(&b, Z, ldz, Wi, O, I, r, H, I_saved ? I_saved + (int64_t)(i - 1) * n * k : 0,
+                listed ? listed + (int64_t)(i - 1) * n : 0);   /* recompute f_i(Y_{i-1}) */
 #pragma omp parallel for schedule(static)
         for (int64_t row = 0; row < n; ++row)
             for (int c = 0; c < dg; ++c) {
@@ -486,7 +540,7 @@ void orc_layer_backward_stored(int64_t n, const int64_t* rp, const int32_t* ci, 
     double* H = (double*)malloc((size_t)C * n * dg * sizeof(double));
     double* Y0 = (double*)malloc((size_t)n * dg * sizeof(double));
     double* dY0 = (double*)calloc((size_t)n * dg, sizeof(double));
-    orc_layer_forward(n, rp, ci, av, D, C, k, norm, eps, sm, W, Yl, I, r, H, Y0);
+    orc_layer_forward(n, rp, ci, av, D, C, k, norm, eps, sm, W, Yl, I, r, H, Y0, 0, 0.0f);
     for (int i = C; i >= 1; --i) {
         const double* Z = (i == 1) ? Y0 : Yl + (i - 2) * dg;
         int64_t ldz = (i == 1) ? dg : D;
@@ -540,12 +594,16 @@ void orc_head(int64_t n, int D, int sm, const double* X, const double* w, double
  * back-propagation (memory grows with L; small cases only).  variant 2: as variant 0, but
  * the indices every block selected in the forward sweep are kept (O(L N k), Section 4.2)
  * and reused by the inverse instead of selecting again on the rebuilt activations.
+ * variant 3: as variant 2, but only for the rows that selected at a near-tie (orc_gs_near_tie
+ * with tie_tol); every other row selects again during the inverse.  (An implementation keeps
+ * the indices of the listed rows only; the oracle keeps all and consults the flags.)
+ * n_listed (or NULL): number of listed (row, block, layer) triples of variant 3.
  * Outputs (any may be NULL except loss): yhat [n], XL [n*D], X0rec [n*D] (variant 0: the
  * rebuilt input), dW [L*C*dg*dg], dwout [D], dbout [1], dX0 [n*D]. */
 int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
              int D, int C, int L, int k, int norm, double eps, int sm,
              const double* X0, const double* W, const double* wout, double bout,
-             const double* target, int variant,
+             const double* target, int variant, float tie_tol, int64_t* n_listed,
              double* loss, double* yhat, double* XL, double* X0rec,
              double* dW, double* dwout, double* dbout, double* dX0) {
     int dg = D / C;
@@ -558,11 +616,15 @@ int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
     double* G = (double*)malloc(plane * sizeof(double));
     double* stored = variant == 1 ? (double*)malloc(plane * (size_t)L * sizeof(double)) : 0;
     size_t per_layer_I = (size_t)C * n * k;
-    int32_t* saved_I = variant == 2 ? (int32_t*)malloc(per_layer_I * (size_t)L * sizeof(int32_t)) : 0;
-    double* tmp_r = variant == 2 ? (double*)malloc((size_t)C * n * sizeof(double)) : 0;
-    double* tmp_H = variant == 2 ? (double*)malloc((size_t)C * n * dg * sizeof(double)) : 0;
-    double* tmp_Y0 = variant == 2 ? (double*)malloc((size_t)n * dg * sizeof(double)) : 0;
-    if (variant == 2 && (!saved_I || !tmp_r || !tmp_H || !tmp_Y0)) return -1;
+    int keep = variant == 2 || variant == 3;
+    int32_t* saved_I = keep ? (int32_t*)malloc(per_layer_I * (size_t)L * sizeof(int32_t)) : 0;
+    double* tmp_r = keep ? (double*)malloc((size_t)C * n * sizeof(double)) : 0;
+    double* tmp_H = keep ? (double*)malloc((size_t)C * n * dg * sizeof(double)) : 0;
+    double* tmp_Y0 = keep ? (double*)malloc((size_t)n * dg * sizeof(double)) : 0;
+    size_t per_layer_T = (size_t)C * n;
+    unsigned char* tie = variant == 3 ? (unsigned char*)malloc(per_layer_T * (size_t)L) : 0;
+    if (keep && (!saved_I || !tmp_r || !tmp_H || !tmp_Y0)) return -1;
+    if (variant == 3 && !tie) return -1;
     double* dw_tmp = (double*)malloc((size_t)D * sizeof(double));
     double* dW_tmp = (double*)malloc((size_t)C * dg * dg * sizeof(double));
     if (!trp || !tci || !tav || !X || !G || !dw_tmp || !dW_tmp || (variant == 1 && !stored)) return -1;
@@ -570,12 +632,18 @@ int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
     for (size_t p = 0; p < plane; ++p) X[p] = store(X0[p], sm);
     for (int l = 0; l < L; ++l) {
         if (stored) memcpy(stored + plane * l, X, plane * sizeof(double));
-        if (variant == 2)
+        if (keep)
             orc_layer_forward(n, rp, ci, av, D, C, k, norm, eps, sm,
-                              W + (int64_t)l * C * dg * dg, X, saved_I + per_layer_I * l, tmp_r, tmp_H, tmp_Y0);
+                              W + (int64_t)l * C * dg * dg, X, saved_I + per_layer_I * l, tmp_r, tmp_H, tmp_Y0,
+                              tie ? tie + per_layer_T * l : 0, tie_tol);
         else
             orc_layer_forward(n, rp, ci, av, D, C, k, norm, eps, sm,
-                              W + (int64_t)l * C * dg * dg, X, 0, 0, 0, 0);
+                              W + (int64_t)l * C * dg * dg, X, 0, 0, 0, 0, 0, 0.0f);
+    }
+    if (n_listed) {
+        *n_listed = 0;
+        if (tie)
+            for (size_t p = 0; p < per_layer_T * (size_t)L; ++p) *n_listed += tie[p];
     }
     if (XL) memcpy(XL, X, plane * sizeof(double));
     double db = 0.0;
@@ -589,13 +657,14 @@ int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
                                       Wl, stored + plane * l, G, dW_tmp);
         else
             orc_layer_backward(n, rp, ci, av, trp, tci, tav, D, C, k, norm, eps, sm,
-                               Wl, X, G, dW_tmp, variant == 2 ? saved_I + per_layer_I * l : 0);
+                               Wl, X, G, dW_tmp, keep ? saved_I + per_layer_I * l : 0,
+                               tie ? tie + per_layer_T * l : 0);
         if (dW) memcpy(dW + (int64_t)l * C * dg * dg, dW_tmp, (size_t)C * dg * dg * sizeof(double));
     }
     if (X0rec) memcpy(X0rec, variant == 1 ? stored : X, plane * sizeof(double));
     if (dX0) memcpy(dX0, G, plane * sizeof(double));
     free(trp); free(tci); free(tav); free(X); free(G); free(stored); free(dw_tmp); free(dW_tmp);
-    free(saved_I); free(tmp_r); free(tmp_H); free(tmp_Y0);
+    free(saved_I); free(tmp_r); free(tmp_H); free(tmp_Y0); free(tie);
     return 0;
 }
 

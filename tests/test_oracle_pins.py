@@ -409,6 +409,94 @@ def test_saved_indices_keep_the_inverse_exact_where_reselection_flips():
     assert rel(again["dX0"], stored["dX0"]) > 5 * rel(saved["dX0"], stored["dX0"])
 
 
+# ------------------------------------------------------------------ indices kept for near-tie rows only
+
+def test_near_tie_rows_against_a_full_sort():
+    """orc_gs_near_tie: gap between the k-th and (k+1)-th largest value against tol * max|row|, in float32.
+    Brute force by a full sort; exact ties (incl. -0 against +0) are always listed, k = Dg never."""
+    rng = np.random.default_rng(31)
+    dg, k, n = 16, 5, 4000
+    Z = rng.standard_normal((n, dg)).astype(np.float32)
+    Z[::7, 3] = Z[::7, 9]                               # exact ties somewhere in the row
+    Z[5] = 0.0
+    Z[5, :8] = -0.0
+    for tol in (0.0, 2.0 ** -12, 2.0 ** -6, 0.3):
+        s = -np.sort(-Z, axis=1)
+        gap = (s[:, k - 1] - s[:, k]).astype(np.float32)
+        bar = (np.float32(tol) * np.abs(Z).max(axis=1)).astype(np.float32)
+        assert np.array_equal(oracle.gs_near_tie(Z, k, tol), gap <= bar)
+    tied = np.array([np.sort(z)[::-1][k - 1] == np.sort(z)[::-1][k] for z in Z])
+    assert tied.sum() > 20 and oracle.gs_near_tie(Z, k, 0.0)[tied].all()
+    assert np.array_equal(np.flatnonzero(oracle.gs_near_tie(Z, k, -1.0)), [5])      # only the all-zero row: 0 <= -1 * 0
+    assert not oracle.gs_near_tie(Z, dg, 1e30).any()
+    # a bf16-like case: many equal values per row
+    Zb = np.round(rng.standard_normal((500, dg)) * 2) / 2
+    s = -np.sort(-Zb, axis=1)
+    assert np.array_equal(oracle.gs_near_tie(Zb, k, 0.0), s[:, k - 1] == s[:, k])
+
+
+def test_listed_rows_take_the_kept_indices_and_the_others_select_again():
+    """orc_layer_backward with (I_saved, listed): a listed row uses its kept indices, any other row the indices a
+    fresh selection gives.  Pinned through the all-rows form (I_saved alone, itself pinned against stored
+    activations): C = 2, rows of block 1 listed with indices that differ from the fresh selection."""
+    g, _ = directed_weighted_graph(40, seed=13)
+    rng = np.random.default_rng(14)
+    C, dg, k = 2, 8, 3
+    D = C * dg
+    cfg = oracle.Cfg(D, C, k, NORM_RMS)
+    Y = rng.standard_normal((g.n, D))
+    dY = rng.standard_normal((g.n, D))
+    W = rng.uniform(-0.4, 0.4, (C, dg, dg))
+    X, _, _ = oracle.layer_backward(g, cfg, W, Y, dY)
+    fresh2 = oracle.gs(Y[:, :dg], k)[1]                 # block 2 selects on Y_1
+    fresh1 = oracle.gs(X[:, dg:], k)[1]                 # block 1 selects on Y_0 = X_2 (C = 2), rebuilt by block 2
+    rows = np.array([1, 7, 8, 22, 39])
+    alt = fresh1.copy()
+    alt[rows] = np.sort((fresh1[rows] + 1 + np.arange(k)) % dg, axis=1)
+    alt[rows[0]] = [0, 1, 2]
+    assert all(len(set(r)) == k for r in alt[rows]) and (alt[rows] != fresh1[rows]).any()
+    junk = np.zeros_like(fresh2)                        # rows that are not listed never read their kept indices
+    saved = np.stack([np.where(np.isin(np.arange(g.n), rows)[:, None], alt, junk), junk])
+    listed = np.zeros((C, g.n), dtype=bool)
+    listed[0, rows] = True
+    got = oracle.layer_backward(g, cfg, W, Y, dY, I_saved=saved, listed=listed)
+    want = oracle.layer_backward(g, cfg, W, Y, dY, I_saved=np.stack([alt, fresh2]))
+    plain = oracle.layer_backward(g, cfg, W, Y, dY)
+    for a, b, c in zip(got, want, plain):
+        assert np.array_equal(a, b) and not np.array_equal(a, c)
+    # nothing listed: the plain call; everything listed: the all-rows form
+    none = oracle.layer_backward(g, cfg, W, Y, dY, I_saved=saved, listed=np.zeros((C, g.n), dtype=bool))
+    every = oracle.layer_backward(g, cfg, W, Y, dY, I_saved=np.stack([alt, fresh2]), listed=np.ones((C, g.n), dtype=bool))
+    for a, b, c, d in zip(none, plain, every, want):
+        assert np.array_equal(a, b) and np.array_equal(c, d)
+
+
+def test_step_with_near_tie_list_between_nothing_kept_and_everything_kept():
+    """variant 3 of the step: tol < 0 lists nothing (= variant 0, bit for bit), a huge tol lists every row
+    (= variant 2, bit for bit); with coarse stores, where selecting again flips rows, a moderate tol brings the
+    rebuilt input and the gradients back to those of the kept-indices run while listing a fraction of the rows."""
+    g = small_graph(300, seed=21)
+    rng = np.random.default_rng(22)
+    C, dg, k, L = 2, 16, 4, 12
+    D = C * dg
+    cfg = oracle.Cfg(D, C, k, NORM_RMS, 1e-5, oracle.STORE_BF16)
+    X0 = oracle.round_store(rng.standard_normal((g.n, D)), oracle.STORE_BF16)
+    W = rng.uniform(-0.3, 0.3, (L, C, dg, dg))
+    w_out = rng.uniform(-0.5, 0.5, D)
+    t = rng.standard_normal(g.n)
+    run = lambda variant, tol=0.0: oracle.step(g, cfg, L, X0, W, w_out, 0.0, t, variant=variant, tie_tol=tol)
+    again, saved = run(0), run(2)
+    lo, hi, mid = run(3, -1.0), run(3, 1e30), run(3, 2.0 ** -5)
+    keys = ("yhat", "XL", "dW", "dwout", "dX0", "X0rec")
+    assert lo["n_listed"] == 0 and hi["n_listed"] == g.n * C * L
+    for key in keys:
+        assert np.array_equal(lo[key], again[key]), key
+        assert np.array_equal(hi[key], saved[key]), key
+    assert 0 < mid["n_listed"] < 0.5 * g.n * C * L
+    err = lambda r: np.abs(r["X0rec"] - X0).max()
+    assert err(again) > 10 * err(saved) and err(mid) <= 2 * err(saved)
+
+
 def test_zero_weights_make_layers_the_identity():
     g = small_graph(50, seed=10)
     rng = np.random.default_rng(11)
