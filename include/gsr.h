@@ -85,7 +85,18 @@ typedef struct gsr_config {
                              1: the column set every block selected in the forward sweep is kept
                              (Section 4.2: selective save of the indices, O(L N k) bits) and reused by
                              the inverse, which is then continuous in its input; the workspace grows
-                             by (L+1) * C * N * (D/C)/8 bytes. */
+                             by (L+1) * C * N * (D/C)/8 bytes.
+                             2: as 1, but only for the rows that selected at a near-tie: with v_k the k-th
+                             and v_(k+1) the (k+1)-th largest value of a row, the row's column set is kept
+                             iff v_k - v_(k+1) <= tie_tol * max|row| (float32 arithmetic; exact ties always
+                             are).  Every other row selects again on its rebuilt values, which gives the
+                             same set as long as the rebuilt row is off by less than half its gap.  The
+                             workspace grows by (L+1) * C * tie_capacity * (4 + (D/C)/8) bytes. */
+    float tie_tol;        /* save_indices == 2: see above; >= 0.  Rounding of the inverse sweep grows with depth
+                             (measured on 1M nodes, D/C = 64, float32: rebuilt input off by 2e-4 of its range at
+                             L = 448): 2^-12 covers that depth, deeper stacks need more. */
+    int32_t tie_capacity; /* save_indices == 2: rows that can be kept per block and layer; 0: N/32 + 1024.
+                             Rows beyond it are not kept and select again (gsr_step_tie_stats counts them). */
 } gsr_config_t;
 
 const char* gsr_last_error(void);
@@ -105,7 +116,8 @@ gsr_status_t gsr_set_option(const char* key, int64_t value);
  * gsr_profile_read waits for the recorded events and returns the summed duration and number
  * of launches of one class since the last gsr_profile_reset.  Classes: 0 block forward,
  * 1 block inverse, 2 block inverse + weight gradient, 3 data gradient, 4 group sum / record,
- * 5 hub first pass, 6 dW reduction (on large graphs it is part of class 3), 7 head, 8 layout copy.  Not thread-safe. */
+ * 5 hub first pass, 6 dW reduction (on large graphs it is part of class 3), 7 head, 8 layout copy, 9 records of
+ * near-tie rows written again (save_indices == 2).  Not thread-safe. */
 gsr_status_t gsr_profile_read(int32_t kernel_class, double* total_ms, int64_t* launches);
 gsr_status_t gsr_profile_reset(void);
 const char* gsr_profile_class_name(int32_t kernel_class);
@@ -219,6 +231,18 @@ gsr_status_t gsr_step(const gsr_graph_t* g, const gsr_config_t* cfg, const void*
                       float* yhat_out, float* dw_all, float* dw_out, float* db_out, void* dx0_out,
                       void* x0_rebuilt_out, void* xl_out, void* workspace, size_t workspace_bytes,
                       void* stream);
+
+/* Counts of the last gsr_step with cfg->save_indices == 2 that ran in `workspace` (same cfg and g): rows kept over
+ * all blocks and layers, the largest number any one block listed, and the rows that were not kept because a block
+ * listed more than cfg->tie_capacity.  Waits for `stream`.  Any output pointer may be NULL. */
+gsr_status_t gsr_step_tie_stats(const gsr_graph_t* g, const gsr_config_t* cfg, const void* workspace,
+                                int64_t* listed, int64_t* max_per_block, int64_t* dropped, void* stream);
+
+/* The rows kept by that step for the input of block `block` (1..C) of layer `layer` (0..L-1), in no particular order:
+ * rows_out (host, cfg->tie_capacity or its default entries) and masks_out (host, same count, bit c set: column c
+ * kept); *count_out = entries written.  Waits for `stream`. */
+gsr_status_t gsr_step_tie_export(const gsr_graph_t* g, const gsr_config_t* cfg, const void* workspace, int32_t layer,
+                                 int32_t block, int32_t* rows_out, uint64_t* masks_out, int64_t* count_out, void* stream);
 
 /* ---- the two-group pipeline as the walk-throughs of Sections 4.3 and 4.4 print it ----
  *

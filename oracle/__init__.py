@@ -220,7 +220,8 @@ def step(g: Graph, cfg: Cfg, L: int, X0, W, w_out, b_out, target, variant: int =
     """One training step.  variant 0: inverse interleaved with backward; 1: stored activations;
     2: as 0 with the indices of the forward sweep kept and reused (Section 4.2); 3: as 2 for the
     rows that selected at a near-tie (gs_near_tie with tie_tol) only.
-    Returns dict(loss, yhat, XL, X0rec, dW [L,C,dg,dg], dwout, dbout, dX0, n_listed)."""
+    Returns dict(loss, yhat, XL, X0rec, dW [L,C,dg,dg], dwout, dbout, dX0, n_listed); with "ties" / "I" in want also
+    the near-tie flags [L,C,n] (variant 3) and the indices of the forward sweep [L,C,n,k] (variants 2, 3)."""
     X0 = _f64(X0)
     n, d = X0.shape
     W = _f64(W)
@@ -235,6 +236,8 @@ def step(g: Graph, cfg: Cfg, L: int, X0, W, w_out, b_out, target, variant: int =
         dW=np.zeros((L, cfg.c, cfg.dg, cfg.dg)) if "dW" in want else None,
         dwout=np.zeros(d) if "dwout" in want else None,
         dX0=np.zeros((n, d)) if "dX0" in want else None,
+        ties=np.zeros((L, cfg.c, n), dtype=np.uint8) if "ties" in want else None,
+        I=np.zeros((L, cfg.c, n, cfg.k), dtype=np.int32) if "I" in want else None,
     )
     loss = C.c_double(0.0)
     db = C.c_double(0.0)
@@ -242,7 +245,7 @@ def step(g: Graph, cfg: Cfg, L: int, X0, W, w_out, b_out, target, variant: int =
     rc = lib().orc_step(C.c_int64(n), _p(g.rp), _p(g.ci), _p(g.av), C.c_int(cfg.d), C.c_int(cfg.c),
                         C.c_int(L), C.c_int(cfg.k), C.c_int(cfg.norm), C.c_double(cfg.eps), C.c_int(cfg.sm),
                         _p(X0), _p(W), _p(w_out), C.c_double(b_out), _p(target), C.c_int(variant),
-                        C.c_float(tie_tol), C.byref(n_listed), C.byref(loss), _p(out["yhat"]), _p(out["XL"]), _p(out["X0rec"]), _p(out["dW"]),
+                        C.c_float(tie_tol), C.byref(n_listed), _p(out["ties"]), _p(out["I"]), C.byref(loss), _p(out["yhat"]), _p(out["XL"]), _p(out["X0rec"]), _p(out["dW"]),
                         _p(out["dwout"]), C.byref(db), _p(out["dX0"]))
     if rc != 0:
         raise MemoryError("orc_step failed")

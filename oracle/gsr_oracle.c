@@ -597,13 +597,16 @@ void orc_head(int64_t n, int D, int sm, const double* X, const double* w, double
  * variant 3: as variant 2, but only for the rows that selected at a near-tie (orc_gs_near_tie
  * with tie_tol); every other row selects again during the inverse.  (An implementation keeps
  * the indices of the listed rows only; the oracle keeps all and consults the flags.)
- * n_listed (or NULL): number of listed (row, block, layer) triples of variant 3.
+ * n_listed (or NULL): number of listed (row, block, layer) triples of variant 3; tie_out
+ * (or NULL; variant 3): the flags [L][C][n]; I_out (or NULL; variants 2 and 3): the indices
+ * [L][C][n][k] every block selected in the forward sweep.
  * Outputs (any may be NULL except loss): yhat [n], XL [n*D], X0rec [n*D] (variant 0: the
  * rebuilt input), dW [L*C*dg*dg], dwout [D], dbout [1], dX0 [n*D]. */
 int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
              int D, int C, int L, int k, int norm, double eps, int sm,
              const double* X0, const double* W, const double* wout, double bout,
              const double* target, int variant, float tie_tol, int64_t* n_listed,
+             unsigned char* tie_out, int32_t* I_out,
              double* loss, double* yhat, double* XL, double* X0rec,
              double* dW, double* dwout, double* dbout, double* dX0) {
     int dg = D / C;
@@ -640,6 +643,8 @@ int orc_step(int64_t n, const int64_t* rp, const int32_t* ci, const float* av,
             orc_layer_forward(n, rp, ci, av, D, C, k, norm, eps, sm,
                               W + (int64_t)l * C * dg * dg, X, 0, 0, 0, 0, 0, 0.0f);
     }
+    if (tie_out && tie) memcpy(tie_out, tie, per_layer_T * (size_t)L);
+    if (I_out && saved_I) memcpy(I_out, saved_I, per_layer_I * (size_t)L * sizeof(int32_t));
     if (n_listed) {
         *n_listed = 0;
         if (tie)

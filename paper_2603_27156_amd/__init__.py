@@ -31,7 +31,7 @@ EXPORTED = [
     "gsr_graph_export", "gsr_graph_destroy", "gsr_group_sparse", "gsr_spmm", "gsr_spmm_noalloc",
     "gsr_spmm_compressed_workspace",
     "gsr_spmm_compressed", "gsr_workspace_size", "gsr_layer_forward", "gsr_layer_inverse", "gsr_layer_backward",
-    "gsr_step", "gsr_walkthrough_workspace", "gsr_slot_block", "gsr_alg1_layer_forward", "gsr_alg2_layer_backward",
+    "gsr_step", "gsr_step_tie_stats", "gsr_step_tie_export", "gsr_walkthrough_workspace", "gsr_slot_block", "gsr_alg1_layer_forward", "gsr_alg2_layer_backward",
     "gsr_sgd_update", "gsr_adam_update",
 ]
 
@@ -50,7 +50,7 @@ def gsr_last_error() -> str:
 class gsr_config_t(C.Structure):
     _fields_ = [("n", C.c_int64), ("d", C.c_int32), ("c", C.c_int32), ("l", C.c_int32), ("k", C.c_int32),
                 ("dtype", C.c_int32), ("norm", C.c_int32), ("eps", C.c_float), ("layout", C.c_int32),
-                ("save_indices", C.c_int32)]
+                ("save_indices", C.c_int32), ("tie_tol", C.c_float), ("tie_capacity", C.c_int32)]
 
 
 _lib = None
@@ -101,7 +101,7 @@ def gsr_set_option(key: str, value: int) -> None:
     _check(lib().gsr_set_option(key.encode(), C.c_int64(value)))
 
 
-KERNEL_CLASSES = 9
+KERNEL_CLASSES = 10
 
 
 def gsr_profile_reset() -> None:
@@ -131,6 +131,8 @@ class Config:
     eps: float = 1e-5
     layout: int = GSR_LAYOUT_ROW_MAJOR
     save_indices: int = 0
+    tie_tol: float = 2.0 ** -12
+    tie_capacity: int = 0
 
     @property
     def dg(self) -> int:
@@ -138,7 +140,7 @@ class Config:
 
     def c_struct(self) -> gsr_config_t:
         return gsr_config_t(self.n, self.d, self.c, self.l, self.k, self.dtype, self.norm, self.eps, self.layout,
-                            self.save_indices)
+                            self.save_indices, self.tie_tol, self.tie_capacity)
 
 
 class Graph:
@@ -368,3 +370,23 @@ def gsr_step(g: Graph, cfg: Config, x0, w_all, w_out, b_out, target, loss_out, d
     _check(lib().gsr_step(g.ptr, C.byref(cs), _dp(x0), _dp(w_all), _dp(w_out), _dp(b_out), _dp(target), _dp(loss_out),
                           _dp(yhat_out), _dp(dw_all), _dp(dw_out), _dp(db_out), _dp(dx0_out), _dp(x0_rebuilt_out),
                           _dp(xl_out), _dp(ws), C.c_size_t(nb), _stream()))
+
+
+def gsr_step_tie_stats(g: Graph, cfg: Config, workspace) -> dict:
+    """Counts of the last gsr_step with save_indices == 2 in `workspace`: rows kept, most per block, rows dropped."""
+    a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+    cs = cfg.c_struct()
+    _check(lib().gsr_step_tie_stats(g.ptr, C.byref(cs), _dp(workspace), C.byref(a), C.byref(b), C.byref(c), _stream()))
+    return dict(listed=a.value, max_per_block=b.value, dropped=c.value)
+
+
+def gsr_step_tie_export(g: Graph, cfg: Config, workspace, layer: int, block: int):
+    """(rows int32 [m], masks uint64 [m]) kept by the last save_indices == 2 step for the input of `block` of `layer`."""
+    cap = cfg.tie_capacity if cfg.tie_capacity > 0 else cfg.n // 32 + 1024
+    rows = np.zeros(cap, dtype=np.int32)
+    masks = np.zeros(cap, dtype=np.uint64)
+    cnt = C.c_int64()
+    cs = cfg.c_struct()
+    _check(lib().gsr_step_tie_export(g.ptr, C.byref(cs), _dp(workspace), C.c_int32(layer), C.c_int32(block), _np(rows),
+                                     _np(masks), C.byref(cnt), _stream()))
+    return rows[:cnt.value].copy(), masks[:cnt.value].copy()

@@ -134,6 +134,16 @@ __device__ __forceinline__ float quarter_sum(float v) {
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+__device__ __forceinline__ float quarter_fmax(float v) {
+    const uint32_t u = __float_as_uint(v);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const float s = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    const uint32_t su = __float_as_uint(s);
+    const auto b = __builtin_amdgcn_permlane32_swap(su, su, false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float quarter_fmin(float v) { return -quarter_fmax(-v); }
+
 // ---- GS: exact top-k of a row ----------------------------------------------------------------
 // The Group-Sparse operator of Section 4.1 of the paper keeps, per row, the k largest entries by
 // signed value.  The row's k-th largest value is found by bisection on an order-preserving
@@ -995,6 +1005,35 @@ __device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int
     return msel;
 }
 
+// Rows whose column set is kept because they selected at a near-tie (a selective form of the save of Section 4.2):
+// one segment per application of GS in the forward sweep.  A row is listed iff k < DG and, with v_k the smallest
+// kept and v_(k+1) the largest dropped value, v_k - v_(k+1) <= tol * max|row| in float32 (exact ties always are).
+// The inverse sweep selects again on the rebuilt rows and then gives the listed rows their kept sets back.
+template <int DG>
+struct TieSeg {
+    using M = typename MaskOf<DG>::type;
+    int* count;        // rows listed so far (may run past cap: the excess is not kept); NULL: nothing is listed
+    uint32_t* rows;    // [cap]
+    M* masks;          // [cap]
+    int cap;
+    float tol;
+};
+
+// The factor GS applies to the kept values of a row held in the quarter layout (x: this lane's quarter); the same
+// value in the four lanes of the row.
+template <int DG>
+__device__ __forceinline__ float record_scale(const float (&x)[DG / 4], int norm, float eps) {
+    float scale = 1.f;
+    if (norm == GSR_NORM_RMS) {
+        float ss = 0.f;
+#pragma unroll
+        for (int j = 0; j < DG / 4; ++j) ss += x[j] * x[j];
+        ss = quarter_sum(ss);
+        scale = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + eps);
+    }
+    return scale;
+}
+
 // GS of the 16 rows of an LDS tile and their records (Section 4.1; record layout of Section 4.3).
 // st holds the rows as they read back from memory (16 x (DG+1) floats, rows past the end zero).
 // Lane (r, q) takes the quarter q of row r into registers, so the 16 searches for the k-th largest
@@ -1012,7 +1051,8 @@ __device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int
 // out.mask may be NULL.
 template <int DG, typename T>
 __device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int norm, float eps, const Record<DG, T>& out,
-                                          bool given, int lane, int32_t* idx_out = nullptr, int* ist = nullptr) {
+                                          bool given, int lane, int32_t* idx_out = nullptr, int* ist = nullptr,
+                                          TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}) {
     using M = typename MaskOf<DG>::type;
     constexpr int QW = DG / 4, LR = DG + 1;
     constexpr int KS = sizeof(T) == 2 ? 16 : 0;   // bf16 values: the low 16 key bits are zero
@@ -1037,14 +1077,24 @@ __device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int n
         mask = (M)(all[0] & 0xFFFFu) | (M)(all[1] & 0xFFFFu) << 16 | (M)(all[2] & 0xFFFFu) << 32 | (M)(all[3] & 0xFFFFu) << 48;
     else
         mask = (all[0] & 0xFFu) | (all[1] & 0xFFu) << 8 | (all[2] & 0xFFu) << 16 | (all[3] & 0xFFu) << 24;
-    float scale = 1.f;
-    if (norm == GSR_NORM_RMS) {
-        float ss = 0.f;
+    if (tie.count && !given) {
+        // near-tie test on the row's values: smallest kept, largest dropped, largest magnitude
+        float vk = __builtin_huge_valf(), vr = -__builtin_huge_valf(), am = 0.f;
 #pragma unroll
-        for (int j = 0; j < QW; ++j) ss += x[j] * x[j];
-        ss = quarter_sum(ss);
-        scale = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + eps);
+        for (int j = 0; j < QW; ++j) {
+            const bool bit = (msel >> j) & 1u;
+            vk = bit ? fminf(vk, x[j]) : vk;
+            vr = bit ? vr : fmaxf(vr, x[j]);
+            am = fmaxf(am, fabsf(x[j]));
+        }
+        vk = quarter_fmin(vk); vr = quarter_fmax(vr); am = quarter_fmax(am);
+        const float gap = vk - vr, bar = tie.tol * am;
+        if (q == 0 && r0 + r < n && k < DG && gap <= bar) {
+            const int pos = atomicAdd(tie.count, 1);
+            if (pos < tie.cap) { tie.rows[pos] = (uint32_t)(r0 + r); tie.masks[pos] = mask; }
+        }
     }
+    const float scale = record_scale<DG>(x, norm, eps);
     wave_sync();   // every lane holds its quarter: the tile can be reused for the compacted values
 #pragma unroll
     for (int j = 0; j < QW; ++j) {

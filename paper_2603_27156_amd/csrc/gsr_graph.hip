@@ -271,10 +271,25 @@ StepWs carve_step(const gsr_config_t* cfg, const gsr_graph_t* g) {
     w.layer = off;
     off += carve_layer(cfg, g).total;
     w.masks = off;
-    if (cfg->save_indices)
-        off += align_up(((size_t)(cfg->l > 0 ? cfg->l : 0) + 1) * (size_t)cfg->c * n * (size_t)(cfg->d / cfg->c / 8));
+    const size_t segs = ((size_t)(cfg->l > 0 ? cfg->l : 0) + 1) * (size_t)cfg->c;
+    if (cfg->save_indices == 1) off += align_up(segs * n * (size_t)(cfg->d / cfg->c / 8));
+    w.tie_counts = w.tie_rows = w.tie_masks = off;
+    w.tie_cap = 0;
+    if (cfg->save_indices == 2) {
+        w.tie_cap = tie_capacity(cfg);
+        off += align_up(segs * sizeof(int));
+        w.tie_rows = off;
+        off += align_up(segs * (size_t)w.tie_cap * sizeof(uint32_t));
+        w.tie_masks = off;
+        off += align_up(segs * (size_t)w.tie_cap * (size_t)(cfg->d / cfg->c / 8));
+    }
     w.total = off;
     return w;
+}
+
+int64_t tie_capacity(const gsr_config_t* cfg) {
+    if (cfg->tie_capacity > 0) return cfg->tie_capacity;
+    return cfg->n / 32 + 1024;
 }
 
 gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool need_l) {
@@ -294,7 +309,9 @@ gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool
         return fail(GSR_ERR_UNSUPPORTED, "n * k = %llu does not fit 32-bit record offsets", (unsigned long long)cfg->n * cfg->k);
     if (need_l && cfg->l < 1) return fail(GSR_ERR_INVALID_ARG, "layers L=%d", cfg->l);
     if (!(cfg->eps >= 0.f)) return fail(GSR_ERR_INVALID_ARG, "eps must be >= 0");
-    if (cfg->save_indices != 0 && cfg->save_indices != 1) return fail(GSR_ERR_INVALID_ARG, "save_indices must be 0 or 1");
+    if (cfg->save_indices < 0 || cfg->save_indices > 2) return fail(GSR_ERR_INVALID_ARG, "save_indices must be 0, 1 or 2");
+    if (cfg->save_indices == 2 && (!(cfg->tie_tol >= 0.f) || cfg->tie_capacity < 0))
+        return fail(GSR_ERR_INVALID_ARG, "tie_tol and tie_capacity must be >= 0");
     return GSR_OK;
 }
 
@@ -344,7 +361,7 @@ gsr_status_t gsr_profile_reset(void) {
 
 const char* gsr_profile_class_name(int32_t kernel_class) {
     static const char* names[KC_COUNT] = {"block_forward", "block_inverse", "block_backward", "grad", "group_sum",
-                                          "hub_first_pass", "dw_reduce", "head", "layout_copy"};
+                                          "hub_first_pass", "dw_reduce", "head", "layout_copy", "tie_fixup"};
     return (kernel_class >= 0 && kernel_class < KC_COUNT) ? names[kernel_class] : "";
 }
 

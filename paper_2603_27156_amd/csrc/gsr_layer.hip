@@ -16,6 +16,7 @@
 #include "gsr_device.h"
 
 #include <algorithm>
+#include <vector>
 
 namespace gsr {
 
@@ -50,6 +51,7 @@ struct BlockArgs {
     float* dw_partial;      // [gridDim.x][DG*DG]              (WITH_DW)
     int* draws;             // tile counters of the dynamic sweep and the sign-off counter (not WITH_DW)
     int* draws_done;
+    TieSeg<DG> tie;         // where rows that select at a near-tie are listed (count == NULL: nowhere)
 };
 
 template <int DG, typename T, int SIGN, bool WITH_DW, bool DEAL>
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         }
         if (a.out.mask) {
             wave_sync();
-            emit_tile<DG, T>(st_h, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane);
+            emit_tile<DG, T>(st_h, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane, nullptr, nullptr, a.tie);
         }
         if (DEAL && deal.on) {
             deal.at += deal.waves;
@@ -394,7 +396,49 @@ struct SumArgs {
     float eps;
     Record<DG, T> out;
     bool out_given;         // out.mask holds the column sets to use
+    TieSeg<DG> tie;         // where rows that select at a near-tie are listed (count == NULL: nowhere)
 };
+
+// The records of listed rows, written again with the column sets kept from the forward sweep: a wave takes sixteen
+// list entries in the quarter layout of emit_tile (lane = (entry, quarter of the row)) and forms the values exactly
+// as emit_tile does when the set is given.  plane: the rows the record was just taken from, row stride ld.
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_tie_fixup(TieSeg<DG> tie, const T* __restrict__ plane, int64_t ld, int k, int norm,
+                                                   float eps, Record<DG, T> out) {
+    using M = typename MaskOf<DG>::type;
+    constexpr int QW = DG / 4;
+    const int lane = lane_id(), r = lane & 15, q = lane >> 4;
+    const int listed = *tie.count, cnt = listed < tie.cap ? listed : tie.cap;
+    const int wave = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6), nwaves = (int)((gridDim.x * blockDim.x) >> 6);
+    for (int e0 = wave * 16; e0 < cnt; e0 += nwaves * 16) {
+        const bool ok = e0 + r < cnt;
+        const int e = ok ? e0 + r : cnt - 1;
+        const size_t row = tie.rows[e];
+        const M m = tie.masks[e];
+        float x[QW];
+#pragma unroll
+        for (int j = 0; j < QW; ++j) x[j] = to_float(plane[row * ld + q * QW + j]);
+        const uint32_t msel = (uint32_t)(m >> (QW * q)) & ((1u << QW) - 1u);
+        uint32_t all[4];
+        quarter_all((uint32_t)__popc(msel), all);
+        size_t slot = row * k;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) slot += i < q ? all[i] : 0u;
+        const float scale = record_scale<DG>(x, norm, eps);
+#pragma unroll
+        for (int j = 0; j < QW; ++j) {
+            const bool bit = (msel >> j) & 1u;
+            if (ok && bit) out.vals[slot] = from_float<T>(x[j] * scale);
+            slot += bit ? 1 : 0;
+        }
+        if (ok && q == 0) out.mask[row] = m;
+    }
+}
+
+__global__ void k_zero_ints(int* p, int count) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0;
+}
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
@@ -435,7 +479,7 @@ __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
             for (int cb = 0; cb < CPL; ++cb) st[rr * LR + CPL * tj + cb] = ok ? y[reg][cb] : 0.f;
         }
         wave_sync();
-        emit_tile<DG, T>(st, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane);
+        emit_tile<DG, T>(st, r0, a.n, a.k, a.norm, a.eps, a.out, a.out_given, lane, nullptr, nullptr, a.tie);
     }
 }
 
@@ -562,6 +606,16 @@ struct Ctx {
     LayerWs lw;
     int tiles;
     M* saved;       // [L+1][C][n] column masks kept from the forward sweep, or NULL
+    // rows kept because they selected at a near-tie (cfg->save_indices == 2), per segment (layer, slot), or NULL
+    int* tie_counts;
+    uint32_t* tie_rows;
+    M* tie_masks;
+    int tie_cap;
+    TieSeg<DG> tie_seg(int layer, int slot) const {
+        if (!tie_counts || layer < 0) return TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f};
+        const size_t seg = (size_t)layer * cfg->c + slot;
+        return TieSeg<DG>{tie_counts + seg, tie_rows + seg * tie_cap, tie_masks + seg * tie_cap, tie_cap, cfg->tie_tol};
+    }
     // Record slot `slot` of layer `layer`: the values always live in the slot (they are rebuilt),
     // the mask in the slot, or in the kept store when indices are saved.
     Record<DG, T> rec(int slot, int layer = 0) const {
@@ -594,8 +648,10 @@ static unsigned persistent_grid(const gsr_graph_t* g, int per_cu) {
 
 template <int DG, typename T>
 static void launch_sum(const Ctx<DG, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0,
-                       const Record<DG, T>& out, bool out_given = false) {
+                       const Record<DG, T>& out, bool out_given = false,
+                       TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}) {
     SumArgs<DG, T> a;
+    a.tie = tie;
     a.n = (int)x.cfg->n; a.src = src; a.ld = ld; a.src_gs = gs; a.nsrc = nsrc; a.y0 = y0;
     a.k = x.cfg->k; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.out = out; a.out_given = out_given;
@@ -642,9 +698,11 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
 // mode 0: forward (+), 1: inverse (-), 2: inverse (-) with dW
 template <int DG, typename T>
 static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>& in, const float* w, T* plane, int64_t ld,
-                             const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg, bool first_pass_done = false) {
+                             const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg, bool first_pass_done = false,
+                             TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}) {
     if (!first_pass_done) launch_hub_records<DG, T>(x, in);
     BlockArgs<DG, T> a;
+    a.tie = tie;
     a.g = make_view(x.g, false);
     a.n = (int)x.cfg->n; a.tiles = x.tiles;
     a.in = in; a.k = x.cfg->k;
@@ -696,16 +754,28 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     else hipLaunchKernelGGL((k_grad<DG, T, false>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
 }
 
+// After a record was taken again from rebuilt rows during the inverse sweep: the rows listed for that application of
+// GS in the forward sweep get their kept column sets back (values from the same rebuilt rows).
+template <int DG, typename T>
+static void launch_tie_fixup(const Ctx<DG, T>& x, const TieSeg<DG>& tie, const T* plane, int64_t ld, const Record<DG, T>& out) {
+    if (!tie.count) return;
+    ProfScope prof(KC_TIE, x.s);
+    const unsigned blocks = (unsigned)std::min((tie.cap + 63) / 64, 1024);
+    hipLaunchKernelGGL((k_tie_fixup<DG, T>), dim3(blocks), dim3(256), 0, x.s, tie, plane, ld, x.cfg->k, x.cfg->norm, x.cfg->eps, out);
+}
+
 // eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of the
 // previous layer's Y_2, emitted when that plane was written).  `layer`: index of the layer inside
 // a step (selects the kept masks when indices are saved; 0 otherwise).
 template <int DG, typename T>
 static void layer_forward_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& p, bool slot0_ready, int layer = 0) {
     const int C = x.cfg->c;
-    if (!slot0_ready) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, x.rec(0, layer));
+    if (!slot0_ready) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, x.rec(0, layer), false, x.tie_seg(layer, 0));
     for (int i = 1; i <= C; ++i) {
         const Record<DG, T> out = i < C ? x.rec(i, layer) : (C == 2 ? x.rec(0, layer + 1) : x.rec(-1));
-        launch_block<DG, T>(x, 0, x.rec(i - 1, layer), w + (size_t)(i - 1) * DG * DG, p.grp(i - 1), p.ld, out, false, nullptr, 0);
+        const TieSeg<DG> tie = i < C ? x.tie_seg(layer, i) : (C == 2 ? x.tie_seg(layer + 1, 0) : x.tie_seg(-1, 0));
+        launch_block<DG, T>(x, 0, x.rec(i - 1, layer), w + (size_t)(i - 1) * DG * DG, p.grp(i - 1), p.ld, out, false, nullptr, 0,
+                            false, out.mask ? tie : TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f});
     }
 }
 
@@ -742,17 +812,24 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         else if (C == 2) { z = y.grp(1); ldz = y.ld; }      // Y_0 = X_2, rebuilt just before
         else {
             launch_sum<DG, T>(x, y.grp(1), y.ld, y.gs, C - 1, x.y0(), x.rec(0, layer), given);
+            launch_tie_fixup<DG, T>(x, x.tie_seg(layer, 0), x.y0(), DG, x.rec(0, layer));
             z = x.y0(); ldz = DG;
         }
         Record<DG, T> out = x.rec(-1);
+        TieSeg<DG> out_tie = x.tie_seg(-1, 0);       // the segment that listed rows of `out` in the forward sweep
         if (i < C) {
-            if (!(in_step && layer == 0)) out = x.rec(i, given ? layer - 1 : 0);      // record of Y_i of the layer below
+            if (!(in_step && layer == 0)) {
+                out = x.rec(i, given ? layer - 1 : 0);                                 // record of Y_i of the layer below
+                if (in_step) out_tie = x.tie_seg(layer - 1, i);
+            }
         } else if (C == 2) {
             out = x.rec(0, layer);                                                     // X_2 = Y_0 of this layer
+            if (in_step) out_tie = x.tie_seg(layer, 0);
         }
         launch_hub_both<DG, T>(x, x.rec(i - 1, layer), dy.grp(i - 1), dy.ld);
         const unsigned nparts =
             launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld, true);
+        if (out.mask) launch_tie_fixup<DG, T>(x, out_tie, y.grp(i - 1), y.ld, out);
         // dW_i is summed from the partials by the first job of the gradient kernel that follows, unless that kernel
         // has so few tiles per wave that it could not make up for the late start of those workgroups (measured on
         // a 49,600-node graph with 3,100 tiles: +80 us on a 405 us kernel): then by a launch of its own
@@ -775,6 +852,7 @@ static Ctx<DG, T> make_ctx(const gsr_graph_t* g, const gsr_config_t* cfg, void* 
     x.g = g; x.cfg = cfg; x.s = s; x.ws = (char*)ws; x.lw = carve_layer(cfg, g);
     x.tiles = (int)((cfg->n + 15) / 16);
     x.saved = nullptr;
+    x.tie_counts = nullptr; x.tie_rows = nullptr; x.tie_masks = nullptr; x.tie_cap = 0;
     return x;
 }
 
@@ -823,8 +901,16 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
     const StepWs sw = carve_step(cfg, g);
     char* base = (char*)ws;
     Ctx<DG, T> x = make_ctx<DG, T>(g, cfg, base + sw.layer, s);
-    if (cfg->save_indices) x.saved = (typename MaskOf<DG>::type*)(base + sw.masks);
+    if (cfg->save_indices == 1) x.saved = (typename MaskOf<DG>::type*)(base + sw.masks);
     const int C = cfg->c, L = cfg->l;
+    if (cfg->save_indices == 2) {
+        x.tie_counts = (int*)(base + sw.tie_counts);
+        x.tie_rows = (uint32_t*)(base + sw.tie_rows);
+        x.tie_masks = (typename MaskOf<DG>::type*)(base + sw.tie_masks);
+        x.tie_cap = (int)sw.tie_cap;
+        const int segs = (L + 1) * C;
+        hipLaunchKernelGGL(k_zero_ints, dim3((segs + 255) / 256), dim3(256), 0, s, x.tie_counts, segs);
+    }
     const int64_t n = cfg->n;
     const Planes<T> act{(T*)(base + sw.act), (int64_t)DG, n * DG};
     const Planes<T> grad{(T*)(base + sw.grad), (int64_t)DG, n * DG};
@@ -901,6 +987,55 @@ gsr_status_t gsr_step(const gsr_graph_t* g, const gsr_config_t* cfg, const void*
     if (dg == 32) GSR_STEP(32, bf16_t);
     GSR_STEP(64, bf16_t);
 #undef GSR_STEP
+}
+
+gsr_status_t gsr_step_tie_stats(const gsr_graph_t* g, const gsr_config_t* cfg, const void* workspace, int64_t* listed,
+                                int64_t* max_per_block, int64_t* dropped, void* stream) {
+    GSR_TRY(validate_config(cfg, g, true));
+    if (!workspace) return fail(GSR_ERR_INVALID_ARG, "null pointer");
+    if (cfg->save_indices != 2) return fail(GSR_ERR_INVALID_ARG, "cfg->save_indices is not 2: nothing was listed");
+    const StepWs sw = carve_step(cfg, g);
+    const int segs = cfg->l * cfg->c;      // (the set listed for a layer above the last is never used)
+    std::vector<int> counts((size_t)segs);
+    GSR_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    GSR_HIP_CHECK(hipMemcpy(counts.data(), (const char*)workspace + sw.tie_counts, (size_t)segs * sizeof(int), hipMemcpyDeviceToHost));
+    int64_t total = 0, most = 0, lost = 0;
+    for (int c : counts) {
+        total += std::min<int64_t>(c, sw.tie_cap);
+        most = std::max<int64_t>(most, c);
+        lost += std::max<int64_t>(0, c - sw.tie_cap);
+    }
+    if (listed) *listed = total;
+    if (max_per_block) *max_per_block = most;
+    if (dropped) *dropped = lost;
+    return GSR_OK;
+}
+
+gsr_status_t gsr_step_tie_export(const gsr_graph_t* g, const gsr_config_t* cfg, const void* workspace, int32_t layer,
+                                 int32_t block, int32_t* rows_out, uint64_t* masks_out, int64_t* count_out, void* stream) {
+    GSR_TRY(validate_config(cfg, g, true));
+    if (!workspace || !rows_out || !masks_out || !count_out) return fail(GSR_ERR_INVALID_ARG, "null pointer");
+    if (cfg->save_indices != 2) return fail(GSR_ERR_INVALID_ARG, "cfg->save_indices is not 2: nothing was listed");
+    if (layer < 0 || layer >= cfg->l || block < 1 || block > cfg->c) return fail(GSR_ERR_INVALID_ARG, "layer %d / block %d out of range", layer, block);
+    const StepWs sw = carve_step(cfg, g);
+    const size_t seg = (size_t)layer * cfg->c + (block - 1);
+    const char* base = (const char*)workspace;
+    GSR_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+    int cnt = 0;
+    GSR_HIP_CHECK(hipMemcpy(&cnt, base + sw.tie_counts + seg * sizeof(int), sizeof(int), hipMemcpyDeviceToHost));
+    const int64_t take = std::min<int64_t>(cnt, sw.tie_cap);
+    *count_out = take;
+    if (take == 0) return GSR_OK;
+    GSR_HIP_CHECK(hipMemcpy(rows_out, base + sw.tie_rows + seg * sw.tie_cap * sizeof(uint32_t), (size_t)take * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    const int dg = cfg->d / cfg->c;
+    if (dg == 64) {
+        GSR_HIP_CHECK(hipMemcpy(masks_out, base + sw.tie_masks + seg * sw.tie_cap * 8, (size_t)take * 8, hipMemcpyDeviceToHost));
+    } else {
+        std::vector<uint32_t> m32((size_t)take);
+        GSR_HIP_CHECK(hipMemcpy(m32.data(), base + sw.tie_masks + seg * sw.tie_cap * 4, (size_t)take * 4, hipMemcpyDeviceToHost));
+        for (int64_t i = 0; i < take; ++i) masks_out[i] = m32[(size_t)i];
+    }
+    return GSR_OK;
 }
 
 }  // extern "C"

@@ -100,10 +100,12 @@ def test_step_against_oracle(name, layout):
     assert_close("X0 rebuilt vs X0", out["X0rec"], c.x0_on_grid(), rtol=1e-4, atol=1e-4)
 
 
-def run_step(c: Case, l=None, raw=False, save_indices=0):
+def run_step(c: Case, l=None, raw=False, save_indices=0, keep=None, **over):
+    """One gsr_step on the case's inputs.  over: further fields of the configuration; keep (a dict, or None)
+    receives the configuration and the workspace, for the calls that read a step's workspace afterwards."""
     w = c.w
     L = w.l if l is None else l
-    cfg = gsr.Config(**{**c.gcfg.__dict__, "l": L, "save_indices": save_indices})
+    cfg = gsr.Config(**{**c.gcfg.__dict__, "l": L, "save_indices": save_indices, **over})
     dv = c.dev
     f32 = dict(dtype=torch.float32, device=dv)
     x0 = c.to_dev(c.inp.x0)
@@ -116,9 +118,12 @@ def run_step(c: Case, l=None, raw=False, save_indices=0):
     dW = torch.empty_like(W)
     dwout = torch.empty(w.d, **f32)
     dx0, x0r, xl = torch.empty_like(x0), torch.empty_like(x0), torch.empty_like(x0)
+    ws = torch.empty(gsr.gsr_workspace_size(c.gg, cfg)[1], dtype=torch.uint8, device=dv)
     gsr.gsr_step(c.gg, cfg, x0, W, w_out, b_out, target, loss, dW, dwout, db, yhat_out=yhat, dx0_out=dx0,
-                 x0_rebuilt_out=x0r, xl_out=xl)
+                 x0_rebuilt_out=x0r, xl_out=xl, workspace=ws)
     torch.cuda.synchronize()
+    if keep is not None:
+        keep["cfg"], keep["ws"] = cfg, ws
     if raw:
         return dict(loss=loss, yhat=yhat, XL=xl, X0rec=x0r, dW=dW, dwout=dwout, dbout=db, dX0=dx0)
     return dict(loss=float(loss.item()), yhat=yhat.cpu().numpy(), XL=c.to_host(xl), X0rec=c.to_host(x0r),
