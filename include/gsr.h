@@ -12,8 +12,9 @@
  * Conventions
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are
  *     ordinary host memory.  The library never frees or reallocates caller memory.
- *   - gsr_graph_create / gsr_graph_destroy own the device memory of the graph they build.
- *     No other call allocates device memory; scratch comes from the caller's `workspace`.
+ *   - gsr_graph_create / gsr_graph_destroy own the device memory of the graph they build (the CSR, its split
+ *     plan, tile counters, and the scratch of gsr_spmm and gsr_graph_normalize).  No other call allocates device
+ *     memory; scratch comes from the caller's `workspace`.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default stream)
  *     and is asynchronous unless stated.  Calls on one graph / workspace must be ordered:
  *     a graph holds the tile counters its kernels draw work from and the first-pass sums of
@@ -70,10 +71,14 @@ typedef enum gsr_adj_norm { GSR_ADJ_UNIT = 0, GSR_ADJ_GCN_SYM = 1 } gsr_adj_norm
 
 typedef struct gsr_graph gsr_graph_t; /* opaque */
 
+/* Limits of this build (anything beyond is refused with GSR_ERR_UNSUPPORTED, never computed wrongly):
+ *   N < 2^31 nodes; fewer than 2^31 stored entries after symmetrisation and self-loops (device row pointers are
+ *   32-bit; the input row pointers may be 64-bit);  N * k < 2^32 (32-bit offsets into the compressed values);
+ *   2 <= C <= 8;  D/C in {32, 64};  gsr_step: D <= 512 (the scalar head). */
 typedef struct gsr_config {
     int64_t n;      /* nodes N */
     int32_t d;      /* feature width D */
-    int32_t c;      /* groups C (>= 2); D/C must be 32 or 64 */
+    int32_t c;      /* groups C (2..8); D/C must be 32 or 64 */
     int32_t l;      /* layers L (gsr_step only) */
     int32_t k;      /* retained elements per row per group, 1 <= k <= D/C */
     int32_t dtype;  /* gsr_dtype_t */
@@ -136,7 +141,8 @@ gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const v
                               const int32_t* colidx, const float* vals, uint32_t flags, void* stream);
 
 /* Recompute the stored values on the device: all ones, or the GCN symmetric normalisation of
- * the stored pattern as defined above.  Asynchronous on `stream`. */
+ * the stored pattern as defined above.  Asynchronous on `stream`: only launches kernels (d^-1/2 passes through a
+ * buffer the graph owns, so two such calls on one graph must not overlap). */
 gsr_status_t gsr_graph_normalize(gsr_graph_t* g, int32_t mode /* gsr_adj_norm_t */, void* stream);
 
 /* Sizes of the stored matrix.  Any output pointer may be NULL.  n_hub_rows = rows whose

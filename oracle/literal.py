@@ -8,8 +8,9 @@ follow the other placement, every neighbour at its own column: oracle.aggregate)
 in this pipeline: Algorithm 1 writes GSR-Forward(V, I, G).
 
 Pinned by the printed numbers of Sections 4.1, 4.3 and 4.4 (tests/golden/).  The two matrices that end the
-Section 4.4 walk-through follow no consistent rule, so what alg2_layer_backward RETURNS is parity unpinned;
-its intermediate steps are pinned.
+Section 4.4 walk-through follow no consistent rule, so no printed number pins what alg2_layer_backward RETURNS;
+its intermediate steps are pinned by the printed ones, and the returned planes by dense algebra over A^T and
+the adjoint identity of the backward block on a directed graph.
 """
 from __future__ import annotations
 

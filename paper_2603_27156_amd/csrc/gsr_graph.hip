@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <new>
 #include <numeric>
 #include <vector>
 
@@ -365,8 +366,26 @@ const char* gsr_profile_class_name(int32_t kernel_class) {
     return (kernel_class >= 0 && kernel_class < KC_COUNT) ? names[kernel_class] : "";
 }
 
+static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz, const void* rowptr,
+                                      const int32_t* colidx, const float* vals, uint32_t flags, void* stream);
+
 gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const void* rowptr,
                               const int32_t* colidx, const float* vals, uint32_t flags, void* stream) {
+    // the host-side preprocessing holds several arrays of nnz entries: running out of host memory is a status,
+    // not an exception across the C boundary
+    try {
+        return graph_create_impl(out, n, nnz, rowptr, colidx, vals, flags, stream);
+    } catch (const std::bad_alloc&) {
+        if (out) *out = nullptr;
+        return fail(GSR_ERR_INVALID_ARG, "out of host memory while preprocessing %lld rows / %lld entries", (long long)n, (long long)nnz);
+    } catch (...) {
+        if (out) *out = nullptr;
+        return fail(GSR_ERR_INVALID_ARG, "unexpected failure while preprocessing the graph");
+    }
+}
+
+static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz, const void* rowptr,
+                                      const int32_t* colidx, const float* vals, uint32_t flags, void* stream) {
     if (!out) return fail(GSR_ERR_INVALID_ARG, "out is null");
     *out = nullptr;
     if (n < 0 || nnz < 0) return fail(GSR_ERR_INVALID_ARG, "negative size");
@@ -470,6 +489,7 @@ gsr_status_t gsr_graph_create(gsr_graph_t** out, int64_t n, int64_t nnz, const v
         const size_t chunks = (size_t)std::max(std::max(g->a.hub.n_chunks, g->at.hub.n_chunks), 1);
         e = hipMalloc((void**)&g->scratch, chunks * 64 * sizeof(float));
         const size_t draw_bytes = ((size_t)kTileCounters + 9 * 32) * sizeof(int);
+        if (e == hipSuccess) e = hipMalloc((void**)&g->dinv, std::max<size_t>((size_t)n, 1) * sizeof(float));
         if (e == hipSuccess) e = hipMalloc((void**)&g->draws, draw_bytes);
         if (e == hipSuccess) e = hipMemset(g->draws, 0, draw_bytes);
         if (e != hipSuccess) st = fail(GSR_ERR_HIP, "hipMalloc: %s", hipGetErrorString(e));
@@ -490,13 +510,9 @@ gsr_status_t gsr_graph_normalize(gsr_graph_t* g, int32_t mode, void* stream) {
     if (mode == GSR_ADJ_GCN_SYM && !g->symmetric)
         return fail(GSR_ERR_UNSUPPORTED, "symmetric GCN normalisation needs a symmetric stored pattern");
     hipStream_t s = (hipStream_t)stream;
-    float* dinv = nullptr;
-    GSR_HIP_CHECK(hipMalloc((void**)&dinv, std::max<size_t>((size_t)g->n, 1) * sizeof(float)));
-    gsr_status_t st = normalise_csr(g->a, g->n, g->nnz, mode, s, dinv);
-    if (st == GSR_OK && !g->symmetric) st = normalise_csr(g->at, g->n, g->nnz, mode, s, dinv);
-    hipError_t e = hipStreamSynchronize(s);
-    (void)hipFree(dinv);
-    if (st == GSR_OK && e != hipSuccess) st = fail(GSR_ERR_HIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
+    // d^-1/2 goes through a buffer the graph owns: nothing is allocated here and the call only launches kernels
+    gsr_status_t st = normalise_csr(g->a, g->n, g->nnz, mode, s, g->dinv);
+    if (st == GSR_OK && !g->symmetric) st = normalise_csr(g->at, g->n, g->nnz, mode, s, g->dinv);
     return st;
 }
 
@@ -528,6 +544,7 @@ gsr_status_t gsr_graph_destroy(gsr_graph_t* g) {
     free_csr(g->a);
     if (g->scratch) (void)hipFree(g->scratch);
     if (g->draws) (void)hipFree(g->draws);
+    if (g->dinv) (void)hipFree(g->dinv);
     delete g;
     return GSR_OK;
 }

@@ -101,6 +101,7 @@ struct gsr_graph {
     int num_cus = 256;
     int grid = 512;          // workgroups of the persistent row-tile kernels (multiple of 8)
     int* draws = nullptr;     // device: tile counters of the dynamic sweeps + their sign-off counter (see tile_draws)
+    float* dinv = nullptr;    // device [n]: d^-1/2 while the values are being normalised
     float* scratch = nullptr; // device [max(chunks of A, chunks of A^T, 1)][64]: first-pass sums of split rows for gsr_spmm
 };
 

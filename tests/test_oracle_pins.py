@@ -110,6 +110,33 @@ def test_sec44_steps_of_algorithm_2():
     assert np.allclose(im["M2"], literal.scatter(c["VALA"], c["IDXA"].astype(np.int32), 2) - c["OUTB"], atol=1e-2)
 
 
+def test_algorithm_2_returns_the_backward_blocks_of_its_pinned_steps():
+    """What alg2_layer_backward returns (Algorithm 2, last step of the loop body): the printed final matrices of
+    Section 4.4 follow no rule, so the composition is pinned by what the mathematics fixes instead.  On a directed
+    weighted graph each returned plane must be the Section 4.1 backward block of the (pinned) intermediate it
+    belongs to, written out with dense loops over A^T, and must satisfy the adjoint identity of that block."""
+    from oracle import literal
+    g, A = directed_weighted_graph(30, seed=17)
+    rng = np.random.default_rng(18)
+    n, dg, k = A.shape[0], 12, 4
+    G1, G2 = rng.standard_normal((n, dg)), rng.standard_normal((n, dg))
+    g1, g2, im = literal.alg2_layer_backward(g, G1, G2, k)
+    for got, M, I in ((g1, im["M1"], im["I1"]), (g2, im["M2"], im["I2"])):
+        want = np.zeros((n, dg))
+        for i in range(n):
+            for t in range(k):
+                want[i, I[i, t]] = sum(A[j, i] * M[j, I[j, t]] for j in range(n))      # sum over G^T, slot by slot
+        assert np.allclose(got, want, atol=1e-12)
+        assert np.count_nonzero(got) <= n * k
+        V = rng.standard_normal((n, k))
+        lhs = np.sum(literal.slot_block(g, V, I, dg) * literal.scatter(M[np.arange(n)[:, None], I], I, dg))
+        rhs = np.sum(V * got[np.arange(n)[:, None], I])
+        assert abs(lhs - rhs) < 1e-10 * max(1.0, abs(lhs))
+    # the intermediates it was fed are the ones the printed steps pin (M1 = G1 - block(GS(G2)), ...)
+    assert np.allclose(im["M1"], G1 - literal.slot_block(g, im["V2"], im["I2"], dg))
+    assert np.allclose(im["M2"], literal.scatter(im["V2"], im["I2"], dg) - literal.slot_block(g, im["V1"], im["I1"], dg))
+
+
 def test_slot_block_against_dense_algebra_and_its_adjoint():
     """out[i, I[i,t]] = (A V)[i,t] written with dense matrices; block_backward is the adjoint of the map
     V -> slot_block(V, I) followed by the same placement (non-symmetric A: G and G^T differ)."""
