@@ -4,20 +4,22 @@ benchmark times (persistent grids over all compute units, hub rows split in two 
 The top-k selection of GS is a discontinuous function of its input: where the k-th and (k+1)-th
 largest entries of a row differ by less than the rounding difference between float32 accumulation
 (GPU) and float64 accumulation rounded to float32 (oracle), the two sides may keep different
-columns, and both selections are valid.  Such a row changes the rows that aggregate it.  The tests
-therefore compare every element at the float32 bar outside the rows such a flip can reach
-(a flip needs a deviation of at least half the row's top-k gap), and bound how many rows lie
-inside."""
+columns, and both selections are valid.  No test here allows a share of rows to be wrong.  Layers are compared
+teacher-forced (the oracle is fed the GPU's own layer input, at the first, a middle and the last layer of the
+stack): in the forward every row outside the bar must be reachable from a provable near-tie
+(gpu_util.audit_layer_forward); in the backward the oracle is handed the GPU's selection for the rows that provably
+sit at a near-tie and then every element must agree (gpu_util.audit_layer_backward).  The step itself is the chain
+of those layer calls, bit for bit."""
 import time
 
 import numpy as np
 import pytest
-import scipy.sparse as sp
 
 import oracle
 import paper_2603_27156_amd as gsr
 from paper_2603_27156_amd import synth
-from gpu_util import Case, violations, rel_norm, BF16_REL
+from gpu_util import (Case, violations, rel_norm, BF16_REL, audit_layer_forward, audit_layer_backward, f32_bar,
+                      bf16_bar)
 from test_gpu_layer import run_step
 
 pytestmark = pytest.mark.gpu
@@ -25,6 +27,7 @@ torch = pytest.importorskip("torch")
 
 PLANAR = gsr.GSR_LAYOUT_GROUP_PLANAR
 _cases = {}
+_chains = {}
 
 
 def case(name) -> Case:
@@ -41,201 +44,91 @@ def case(name) -> Case:
     return _cases[name]
 
 
-def adjacency(c: Case):
-    n = c.w.n
-    return sp.csr_matrix((np.ones(len(c.og.ci), dtype=np.int32), c.og.ci, c.og.rp), shape=(n, n))
+def head_gradient(c: Case, yhat):
+    """dX^L of the scalar head + mean squared error from the step's own yhat, in float32 as the head kernel forms it."""
+    yh = yhat.cpu().numpy().astype(np.float32)
+    gy = (np.float32(2.0) * (yh - c.inp.target) / np.float32(c.w.n)).astype(np.float32)
+    return (gy[:, None] * c.inp.w_out[None, :]).astype(np.float32)
 
 
-def row_gap(z, k):
-    """Gap between the k-th and (k+1)-th largest entry of every row."""
-    if k >= z.shape[1]:
-        return np.full(z.shape[0], np.inf)
-    s = -np.sort(-z, axis=1)
-    return s[:, k - 1] - s[:, k]
-
-
-def audit_layer_forward(c: Case, X, Y, Y_ref, tag):
-    """Element-wise comparison of a layer output with the oracle's, group by group.
-
-    Group i is X_i + f_i(Y_{i-1}).  A row of Y_{i-1} can select different columns on the two
-    sides only if its two versions differ by at least half its top-k gap; a row of group i can
-    leave the tolerance only if it aggregates such a row, or a row of group i-1 that already left
-    it.  Every other row must agree at the float32 bar.  Returns the fraction of rows outside the
-    tolerance; asserts that each of them is explained."""
+def gpu_chain(name, L, capture):
+    """The GPU's own activations and gradients through L layers, by layer calls: forward chain from X0, the head's
+    gradient, backward chain (each layer rebuilding its input).  Returns, for every layer l in `capture`,
+    X[l] (the layer's input in the forward chain) and (Y[l], dY[l]) (what the backward call of layer l was given),
+    as float32 host arrays, the device tensors of the rebuilt X0 / dX0 / dW, and the outputs of gsr_step on the same
+    inputs with nothing kept ("step"), whose yhat seeds the backward chain."""
+    key = (name, L, tuple(capture))
+    if key in _chains:
+        return _chains[key]
+    c = case(name)
     w = c.w
-    dg, C = w.dg, w.c
-    A = adjacency(c)
-    if C > 2:
-        # Y_0 as the kernel forms it (float32, planes added in order) and as the oracle does
-        z_gpu = X[:, dg:2 * dg].astype(np.float32)
-        for j in range(2, C):
-            z_gpu = z_gpu + X[:, j * dg:(j + 1) * dg].astype(np.float32)
-        z_gpu = z_gpu.astype(np.float64)
-        z_ref = oracle.round_store(X[:, dg:].reshape(w.n, C - 1, dg).sum(axis=1), c.ocfg.sm)
-    else:
-        z_gpu = z_ref = X[:, dg:2 * dg]
-    prev_bad = np.zeros(w.n, dtype=bool)
-    total_bad = np.zeros(w.n, dtype=bool)
-    for i in range(C):
-        dev = np.abs(z_gpu - z_ref).max(axis=1)
-        may_flip = row_gap(z_ref, w.k) <= 2.0 * dev + 1e-30 * (dev > 0)
-        may_flip &= dev > 0
-        allowed = (A @ (may_flip | prev_bad).astype(np.int32)) > 0
-        sl = slice(i * dg, (i + 1) * dg)
-        bad, worst = violations(Y[:, sl], Y_ref[:, sl])
-        rows = bad.any(axis=1)
-        print(f"[{tag}] group {i}: rows that may flip {int(may_flip.sum())}, reachable {int(allowed.sum())}, "
-              f"outside tolerance {int(rows.sum())}, unexplained {int((rows & ~allowed).sum())}", flush=True)
-        assert not (rows & ~allowed).any(), f"group {i}: rows outside tolerance that no flipped selection explains"
-        assert allowed.mean() < 2e-2
-        prev_bad = rows
-        total_bad |= rows
-        z_gpu, z_ref = Y[:, sl], Y_ref[:, sl]
-    return float(total_bad.mean())
-
-
-def test_cfg1_full_size_layer():
-    c = case("cfg1")
-    w = c.w
-    X = c.x0_on_grid()
-    for l in range(2):
-        X = oracle.layer_forward(c.og, c.ocfg, c.inp.weights[l], X)
-    W = c.inp.weights[2]
-    Wd = torch.from_numpy(W).to(c.dev)
-    Y_ref = oracle.layer_forward(c.og, c.ocfg, W, X)
-    y = c.to_dev(X)
-    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y)
-    frac = audit_layer_forward(c, X, c.to_host(y), Y_ref, "cfg1 fwd")
-    assert frac < 1e-3
-
-    rng = np.random.default_rng(5)
-    dY = (rng.standard_normal((w.n, w.d)) * 1e-3).astype(np.float32).astype(np.float64)
-    Xb_ref, dX_ref, dW_ref = oracle.layer_backward(c.og, c.ocfg, W, Y_ref, dY)
-    yb, dyb = c.to_dev(Y_ref), c.to_dev(dY)
-    dW = torch.empty((w.c, w.dg, w.dg), dtype=torch.float32, device=c.dev)
-    gsr.gsr_layer_backward(c.gg, c.gcfg, Wd, yb, dyb, dW)
-    for name, got, ref in (("X rebuilt", c.to_host(yb), Xb_ref), ("dX", c.to_host(dyb), dX_ref)):
-        bad, worst = violations(got, ref)
-        print(f"[cfg1 bwd] {name}: bad rows {int(bad.any(axis=1).sum())} of {w.n}, worst {worst:.2f}, "
-              f"rel {rel_norm(got, ref):.2e}", flush=True)
-        assert bad.any(axis=1).mean() < 2e-3
-        assert rel_norm(got, ref) < 1e-3
-    print(f"[cfg1 bwd] dW rel {rel_norm(dW.cpu().numpy(), dW_ref):.2e}", flush=True)
-    assert rel_norm(dW.cpu().numpy(), dW_ref) < 1e-4
-
-
-def test_cfg2_full_size_layer_forward_and_properties():
-    c = case("cfg2")
-    w = c.w
-    X = c.x0_on_grid()
-    W = c.inp.weights[0]
-    Wd = torch.from_numpy(W).to(c.dev)
     t = time.time()
-    Y_ref = oracle.layer_forward(c.og, c.ocfg, W, X)
-    print(f"[cfg2] oracle layer forward {time.time() - t:.1f}s", flush=True)
-    y = c.to_dev(X)
-    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y)
-    Y = c.to_host(y)
-    frac = audit_layer_forward(c, X, Y, Y_ref, "cfg2 fwd")
-    assert frac < 5e-3
-    assert rel_norm(Y, Y_ref) < 1e-3
-
-    # bit-identical reruns, and inverse(forward(X)) returns X outside the rows a recomputed
-    # selection flipped
-    y2 = c.to_dev(X)
-    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y2)
-    assert torch.equal(y, y2)
-    gsr.gsr_layer_inverse(c.gg, c.gcfg, Wd, y2)
-    Xr = c.to_host(y2)
-    bad, worst = violations(Xr, X, rtol=1e-4, atol=1e-4)
-    print(f"[cfg2] inverse(forward(X)): bad rows {int(bad.any(axis=1).sum())}, worst {worst:.2f}", flush=True)
-    assert bad.any(axis=1).mean() < 5e-3
-
-    # backward fused with the inverse, from the oracle's Y: the inverse recomputes GS on rebuilt
-    # activations, so a few selections flip on either side; bounded in count and in norm
-    rng = np.random.default_rng(5)
-    dY = (rng.standard_normal((w.n, w.d)) * 1e-3).astype(np.float32).astype(np.float64)
-    Xb_ref, dX_ref, dW_ref = oracle.layer_backward(c.og, c.ocfg, W, Y_ref, dY)
-    yb, dyb = c.to_dev(Y_ref), c.to_dev(dY)
-    dW = torch.empty((w.c, w.dg, w.dg), dtype=torch.float32, device=c.dev)
-    gsr.gsr_layer_backward(c.gg, c.gcfg, Wd, yb, dyb, dW)
-    for name, got, ref, frac, rel in (("X rebuilt", c.to_host(yb), Xb_ref, 5e-3, 1e-3),
-                                      ("dX", c.to_host(dyb), dX_ref, 2e-2, 1e-2)):
-        bad, worst = violations(got, ref)
-        print(f"[cfg2 bwd] {name}: bad rows {int(bad.any(axis=1).sum())} of {w.n}, rel {rel_norm(got, ref):.2e}",
-              flush=True)
-        assert bad.any(axis=1).mean() < frac, name
-        assert rel_norm(got, ref) < rel, name
-    print(f"[cfg2 bwd] dW rel {rel_norm(dW.cpu().numpy(), dW_ref):.2e}", flush=True)
-    assert rel_norm(dW.cpu().numpy(), dW_ref) < 1e-3
-
-
-def test_cfg2_full_size_step_equals_chain_of_layers():
-    c = case("cfg2")
-    w = c.w
-    L = 2
-    a = run_step(c, l=L, raw=True)
-    b = run_step(c, l=L, raw=True)
-    for key in a:
-        assert torch.equal(a[key], b[key]), key
-    x = c.to_dev(c.inp.x0)
     Wd = torch.from_numpy(np.ascontiguousarray(c.inp.weights[:L])).to(c.dev)
+    x = c.to_dev(c.inp.x0)
+    host = lambda t_: c.to_host(t_).astype(np.float32)
+    out = {"X": {}, "Y": {}, "dY": {}}
     for l in range(L):
+        if l in capture:
+            out["X"][l] = host(x)
         gsr.gsr_layer_forward(c.gg, c.gcfg, Wd[l], x)
-    assert torch.equal(x, a["XL"])
-    yh = a["yhat"].cpu().numpy().astype(np.float32)
-    gy = (np.float32(2.0) * (yh - c.inp.target) / np.float32(w.n)).astype(np.float32)
-    dy = c.to_dev((gy[:, None] * c.inp.w_out[None, :]).astype(np.float32))
+    out["XL"] = x.clone()
+    out["step"] = run_step(c, l=L, raw=True)
+    dXL = head_gradient(c, out["step"]["yhat"])
+    if w.dtype == "bf16":
+        dXL = synth.to_bf16_grid(dXL)
+    dy = c.to_dev(dXL)
     dW = torch.empty_like(Wd)
     for l in reversed(range(L)):
+        if l in capture:
+            out["Y"][l], out["dY"][l] = host(x), host(dy)
         gsr.gsr_layer_backward(c.gg, c.gcfg, Wd[l], x, dy, dW[l])
-    assert torch.equal(x, a["X0rec"]) and torch.equal(dW, a["dW"]) and torch.equal(dy, a["dX0"])
-    # the head against the oracle's head on the same X^L is covered at small size; here the loss
-    # only has to be finite and the rebuilt input close to X0 for all but flipped rows
-    assert np.isfinite(float(a["loss"].item()))
-    bad, worst = violations(c.to_host(a["X0rec"]), c.x0_on_grid(), rtol=1e-4, atol=1e-4)
-    print(f"[cfg2 step L={L}] X0 rebuilt: bad rows {int(bad.any(axis=1).sum())}, worst {worst:.2f}", flush=True)
-    assert bad.any(axis=1).mean() < 2e-2
+    out["X0rec"], out["dX0"], out["dW"] = x, dy, dW
+    torch.cuda.synchronize()
+    print(f"[chain] {name} L={L}: {2 * L} layer calls, captures at {sorted(capture)}, {time.time() - t:.1f}s", flush=True)
+    _chains[key] = out
+    return out
 
 
-def test_cfg1_full_size_step():
-    c = case("cfg1")
-    w = c.w
-    L = 6
+def audit_forward_at(c: Case, chain, l, tag, bar=f32_bar, max_reachable=2e-2):
+    X = chain["X"][l].astype(np.float64)
+    W = c.inp.weights[l]
     t = time.time()
-    ref = oracle.step(c.og, c.ocfg, L, c.x0_on_grid(), c.inp.weights[:L], c.inp.w_out, c.inp.b_out, c.inp.target)
-    print(f"[cfg1 step L={L}] oracle {time.time() - t:.1f}s", flush=True)
-    out = run_step(c, l=L)
-    for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
-        bad, worst = violations(out[key], ref[key])
-        rows = bad.reshape(bad.shape[0], -1).any(axis=1) if bad.ndim > 1 else bad
-        print(f"[cfg1 step L={L}] {key}: rel {rel_norm(out[key], ref[key]):.2e}, bad {rows.mean():.2e}, worst {worst:.1f}",
-              flush=True)
-    assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
-    for key, rel, frac in (("yhat", 1e-3, 2e-2), ("XL", 1e-3, 2e-2), ("X0rec", 3e-2, 1e-1), ("dX0", 5e-2, 2e-1)):
-        bad, _ = violations(out[key], ref[key])
-        rows = bad.reshape(bad.shape[0], -1).any(axis=1)
-        assert rel_norm(out[key], ref[key]) < rel, key
-        assert rows.mean() < frac, key
-    assert rel_norm(out["dW"], ref["dW"]) < 2e-2
-    assert rel_norm(out["dwout"], ref["dwout"]) < 1e-3
-
-
-def test_cfg2_bf16_full_size_layer():
-    c = case("cfg2-bf16")
-    w = c.w
-    X = c.x0_on_grid()
-    W = c.inp.weights[0]
     Y_ref = oracle.layer_forward(c.og, c.ocfg, W, X)
     y = c.to_dev(X)
     gsr.gsr_layer_forward(c.gg, c.gcfg, torch.from_numpy(W).to(c.dev), y)
-    Y = c.to_host(y)
-    print(f"[cfg2 bf16] layer forward rel {rel_norm(Y, Y_ref):.2e}", flush=True)
-    assert rel_norm(Y, Y_ref) <= BF16_REL
-    # rows no bf16 rounding tie can reach agree to one bf16 ulp
-    err = np.abs(Y - Y_ref) / np.maximum(np.abs(Y_ref), 1e-3)
-    print(f"[cfg2 bf16] elements beyond 2^-7 relative: {(err > 2.0 ** -7).mean():.2e}", flush=True)
-    assert (err > 2.0 ** -7).mean() < 5e-2
+    frac = audit_layer_forward(c, X, c.to_host(y), Y_ref, f"{tag} fwd layer {l}", bar=bar, max_reachable=max_reachable)
+    print(f"[{tag} fwd layer {l}] rows outside the bar {frac:.2e}, rms of the input {np.sqrt((X ** 2).mean()):.2f}, "
+          f"{time.time() - t:.1f}s", flush=True)
+    return frac
+
+
+def audit_backward_at(c: Case, chain, l, tag, **kw):
+    t = time.time()
+    n = audit_layer_backward(c, c.inp.weights[l], chain["Y"][l].astype(np.float64), chain["dY"][l].astype(np.float64),
+                             f"{tag} bwd layer {l}", **kw)
+    print(f"[{tag} bwd layer {l}] rows handed over {n}, {time.time() - t:.1f}s", flush=True)
+
+
+# ------------------------------------------------------------------------------------------------ cfg1: 100k nodes, L = 28
+
+def test_cfg1_step_is_the_chain_of_layer_calls_at_full_depth():
+    c = case("cfg1")
+    w = c.w
+    chain = gpu_chain("cfg1", w.l, (0, 14, 27))
+    a = chain["step"]
+    assert torch.equal(a["XL"], chain["XL"]) and torch.equal(a["X0rec"], chain["X0rec"])
+    assert torch.equal(a["dW"], chain["dW"]) and torch.equal(a["dX0"], chain["dX0"])
+    b = run_step(c, raw=True)
+    for key in a:
+        assert torch.equal(a[key], b[key]), key
+
+
+@pytest.mark.parametrize("layer", [0, 14, 27])
+def test_cfg1_layers_forward_and_backward_teacher_forced(layer):
+    c = case("cfg1")
+    chain = gpu_chain("cfg1", c.w.l, (0, 14, 27))
+    assert audit_forward_at(c, chain, layer, "cfg1") < 2e-3
+    audit_backward_at(c, chain, layer, "cfg1")
 
 
 def test_cfg1_full_depth_step_in_the_three_index_modes():
@@ -285,6 +178,143 @@ def test_cfg1_full_depth_step_in_the_three_index_modes():
             assert rel_norm(r[key], ref[key]) <= bound, (name, key)
 
 
+# ------------------------------------------------------------------------------------------------ cfg2: 1M nodes, L = 112
+
+CFG2_LAYERS = (0, 56, 111)
+
+
+@pytest.mark.parametrize("layer", CFG2_LAYERS)
+def test_cfg2_layer_forward_teacher_forced(layer):
+    c = case("cfg2")
+    chain = gpu_chain("cfg2", c.w.l, CFG2_LAYERS)
+    assert audit_forward_at(c, chain, layer, "cfg2") < 5e-3
+
+
+@pytest.mark.parametrize("layer", CFG2_LAYERS)
+def test_cfg2_layer_backward_teacher_forced(layer):
+    c = case("cfg2")
+    chain = gpu_chain("cfg2", c.w.l, CFG2_LAYERS)
+    audit_backward_at(c, chain, layer, "cfg2")
+
+
+def test_cfg2_full_size_step_equals_chain_of_layers_and_reruns():
+    c = case("cfg2")
+    w = c.w
+    chain = gpu_chain("cfg2", w.l, CFG2_LAYERS)
+    a = chain["step"]
+    assert torch.equal(a["XL"], chain["XL"]) and torch.equal(a["X0rec"], chain["X0rec"])
+    assert torch.equal(a["dW"], chain["dW"]) and torch.equal(a["dX0"], chain["dX0"])
+    b = run_step(c, raw=True)
+    for key in a:
+        assert torch.equal(a[key], b[key]), key
+    # the head on the step's own X^L
+    XL = c.to_host(a["XL"])
+    yh = XL @ c.inp.w_out.astype(np.float64) + c.inp.b_out
+    assert np.allclose(a["yhat"].cpu().numpy(), yh, rtol=1e-4, atol=1e-4)
+    assert np.isclose(float(a["loss"].item()), np.mean((yh - c.inp.target) ** 2), rtol=1e-4)
+    # inverse(forward(X)) at the first layer: rows come back unless block 1 selected again differently (few rows)
+    y = c.to_dev(c.inp.x0)
+    Wd = torch.from_numpy(c.inp.weights[0]).to(c.dev)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y)
+    gsr.gsr_layer_inverse(c.gg, c.gcfg, Wd, y)
+    bad, worst = violations(c.to_host(y), c.x0_on_grid(), rtol=1e-4, atol=1e-4)
+    print(f"[cfg2] inverse(forward(X)): rows off {int(bad.any(axis=1).sum())} of {w.n}", flush=True)
+    assert bad.any(axis=1).sum() <= 64
+
+
+def test_cfg2_bf16_layers_teacher_forced():
+    """bf16 storage at 1M nodes: the same audits with the bar for bf16 planes (two bf16 steps).  Exact ties and
+    near-ties are the rule here, so more rows are reachable from a selection that may differ; none may be unexplained."""
+    c = case("cfg2-bf16")
+    chain = gpu_chain("cfg2-bf16", 8, (0, 7))
+    for l in (0, 7):
+        audit_forward_at(c, chain, l, "cfg2 bf16", bar=bf16_bar, max_reachable=0.5)
+        audit_backward_at(c, chain, l, "cfg2 bf16", bar=bf16_bar, dw_rtol=2e-2, max_flips=0.2)
+
+
+# ------------------------------------------------------------------------------------------------ cfg3: depth sweep on the cfg2 graph
+
+def test_cfg3_depth_sweep_memory_and_rebuild():
+    """L = 8 and 448 on the 1M-node graph: with nothing kept the step's device memory is the same at both depths up to
+    the weights and their gradients (2 L C (D/C)^2 floats); with the near-tie list it grows by that list only, and the
+    step rebuilds its input at both depths."""
+    c = case("cfg2")
+    w = c.w
+    dv = c.dev
+    f32 = dict(dtype=torch.float32, device=dv)
+    rng = np.random.Generator(np.random.PCG64(1))
+    deep = torch.from_numpy(synth.glorot_uniform(rng, w.dg, w.dg, (448, w.c, w.dg, w.dg))).to(dv)
+    x0 = c.to_dev(c.inp.x0)
+    w_out, target = torch.from_numpy(c.inp.w_out).to(dv), torch.from_numpy(c.inp.target).to(dv)
+    b_out = torch.zeros(1, **f32)
+    used = {}
+    for mode in (0, 2):
+        for L in (8, 448):
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+            torch.cuda.reset_peak_memory_stats()
+            before = torch.cuda.memory_allocated()
+            cfg = gsr.Config(**{**c.gcfg.__dict__, "l": L, "save_indices": mode, "tie_tol": 2.0 ** -12})
+            W = deep[:L]
+            loss, db = torch.zeros(1, **f32), torch.zeros(1, **f32)
+            dW, dw = torch.empty_like(W), torch.empty(w.d, **f32)
+            x0r = torch.empty_like(x0)
+            ws_bytes = gsr.gsr_workspace_size(c.gg, cfg)[1]
+            ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dv)
+            t = time.time()
+            gsr.gsr_step(c.gg, cfg, x0, W, w_out, b_out, target, loss, dW, dw, db, x0_rebuilt_out=x0r, workspace=ws)
+            torch.cuda.synchronize()
+            peak = torch.cuda.max_memory_allocated() - before
+            err = float((x0r - x0).abs().max().item())
+            weights = L * w.c * w.dg * w.dg * 4            # dW (W itself is a view of the 448-layer draw)
+            used[(mode, L)] = (peak - weights, ws_bytes)
+            print(f"[cfg3] index mode {mode}, L={L}: step {time.time() - t:.2f}s, device bytes beyond the weight gradients "
+                  f"{peak - weights}, workspace {ws_bytes}, max|X0 rebuilt - X0| {err:.3g}, loss {loss.item():.4f}", flush=True)
+            assert np.isfinite(loss.item())
+            if mode == 2:
+                st = gsr.gsr_step_tie_stats(c.gg, cfg, ws)
+                assert st["dropped"] == 0 and err <= 1e-3
+            del ws, dW, x0r
+    assert used[(0, 8)][1] == used[(0, 448)][1]                              # workspace: flat in L
+    assert abs(used[(0, 8)][0] - used[(0, 448)][0]) <= 1 << 20               # allocator rounding only
+    cap = w.n // 32 + 1024
+    per_layer = w.c * (4 + cap * (4 + w.dg // 8))
+    grow = used[(2, 448)][1] - used[(2, 8)][1]
+    assert abs(grow - 440 * per_layer) <= 4096
+    assert grow <= 0.05 * (440 * w.c * w.n * (w.dg // 8))                    # a twentieth of what keeping all sets costs
+
+
+_cfg4 = {}
+
+
+def cfg4_case():
+    """Workload, inputs and both graphs of cfg4 (built once: the host-side graph construction takes the longest)."""
+    if not _cfg4:
+        w = synth.workload(4)
+        t = time.time()
+        inp = synth.make_inputs(w, 0)
+        assert inp.rowptr.dtype == np.int64
+        gg = gsr.gsr_graph_create(inp.rowptr, inp.colidx)
+        og = oracle.graph_build(inp.rowptr, inp.colidx)
+        print(f"[cfg4] n={w.n} nnz={og.nnz} built in {time.time() - t:.1f}s", flush=True)
+        _cfg4.update(w=w, inp=inp, gg=gg, og=og)
+    return _cfg4["w"], _cfg4["inp"], _cfg4["gg"], _cfg4["og"]
+
+
+def sampled_neighbourhood(og, S):
+    """Rows S of the adjacency as a CSR over the local numbering of their neighbourhood `nodes` (which holds S:
+    self-loops).  Returns (nodes, pos of S in nodes, sub-graph whose only non-empty rows are those of S)."""
+    deg = og.rp[S + 1] - og.rp[S]
+    cols = np.concatenate([og.ci[og.rp[i]:og.rp[i + 1]] for i in S])
+    vals = np.concatenate([og.av[og.rp[i]:og.rp[i + 1]] for i in S])
+    nodes, inv = np.unique(cols, return_inverse=True)
+    pos = np.searchsorted(nodes, S)
+    rp = np.zeros(len(nodes) + 1, dtype=np.int64)
+    rp[pos + 1] = deg
+    rp = np.cumsum(rp)
+    return nodes, pos, oracle.graph_from_csr(rp, inv.astype(np.int32), vals), deg
+
+
 def test_cfg4_full_size_sampled_rows_and_properties():
     """cfg4 (8M nodes, D 256, C 8, k 8, bf16 storage, int64 row pointers) in the launch
     configuration the benchmark uses.  The oracle cannot run a layer on 8M x 256 doubles inside
@@ -292,13 +322,7 @@ def test_cfg4_full_size_sampled_rows_and_properties():
     the oracle's operators from its own neighbourhood (GS of the neighbours' Y_0 rows, aggregation
     over the row's stored edges, weight product in float64); reruns must be bit-identical and
     inverse(forward(X)) must return X to bf16 rounding."""
-    w = synth.workload(4)
-    t = time.time()
-    inp = synth.make_inputs(w, 0)
-    assert inp.rowptr.dtype == np.int64
-    gg = gsr.gsr_graph_create(inp.rowptr, inp.colidx)
-    og = oracle.graph_build(inp.rowptr, inp.colidx)
-    print(f"[cfg4] n={w.n} nnz={og.nnz} built in {time.time() - t:.1f}s", flush=True)
+    w, inp, gg, og = cfg4_case()
     dev = torch.device("cuda:0")
     dg, C, k = w.dg, w.c, w.k
     cfg = gsr.Config(n=w.n, d=w.d, c=C, k=k, l=1, dtype=gsr.GSR_BF16, norm=gsr.GSR_NORM_RMS, eps=1e-5, layout=PLANAR)
@@ -310,41 +334,121 @@ def test_cfg4_full_size_sampled_rows_and_properties():
     y2 = x.clone()
     gsr.gsr_layer_forward(gg, cfg, Wd, y2)
     assert torch.equal(y, y2)
+    # inverse(forward(X)).  Blocks C..2 select on the layer output itself, so groups 2..C come back to bf16 rounding
+    # on every row.  Block 1 selects on Y_0 formed from the rebuilt groups, which with seven bf16-rounded planes added
+    # up is the forward's Y_0 bit for bit on hardly any row: with nothing kept, group 1 of a bf16 layer is not expected
+    # back (measured and printed, not asserted; keeping the forward's column sets is what restores it, see
+    # test_gpu_ties.py).
     gsr.gsr_layer_inverse(gg, cfg, Wd, y2)
-    diff = (y2.float() - x.float()).abs().amax(dim=(0, 2))           # per row
-    frac = float((diff > 0.05).float().mean().item())
-    print(f"[cfg4] inverse(forward(X)): rows off by more than 0.05: {frac:.2e}", flush=True)
-    assert frac < 4e-2          # bf16 near-ties re-selected differently; everything else to rounding
 
-    # sampled rows of block 1: the two first tiles (they hold the split rows) and 3,000 random rows
+    def y0_of(planes):
+        z = planes[1].float()
+        for j in range(2, C):
+            z = z + planes[j].float()
+        return z.to(torch.bfloat16)
+
+    def off(i):
+        """Elements of group i + 1 that did not come back: X' = bf16(Y - O) with Y = bf16(X + O) is within a bf16
+        step of Y plus one of X of the original, whatever the size of O."""
+        xi, yi, ri = x[i].float(), y[i].float(), y2[i].float()
+        return (ri - xi).abs() > 2.0 ** -7 * (yi.abs() + xi.abs())
+
+    for i in range(1, C):
+        assert not bool(off(i).any().item()), f"group {i + 1} of inverse(forward(X))"
+    differs = (y0_of(y2) != y0_of(x)).any(dim=1).cpu().numpy()
+    from gpu_util import adjacency_pattern
+    reachable = (adjacency_pattern(og) @ differs.astype(np.int32)) > 0
+    rows1 = off(0).any(dim=1).cpu().numpy()
+    print(f"[cfg4] inverse(forward(X)): rows whose rebuilt Y_0 differs {int(differs.sum())}, rows they reach {int(reachable.sum())}, "
+          f"rows of group 1 outside the bar {int(rows1.sum())}, not reached by any of them {int((rows1 & ~reachable).sum())}", flush=True)
+    assert not (rows1 & ~reachable).any()          # (a row no differing Y_0 reaches must come back)
+
+    # sampled rows of block 1: the two first tiles (they hold the split rows) and 3,000 random rows, every element
     rng = np.random.default_rng(11)
     S = np.unique(np.concatenate([np.arange(32), rng.integers(0, w.n, 3000)]))
-    deg = og.rp[S + 1] - og.rp[S]
-    cols = np.concatenate([og.ci[og.rp[i]:og.rp[i + 1]] for i in S])
-    vals = np.concatenate([og.av[og.rp[i]:og.rp[i + 1]] for i in S])
-    nodes, inv = np.unique(cols, return_inverse=True)                # neighbourhood of the sample (holds S: self-loops)
+    nodes, pos, sub, deg = sampled_neighbourhood(og, S)
     xs = synth.to_bf16_grid(inp.x0[nodes]).astype(np.float64)
-    y0 = oracle.round_store(xs[:, dg:].reshape(len(nodes), C - 1, dg).sum(axis=1), oracle.STORE_BF16)
+    from gpu_util import group_sum_as_the_kernel
+    y0 = group_sum_as_the_kernel(xs, C, dg, bf16=True)               # the same bits the kernel selects on
     V, I, _ = oracle.gs(y0, k, oracle.NORM_RMS, 1e-5, oracle.STORE_BF16)
-    # a CSR over the neighbourhood's local numbering with the sampled rows' edges only
-    pos = np.searchsorted(nodes, S)
-    rp = np.zeros(len(nodes) + 1, dtype=np.int64)
-    rp[pos + 1] = deg
-    rp = np.cumsum(rp)
-    order = np.argsort(pos, kind="stable")                           # S is sorted, so pos is: identity
-    assert np.array_equal(order, np.arange(len(S)))
-    sub = oracle.graph_from_csr(rp, inv.astype(np.int32), vals)
     H = oracle.aggregate(sub, V, I, dg)[pos]
     ref = oracle.round_store(xs[pos, :dg] + H @ W[0].astype(np.float64), oracle.STORE_BF16)
     got = y[0].index_select(0, torch.from_numpy(S).to(dev)).float().cpu().numpy().astype(np.float64)
-    rel = rel_norm(got, ref)
-    ulp_off = np.abs(got - ref) > 2.0 ** -7 * np.maximum(np.abs(ref), 2.0 ** -6)
-    print(f"[cfg4] block 1 on {len(S)} sampled rows (max degree {int(deg.max())}): rel {rel:.2e}, "
-          f"elements off by more than one bf16 ulp {ulp_off.mean():.2e}", flush=True)
-    assert rel <= BF16_REL
-    assert ulp_off.mean() < 2e-2
+    bad = bf16_bar(got, ref)
+    print(f"[cfg4] block 1 on {len(S)} sampled rows (max degree {int(deg.max())}): elements outside the bar {int(bad.sum())}, "
+          f"rel {rel_norm(got, ref):.2e}", flush=True)
+    assert not bad.any()
     del x, y, y2
     torch.cuda.empty_cache()
+
+
+def test_cfg4_backward_of_one_block_at_full_size():
+    """Backward of block C of a layer at 8M nodes / D/C = 32 / bf16 / int64 row pointers, through gsr_layer_backward
+    in the benchmark's launch configuration.  With W_1 .. W_{C-1} = 0 the other blocks pass everything through
+    (O = 0, dH = 0), so the call returns X_C = Y_C - f_C(Y_{C-1}) in group C, dY_{C-1} + dZ_C in group C-1 and the
+    inputs elsewhere.  Rebuilt rows and data-gradient rows are checked on sampled rows against the oracle's operators
+    on each row's own neighbourhood (the 32 first rows hold the split rows); dW_C, a sum over all 8M rows, against
+    the oracle's GS and aggregation over the whole graph."""
+    w, inp, gg, og = cfg4_case()
+    dev = torch.device("cuda:0")
+    dg, C, k = w.dg, w.c, w.k
+    cfg = gsr.Config(n=w.n, d=w.d, c=C, k=k, l=1, dtype=gsr.GSR_BF16, norm=gsr.GSR_NORM_RMS, eps=1e-5, layout=PLANAR)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(41)
+    y = torch.from_numpy(inp.x0).to(dev).to(torch.bfloat16).view(w.n, C, dg).permute(1, 0, 2).contiguous()
+    gsr.gsr_layer_forward(gg, cfg, torch.from_numpy(inp.weights[0]).to(dev), y)        # a realistic layer output
+    dy = (torch.randn(y.shape, generator=gen, device=dev, dtype=torch.float32) * 1e-3).to(torch.bfloat16)
+    W = np.zeros((C, dg, dg), dtype=np.float32)
+    W[C - 1] = inp.weights[1][C - 1]
+    Wd = torch.from_numpy(W).to(dev)
+    yC, zfull = y[C - 1].float().cpu().numpy(), y[C - 2].float().cpu().numpy()          # Y_C, Y_{C-1}: [n, dg]
+    gC, gZ = dy[C - 1].float().cpu().numpy(), dy[C - 2].float().cpu().numpy()           # dY_C, dY_{C-1}
+    y_in, dy_in = y.clone(), dy.clone()
+    dW = torch.empty((C, dg, dg), dtype=torch.float32, device=dev)
+    gsr.gsr_layer_backward(gg, cfg, Wd, y, dy, dW)
+    torch.cuda.synchronize()
+    # everything but group C of X and group C-1 of dX passes through bit for bit
+    for i in range(C):
+        if i != C - 1:
+            assert torch.equal(y[i], y_in[i]), i
+        if i != C - 2:
+            assert torch.equal(dy[i], dy_in[i]), i
+    del y_in, dy_in
+
+    t = time.time()
+    V, I, r = oracle.gs(zfull, k, oracle.NORM_RMS, 1e-5, oracle.STORE_BF16)             # records of Y_{C-1}, all rows
+    H = oracle.aggregate(og, V, I, dg)
+    dW_ref = H.T @ gC.astype(np.float64)
+    err = np.abs(dW[C - 1].cpu().numpy() - dW_ref).max() / np.abs(dW_ref).max()
+    print(f"[cfg4 bwd] dW_C over {w.n} rows: max error relative to its largest entry {err:.2e} ({time.time() - t:.1f}s)", flush=True)
+    assert err <= 1e-4
+
+    rng = np.random.default_rng(12)
+    S = np.unique(np.concatenate([np.arange(32), rng.integers(0, w.n, 3000)]))
+    Wc = W[C - 1].astype(np.float64)
+    X_ref = oracle.round_store(yC[S].astype(np.float64) - H[S] @ Wc, oracle.STORE_BF16)
+    X_got = y[C - 1].index_select(0, torch.from_numpy(S).to(dev)).float().cpu().numpy().astype(np.float64)
+    bad = bf16_bar(X_got, X_ref)
+    print(f"[cfg4 bwd] X_C rebuilt on {len(S)} sampled rows: elements outside the bar {int(bad.sum())}, rel {rel_norm(X_got, X_ref):.2e}",
+          flush=True)
+    assert not bad.any()
+    # data gradient of the sampled rows: Q = A^T dY_C over the row's own neighbourhood (the matrix is symmetric),
+    # dH = Q W^T, read at the recorded positions only, back through the RMS scale
+    nodes, pos, sub, deg = sampled_neighbourhood(og, S)
+    Q = oracle.spmm(sub, gC[nodes].astype(np.float64))[pos]
+    dH = Q @ Wc.T
+    Zs, Is, rs = zfull[S].astype(np.float64), I[S], r[S]
+    g = np.take_along_axis(dH, Is, axis=1)
+    dot = (g * np.take_along_axis(Zs, Is, axis=1)).sum(axis=1)
+    dZ = -Zs * (dot / (dg * rs ** 3))[:, None]
+    np.put_along_axis(dZ, Is, np.take_along_axis(dZ, Is, axis=1) + g / rs[:, None], axis=1)
+    dX_ref = oracle.round_store(gZ[S].astype(np.float64) + dZ, oracle.STORE_BF16)
+    dX_got = dy[C - 2].index_select(0, torch.from_numpy(S).to(dev)).float().cpu().numpy().astype(np.float64)
+    bad = bf16_bar(dX_got, dX_ref)
+    moved = np.abs(dX_ref - gZ[S]).max()
+    print(f"[cfg4 bwd] dX_(C-1) on {len(S)} sampled rows (max degree {int(deg.max())}): elements outside the bar {int(bad.sum())}, "
+          f"rel {rel_norm(dX_got, dX_ref):.2e}, largest change of a gradient entry {moved:.2e}", flush=True)
+    assert not bad.any() and moved > 0
 
 
 def test_cfg2_full_size_walkthrough_layers():
