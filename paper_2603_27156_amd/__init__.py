@@ -16,7 +16,8 @@ from typing import Optional, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgsr.so")
+# GSR_LIB names another build of the library (kernel variants under measurement); default: the one built in-tree
+LIB_PATH = os.environ.get("GSR_LIB") or os.path.join(_HERE, "libgsr.so")
 
 GSR_OK, GSR_ERR_INVALID_ARG, GSR_ERR_BAD_CSR, GSR_ERR_UNSUPPORTED, GSR_ERR_WORKSPACE_TOO_SMALL, GSR_ERR_HIP = range(6)
 GSR_F32, GSR_BF16 = 0, 1
