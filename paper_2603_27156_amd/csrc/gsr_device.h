@@ -906,6 +906,106 @@ __device__ __forceinline__ void mfma_tile(const float* st, const WLds<DG>& wl, f
     }
 }
 
+// ---- the same products on the bf16 matrix pipe, exact to float32 rounding --------------------------------
+// A float32 value is the exact sum of three bf16 terms (8 + 8 + 8 significant bits: hi = the value truncated to bf16,
+// mid = the remainder truncated, lo = what is left).  A product a b is then the sum of nine exact bf16 products, of
+// which the six with the largest weights (hi hi, hi mid, mid hi, hi lo, mid mid, lo hi) carry it to 2^-24 relative:
+// what a float32 multiply would round away.  v_mfma_f32_16x16x16_bf16 forms such products exactly and adds them in
+// float32, takes 16 K-slots per instruction and, unlike the float32 matrix instructions of this chip, runs beside
+// the vector pipe, so the six products of a 16-deep step cost less than the one float32 instruction sequence they
+// replace and hide under the vector work of the other waves.
+// W is kept in LDS already split and laid out as B operands: entry [term][s][cb][lane] holds, for lane (kk = lane / 16,
+// j = lane % 16), the four bf16 of rows 16 s + 4 kk .. + 3 of column CPL j + cb (of W, or of W^T).
+template <int DG>
+struct WLdsB3 {
+    uint64_t w[3][DG / 16][DG / 16][64];
+};
+
+__device__ __forceinline__ uint64_t as_u64(bf16x4 v) { return __builtin_bit_cast(uint64_t, v); }
+__device__ __forceinline__ bf16x4 as_bf16x4(uint64_t v) { return __builtin_bit_cast(bf16x4, v); }
+
+template <int DG>
+__device__ __forceinline__ void load_w_lds_b3(const float* __restrict__ w, bool transposed, WLdsB3<DG>& l) {
+    constexpr int CPL = DG / 16, NB = DG / 16;
+    for (int e = threadIdx.x; e < NB * NB * 64; e += blockDim.x) {
+        const int lane = e & 63, cb = (e >> 6) % NB, s = (e >> 6) / NB;
+        const int kk = lane >> 4, j = lane & 15, col = CPL * j + cb;
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int row = 16 * s + 4 * kk + u;
+            v[u] = transposed ? w[col * DG + row] : w[row * DG + col];
+        }
+        bf16x4 hi, mid, lo;
+        split_p4(v, hi, mid, lo);
+        l.w[0][s][cb][lane] = as_u64(hi);
+        l.w[1][s][cb][lane] = as_u64(mid);
+        l.w[2][s][cb][lane] = as_u64(lo);
+    }
+    __syncthreads();
+}
+
+// acc = tile (16 x DG float32, LDS, row stride DG+1) * W, in the tile register layout of mfma_tile.
+template <int DG>
+__device__ __forceinline__ void mfma_tile_b3(const float* st, const WLdsB3<DG>& wl, f32x4 (&acc)[DG / 16]) {
+    constexpr int CPL = DG / 16;
+    const int lane = lane_id(), i = lane & 15, kk = lane >> 4;
+    const int arow = 4 * (i & 3) + (i >> 2);
+#pragma unroll
+    for (int cb = 0; cb < CPL; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < DG / 16; ++s) {
+        float a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a[u] = st[arow * (DG + 1) + 16 * s + 4 * kk + u];
+        bf16x4 ah, am, al;
+        split_p4(a, ah, am, al);
+#pragma unroll
+        for (int cb = 0; cb < CPL; ++cb) {
+            const bf16x4 bh = as_bf16x4(wl.w[0][s][cb][lane]), bm = as_bf16x4(wl.w[1][s][cb][lane]),
+                         bl = as_bf16x4(wl.w[2][s][cb][lane]);
+            // smallest terms first
+            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(al, bh, acc[cb], 0, 0, 0);
+            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(am, bm, acc[cb], 0, 0, 0);
+            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bl, acc[cb], 0, 0, 0);
+            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(am, bh, acc[cb], 0, 0, 0);
+            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bm, acc[cb], 0, 0, 0);
+            acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bh, acc[cb], 0, 0, 0);
+        }
+    }
+}
+
+// dW += H^T dY over the 16 rows of the tile, as mfma_outer, on the bf16 pipe.  The 16 rows are the 16 K-slots of one
+// instruction; K-slot 4 kk + u stands for tile row 4 u + kk, so that the B operand of lane (kk, j) is what the lane
+// already holds of dY (gy[u][ob], rows 4 u + kk) and the A operand is H[4 u + kk][16 mb + j] from the LDS tile.
+template <int DG>
+__device__ __forceinline__ void mfma_outer_b3(const float* st_h, const float (&gy)[4][DG / 16], f32x4 (&acc)[DG / 16][DG / 16]) {
+    const int lane = lane_id(), kk = lane >> 4, j = lane & 15;
+    bf16x4 bh[DG / 16], bm[DG / 16], bl[DG / 16];
+#pragma unroll
+    for (int ob = 0; ob < DG / 16; ++ob) {
+        const float b[4] = {gy[0][ob], gy[1][ob], gy[2][ob], gy[3][ob]};
+        split_p4(b, bh[ob], bm[ob], bl[ob]);
+    }
+#pragma unroll
+    for (int mb = 0; mb < DG / 16; ++mb) {
+        float a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a[u] = st_h[(4 * u + kk) * (DG + 1) + 16 * mb + j];
+        bf16x4 ah, am, al;
+        split_p4(a, ah, am, al);
+#pragma unroll
+        for (int ob = 0; ob < DG / 16; ++ob) {
+            acc[mb][ob] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(al, bh[ob], acc[mb][ob], 0, 0, 0);
+            acc[mb][ob] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(am, bm[ob], acc[mb][ob], 0, 0, 0);
+            acc[mb][ob] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bl[ob], acc[mb][ob], 0, 0, 0);
+            acc[mb][ob] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(am, bh[ob], acc[mb][ob], 0, 0, 0);
+            acc[mb][ob] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bm[ob], acc[mb][ob], 0, 0, 0);
+            acc[mb][ob] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ah, bh[ob], acc[mb][ob], 0, 0, 0);
+        }
+    }
+}
+
 // dW += H^T dY over the 16 rows of the tile: D[m][o] += sum_n H[n][m] dY[n][o].  H comes from the
 // LDS tile; dY is held in the tile register layout (gy[reg][cb] = dY[row 4 reg + lane / 16]
 // [column CPL (lane % 16) + cb]), which is the B operand as it stands.  The result has its

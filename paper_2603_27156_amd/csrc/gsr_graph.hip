@@ -467,6 +467,7 @@ static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz,
     // every row goes through the first pass, whose lanes add a row's entries in ordinary arithmetic instead of spending
     // a 16-row matrix product on them.
     const bool long_rows = g->nnz >= 64 * n;
+    g->long_rows = long_rows;
     const int64_t hub_threshold = options().hub_threshold > 0 ? options().hub_threshold : (long_rows ? 64 : 512);
     const int64_t hub_chunk = options().hub_chunk > 0 ? options().hub_chunk : (long_rows ? 256 : 64);
     g->hub_threshold = (int32_t)hub_threshold;

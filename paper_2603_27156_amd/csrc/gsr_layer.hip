@@ -54,15 +54,26 @@ struct BlockArgs {
     TieSeg<DG> tie;         // where rows that select at a near-tie are listed (count == NULL: nowhere)
 };
 
-template <int DG, typename T, int SIGN, bool WITH_DW, bool DEAL>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
+// B3: the H W_i (and dW_i) products on the bf16 matrix pipe from three-term splits (mfma_tile_b3), with W_i kept
+// split in LDS.  That copy is half as large again as the float32 one, so the kernels without dW accumulators run
+// eight waves per workgroup on it to keep sixteen waves per compute unit resident.  Measured on the 1M-node workload:
+// forward 345 -> 319 us, inverse + dW 516 -> 477 us per launch.  The forward kernel keeps a float32 variant (B3 =
+// false, four waves per workgroup) for graphs whose rows nearly all go through the first pass, where a launch is a
+// single short tile per wave and the variant with the larger workgroups took 121 us against 84.  Both inverse kernels
+// always use the split form: the plain and the fused inverse must rebuild the same bits.
+constexpr int block_waves(bool with_dw, bool b3) { return (!with_dw && b3) ? 8 : 4; }
+
+template <int DG, typename T, int SIGN, bool WITH_DW, bool DEAL, bool B3 = true>
+__global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
+    static_assert(B3 || (SIGN > 0 && !WITH_DW), "only the forward kernel has a float32 variant");
     constexpr int LR = DG + 1, CPL = DG / 16;
-    __shared__ WaveLds<DG, 1> lds[4];
+    __shared__ WaveLds<DG, 1> lds[block_waves(WITH_DW, B3)];
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tg = lane >> 4, tj = lane & 15;
     WaveLds<DG, 1>& L = lds[wave];
     float* st_h = L.st[0];
-    __shared__ WLds<DG> wl;
-    load_w_lds<DG>(a.w, false, wl);
+    __shared__ typename std::conditional<B3, WLdsB3<DG>, WLds<DG>>::type wl;
+    if constexpr (B3) load_w_lds_b3<DG>(a.w, false, wl);
+    else load_w_lds<DG>(a.w, false, wl);
     f32x4 dw[WITH_DW ? DG / 16 : 1][WITH_DW ? DG / 16 : 1];
     if constexpr (WITH_DW) {
 #pragma unroll
@@ -136,8 +147,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2
         }
         wave_sync();
         f32x4 acc[CPL];
-        mfma_tile<DG>(st_h, wl, acc);                      // O = H W_i in the tile register layout
-        if constexpr (WITH_DW) mfma_outer<DG>(st_h, gy, dw);
+        if constexpr (B3) {
+            mfma_tile_b3<DG>(st_h, wl, acc);               // O = H W_i in the tile register layout
+            if constexpr (WITH_DW) mfma_outer_b3<DG>(st_h, gy, dw);
+        } else {
+            mfma_tile<DG>(st_h, wl, acc);
+            if constexpr (WITH_DW) mfma_outer<DG>(st_h, gy, dw);
+        }
         wave_sync();                                       // H has been read: the tile is free
         // residual: four rows per instruction, CPL adjacent elements per lane
 #pragma unroll
@@ -266,29 +282,34 @@ __device__ __forceinline__ void dw_reduce_slices(const float* __restrict__ parti
         }
         for (; p < p1; ++p) acc += src[(size_t)p * ELEMS];
         __syncthreads();
-        red[seg * 64 + col] = acc;
+        if (seg < 4) red[seg * 64 + col] = acc;
         __syncthreads();
         if (seg == 0) out[slice * 64 + col] = ((red[col] + red[64 + col]) + red[128 + col]) + red[192 + col];
     }
     __syncthreads();
 }
 
-// Waves per workgroup of k_grad (they share one copy of W^T in LDS).  Measured at 1M rows, Dg = 64:
+// Waves per workgroup of k_grad (they share one copy of W^T in LDS).  Measured at 1M rows, Dg = 64, float32 product:
 // 4 and 8 waves (16 resident waves per compute unit either way) take the same time; 6 and 10
 // waves, which would allow 18 and 20 resident waves, are 20 % and 10 % slower.
-constexpr int GRAD_WAVES = 4;
+// B3 as in k_block: dH = Q W^T on the bf16 pipe with eight waves per workgroup (322 -> 309 us on the 1M-node
+// workload), or the float32 product with four (graphs whose rows nearly all go through the first pass: 106 us
+// against 132).
+constexpr int grad_waves(bool b3) { return b3 ? 8 : 4; }
 
-template <int DG, typename T, bool DEAL>
-__global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
+template <int DG, typename T, bool DEAL, bool B3>
+__global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
     constexpr int CPL = DG / 16;
+    constexpr int GRAD_WAVES = grad_waves(B3);
     __shared__ WaveLds<DG, 1> lds[GRAD_WAVES];
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tg = lane >> 4, tj = lane & 15;
     WaveLds<DG, 1>& L = lds[wave];
     float* st = L.st[0];
-    __shared__ WLds<DG> wl;
-    static_assert(GRAD_WAVES == 4 && sizeof(lds) >= 256 * sizeof(float), "dw_reduce_slices expects 256 threads");
+    __shared__ typename std::conditional<B3, WLdsB3<DG>, WLds<DG>>::type wl;
+    static_assert(GRAD_WAVES >= 4 && sizeof(lds) >= 256 * sizeof(float), "dw_reduce_slices works with the first 256 threads");
     if (a.dw_out) dw_reduce_slices<DG * DG>(a.dw_partial, a.dw_parts, a.dw_out, reinterpret_cast<float*>(lds));
-    load_w_lds<DG>(a.w, true, wl);
+    if constexpr (B3) load_w_lds_b3<DG>(a.w, true, wl);
+    else load_w_lds<DG>(a.w, true, wl);
     TileDraws td = tile_draws(a.tiles, a.draws, a.draws_done);
     TileDeal deal{0, 0, false};
     if constexpr (DEAL) deal = tile_deal(a.gt);
@@ -335,7 +356,8 @@ __global__ __launch_bounds__(64 * GRAD_WAVES) __attribute__((amdgpu_waves_per_eu
         }
         wave_sync();
         f32x4 acc[CPL];
-        mfma_tile<DG>(st, wl, acc);          // dH = Q W^T in the tile register layout
+        if constexpr (B3) mfma_tile_b3<DG>(st, wl, acc);          // dH = Q W^T in the tile register layout
+        else mfma_tile<DG>(st, wl, acc);
         // epilogue on registers: row 4 reg + tg, columns CPL tj + cb
 #pragma unroll
         for (int reg = 0; reg < 4; ++reg) {
@@ -711,24 +733,27 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
     if (mode != 2) tile_counters(x.g, &a.draws, &a.draws_done);
     else a.draws = a.draws_done = nullptr;
-    const dim3 block(256);
+    const bool b3 = mode != 0 || !x.g->long_rows;       // (see k_block)
+    const dim3 block(64 * block_waves(mode == 2, b3));
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
     unsigned grid;
-    if (mode == 0) {
-        static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false, false>);
+    auto go = [&](auto plain, auto deal, int per_cu) {
         grid = persistent_grid(x.g, per_cu);
-        if (heavy_first(a.g.n_heavy, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, +1, false, true>), dim3(grid), block, 0, x.s, a);
-        else hipLaunchKernelGGL((k_block<DG, T, +1, false, false>), dim3(grid), block, 0, x.s, a);
+        if (heavy_first(a.g.n_heavy, x.tiles, grid * (block.x / 64) / 4)) hipLaunchKernelGGL(deal, dim3(grid), block, 0, x.s, a);
+        else hipLaunchKernelGGL(plain, dim3(grid), block, 0, x.s, a);
+    };
+    if (mode == 0 && b3) {
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false, false, true>, 512);
+        go(k_block<DG, T, +1, false, false, true>, k_block<DG, T, +1, false, true, true>, per_cu);
+    } else if (mode == 0) {
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false, false, false>, 256);
+        go(k_block<DG, T, +1, false, false, false>, k_block<DG, T, +1, false, true, false>, per_cu);
     } else if (mode == 1) {
-        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false, false>);
-        grid = persistent_grid(x.g, per_cu);
-        if (heavy_first(a.g.n_heavy, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, -1, false, true>), dim3(grid), block, 0, x.s, a);
-        else hipLaunchKernelGGL((k_block<DG, T, -1, false, false>), dim3(grid), block, 0, x.s, a);
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false, false, true>, 512);
+        go(k_block<DG, T, -1, false, false, true>, k_block<DG, T, -1, false, true, true>, per_cu);
     } else {
-        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true, false>);
-        grid = persistent_grid(x.g, per_cu);
-        if (heavy_first(a.g.n_heavy, x.tiles, grid)) hipLaunchKernelGGL((k_block<DG, T, -1, true, true>), dim3(grid), block, 0, x.s, a);
-        else hipLaunchKernelGGL((k_block<DG, T, -1, true, false>), dim3(grid), block, 0, x.s, a);
+        static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true, false, true>, 256);
+        go(k_block<DG, T, -1, true, false, true>, k_block<DG, T, -1, true, true, true>, per_cu);
     }
     return grid;
 }
@@ -748,10 +773,18 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
     a.dw_partial = x.dw_partial(); a.dw_parts = dw_parts; a.dw_out = dw_out;
     tile_counters(x.g, &a.draws, &a.draws_done);
     ProfScope prof(KC_GRAD, x.s);
-    static const int per_cu = resident_blocks((const void*)k_grad<DG, T, false>, 64 * GRAD_WAVES);
-    const unsigned grid = persistent_grid(x.g, per_cu);
-    if (heavy_first(a.gt.n_heavy, x.tiles, grid)) hipLaunchKernelGGL((k_grad<DG, T, true>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
-    else hipLaunchKernelGGL((k_grad<DG, T, false>), dim3(grid), dim3(64 * GRAD_WAVES), 0, x.s, a);
+    auto go = [&](auto plain, auto deal, int per_cu, unsigned threads) {
+        const unsigned grid = persistent_grid(x.g, per_cu);
+        if (heavy_first(a.gt.n_heavy, x.tiles, grid * (threads / 64) / 4)) hipLaunchKernelGGL(deal, dim3(grid), dim3(threads), 0, x.s, a);
+        else hipLaunchKernelGGL(plain, dim3(grid), dim3(threads), 0, x.s, a);
+    };
+    if (!x.g->long_rows) {
+        static const int per_cu = resident_blocks((const void*)k_grad<DG, T, false, true>, 512);
+        go(k_grad<DG, T, false, true>, k_grad<DG, T, true, true>, per_cu, 512u);
+    } else {
+        static const int per_cu = resident_blocks((const void*)k_grad<DG, T, false, false>, 256);
+        go(k_grad<DG, T, false, false>, k_grad<DG, T, true, false>, per_cu, 256u);
+    }
 }
 
 // After a record was taken again from rebuilt rows during the inverse sweep: the rows listed for that application of

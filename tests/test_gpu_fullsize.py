@@ -89,7 +89,7 @@ def gpu_chain(name, L, capture):
     return out
 
 
-def audit_forward_at(c: Case, chain, l, tag, bar=f32_bar, max_reachable=2e-2):
+def audit_forward_at(c: Case, chain, l, tag, bar=f32_bar, max_reachable=5e-2):
     X = chain["X"][l].astype(np.float64)
     W = c.inp.weights[l]
     t = time.time()
