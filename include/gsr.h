@@ -40,7 +40,7 @@ typedef enum gsr_status {
     GSR_OK = 0,
     GSR_ERR_INVALID_ARG = 1,         /* null pointer, negative size, inconsistent sizes */
     GSR_ERR_BAD_CSR = 2,             /* non-monotone row pointers, column out of range */
-    GSR_ERR_UNSUPPORTED = 3,         /* C < 2, k < 1, k > D/C, D % C != 0, D/C not in {32, 64}, dtype */
+    GSR_ERR_UNSUPPORTED = 3,         /* C < 2, k < 1, k > D/C, D % C != 0, D/C not among those built, dtype */
     GSR_ERR_WORKSPACE_TOO_SMALL = 4, /* workspace_bytes below gsr_workspace_size() */
     GSR_ERR_HIP = 5                  /* a HIP runtime call failed (message has the HIP error) */
 } gsr_status_t;
@@ -74,11 +74,14 @@ typedef struct gsr_graph gsr_graph_t; /* opaque */
 /* Limits of this build (anything beyond is refused with GSR_ERR_UNSUPPORTED, never computed wrongly):
  *   N < 2^31 nodes; fewer than 2^31 stored entries after symmetrisation and self-loops (device row pointers are
  *   32-bit; the input row pointers may be 64-bit);  N * k < 2^32 (32-bit offsets into the compressed values);
- *   2 <= C <= 8;  D/C in {32, 64};  gsr_step: D <= 512 (the scalar head). */
+ *   2 <= C <= 8;  D/C in {32, 64, 128, 192, 256};  gsr_step: D <= 512 (the scalar head).
+ *   D/C above 64 (the paper's own models: hidden 256 or 384 in two groups, Section 5) runs as D/C / 64 column blocks of
+ *   64 through the same kernels, (D/C / 64)^2 launches per block, with GS over the whole row; it takes
+ *   save_indices 0 or 1. */
 typedef struct gsr_config {
     int64_t n;      /* nodes N */
     int32_t d;      /* feature width D */
-    int32_t c;      /* groups C (2..8); D/C must be 32 or 64 */
+    int32_t c;      /* groups C (2..8); D/C must be 32, 64, 128, 192 or 256 */
     int32_t l;      /* layers L (gsr_step only) */
     int32_t k;      /* retained elements per row per group, 1 <= k <= D/C */
     int32_t dtype;  /* gsr_dtype_t */

@@ -869,7 +869,7 @@ __device__ __forceinline__ void tile_gather(const CsrView& g, const float* __res
 // A wave multiplies its 16 x DG tile (staged in LDS, row stride DG+1) by a DG x DG matrix with
 // v_mfma_f32_16x16x4_f32:
 //   A[i][kk]: lane = kk*16 + i;  B[kk][j]: lane = kk*16 + j;  D[4*(lane/16)+r][lane%16] in reg r.
-// The DG x DG weight matrix sits in LDS (odd row stride DG + 1, which spreads the four k-rows of a
+// The DG x DG weight matrix (row stride ldw in memory: DG, or more when it is a block of a wider matrix) sits in LDS (odd row stride DG + 1, which spreads the four k-rows of a
 // B operand over different banks), loaded once per workgroup; transposed = true stores W^T.
 template <int DG>
 struct WLds {
@@ -878,10 +878,10 @@ struct WLds {
 };
 
 template <int DG>
-__device__ __forceinline__ void load_w_lds(const float* __restrict__ w, bool transposed, WLds<DG>& l) {
+__device__ __forceinline__ void load_w_lds(const float* __restrict__ w, int ldw, bool transposed, WLds<DG>& l) {
     for (int i = threadIdx.x; i < DG * DG; i += blockDim.x) {
         const int r = i / DG, cc = i % DG;
-        l.w[r * WLds<DG>::WP + cc] = transposed ? w[cc * DG + r] : w[i];
+        l.w[r * WLds<DG>::WP + cc] = transposed ? w[cc * ldw + r] : w[r * ldw + cc];
     }
     __syncthreads();
 }
@@ -925,7 +925,7 @@ __device__ __forceinline__ uint64_t as_u64(bf16x4 v) { return __builtin_bit_cast
 __device__ __forceinline__ bf16x4 as_bf16x4(uint64_t v) { return __builtin_bit_cast(bf16x4, v); }
 
 template <int DG>
-__device__ __forceinline__ void load_w_lds_b3(const float* __restrict__ w, bool transposed, WLdsB3<DG>& l) {
+__device__ __forceinline__ void load_w_lds_b3(const float* __restrict__ w, int ldw, bool transposed, WLdsB3<DG>& l) {
     constexpr int CPL = DG / 16, NB = DG / 16;
     for (int e = threadIdx.x; e < NB * NB * 64; e += blockDim.x) {
         const int lane = e & 63, cb = (e >> 6) % NB, s = (e >> 6) / NB;
@@ -934,7 +934,7 @@ __device__ __forceinline__ void load_w_lds_b3(const float* __restrict__ w, bool 
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int row = 16 * s + 4 * kk + u;
-            v[u] = transposed ? w[col * DG + row] : w[row * DG + col];
+            v[u] = transposed ? w[col * ldw + row] : w[row * ldw + col];
         }
         bf16x4 hi, mid, lo;
         split_p4(v, hi, mid, lo);

@@ -239,22 +239,26 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     LayerWs w;
     memset(&w, 0, sizeof(w));
     size_t n = (size_t)cfg->n, dg = (size_t)(cfg->d / cfg->c), b = dtype_size(cfg->dtype);
+    const int S = sub_planes(cfg);
+    const size_t dgs = dg / S;                       // columns of a tile: 32 or 64
     size_t off = 0;
-    for (int s = 0; s < cfg->c && s < 8; ++s) {
+    for (int s = 0; s < cfg->c * S && s < kMaxRecordSlots; ++s) {
         w.rec_vals[s] = off;
         off += align_up(n * (size_t)cfg->k * b + 16);   // the record gather loads up to 16 bytes past a record
         w.rec_mask[s] = off;
-        off += align_up(n * (dg == 32 ? 4 : 8));
+        off += align_up(n * (dgs == 32 ? 4 : 8));
     }
     w.y0 = off;
     off += align_up(n * dg * b);
+    w.dh = off;
+    if (S > 1) off += align_up(n * dg * sizeof(float));
     w.dw_partial = off;
-    off += align_up((size_t)g->grid * dg * dg * sizeof(float));
+    off += align_up((size_t)g->grid * dgs * dgs * sizeof(float));
     w.hub_partial = off;
     size_t chunks = (size_t)std::max(g->a.hub.n_chunks, g->at.hub.n_chunks);
-    off += align_up(std::max<size_t>(chunks, 1) * dg * sizeof(float));
+    off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
     w.hub_partial2 = off;
-    off += align_up(std::max<size_t>(chunks, 1) * dg * sizeof(float));
+    off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
     w.total = off;
     return w;
 }
@@ -300,7 +304,10 @@ gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool
     if (cfg->c < 2 || cfg->c > 8) return fail(GSR_ERR_UNSUPPORTED, "groups C=%d outside [2,8]", cfg->c);
     if (cfg->d <= 0 || cfg->d % cfg->c != 0) return fail(GSR_ERR_UNSUPPORTED, "D=%d not divisible by C=%d", cfg->d, cfg->c);
     int dg = cfg->d / cfg->c;
-    if (dg != 32 && dg != 64) return fail(GSR_ERR_UNSUPPORTED, "D/C=%d: only 32 and 64 are built", dg);
+    if (dg != 32 && dg != 64 && dg != 128 && dg != 192 && dg != 256)
+        return fail(GSR_ERR_UNSUPPORTED, "D/C=%d: 32, 64, 128, 192 and 256 are built", dg);
+    if (dg > 64 && cfg->save_indices == 2)
+        return fail(GSR_ERR_UNSUPPORTED, "save_indices = 2 is built for D/C <= 64; use 0 or 1 with D/C=%d", dg);
     if (cfg->k < 1 || cfg->k > dg) return fail(GSR_ERR_UNSUPPORTED, "k=%d outside [1, D/C=%d]", cfg->k, dg);
     if (cfg->dtype != GSR_F32 && cfg->dtype != GSR_BF16) return fail(GSR_ERR_UNSUPPORTED, "dtype %d", cfg->dtype);
     if (cfg->norm != GSR_NORM_NONE && cfg->norm != GSR_NORM_RMS) return fail(GSR_ERR_UNSUPPORTED, "norm %d", cfg->norm);

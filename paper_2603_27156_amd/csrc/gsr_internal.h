@@ -112,10 +112,12 @@ namespace gsr {
 gsr_status_t validate_config(const gsr_config_t* cfg, const gsr_graph_t* g, bool need_l);
 
 // Workspace carving shared by gsr_workspace_size and the layer / step calls.
+constexpr int kMaxRecordSlots = 32;   // groups (at most 8) x sub-planes of a group (at most 4)
 struct LayerWs {
-    size_t rec_vals[8];  // per slot: compressed values  [n][k] of T
-    size_t rec_mask[8];  // per slot: column bit mask    [n] of uint32 (dg=32) / uint64 (dg=64)
-    size_t y0;           // Y_0 plane [n][dg] of T (C > 2)
+    size_t rec_vals[kMaxRecordSlots];  // per slot and sub-plane: compressed values  [n][k] of T
+    size_t rec_mask[kMaxRecordSlots];  // per slot and sub-plane: column bit mask    [n] of uint32 (32 columns) / uint64 (64)
+    size_t y0;           // Y_0 plane [n][dg] of T (C > 2); wide groups: [S][n][64]
+    size_t dh;           // wide groups only: [S][n][64] float, the block gradient summed over column blocks
     size_t dw_partial;   // [grid][dg*dg] float
     size_t hub_partial;  // [max(n_chunks A, n_chunks A^T)][dg] float
     size_t hub_partial2; // same size: the backward's two first passes of a block run as one launch
@@ -155,6 +157,8 @@ inline bool heavy_first(int n_heavy, int tiles, unsigned grid) {
 }
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+// A group wider than one 64-column tile is handled as D/C / 64 sub-planes of 64 columns.
+inline int sub_planes(const gsr_config_t* cfg) { const int dg = cfg->d / cfg->c; return dg > 64 ? dg / 64 : 1; }
 inline size_t dtype_size(int32_t dtype) { return dtype == GSR_BF16 ? 2 : 4; }
 
 }  // namespace gsr

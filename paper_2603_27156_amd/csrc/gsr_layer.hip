@@ -39,7 +39,8 @@ struct BlockArgs {
     Record<DG, T> in;       // record of Y_{i-1}
     int k;
     const float* hub_part;  // first-pass partial rows of split rows
-    const float* w;         // W_i [DG][DG]
+    const float* w;         // W_i [DG][DG], row stride ldw (DG, or D/C when the block is a part of a wider matrix)
+    int ldw;
     T* plane;               // X_i on entry / Y_i on return (or the reverse), row stride ld
     int64_t ld;
     Record<DG, T> out;      // record of the row written (out.mask == NULL: none)
@@ -72,8 +73,8 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
     WaveLds<DG, 1>& L = lds[wave];
     float* st_h = L.st[0];
     __shared__ typename std::conditional<B3, WLdsB3<DG>, WLds<DG>>::type wl;
-    if constexpr (B3) load_w_lds_b3<DG>(a.w, false, wl);
-    else load_w_lds<DG>(a.w, false, wl);
+    if constexpr (B3) load_w_lds_b3<DG>(a.w, a.ldw, false, wl);
+    else load_w_lds<DG>(a.w, a.ldw, false, wl);
     f32x4 dw[WITH_DW ? DG / 16 : 1][WITH_DW ? DG / 16 : 1];
     if constexpr (WITH_DW) {
 #pragma unroll
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
 // few tiles per wave to absorb the work, see layer_backward_impl).  A block owns 64 entries; its 16 thread rows each sum a
 // contiguous sixteenth of the partials in ascending order, then the 16 sums are added in order.
 __global__ __launch_bounds__(1024) void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems,
-                                                    float* __restrict__ out) {
+                                                    float* __restrict__ out, int cols, int ld_out) {
     __shared__ float red[16][64];
     const int e = blockIdx.x * 64 + (threadIdx.x & 63), seg = threadIdx.x >> 6;
     const int per = (nparts + 15) / 16, p0 = seg * per, p1 = min(nparts, p0 + per);
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(1024) void k_dw_reduce(const float* __restrict__ pa
         float s = red[0][threadIdx.x];
 #pragma unroll
         for (int q = 1; q < 16; ++q) s += red[q][threadIdx.x];
-        out[e] = s;
+        out[(size_t)(e / cols) * ld_out + e % cols] = s;       // entry (e / cols, e % cols) of a matrix of row stride ld_out
     }
 }
 
@@ -242,7 +243,8 @@ struct GradArgs {
     const T* dy;            // dY_i (complete), row stride ldg
     int64_t ldg;
     const float* hub_part;
-    const float* w;         // W_i
+    const float* w;         // W_i, row stride ldw
+    int ldw;
     const M* own_mask;      // columns recorded for Y_{i-1}
     const T* z;             // Y_{i-1} rows (RMS only), row stride ldz
     int64_t ldz;
@@ -258,6 +260,10 @@ struct GradArgs {
     const float* dw_partial;
     int dw_parts;
     float* dw_out;
+    // ACC (groups wider than one tile: the gradient of a block is summed over its column blocks before the epilogue):
+    // dh [n][DG] float32 receives dH = Q W^T (dh_first) or has it added
+    float* dh;
+    bool dh_first;
 };
 
 // dW_i[e] = sum over the workgroup partials, in a fixed order: a workgroup takes 64 entries at a time; its four
@@ -297,7 +303,7 @@ __device__ __forceinline__ void dw_reduce_slices(const float* __restrict__ parti
 // against 132).
 constexpr int grad_waves(bool b3) { return b3 ? 8 : 4; }
 
-template <int DG, typename T, bool DEAL, bool B3>
+template <int DG, typename T, bool DEAL, bool B3, bool ACC = false>
 __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
     constexpr int CPL = DG / 16;
     constexpr int GRAD_WAVES = grad_waves(B3);
@@ -308,8 +314,8 @@ __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_pe
     __shared__ typename std::conditional<B3, WLdsB3<DG>, WLds<DG>>::type wl;
     static_assert(GRAD_WAVES >= 4 && sizeof(lds) >= 256 * sizeof(float), "dw_reduce_slices works with the first 256 threads");
     if (a.dw_out) dw_reduce_slices<DG * DG>(a.dw_partial, a.dw_parts, a.dw_out, reinterpret_cast<float*>(lds));
-    if constexpr (B3) load_w_lds_b3<DG>(a.w, true, wl);
-    else load_w_lds<DG>(a.w, true, wl);
+    if constexpr (B3) load_w_lds_b3<DG>(a.w, a.ldw, true, wl);
+    else load_w_lds<DG>(a.w, a.ldw, true, wl);
     TileDraws td = tile_draws(a.tiles, a.draws, a.draws_done);
     TileDeal deal{0, 0, false};
     if constexpr (DEAL) deal = tile_deal(a.gt);
@@ -330,8 +336,10 @@ __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_pe
         for (int reg = 0; reg < 4; ++reg) {
             const int row = r0 + 4 * reg + tg;
             const size_t rowc = (size_t)(row < a.n ? row : a.n - 1);
-            own[reg] = a.own_mask[rowc];
-            if (a.norm == GSR_NORM_RMS) load_cols<CPL, T>(a.z + rowc * a.ldz + CPL * tj, z[reg]);
+            if constexpr (!ACC) {
+                own[reg] = a.own_mask[rowc];
+                if (a.norm == GSR_NORM_RMS) load_cols<CPL, T>(a.z + rowc * a.ldz + CPL * tj, z[reg]);
+            }
         }
         const bool has_hub = tile_begin(a.gt, rpv, L.rp, lane);
         if constexpr (DEAL) {
@@ -364,6 +372,17 @@ __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_pe
             const int row = r0 + 4 * reg + tg;
             const bool ok = row < a.n;
             const int rowc = ok ? row : a.n - 1;
+            if constexpr (ACC) {
+                float* p = a.dh + (size_t)rowc * DG + CPL * tj;
+                float g[CPL];
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) g[cb] = 0.f;
+                if (!a.dh_first) load_cols<CPL, float>(p, g);
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) g[cb] += acc[cb][reg];
+                if (ok) store_cols<CPL, float>(p, g);
+                continue;
+            }
             const uint32_t bits = ok ? (uint32_t)(own[reg] >> (CPL * tj)) & ((1u << CPL) - 1u) : 0u;
             float dz[CPL];
             if (a.norm == GSR_NORM_RMS) {
@@ -505,6 +524,227 @@ __global__ __launch_bounds__(256) void k_sum(SumArgs<DG, T> a) {
     }
 }
 
+// ---- groups wider than one tile: D/C = 64 S, S = 2, 3 or 4 ---------------------------------------------------
+// Such a group is handled as S column blocks of 64 ("sub-planes": block s of a row starts 64 s elements into it).  The
+// aggregation is column-wise, so every sub-plane has a record of its own in the 64-column format (the kept values that
+// fall into it, at most k, and its 64-bit mask) and the 64-column block kernels compute Y_i[:, ob] (+)= H_mb W_i[mb][ob]
+// one pair (mb, ob) per launch.  What couples the sub-planes is GS, which selects over the whole row (Section 4.1),
+// and the scale and the backward through it: those are the two kernels below.
+
+template <int S, typename T>
+struct WideGsArgs {
+    int n;
+    const T* src;           // nsrc groups, src_gs apart, row stride ld; sub-plane s of a row starts at + 64 s
+    int64_t ld, src_gs;
+    int nsrc;
+    T* y0;                  // [S][n][64]: the sum, sub-plane by sub-plane (NULL: not kept)
+    int k, norm;
+    float eps;
+    Record<64, T> out[S];
+    bool out_given;         // out[s].mask hold the column sets to use
+};
+
+// GS of a 16-row tile of a wide group, lane (r, q) holding the q-th quarter (16 columns) of every sub-plane of row r:
+// the same search as select_quarter over 16 S keys per lane; ties go to the lowest column of the whole row (sub-plane,
+// then quarter, then column).  Records leave sub-plane by sub-plane in the layout emit_tile writes.
+template <int S, typename T>
+__global__ __launch_bounds__(256) void k_gs_wide(WideGsArgs<S, T> a) {
+    constexpr int DGW = 64 * S, LRW = DGW + 1;
+    constexpr int KS = sizeof(T) == 2 ? 16 : 0;
+    __shared__ float tile[4][16 * LRW + 64];
+    const int lane = lane_id(), tg = lane >> 4, tj = lane & 15, r = lane & 15, q = lane >> 4;
+    float* st = tile[threadIdx.x >> 6];
+    const int nwaves = (gridDim.x * blockDim.x) >> 6, tiles = (a.n + 15) / 16;
+    for (int t = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; t < tiles; t += nwaves) {
+        const int r0 = t * 16;
+        wave_sync();          // the previous tile's records have left the scratch
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            float y[4][4];
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) {
+                const int row = r0 + 4 * reg + tg;
+                load_cols<4, T>(a.src + (size_t)(row < a.n ? row : a.n - 1) * a.ld + 64 * s + 4 * tj, y[reg]);
+            }
+            for (int j = 1; j < a.nsrc; ++j) {
+#pragma unroll
+                for (int reg = 0; reg < 4; ++reg) {
+                    const int row = r0 + 4 * reg + tg;
+                    float v[4];
+                    load_cols<4, T>(a.src + (size_t)j * a.src_gs + (size_t)(row < a.n ? row : a.n - 1) * a.ld + 64 * s + 4 * tj, v);
+#pragma unroll
+                    for (int cb = 0; cb < 4; ++cb) y[reg][cb] += v[cb];
+                }
+            }
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) {
+                const int rr = 4 * reg + tg, row = r0 + rr;
+                const bool ok = row < a.n;
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) y[reg][cb] = stored<T>(y[reg][cb]);
+                if (ok && a.y0) store_cols<4, T>(a.y0 + ((size_t)s * a.n + row) * 64 + 4 * tj, y[reg]);
+#pragma unroll
+                for (int cb = 0; cb < 4; ++cb) st[rr * LRW + 64 * s + 4 * tj + cb] = ok ? y[reg][cb] : 0.f;
+            }
+        }
+        wave_sync();
+        const bool valid = r0 + r < a.n;
+        float x[S][16];
+        uint32_t key[S][16];
+        uint32_t top = 0u;
+        float ss = 0.f;
+#pragma unroll
+        for (int s = 0; s < S; ++s)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                x[s][j] = st[r * LRW + 64 * s + 16 * q + j];
+                ss += x[s][j] * x[s][j];
+                const uint32_t u = __float_as_uint(x[s][j]);
+                uint32_t kk = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
+                kk = kk == 0x7FFFFFFFu ? 0x80000000u : kk;          // -0 -> +0
+                key[s][j] = kk >> KS;
+                top = max(top, key[s][j]);
+            }
+        uint32_t msel[S];
+        if (a.out_given) {
+#pragma unroll
+            for (int s = 0; s < S; ++s) msel[s] = (uint32_t)(a.out[s].mask[valid ? r0 + r : a.n - 1] >> (16 * q)) & 0xFFFFu;
+        } else {
+            top = quarter_max(top);
+            auto count_ge = [&](uint32_t th) {
+                uint32_t cnt = 0u;
+#pragma unroll
+                for (int s = 0; s < S; ++s)
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) cnt += key[s][j] >= th ? 1u : 0u;
+                return quarter_sum(cnt);
+            };
+            constexpr uint32_t span = (4u << 23) >> KS;
+            const uint32_t uk = (uint32_t)a.k;
+            uint32_t lo = top > span ? top - span : 0u, hi = top + 1u;
+            {
+                const uint32_t cnt = count_ge(lo);
+                lo = (cnt >= uk && a.k < DGW) ? lo : 0u;
+                uint32_t open = (cnt != uk && a.k < DGW && valid) ? 1u : 0u;
+                for (int round = 0; round < 33 && ballot(open != 0u) != 0ull; ++round) {
+                    const uint32_t mid = lo + ((hi - lo) >> 1);
+                    const uint32_t c2 = count_ge(mid);
+                    lo = c2 >= uk ? mid : lo;
+                    hi = c2 >= uk ? hi : mid;
+                    open = (c2 == uk || hi - lo <= 1u) ? 0u : open;
+                }
+            }
+            // kept: every key above the threshold, and of those at the threshold the lowest columns of the row
+            uint32_t mgt[S], meq[S];
+            int ngt = 0;
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                mgt[s] = meq[s] = 0u;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    mgt[s] |= key[s][j] > lo ? 1u << j : 0u;
+                    meq[s] |= key[s][j] == lo ? 1u << j : 0u;
+                }
+                ngt += __popc(mgt[s]);
+            }
+            int need = a.k - (int)quarter_sum((uint32_t)ngt);      // ties to take, in column order
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                uint32_t all[4];
+                quarter_all((uint32_t)__popc(meq[s]), all);
+                int before = 0;
+#pragma unroll
+                for (int i = 0; i < 3; ++i) before += i < q ? (int)all[i] : 0;
+                int take = min(max(need - before, 0), (int)__popc(meq[s]));
+                msel[s] = mgt[s];
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const uint32_t sbit = ((meq[s] >> j) & 1u) & (take > 0 ? 1u : 0u);
+                    msel[s] |= sbit << j;
+                    take -= (int)sbit;
+                }
+                need -= (int)(all[0] + all[1] + all[2] + all[3]);
+            }
+        }
+        float scale = 1.f;
+        if (a.norm == GSR_NORM_RMS) scale = __builtin_amdgcn_rsqf(quarter_sum(ss) * (1.0f / (float)DGW) + a.eps);
+        const int rows = min(16, a.n - r0), total = rows * a.k;
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            uint32_t all[4];
+            quarter_all(msel[s] | (uint32_t)__popc(msel[s]) << 16, all);
+            int slot = r * a.k;
+#pragma unroll
+            for (int i = 0; i < 3; ++i) slot += i < q ? (int)(all[i] >> 16) : 0;
+            const uint64_t mask = (uint64_t)(all[0] & 0xFFFFu) | (uint64_t)(all[1] & 0xFFFFu) << 16 |
+                                  (uint64_t)(all[2] & 0xFFFFu) << 32 | (uint64_t)(all[3] & 0xFFFFu) << 48;
+            wave_sync();   // every lane holds its values (s = 0) / the previous sub-plane's record has left the scratch
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const uint32_t bit = (msel[s] >> j) & 1u;
+                st[bit ? slot : 16 * LRW + lane] = x[s][j] * scale;      // dropped columns go to the dump words
+                slot += (int)bit;
+            }
+            wave_sync();
+            T* dst = a.out[s].vals + (size_t)r0 * a.k;
+            for (int i = lane; i < total; i += 64) dst[i] = from_float<T>(st[i]);
+            if (!a.out_given && q == 0 && r < rows) a.out[s].mask[r0 + r] = mask;
+        }
+    }
+}
+
+// Backward through GS and its scale for a wide group, after dH = sum over column blocks of Q W^T has been summed into
+// dh [S][n][64]: one wave per row, lane c holding column c of every sub-plane.  dZ_c = [c in I] g_c / r - Z_c (sum_t g_t
+// Z_{I_t}) / (D/C r^3) with g = dH at the recorded positions (eq. (11): only those are read); dst planes += dZ.
+template <int S, typename T>
+struct WideEpiArgs {
+    int n;
+    const float* dh;                    // [S][n][64]
+    const uint64_t* mask[S];            // column sets recorded for the block's input
+    const T* z;                         // rows of the block's input (RMS only): row stride ldz, sub-plane s at + s * z_sub
+    int64_t ldz, z_sub;
+    int norm;
+    float eps;
+    T* dst;                             // ndst groups, dst_gs apart, row stride ldd
+    int64_t ldd, dst_gs;
+    int ndst;
+};
+
+template <int S, typename T>
+__global__ __launch_bounds__(256) void k_grad_epi_wide(WideEpiArgs<S, T> a) {
+    constexpr int DGW = 64 * S;
+    const int lane = lane_id();
+    const int nwaves = (gridDim.x * blockDim.x) >> 6;
+    for (int row = (blockIdx.x * blockDim.x + threadIdx.x) >> 6; row < a.n; row += nwaves) {
+        float g[S], zz[S];
+        bool kept[S];
+        float ss = 0.f, dot = 0.f;
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            g[s] = a.dh[((size_t)s * a.n + row) * 64 + lane];
+            kept[s] = (a.mask[s][row] >> lane) & 1ull;
+            zz[s] = a.norm == GSR_NORM_RMS ? to_float(a.z[(size_t)row * a.ldz + (size_t)s * a.z_sub + lane]) : 0.f;
+            ss += zz[s] * zz[s];
+            dot += kept[s] ? g[s] * zz[s] : 0.f;
+        }
+        float rinv = 1.f, coef = 0.f;
+        if (a.norm == GSR_NORM_RMS) {
+            ss = sub_sum<64>(ss);
+            dot = sub_sum<64>(dot);
+            rinv = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DGW) + a.eps);
+            coef = dot * (rinv * rinv * rinv) * (1.0f / (float)DGW);
+        }
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const float dz = (kept[s] ? g[s] * rinv : 0.f) - zz[s] * coef;
+            for (int j = 0; j < a.ndst; ++j) {
+                T* p = a.dst + (size_t)j * a.dst_gs + (size_t)row * a.ldd + 64 * s + lane;
+                *p = from_float<T>(to_float(*p) + dz);
+            }
+        }
+    }
+}
+
 // ---- head: yhat = X w + b, loss = mean (yhat - t)^2 ----------------------------------------------------
 template <typename T>
 struct HeadArgs {
@@ -627,7 +867,8 @@ struct Ctx {
     char* ws;
     LayerWs lw;
     int tiles;
-    M* saved;       // [L+1][C][n] column masks kept from the forward sweep, or NULL
+    int S;          // sub-planes of a group: 1, or D/C / 64 for groups wider than a tile (then DG = 64)
+    M* saved;       // [L+1][C][S][n] column masks kept from the forward sweep, or NULL
     // rows kept because they selected at a near-tie (cfg->save_indices == 2), per segment (layer, slot), or NULL
     int* tie_counts;
     uint32_t* tie_rows;
@@ -640,14 +881,15 @@ struct Ctx {
     }
     // Record slot `slot` of layer `layer`: the values always live in the slot (they are rebuilt),
     // the mask in the slot, or in the kept store when indices are saved.
-    Record<DG, T> rec(int slot, int layer = 0) const {
+    Record<DG, T> rec(int slot, int layer = 0, int sub = 0) const {
         Record<DG, T> r;
         if (slot < 0) { r.vals = nullptr; r.mask = nullptr; return r; }
-        r.vals = (T*)(ws + lw.rec_vals[slot]);
-        r.mask = saved ? saved + ((size_t)layer * cfg->c + slot) * (size_t)cfg->n : (M*)(ws + lw.rec_mask[slot]);
+        r.vals = (T*)(ws + lw.rec_vals[slot * S + sub]);
+        r.mask = saved ? saved + (((size_t)layer * cfg->c + slot) * S + sub) * (size_t)cfg->n : (M*)(ws + lw.rec_mask[slot * S + sub]);
         return r;
     }
     T* y0() const { return (T*)(ws + lw.y0); }
+    float* dh() const { return (float*)(ws + lw.dh); }
     float* dw_partial() const { return (float*)(ws + lw.dw_partial); }
     float* hub_part() const { return (float*)(ws + lw.hub_partial); }
     float* hub_part2() const { return (float*)(ws + lw.hub_partial2); }
@@ -721,14 +963,14 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
 template <int DG, typename T>
 static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>& in, const float* w, T* plane, int64_t ld,
                              const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg, bool first_pass_done = false,
-                             TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}) {
+                             TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, int ldw = DG) {
     if (!first_pass_done) launch_hub_records<DG, T>(x, in);
     BlockArgs<DG, T> a;
     a.tie = tie;
     a.g = make_view(x.g, false);
     a.n = (int)x.cfg->n; a.tiles = x.tiles;
     a.in = in; a.k = x.cfg->k;
-    a.hub_part = x.hub_part(); a.w = w; a.plane = plane; a.ld = ld;
+    a.hub_part = x.hub_part(); a.w = w; a.ldw = ldw; a.plane = plane; a.ld = ld;
     a.out = out; a.out_given = out_given;
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
     if (mode != 2) tile_counters(x.g, &a.draws, &a.draws_done);
@@ -765,6 +1007,7 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
                         bool first_pass_done = false) {
     if (!first_pass_done) launch_hub_dense<DG, T>(x, dy, ldg);
     GradArgs<DG, T> a;
+    a.ldw = DG; a.dh = nullptr; a.dh_first = false;
     a.gt = make_view(x.g, true);
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = first_pass_done ? x.hub_part2() : x.hub_part();
     a.w = w;
@@ -797,11 +1040,158 @@ static void launch_tie_fixup(const Ctx<DG, T>& x, const TieSeg<DG>& tie, const T
     hipLaunchKernelGGL((k_tie_fixup<DG, T>), dim3(blocks), dim3(256), 0, x.s, tie, plane, ld, x.cfg->k, x.cfg->norm, x.cfg->eps, out);
 }
 
+// ---- groups wider than one tile (see k_gs_wide): D/C = 64 S as S sub-planes of 64 columns -----------------------
+// Sub-plane s of group i of a plane set p starts 64 s elements into the group's rows (both caller layouts and the
+// step's arena keep a group's columns adjacent in a row), so the 64-column kernels work on it in place with the row
+// stride of the set.  W_i is D/C x D/C row-major; its block (mb, ob) starts at w + 64 mb D/C + 64 ob with row stride D/C.
+
+// dH_mb (+)= (A^T dY_ob) W_i[mb][ob]^T: the gradient kernel without its epilogue (always the bf16-pipe variant)
+template <typename T>
+static void launch_grad_acc(const Ctx<64, T>& x, const T* dy, int64_t ldg, const float* w, int ldw, float* dh, bool first,
+                            bool first_pass_done) {
+    if (!first_pass_done) launch_hub_dense<64, T>(x, dy, ldg);
+    GradArgs<64, T> a;
+    a.gt = make_view(x.g, true);
+    a.n = (int)x.cfg->n; a.tiles = x.tiles; a.dy = dy; a.ldg = ldg; a.hub_part = x.hub_part();
+    a.w = w; a.ldw = ldw;
+    a.own_mask = nullptr; a.z = nullptr; a.ldz = 0; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
+    a.dst = nullptr; a.ldd = 0; a.dst_gs = 0; a.ndst = 0;
+    a.dw_partial = nullptr; a.dw_parts = 0; a.dw_out = nullptr;
+    a.dh = dh; a.dh_first = first;
+    tile_counters(x.g, &a.draws, &a.draws_done);
+    ProfScope prof(KC_GRAD, x.s);
+    static const int per_cu = resident_blocks((const void*)k_grad<64, T, false, true, true>, 512);
+    const unsigned grid = persistent_grid(x.g, per_cu);
+    if (heavy_first(a.gt.n_heavy, x.tiles, grid * 2)) hipLaunchKernelGGL((k_grad<64, T, true, true, true>), dim3(grid), dim3(512), 0, x.s, a);
+    else hipLaunchKernelGGL((k_grad<64, T, false, true, true>), dim3(grid), dim3(512), 0, x.s, a);
+}
+
+// GS over the whole rows of a wide group (sum of nsrc groups first when nsrc > 1), records of slot `slot`
+template <int S, typename T>
+static void launch_gs_wide_s(const Ctx<64, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0, int slot, int layer,
+                             bool given) {
+    WideGsArgs<S, T> a;
+    a.n = (int)x.cfg->n; a.src = src; a.ld = ld; a.src_gs = gs; a.nsrc = nsrc; a.y0 = y0;
+    a.k = x.cfg->k; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
+    for (int s = 0; s < S; ++s) a.out[s] = x.rec(slot, layer, s);
+    a.out_given = given;
+    ProfScope prof(KC_SUM, x.s);
+    hipLaunchKernelGGL((k_gs_wide<S, T>), dim3((unsigned)x.g->grid * 2), dim3(256), 0, x.s, a);
+}
+template <typename T>
+static void launch_gs_wide(const Ctx<64, T>& x, const T* src, int64_t ld, int64_t gs, int nsrc, T* y0, int slot, int layer,
+                           bool given = false) {
+    if (x.S == 2) launch_gs_wide_s<2, T>(x, src, ld, gs, nsrc, y0, slot, layer, given);
+    else if (x.S == 3) launch_gs_wide_s<3, T>(x, src, ld, gs, nsrc, y0, slot, layer, given);
+    else launch_gs_wide_s<4, T>(x, src, ld, gs, nsrc, y0, slot, layer, given);
+}
+
+template <int S, typename T>
+static void launch_epi_wide_s(const Ctx<64, T>& x, int slot, int layer, const T* z, int64_t ldz, int64_t z_sub, T* dst, int64_t ldd,
+                              int64_t dst_gs, int ndst) {
+    WideEpiArgs<S, T> a;
+    a.n = (int)x.cfg->n; a.dh = x.dh();
+    for (int s = 0; s < S; ++s) a.mask[s] = x.rec(slot, layer, s).mask;
+    a.z = z; a.ldz = ldz; a.z_sub = z_sub; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
+    a.dst = dst; a.ldd = ldd; a.dst_gs = dst_gs; a.ndst = ndst;
+    ProfScope prof(KC_GRAD, x.s);
+    hipLaunchKernelGGL((k_grad_epi_wide<S, T>), dim3((unsigned)x.g->grid * 4), dim3(256), 0, x.s, a);
+}
+template <typename T>
+static void launch_epi_wide(const Ctx<64, T>& x, int slot, int layer, const T* z, int64_t ldz, int64_t z_sub, T* dst, int64_t ldd,
+                            int64_t dst_gs, int ndst) {
+    if (x.S == 2) launch_epi_wide_s<2, T>(x, slot, layer, z, ldz, z_sub, dst, ldd, dst_gs, ndst);
+    else if (x.S == 3) launch_epi_wide_s<3, T>(x, slot, layer, z, ldz, z_sub, dst, ldd, dst_gs, ndst);
+    else launch_epi_wide_s<4, T>(x, slot, layer, z, ldz, z_sub, dst, ldd, dst_gs, ndst);
+}
+
+// plane (+/-)= f_i(Y_{i-1}) for one group: S x S launches of the 64-column block kernel.  mode as launch_block;
+// dw_i (mode 2): D/C x D/C, receives dW_i block by block.
+template <typename T>
+static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, const float* wi, T* plane, int64_t ld, const T* dy,
+                       int64_t ldg, float* dw_i) {
+    const int S = x.S, dgw = 64 * S;
+    const Record<64, T> none = x.rec(-1);
+    for (int mb = 0; mb < S; ++mb)
+        for (int ob = 0; ob < S; ++ob) {
+            const float* wsub = wi + (size_t)mb * 64 * dgw + 64 * ob;
+            const unsigned nparts = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false,
+                                                        dy ? dy + 64 * ob : nullptr, ldg, ob > 0,
+                                                        TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw);
+            if (mode == 2) {
+                ProfScope prof(KC_DW_REDUCE, x.s);
+                hipLaunchKernelGGL(k_dw_reduce, dim3(64), dim3(1024), 0, x.s, (const float*)x.dw_partial(), (int)nparts, 64 * 64,
+                                   dw_i + (size_t)mb * 64 * dgw + 64 * ob, 64, dgw);
+            }
+        }
+}
+
+template <typename T>
+static void wide_forward(const Ctx<64, T>& x, const float* w, const Planes<T>& p, bool slot0_ready, int layer) {
+    const int C = x.cfg->c, dgw = 64 * x.S;
+    if (!slot0_ready) launch_gs_wide<T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, 0, layer);
+    for (int i = 1; i <= C; ++i) {
+        wide_block<T>(x, 0, i - 1, layer, w + (size_t)(i - 1) * dgw * dgw, p.grp(i - 1), p.ld, nullptr, 0, nullptr);
+        if (i < C) launch_gs_wide<T>(x, p.grp(i - 1), p.ld, p.gs, 1, nullptr, i, layer);
+        else if (C == 2) launch_gs_wide<T>(x, p.grp(i - 1), p.ld, p.gs, 1, nullptr, 0, layer + 1);
+    }
+}
+
+template <typename T>
+static void wide_inverse(const Ctx<64, T>& x, const float* w, const Planes<T>& p) {
+    const int C = x.cfg->c, dgw = 64 * x.S;
+    for (int i = 1; i < C; ++i) launch_gs_wide<T>(x, p.grp(i - 1), p.ld, p.gs, 1, nullptr, i, 0);
+    for (int i = C; i >= 1; --i) {
+        if (i == 1 && C > 2) launch_gs_wide<T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, 0, 0);
+        wide_block<T>(x, 1, i - 1, 0, w + (size_t)(i - 1) * dgw * dgw, p.grp(i - 1), p.ld, nullptr, 0, nullptr);
+        if (i == 2 && C == 2) launch_gs_wide<T>(x, p.grp(1), p.ld, p.gs, 1, nullptr, 0, 0);
+    }
+}
+
+// as layer_backward_impl
+template <typename T>
+static void wide_backward(const Ctx<64, T>& x, const float* w, const Planes<T>& y, const Planes<T>& dy, float* dw_out, bool slots_ready,
+                          int layer, bool in_step) {
+    const int C = x.cfg->c, S = x.S, dgw = 64 * S;
+    const int64_t n = x.cfg->n;
+    const bool given = x.saved != nullptr;
+    if (!slots_ready)
+        for (int i = 1; i < C; ++i) launch_gs_wide<T>(x, y.grp(i - 1), y.ld, y.gs, 1, nullptr, i, layer, given);
+    for (int i = C; i >= 1; --i) {
+        const float* wi = w + (size_t)(i - 1) * dgw * dgw;
+        const T* z;          // rows of Y_{i-1}: row stride ldz, sub-plane s at + s * z_sub
+        int64_t ldz, z_sub;
+        if (i >= 2) { z = y.grp(i - 2); ldz = y.ld; z_sub = 64; }
+        else if (C == 2) { z = y.grp(1); ldz = y.ld; z_sub = 64; }      // Y_0 = X_2, rebuilt just before
+        else {
+            launch_gs_wide<T>(x, y.grp(1), y.ld, y.gs, C - 1, x.y0(), 0, layer, given);
+            z = x.y0(); ldz = 64; z_sub = n * 64;
+        }
+        wide_block<T>(x, 2, i - 1, layer, wi, y.grp(i - 1), y.ld, dy.grp(i - 1), dy.ld, dw_out + (size_t)(i - 1) * dgw * dgw);
+        // the record of the rebuilt X_i, where the next block or the layer below needs it
+        if (i < C) {
+            if (!(in_step && layer == 0)) launch_gs_wide<T>(x, y.grp(i - 1), y.ld, y.gs, 1, nullptr, i, given ? layer - 1 : 0, given);
+        } else if (C == 2) {
+            launch_gs_wide<T>(x, y.grp(i - 1), y.ld, y.gs, 1, nullptr, 0, layer, given);      // X_2 = Y_0 of this layer
+        }
+        // dH_mb = sum_ob (A^T dY_i[:, ob]) W_i[mb][ob]^T, then back through GS of the whole row
+        for (int ob = 0; ob < S; ++ob)
+            for (int mb = 0; mb < S; ++mb)
+                launch_grad_acc<T>(x, dy.grp(i - 1) + 64 * ob, dy.ld, wi + (size_t)mb * 64 * dgw + 64 * ob, dgw, x.dh() + (size_t)mb * n * 64,
+                                   ob == 0, mb > 0);
+        if (i >= 2) launch_epi_wide<T>(x, i - 1, layer, z, ldz, z_sub, dy.grp(i - 2), dy.ld, dy.gs, 1);
+        else launch_epi_wide<T>(x, 0, layer, z, ldz, z_sub, dy.grp(1), dy.ld, dy.gs, C - 1);
+    }
+}
+
 // eq. (6).  slot0_ready: the record of Y_0 is already in slot 0 (C = 2: it is the record of the
 // previous layer's Y_2, emitted when that plane was written).  `layer`: index of the layer inside
 // a step (selects the kept masks when indices are saved; 0 otherwise).
 template <int DG, typename T>
 static void layer_forward_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& p, bool slot0_ready, int layer = 0) {
+    if constexpr (DG == 64) {
+        if (x.S > 1) { wide_forward<T>(x, w, p, slot0_ready, layer); return; }
+    }
     const int C = x.cfg->c;
     if (!slot0_ready) launch_sum<DG, T>(x, p.grp(1), p.ld, p.gs, C - 1, nullptr, x.rec(0, layer), false, x.tie_seg(layer, 0));
     for (int i = 1; i <= C; ++i) {
@@ -815,6 +1205,9 @@ static void layer_forward_impl(const Ctx<DG, T>& x, const float* w, const Planes
 // eq. (7)
 template <int DG, typename T>
 static void layer_inverse_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& p) {
+    if constexpr (DG == 64) {
+        if (x.S > 1) { wide_inverse<T>(x, w, p); return; }
+    }
     const int C = x.cfg->c;
     for (int i = 1; i < C; ++i) launch_sum<DG, T>(x, p.grp(i - 1), p.ld, p.gs, 1, nullptr, x.rec(i));
     for (int i = C; i >= 1; --i) {
@@ -833,6 +1226,9 @@ static void layer_inverse_impl(const Ctx<DG, T>& x, const float* w, const Planes
 template <int DG, typename T>
 static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Planes<T>& y, const Planes<T>& dy, float* dw_out,
                                 bool slots_ready, int layer = 0, bool in_step = false) {
+    if constexpr (DG == 64) {
+        if (x.S > 1) { wide_backward<T>(x, w, y, dy, dw_out, slots_ready, layer, in_step); return; }
+    }
     const int C = x.cfg->c;
     const bool given = x.saved != nullptr;
     if (!slots_ready)
@@ -870,7 +1266,7 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         if (x.tiles < 4 * 4 * x.g->grid) {
             ProfScope prof(KC_DW_REDUCE, x.s);
             hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 63) / 64), dim3(1024), 0, x.s, (const float*)x.dw_partial(),
-                               (int)nparts, DG * DG, dwi);
+                               (int)nparts, DG * DG, dwi, DG, DG);
             dwi = nullptr;
         }
         const typename MaskOf<DG>::type* own = x.rec(i - 1, layer).mask;
@@ -884,6 +1280,7 @@ static Ctx<DG, T> make_ctx(const gsr_graph_t* g, const gsr_config_t* cfg, void* 
     Ctx<DG, T> x;
     x.g = g; x.cfg = cfg; x.s = s; x.ws = (char*)ws; x.lw = carve_layer(cfg, g);
     x.tiles = (int)((cfg->n + 15) / 16);
+    x.S = sub_planes(cfg);
     x.saved = nullptr;
     x.tie_counts = nullptr; x.tie_rows = nullptr; x.tie_masks = nullptr; x.tie_cap = 0;
     return x;
@@ -945,21 +1342,22 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
         hipLaunchKernelGGL(k_zero_ints, dim3((segs + 255) / 256), dim3(256), 0, s, x.tie_counts, segs);
     }
     const int64_t n = cfg->n;
-    const Planes<T> act{(T*)(base + sw.act), (int64_t)DG, n * DG};
-    const Planes<T> grad{(T*)(base + sw.grad), (int64_t)DG, n * DG};
+    const int dgw = DG * x.S;            // columns of a group (DG, or 64 S for the groups handled as sub-planes)
+    const Planes<T> act{(T*)(base + sw.act), (int64_t)dgw, n * dgw};
+    const Planes<T> grad{(T*)(base + sw.grad), (int64_t)dgw, n * dgw};
     const Planes<T> in = caller_planes<T>(const_cast<void*>(x0), cfg);
     const dim3 cgrid((unsigned)g->grid * 4), cblock(256);
     auto copy = [&](const Planes<T>& from, const Planes<T>& to) {
         ProfScope prof(KC_COPY, s);
-        hipLaunchKernelGGL((k_copy_planes<T>), cgrid, cblock, 0, s, n, DG, C, (const T*)from.base, from.ld, from.gs, to.base,
+        hipLaunchKernelGGL((k_copy_planes<T>), cgrid, cblock, 0, s, n, dgw, C, (const T*)from.base, from.ld, from.gs, to.base,
                            to.ld, to.gs);
     };
     copy(in, act);
-    const size_t wl = (size_t)C * DG * DG;
+    const size_t wl = (size_t)C * dgw * dgw;
     for (int l = 0; l < L; ++l) layer_forward_impl<DG, T>(x, w_all + l * wl, act, C == 2 && l > 0, l);
     if (xl_out) copy(act, caller_planes<T>(xl_out, cfg));
     HeadArgs<T> h;
-    h.n = (int)n; h.d = cfg->d; h.dg = DG; h.act = act.base; h.grad = grad.base; h.ld = act.ld; h.gs = act.gs;
+    h.n = (int)n; h.d = cfg->d; h.dg = dgw; h.act = act.base; h.grad = grad.base; h.ld = act.ld; h.gs = act.gs;
     h.w_out = w_out; h.b_out = b_out; h.target = target; h.yhat = yhat_out; h.partial = (float*)(base + sw.head);
     {
         ProfScope prof(KC_HEAD, s);
