@@ -2,7 +2,7 @@
 """Benchmark of the GSR-GNN training step (forward + inverse recomputation + backward) on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg1|cfg0|cfg2-bf16|cfg4|dense]
-                    [--layers L] [--k K] [--index-mode near-ties|all|none] [--no-extras]
+                    [--layers L] [--k K] [--c C] [--index-mode near-ties|all|none] [--no-extras]
 
 A "step" is one gsr_step call: L grouped reversible layers forward, head + loss, and the backward
 sweep that rebuilds every layer input instead of storing it.  Inputs are synthetic (seeded circuit
@@ -82,6 +82,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override L")
     ap.add_argument("--k", type=int, default=0, help="override k (sweep over the paper's K = 4 ... 64)")
+    ap.add_argument("--c", type=int, default=0, help="override the number of groups C (dense workload: 2 is the paper's split, D/C = 192)")
     ap.add_argument("--max-workgroups", type=int, default=0, help="override the persistent grid (multiple of 8)")
     ap.add_argument("--index-mode", choices=sorted(INDEX_MODES), default=None,
                     help="what the forward sweep keeps for the inverse: the column sets of near-tie rows (default with "
@@ -119,6 +120,8 @@ def main() -> int:
         w = synth.workload(idx, l=args.layers, dtype=w.dtype, name=w.name)
     if args.k > 0:
         w = synth.workload(idx, l=w.l, dtype=w.dtype, name=f"{w.name}-k{args.k}", k=args.k)
+    if args.c > 0:
+        w = synth.workload(idx, l=w.l, dtype=w.dtype, name=f"{w.name}-c{args.c}", k=w.k, c=args.c)
     if args.max_workgroups:
         gsr.gsr_set_option("max_workgroups", args.max_workgroups)
     if args.hub_threshold:
@@ -133,8 +136,9 @@ def main() -> int:
 
     bf16 = w.dtype == "bf16"
     mode_name = "all" if args.save_indices else args.index_mode
+    wide = w.dg > 64                    # groups of more than 64 columns run as column blocks; they take "all" or "none"
     if mode_name is None:
-        mode_name = "all" if bf16 else "near-ties"
+        mode_name = "all" if (bf16 or wide) else "near-ties"
     f32 = dict(dtype=torch.float32, device=dev)
     w_out = torch.from_numpy(inp.w_out).to(dev)
     b_out = torch.zeros(1, **f32)
@@ -236,7 +240,8 @@ def main() -> int:
     bpe = 2 if bf16 else 4
     roofline = None
     if kernels:
-        ab = algorithmic_bytes(w.n, info["nnz"], w.dg, w.k, w.c, bpe, w.norm == "rms")
+        # (groups wider than 64 columns: a launch handles one 64-column block pair)
+        ab = algorithmic_bytes(w.n, info["nnz"], min(w.dg, 64), w.k, w.c, bpe, w.norm == "rms")
         cand = {k: v for k, v in kernels.items() if k in ab}
         dom = max(cand, key=lambda k: cand[k]["ms_per_step"])
         achieved = ab[dom] / (cand[dom]["avg_us"] * 1e-6) / 1e9
@@ -263,7 +268,7 @@ def main() -> int:
     if extras and w.l * w.n <= 120_000_000:
         others = {}
         for m in ("all", "none", "near-ties"):
-            if m == mode_name:
+            if m == mode_name or (wide and m == "near-ties"):
                 continue
             r = Run(w.l, W, m)
             ms = r.timed(1, 1)
@@ -288,7 +293,7 @@ def main() -> int:
     # Depth sweep (the graph and X0 of this workload at L = 8 .. 448; weights of one 448-layer draw, prefixes used):
     # peak HBM against L, one timed step each.
     depth_sweep = None
-    if extras and idx == 2 and not args.layers and not args.k:
+    if extras and idx == 2 and not args.layers and not args.k and not args.c:
         depth_sweep = []
         deep = torch.from_numpy(synth.glorot_uniform(np.random.Generator(np.random.PCG64(1)), w.dg, w.dg,
                                                      (448, w.c, w.dg, w.dg))).to(dev)
@@ -313,7 +318,7 @@ def main() -> int:
             del r
         del deep
         torch.cuda.empty_cache()
-    if extras and idx == 2 and not bf16 and not args.layers and not args.k:
+    if extras and idx == 2 and not bf16 and not args.layers and not args.k and not args.c:
         r = Run(w.l, W, "all", use_bf16=True)
         ms = r.timed(1, 1)
         err, rows = r.rebuild_error()
