@@ -367,24 +367,17 @@ __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_pe
         if constexpr (B3) mfma_tile_b3<DG>(st, wl, acc);          // dH = Q W^T in the tile register layout
         else mfma_tile<DG>(st, wl, acc);
         // epilogue on registers: row 4 reg + tg, columns CPL tj + cb
+        float dz[4][CPL];
 #pragma unroll
         for (int reg = 0; reg < 4; ++reg) {
             const int row = r0 + 4 * reg + tg;
             const bool ok = row < a.n;
-            const int rowc = ok ? row : a.n - 1;
             if constexpr (ACC) {
-                float* p = a.dh + (size_t)rowc * DG + CPL * tj;
-                float g[CPL];
 #pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) g[cb] = 0.f;
-                if (!a.dh_first) load_cols<CPL, float>(p, g);
-#pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) g[cb] += acc[cb][reg];
-                if (ok) store_cols<CPL, float>(p, g);
+                for (int cb = 0; cb < CPL; ++cb) dz[reg][cb] = acc[cb][reg];
                 continue;
             }
             const uint32_t bits = ok ? (uint32_t)(own[reg] >> (CPL * tj)) & ((1u << CPL) - 1u) : 0u;
-            float dz[CPL];
             if (a.norm == GSR_NORM_RMS) {
                 // V = Z[I] * rinv, rinv = (mean Z^2 + eps)^-1/2:
                 // dZ_c = [c in I] g_c rinv - Z_c (sum_t g_t Z_{I_t}) rinv^3 / DG
@@ -399,18 +392,46 @@ __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_pe
                 const float rinv = __builtin_amdgcn_rsqf(ss * (1.0f / (float)DG) + a.eps);
                 const float coef = dot * (rinv * rinv * rinv) * (1.0f / (float)DG);
 #pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) dz[cb] = (((bits >> cb) & 1u) ? acc[cb][reg] * rinv : 0.f) - z[reg][cb] * coef;
+                for (int cb = 0; cb < CPL; ++cb) dz[reg][cb] = (((bits >> cb) & 1u) ? acc[cb][reg] * rinv : 0.f) - z[reg][cb] * coef;
             } else {
 #pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) dz[cb] = ((bits >> cb) & 1u) ? acc[cb][reg] : 0.f;
+                for (int cb = 0; cb < CPL; ++cb) dz[reg][cb] = ((bits >> cb) & 1u) ? acc[cb][reg] : 0.f;
             }
-            for (int j = 0; j < a.ndst; ++j) {
-                T* p = a.dst + (size_t)j * a.dst_gs + (size_t)rowc * a.ldd + CPL * tj;
-                float g[CPL];
-                load_cols<CPL, T>(p, g);
+        }
+        // the planes that receive dZ (or the float32 sum of dH): the four rows of a plane are requested together
+        if constexpr (ACC) {
+            float g[4][CPL];
 #pragma unroll
-                for (int cb = 0; cb < CPL; ++cb) g[cb] = stored<T>(g[cb] + dz[cb]);
-                if (ok) store_cols<CPL, T>(p, g);
+            for (int reg = 0; reg < 4; ++reg) {
+                const int row = r0 + 4 * reg + tg;
+                const int rowc = row < a.n ? row : a.n - 1;
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) g[reg][cb] = 0.f;
+                if (!a.dh_first) load_cols<CPL, float>(a.dh + (size_t)rowc * DG + CPL * tj, g[reg]);
+            }
+#pragma unroll
+            for (int reg = 0; reg < 4; ++reg) {
+                const int row = r0 + 4 * reg + tg;
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) g[reg][cb] += dz[reg][cb];
+                if (row < a.n) store_cols<CPL, float>(a.dh + (size_t)row * DG + CPL * tj, g[reg]);
+            }
+        } else {
+            for (int j = 0; j < a.ndst; ++j) {
+                float g[4][CPL];
+#pragma unroll
+                for (int reg = 0; reg < 4; ++reg) {
+                    const int row = r0 + 4 * reg + tg;
+                    const int rowc = row < a.n ? row : a.n - 1;
+                    load_cols<CPL, T>(a.dst + (size_t)j * a.dst_gs + (size_t)rowc * a.ldd + CPL * tj, g[reg]);
+                }
+#pragma unroll
+                for (int reg = 0; reg < 4; ++reg) {
+                    const int row = r0 + 4 * reg + tg;
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) g[reg][cb] = stored<T>(g[reg][cb] + dz[reg][cb]);
+                    if (row < a.n) store_cols<CPL, T>(a.dst + (size_t)j * a.dst_gs + (size_t)row * a.ldd + CPL * tj, g[reg]);
+                }
             }
         }
         if (DEAL && deal.on) {

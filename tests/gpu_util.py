@@ -230,6 +230,7 @@ def audit_layer_backward(c: Case, W, Y, dY, tag, bar=f32_bar, dw_rtol=1e-4, max_
         assert not bad.any(), name
     # dW sums n products per entry in float32 (per-wave partial sums, then a fixed tree)
     err = np.abs(dWg - dWr).max(axis=(1, 2)) / np.abs(dWr).max(axis=(1, 2))
-    print(f"[{tag}] dW: max error per block relative to its largest entry {", ".join(f"{e:.2e}" for e in err)}", flush=True)
+    shown = ", ".join(f"{e:.2e}" for e in err)
+    print(f"[{tag}] dW: max error per block relative to its largest entry {shown}", flush=True)
     assert (err <= dw_rtol).all()
     return int(flips.sum())

@@ -35,9 +35,11 @@ def test_spmm_noalloc_matches_spmm_on_two_calls_in_a_row():
             for transpose in (False, True):
                 want = gsr.gsr_spmm(g, x, transpose=transpose)
                 got = torch.full_like(want, float("nan"))
-                before = torch.cuda.memory_allocated()
+                # allocations made through torch's allocator since the process started (frees by the garbage collector,
+                # which other tests' tensors may meet here, do not count)
+                before = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
                 gsr.gsr_spmm_noalloc(g, x, got, transpose=transpose)
-                assert torch.cuda.memory_allocated() == before
+                assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == before
                 torch.cuda.synchronize()
                 assert torch.equal(got, want), (n, width, transpose)
     # a width without a tiled path takes the row-per-wave kernel, which needs no scratch at all
