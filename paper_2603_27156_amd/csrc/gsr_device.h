@@ -821,13 +821,33 @@ __device__ __forceinline__ void tile_gather_rows(const CsrView& g, const float* 
     if (has_hub) hub_rows_fill<DG>(g, hub_part, r0, s_rp, st, lane);
 }
 
-// sum of the first-pass partial rows of every split row of the tile into st
+// sum of the first-pass partial rows of every split row of the tile into st.  The sixteen rows look up their chunk
+// ranges side by side (lane r for row r: one chain of dependent loads instead of sixteen), then each split row's
+// partial rows are added in chunk order, sixteen loads in flight.
 template <int DG>
 __device__ __forceinline__ void hub_rows_fill(const CsrView& g, const float* __restrict__ hub_part, int r0, const int* s_rp,
                                               float* st, int lane) {
+    int q0v = 0, q1v = 0;
+    if (lane < 16 && (s_rp[lane + 1] - s_rp[lane]) > g.hub_threshold) {
+        const int h = find_hub(g, r0 + lane);
+        q0v = g.hub_cptr[h];
+        q1v = g.hub_cptr[h + 1];
+    }
     for (int r = 0; r < 16; ++r) {
-        const bool hub = (s_rp[r + 1] - s_rp[r]) > g.hub_threshold;
-        if (hub && lane < DG) st[r * (DG + 1) + lane] = hub_row_sum<DG>(g, hub_part, r0 + r, lane);
+        int q = __builtin_amdgcn_readlane(q0v, r);
+        const int q1 = __builtin_amdgcn_readlane(q1v, r);
+        if (q1 <= q) continue;                 // not a split row
+        const int c = lane < DG ? lane : 0;
+        float acc = 0.f;
+        for (; q + 16 <= q1; q += 16) {
+            float v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = hub_part[(size_t)(q + u) * DG + c];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) acc += v[u];
+        }
+        for (; q < q1; ++q) acc += hub_part[(size_t)q * DG + c];
+        if (lane < DG) st[r * (DG + 1) + lane] = acc;
     }
 }
 
