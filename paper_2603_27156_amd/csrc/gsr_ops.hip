@@ -95,12 +95,22 @@ __device__ __forceinline__ void store_acc_rows(const f32x4 (&acc)[W / 16], const
     }
 }
 
+// Widths 32 and 64: the sums of a tile in ordinary arithmetic into an LDS tile (gather_dense_rows: on this chip the
+// float32 matrix instructions do not run beside the vector pipe, and a 16-row product spends fifteen rows of every
+// edge on zeros), rows stored from there; width 16: on the matrix cores, rows stored from the accumulators.
 template <int W, bool DEAL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k_spmm_tile(CsrView g, int n, int tiles, const float* __restrict__ x, int64_t ldx,
                                                    float* __restrict__ y, int64_t ldy, const float* __restrict__ hub_part,
                                                    int* draws, int* draws_done) {
-    __shared__ TileLds lds[4];
-    TileLds& L = lds[threadIdx.x >> 6];
+    constexpr int LR = W + 1, CPL = W / 16;
+    constexpr bool ROWS = W >= 32;
+    struct Wave {
+        TileLds t;
+        float st[ROWS ? 16 * LR : 1];
+    };
+    __shared__ Wave lds[4];
+    Wave& Wv = lds[threadIdx.x >> 6];
+    TileLds& L = Wv.t;
     const int lane = lane_id();
     TileWalk<DEAL> walk(g, tiles, draws, draws_done);
     while (walk.more()) {
@@ -110,14 +120,31 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
         const int rpv = tile_rp_load(g, r0, n, lane);
         const bool has_hub = tile_begin(g, rpv, L.rp, lane);
         if (walk.dealt(g, rpv, L.rp, has_hub)) { walk.next(g); continue; }
-        f32x4 acc[W / 16];
+        if constexpr (ROWS) {
+            tile_gather_rows<W>(g, hub_part, has_hub, r0, L.rp, Wv.st, lane, [&](int e_a, int e_b) {
+                gather_dense_rows<W, 8>(g, x, ldx, __builtin_amdgcn_readfirstlane(e_a), __builtin_amdgcn_readfirstlane(e_b), L.rp,
+                                        L.ebuf, lane, Wv.st);
+            });
+            wave_sync();
+            // four rows per store instruction, CPL adjacent columns per lane
 #pragma unroll
-        for (int cb = 0; cb < W / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        tile_ranges(g, has_hub, L.rp, [&](int e_a, int e_b) {
-            gather_dense_mfma<W, float, 16>(g, x, ldx, __builtin_amdgcn_readfirstlane(e_a), __builtin_amdgcn_readfirstlane(e_b),
-                                            L.rp, L.ebuf, lane, acc);
-        });
-        store_acc_rows<W>(acc, g, hub_part, has_hub, r0, n, L.rp, y, ldy, lane);
+            for (int reg = 0; reg < 4; ++reg) {
+                const int rr = 4 * reg + (lane >> 4), row = r0 + rr;
+                float v[CPL];
+#pragma unroll
+                for (int cb = 0; cb < CPL; ++cb) v[cb] = Wv.st[rr * LR + CPL * (lane & 15) + cb];
+                if (row < n) store_cols<CPL, float>(y + (size_t)row * ldy + CPL * (lane & 15), v);
+            }
+        } else {
+            f32x4 acc[W / 16];
+#pragma unroll
+            for (int cb = 0; cb < W / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+            tile_ranges(g, has_hub, L.rp, [&](int e_a, int e_b) {
+                gather_dense_mfma<W, float, 16>(g, x, ldx, __builtin_amdgcn_readfirstlane(e_a), __builtin_amdgcn_readfirstlane(e_b),
+                                                L.rp, L.ebuf, lane, acc);
+            });
+            store_acc_rows<W>(acc, g, hub_part, has_hub, r0, n, L.rp, y, ldy, lane);
+        }
         walk.next(g);
     }
     walk.finish();
