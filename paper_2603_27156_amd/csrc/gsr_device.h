@@ -547,6 +547,28 @@ struct RecEdge {
     uint32_t mlo, mhi;
 };
 
+// Dealing 16-bit record values to a lane's four columns with two byte permutes.  The window of four slots is two
+// words (slot t in bytes 2t, 2t+1); column c takes slot popcount(mask bits below c) if its bit is set, else zero.
+// For each of the 16 values of the lane's four mask bits a table holds the two v_perm_b32 selectors that build
+// (column 0 | column 1 << 16) and (column 2 | column 3 << 16) from the window (selector byte 0x0c yields zero).
+// The table sits in LDS (16 entries of 8 bytes, one ds_read_b64 per staged edge and lane).
+struct DealLut {
+    uint2 sel[16];
+};
+__device__ __forceinline__ void deal_lut_fill(DealLut& l) {
+    if (threadIdx.x < 16) {
+        const uint32_t nib = threadIdx.x;
+        uint32_t s[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t t = (uint32_t)__popc(nib & ((1u << c) - 1u));
+            s[c] = ((nib >> c) & 1u) ? ((2u * t + 1u) << 8 | (2u * t)) : 0x0c0cu;
+        }
+        l.sel[nib] = make_uint2(s[0] | s[1] << 16, s[2] | s[3] << 16);
+    }
+    __syncthreads();
+}
+
 // acc += P * scatter(V, I) over the edges [e_a, e_b) of ordinary rows (Section 4.1, eq. (10)).
 // The record of neighbour j is its k kept values in ascending column order plus a DG-bit column
 // mask.  A lane's CPL adjacent columns occupy adjacent slots of the record, starting at
@@ -558,7 +580,8 @@ template <int DG, typename T, int MAXB, bool ONE_ROW = false>
 __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* __restrict__ vals,
                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
                                                     int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, int lane,
-                                                    f32x4 (&acc)[DG / 16]) {
+                                                    f32x4 (&acc)[DG / 16], const DealLut* lut = nullptr) {
+    constexpr bool PERM = sizeof(T) == 2 && DG == 64 && !ONE_ROW;     // (callers of that case pass the table)
     using M = typename MaskOf<DG>::type;
     constexpr int CPL = DG / 16, NW = sizeof(T) == 4 ? CPL : CPL / 2 + 1;
     const int i16 = lane & 15, kk = lane >> 4, bp = CPL * i16;
@@ -601,6 +624,33 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
                     nib[u] |= at << 31;
                 }
                 p[u] = (ONE_ROW || (int)rbuf[ei] == i16) ? er.a : 0.f;
+            }
+            if constexpr (PERM) {
+                uint32_t o01[GB], o23[GB];      // columns (0 | 1 << 16) and (2 | 3 << 16) of every staged edge, as bf16
+#pragma unroll
+                for (int u = 0; u < GB; ++u) {
+                    const uint32_t shift = (nib[u] >> 31) * 16u;
+                    const uint32_t lo = __builtin_amdgcn_alignbit(w[u][1], w[u][0], shift);
+                    const uint32_t hi = __builtin_amdgcn_alignbit(w[u][2], w[u][1], shift);
+                    const uint2 sel = lut->sel[nib[u] & 15u];
+                    o01[u] = __builtin_amdgcn_perm(hi, lo, sel.x);
+                    o23[u] = __builtin_amdgcn_perm(hi, lo, sel.y);
+                }
+#pragma unroll
+                for (int u = 0; u < GB; u += 4) {
+                    bf16x4 ph, pm, pl;
+                    split_p4(p + u, ph, pm, pl);
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) {
+                        const uint32_t* o = cb < 2 ? o01 : o23;
+                        const bf16x4 b = (cb & 1) ? pack_upper4(o[u], o[u + 1], o[u + 2], o[u + 3])
+                                                  : pack_lower4(o[u], o[u + 1], o[u + 2], o[u + 3]);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ph, b, acc[cb], 0, 0, 0);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pm, b, acc[cb], 0, 0, 0);
+                        acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl, b, acc[cb], 0, 0, 0);
+                    }
+                }
+                return;
             }
             uint32_t bq[sizeof(T) == 4 ? 1 : GB][CPL];   // dealt-out values (float bits) of the 16-bit variant
 #pragma unroll

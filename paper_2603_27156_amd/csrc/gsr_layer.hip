@@ -73,6 +73,8 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
     WaveLds<DG, 1>& L = lds[wave];
     float* st_h = L.st[0];
     __shared__ typename std::conditional<B3, WLdsB3<DG>, WLds<DG>>::type wl;
+    __shared__ DealLut dlut;
+    if constexpr (sizeof(T) == 2 && DG == 64) deal_lut_fill(dlut);
     if constexpr (B3) load_w_lds_b3<DG>(a.w, a.ldw, false, wl);
     else load_w_lds<DG>(a.w, a.ldw, false, wl);
     f32x4 dw[WITH_DW ? DG / 16 : 1][WITH_DW ? DG / 16 : 1];
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
             tile_gather<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, hacc, [&](int e_a, int e_b) {
                 gather_records_mfma<DG, T, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
                                               __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
-                                              lane, hacc);
+                                              lane, hacc, &dlut);
             });
         }
         if constexpr (WITH_DW) {

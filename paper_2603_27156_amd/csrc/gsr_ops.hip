@@ -163,6 +163,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
         float st[sizeof(T) == 4 ? 16 * LR : 1];
     };
     __shared__ Wave lds[4];
+    __shared__ DealLut dlut;
+    if constexpr (sizeof(T) == 2 && DG == 64) deal_lut_fill(dlut);
     Wave& W = lds[threadIdx.x >> 6];
     TileLds& L = W.t;
     const int lane = lane_id();
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
             tile_ranges(g, has_hub, L.rp, [&](int e_a, int e_b) {
                 gather_records_mfma<DG, T, 8>(g, vals, masks, k, __builtin_amdgcn_readfirstlane(e_a),
                                               __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
-                                              lane, acc);
+                                              lane, acc, &dlut);
             });
             store_acc_rows<DG>(acc, g, hub_part, has_hub, r0, n, L.rp, h_out, DG, lane);
         }
