@@ -581,7 +581,7 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
                                                     int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, int lane,
                                                     f32x4 (&acc)[DG / 16], const DealLut* lut = nullptr) {
-    constexpr bool PERM = sizeof(T) == 2 && DG == 64 && !ONE_ROW;     // (callers of that case pass the table)
+    constexpr bool PERM = sizeof(T) == 2 && !ONE_ROW;     // (callers of that case pass the table)
     using M = typename MaskOf<DG>::type;
     constexpr int CPL = DG / 16, NW = sizeof(T) == 4 ? CPL : CPL / 2 + 1;
     const int i16 = lane & 15, kk = lane >> 4, bp = CPL * i16;
@@ -626,15 +626,20 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
                 p[u] = (ONE_ROW || (int)rbuf[ei] == i16) ? er.a : 0.f;
             }
             if constexpr (PERM) {
-                uint32_t o01[GB], o23[GB];      // columns (0 | 1 << 16) and (2 | 3 << 16) of every staged edge, as bf16
+                // columns (0 | 1 << 16) and, with four columns per lane, (2 | 3 << 16) of every staged edge, as bf16
+                uint32_t o01[GB], o23[CPL == 4 ? GB : 1];
 #pragma unroll
                 for (int u = 0; u < GB; ++u) {
                     const uint32_t shift = (nib[u] >> 31) * 16u;
                     const uint32_t lo = __builtin_amdgcn_alignbit(w[u][1], w[u][0], shift);
-                    const uint32_t hi = __builtin_amdgcn_alignbit(w[u][2], w[u][1], shift);
                     const uint2 sel = lut->sel[nib[u] & 15u];
-                    o01[u] = __builtin_amdgcn_perm(hi, lo, sel.x);
-                    o23[u] = __builtin_amdgcn_perm(hi, lo, sel.y);
+                    if constexpr (CPL == 4) {
+                        const uint32_t hi = __builtin_amdgcn_alignbit(w[u][2], w[u][1], shift);
+                        o01[u] = __builtin_amdgcn_perm(hi, lo, sel.x);
+                        o23[u] = __builtin_amdgcn_perm(hi, lo, sel.y);
+                    } else {
+                        o01[u] = __builtin_amdgcn_perm(0u, lo, sel.x);      // (two mask bits: the window is one word)
+                    }
                 }
 #pragma unroll
                 for (int u = 0; u < GB; u += 4) {

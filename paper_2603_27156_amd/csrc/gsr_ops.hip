@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
     };
     __shared__ Wave lds[4];
     __shared__ DealLut dlut;
-    if constexpr (sizeof(T) == 2 && DG == 64) deal_lut_fill(dlut);
+    if constexpr (sizeof(T) == 2) deal_lut_fill(dlut);
     Wave& W = lds[threadIdx.x >> 6];
     TileLds& L = W.t;
     const int lane = lane_id();
