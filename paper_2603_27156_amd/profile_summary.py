@@ -45,6 +45,14 @@ def kernel_class(name: str):
         return "tie_fixup"
     if "k_head" in name:
         return "head"
+    if "k_spmm_tile<" in name:
+        return "gsr_spmm"
+    if "k_gs_tile<" in name:
+        return "gsr_group_sparse"
+    if "k_aggregate_tile<" in name:
+        return "gsr_spmm_compressed"
+    if "k_slot_tile<" in name:
+        return "slot_block"
     return None
 
 
