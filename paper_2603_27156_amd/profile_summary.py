@@ -28,7 +28,7 @@ import subprocess
 
 def kernel_class(name: str):
     """bench.py's kernel class of a kernel name, or None."""
-    m = re.search(r"k_block<\d+, [\w:]+, (-?\d+), (true|false), (true|false)>", name)
+    m = re.search(r"k_block<\d+, [\w:]+, (-?\d+), (true|false), (true|false)[,>]", name)
     if m:
         if m.group(1) == "1":
             return "block_forward"
