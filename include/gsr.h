@@ -170,7 +170,7 @@ gsr_status_t gsr_group_sparse(const void* x, int64_t n, int32_t dg, int64_t ld, 
 
 /* Y = A X (transpose = 0) or A^T X (transpose = 1) for dense float32 X: device n x width, row
  * strides ldx / ldy elements.  The plain neighbour aggregation of Section 3, eq. (2).
- * Widths 32 and 64 with 8- / 16-byte aligned rows take the tiled path, which keeps the
+ * Widths 16, 32 and 64 with 4- / 8- / 16-byte aligned rows take the tiled path, which keeps the
  * first-pass sums of rows longer than "hub_threshold" in a buffer owned by the graph: two calls
  * on the same graph must not overlap on different streams. */
 gsr_status_t gsr_spmm(const gsr_graph_t* g, const float* x, int64_t ldx, int32_t width, float* y,
