@@ -113,7 +113,7 @@ const char* gsr_version(void);
 /* Process-wide tunables, read by the next gsr_graph_create:
  *   "hub_threshold"   rows with more stored entries than this are reduced in two passes (Section 2 notes nets
  *                     with more than 8,000 neighbours); 0, the default: 512, or 64 on graphs whose mean row has
- *                     64 stored entries or more
+ *                     64 stored entries or more and on graphs with fewer than four 16-row tiles per resident wave
  *   "hub_chunk"       neighbours per first-pass partial sum; 0, the default: 64, or 256 on such graphs
  *   "max_workgroups"  workgroups of the persistent kernels, multiple of 8 (0: as many as stay resident, at most 4 per CU)
  *   "profile"         bit mask of kernel classes to time (see gsr_profile_read); read at once */
