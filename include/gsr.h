@@ -125,7 +125,8 @@ gsr_status_t gsr_set_option(const char* key, int64_t value);
  * of launches of one class since the last gsr_profile_reset.  Classes: 0 block forward,
  * 1 block inverse, 2 block inverse + weight gradient, 3 data gradient, 4 group sum / record,
  * 5 hub first pass, 6 dW reduction (on large graphs it is part of class 3), 7 head, 8 layout copy, 9 records of
- * near-tie rows written again (save_indices == 2).  Not thread-safe. */
+ * near-tie rows written again (save_indices == 2), 10 weight gradient dW_i = H^T dY_i (class 2 is no longer launched:
+ * the inverse of the backward runs as class 1).  Not thread-safe. */
 gsr_status_t gsr_profile_read(int32_t kernel_class, double* total_ms, int64_t* launches);
 gsr_status_t gsr_profile_reset(void);
 const char* gsr_profile_class_name(int32_t kernel_class);

@@ -102,7 +102,7 @@ def gsr_set_option(key: str, value: int) -> None:
     _check(lib().gsr_set_option(key.encode(), C.c_int64(value)))
 
 
-KERNEL_CLASSES = 10
+KERNEL_CLASSES = 11
 
 
 def gsr_profile_reset() -> None:

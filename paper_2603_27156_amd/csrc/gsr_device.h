@@ -1112,11 +1112,11 @@ struct Record {
 };
 
 // Bits of the quarter's columns that belong to the row's k largest entries (x: the quarter's QW
-// values; valid: the row exists; q: the quarter; key: receives the order-preserving integer images the search ran on).
-// All four lanes of a row must call it together.
+// values; valid: the row exists; q: the quarter).  All four lanes of a row must call it together.
 template <int DG, int KS>
-__device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int k, bool valid, int q, uint32_t (&key)[DG / 4]) {
+__device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int k, bool valid, int q) {
     constexpr int QW = DG / 4;
+    uint32_t key[QW];
     uint32_t top = 0u;
 #pragma unroll
     for (int j = 0; j < QW; ++j) {
@@ -1236,12 +1236,11 @@ __device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int n
 #pragma unroll
     for (int j = 0; j < QW; ++j) x[j] = st[r * LR + q * QW + j];
     uint32_t msel;
-    uint32_t key[QW];
     if (given) {
         const M m = out.mask[r0 + r < n ? r0 + r : n - 1];
         msel = (uint32_t)(m >> (QW * q)) & ((1u << QW) - 1u);
     } else {
-        msel = select_quarter<DG, KS>(x, k, r0 + r < n, q, key);
+        msel = select_quarter<DG, KS>(x, k, r0 + r < n, q);
     }
     uint32_t all[4];
     quarter_all(msel | (uint32_t)__popc(msel) << 16, all);
@@ -1254,24 +1253,16 @@ __device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int n
     else
         mask = (all[0] & 0xFFu) | (all[1] & 0xFFu) << 8 | (all[2] & 0xFFu) << 16 | (all[3] & 0xFFu) << 24;
     if (tie.count && !given) {
-        // near-tie test: smallest kept and largest dropped value (found on the integer images the search ran on:
-        // integer min / max need no float canonicalisation) and the largest magnitude of the row
-        uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
-        float am = 0.f;
+        // near-tie test on the row's values: smallest kept, largest dropped, largest magnitude
+        float vk = __builtin_huge_valf(), vr = -__builtin_huge_valf(), am = 0.f;
 #pragma unroll
         for (int j = 0; j < QW; ++j) {
             const bool bit = (msel >> j) & 1u;
-            kmin = min(kmin, bit ? key[j] : 0xFFFFFFFFu);
-            kmax = max(kmax, bit ? 0u : key[j]);
+            vk = bit ? fminf(vk, x[j]) : vk;
+            vr = bit ? vr : fmaxf(vr, x[j]);
             am = fmaxf(am, fabsf(x[j]));
         }
-        kmin = ~quarter_max(~kmin); kmax = quarter_max(kmax); am = quarter_fmax(am);
-        // back from the image to the value (-0 was mapped to +0, which leaves the gap unchanged)
-        auto value_of = [](uint32_t kk) {
-            const uint32_t t = kk << KS;
-            return __uint_as_float((t & 0x80000000u) ? t ^ 0x80000000u : ~t & (0xFFFFFFFFu << KS));
-        };
-        const float vk = value_of(kmin), vr = value_of(kmax);
+        vk = quarter_fmin(vk); vr = quarter_fmax(vr); am = quarter_fmax(am);
         const float gap = vk - vr, bar = tie.tol * am;
         if (q == 0 && r0 + r < n && k < DG && gap <= bar) {
             const int pos = atomicAdd(tie.count, 1);

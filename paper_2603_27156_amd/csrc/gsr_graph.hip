@@ -259,6 +259,8 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
     w.hub_partial2 = off;
     off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
+    w.h = off;               // (float32 storage only: the bf16 backward keeps H on chip)
+    if (b == 4) off += align_up(n * dgs * sizeof(float));
     w.total = off;
     return w;
 }
@@ -369,7 +371,7 @@ gsr_status_t gsr_profile_reset(void) {
 
 const char* gsr_profile_class_name(int32_t kernel_class) {
     static const char* names[KC_COUNT] = {"block_forward", "block_inverse", "block_backward", "grad", "group_sum",
-                                          "hub_first_pass", "dw_reduce", "head", "layout_copy", "tie_fixup"};
+                                          "hub_first_pass", "dw_reduce", "head", "layout_copy", "tie_fixup", "weight_gradient"};
     return (kernel_class >= 0 && kernel_class < KC_COUNT) ? names[kernel_class] : "";
 }
 

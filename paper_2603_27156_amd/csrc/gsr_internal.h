@@ -48,6 +48,7 @@ enum KernelClass {
     KC_HEAD,
     KC_COPY,
     KC_TIE,            // records of listed rows written again with their kept column sets
+    KC_DW,             // k_dw: dW_i = H^T dY_i
     KC_COUNT
 };
 // Records a HIP event on `s` before and after the launches made while it is alive, if the
@@ -117,6 +118,7 @@ struct LayerWs {
     size_t rec_vals[kMaxRecordSlots];  // per slot and sub-plane: compressed values  [n][k] of T
     size_t rec_mask[kMaxRecordSlots];  // per slot and sub-plane: column bit mask    [n] of uint32 (32 columns) / uint64 (64)
     size_t y0;           // Y_0 plane [n][dg] of T (C > 2); wide groups: [S][n][64]
+    size_t h;            // [n][min(dg, 64)] float: H of the block being inverted, for the weight-gradient kernel
     size_t dh;           // wide groups only: [S][n][64] float, the block gradient summed over column blocks
     size_t dw_partial;   // [grid][dg*dg] float
     size_t hub_partial;  // [max(n_chunks A, n_chunks A^T)][dg] float

@@ -53,6 +53,7 @@ struct BlockArgs {
     int* draws;             // tile counters of the dynamic sweep and the sign-off counter (not WITH_DW)
     int* draws_done;
     TieSeg<DG> tie;         // where rows that select at a near-tie are listed (count == NULL: nowhere)
+    float* h_out;           // [n][DG] float32: receives H = A scatter(V, I) of the block for k_dw (NULL: not kept)
 };
 
 // B3: the H W_i (and dW_i) products on the bf16 matrix pipe from three-term splits (mfma_tile_b3), with W_i kept
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
         // float32 forward: the sums in ordinary arithmetic (329 us against 370 through the matrix cores on the 1M-node
         // workload).  The inverse kernels keep the matrix product: at two waves per SIMD the row sums' LDS round trips are
         // not hidden (531 us against 513), and the plain and the fused inverse must rebuild the same bits.
-        if constexpr (sizeof(T) == 4 && SIGN > 0) {
+        if constexpr (sizeof(T) == 4 && !WITH_DW) {
             tile_gather_rows<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
                 gather_records_rows<DG, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
                                            __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
@@ -149,6 +150,18 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
                 for (int cb = 0; cb < CPL; ++cb) gy[reg][cb] = r0 + 4 * reg + tg < a.n ? gy[reg][cb] : 0.f;   // rows past the end
         }
         wave_sync();
+        if constexpr (!WITH_DW) {
+            if (a.h_out) {                                 // H leaves for the weight-gradient kernel, four rows per store
+#pragma unroll
+                for (int reg = 0; reg < 4; ++reg) {
+                    const int rr = 4 * reg + tg, row = r0 + rr;
+                    float hv[CPL];
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) hv[cb] = st_h[rr * LR + CPL * tj + cb];
+                    if (row < a.n) store_cols<CPL, float>(a.h_out + (size_t)row * DG + CPL * tj, hv);
+                }
+            }
+        }
         f32x4 acc[CPL];
         if constexpr (B3) {
             mfma_tile_b3<DG>(st_h, wl, acc);               // O = H W_i in the tile register layout
@@ -213,6 +226,83 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
         __syncthreads();
         for (int i = threadIdx.x; i < DG * DG; i += 256) a.dw_partial[(size_t)blockIdx.x * DG * DG + i] = red[i];
     }
+}
+
+// dW_i = H^T dY_i as a pass of its own over H (left by the inverse kernel) and dY_i: a wave sums over the tiles of a
+// fixed sweep (so the partial sums do not depend on timing), 64 x 64 accumulators in registers, products on the bf16
+// pipe (mfma_outer_b3); workgroup partials as k_block writes them.  The inverse kernel then runs without the 64
+// accumulator registers per lane, at sixteen waves per compute unit with the row-wise sums of the forward kernel.
+template <int DG, typename T>
+struct DwArgs {
+    int n, tiles;
+    const float* h;         // [n][DG]
+    const T* dy;            // row stride ldg
+    int64_t ldg;
+    float* dw_partial;      // [gridDim.x][DG*DG]
+};
+
+template <int DG, typename T>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_dw(DwArgs<DG, T> a) {
+    constexpr int LR = DG + 1, CPL = DG / 16;
+    __shared__ float tile[4][16 * LR];
+    const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tg = lane >> 4, tj = lane & 15;
+    float* st = tile[wave];
+    f32x4 dw[DG / 16][DG / 16];
+#pragma unroll
+    for (int mb = 0; mb < DG / 16; ++mb)
+#pragma unroll
+        for (int ob = 0; ob < DG / 16; ++ob) dw[mb][ob] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const TileSweep ts = tile_sweep(a.tiles);
+    // the next tile's rows are requested while the present tile is multiplied
+    float hv[4][CPL], gy[4][CPL];
+    auto request = [&](int t) {
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) {
+            const int row = t * 16 + 4 * reg + tg;
+            const size_t rowc = (size_t)(row < a.n ? row : a.n - 1);
+            load_cols<CPL, float>(a.h + rowc * DG + CPL * tj, hv[reg]);
+            load_cols<CPL, T>(a.dy + rowc * a.ldg + CPL * tj, gy[reg]);
+        }
+    };
+    int t = ts.first;
+    if (t < ts.end) request(t);
+    while (t < ts.end) {
+        const int r0 = t * 16;
+        float g[4][CPL];
+        wave_sync();          // the tile before has been read
+#pragma unroll
+        for (int reg = 0; reg < 4; ++reg) {
+            const bool ok = r0 + 4 * reg + tg < a.n;
+#pragma unroll
+            for (int cb = 0; cb < CPL; ++cb) {
+                st[(4 * reg + tg) * LR + CPL * tj + cb] = ok ? hv[reg][cb] : 0.f;
+                g[reg][cb] = ok ? gy[reg][cb] : 0.f;          // rows past the end
+            }
+        }
+        t += ts.step;
+        if (t < ts.end) request(t);
+        wave_sync();
+        mfma_outer_b3<DG>(st, g, dw);
+    }
+    // workgroup partial of dW_i: the four waves add their accumulators in wave order
+    __shared__ float red[DG * DG];
+    for (int w = 0; w < 4; ++w) {
+        __syncthreads();
+        if (wave == w) {
+#pragma unroll
+            for (int mb = 0; mb < DG / 16; ++mb)
+#pragma unroll
+                for (int ob = 0; ob < DG / 16; ++ob)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int m = 16 * mb + 4 * (lane >> 4) + r, o = CPL * (lane & 15) + ob;
+                        if (w == 0) red[m * DG + o] = dw[mb][ob][r];
+                        else red[m * DG + o] += dw[mb][ob][r];
+                    }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < DG * DG; i += 256) a.dw_partial[(size_t)blockIdx.x * DG * DG + i] = red[i];
 }
 
 // dW_i[e] = sum over workgroup partials, as a launch of its own (used when the gradient kernel that follows has too
@@ -940,6 +1030,7 @@ struct Ctx {
     }
     T* y0() const { return (T*)(ws + lw.y0); }
     float* dh() const { return (float*)(ws + lw.dh); }
+    float* hplane() const { return (float*)(ws + lw.h); }
     float* dw_partial() const { return (float*)(ws + lw.dw_partial); }
     float* hub_part() const { return (float*)(ws + lw.hub_partial); }
     float* hub_part2() const { return (float*)(ws + lw.hub_partial2); }
@@ -1009,14 +1100,23 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
     return true;
 }
 
+// How the backward of a block takes dW_i.  float32: the inverse kernel (sixteen waves per compute unit, row-wise sums as
+// in the forward kernel, so f_i is recomputed in the arithmetic it was computed in) leaves H in memory and k_dw takes
+// H^T dY_i in a pass of its own: 476 -> 320 + 112 us per block on the 1M-node workload (-3.8 % on the step) for 512 more
+// bytes per row.  bf16 storage: the fused kernel (inverse + dW accumulators at eight waves per compute unit), whose
+// neighbour sums hide on the bf16 pipe: split 253 + 80 us against 337 fused at 1M nodes, 1,243 + 228 against 1,205 at 8M.
+template <typename T>
+constexpr bool split_dw() { return sizeof(T) == 4; }
+
 // mode 0: forward (+), 1: inverse (-), 2: inverse (-) with dW
 template <int DG, typename T>
 static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>& in, const float* w, T* plane, int64_t ld,
                              const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg, bool first_pass_done = false,
-                             TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, int ldw = DG) {
+                             TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, int ldw = DG, float* h_out = nullptr) {
     if (!first_pass_done) launch_hub_records<DG, T>(x, in);
     BlockArgs<DG, T> a;
     a.tie = tie;
+    a.h_out = h_out;
     a.g = make_view(x.g, false);
     a.n = (int)x.cfg->n; a.tiles = x.tiles;
     a.in = in; a.k = x.cfg->k;
@@ -1028,7 +1128,7 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     const bool b3 = mode != 0 || !x.g->long_rows;       // (see k_block)
     const dim3 block(64 * block_waves(mode == 2, b3));
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
-    unsigned grid;
+    unsigned grid = 0;
     auto go = [&](auto plain, auto deal, int per_cu) {
         grid = persistent_grid(x.g, per_cu);
         if (heavy_first(a.g.n_heavy, x.tiles, grid * (block.x / 64) / 4)) hipLaunchKernelGGL(deal, dim3(grid), block, 0, x.s, a);
@@ -1043,7 +1143,7 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     } else if (mode == 1) {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false, false, true>, 512);
         go(k_block<DG, T, -1, false, false, true>, k_block<DG, T, -1, false, true, true>, per_cu);
-    } else {
+    } else if constexpr (!split_dw<T>()) {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true, false, true>, 256);
         go(k_block<DG, T, -1, true, false, true>, k_block<DG, T, -1, true, true, true>, per_cu);
     }
@@ -1088,6 +1188,18 @@ static void launch_tie_fixup(const Ctx<DG, T>& x, const TieSeg<DG>& tie, const T
     ProfScope prof(KC_TIE, x.s);
     const unsigned blocks = (unsigned)std::min((tie.cap + 63) / 64, 1024);
     hipLaunchKernelGGL((k_tie_fixup<DG, T>), dim3(blocks), dim3(256), 0, x.s, tie, plane, ld, x.cfg->k, x.cfg->norm, x.cfg->eps, out);
+}
+
+// dW_i's workgroup partials from H (in x.hplane()) and dY_i; returns their number
+template <int DG, typename T>
+static unsigned launch_dw(const Ctx<DG, T>& x, const T* dy, int64_t ldg) {
+    DwArgs<DG, T> a;
+    a.n = (int)x.cfg->n; a.tiles = x.tiles; a.h = x.hplane(); a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
+    ProfScope prof(KC_DW, x.s);
+    static const int per_cu = resident_blocks((const void*)k_dw<DG, T>, 256);
+    const unsigned grid = persistent_grid(x.g, per_cu);
+    hipLaunchKernelGGL((k_dw<DG, T>), dim3(grid), dim3(256), 0, x.s, a);
+    return grid;
 }
 
 // ---- groups wider than one tile (see k_gs_wide): D/C = 64 S as S sub-planes of 64 columns -----------------------
@@ -1165,9 +1277,15 @@ static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, co
     for (int mb = 0; mb < S; ++mb)
         for (int ob = 0; ob < S; ++ob) {
             const float* wsub = wi + (size_t)mb * 64 * dgw + 64 * ob;
-            const unsigned nparts = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false,
-                                                        dy ? dy + 64 * ob : nullptr, ldg, ob > 0,
-                                                        TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw);
+            unsigned nparts = 0;
+            if (mode == 2 && split_dw<T>()) {
+                launch_block<64, T>(x, 1, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false, nullptr, 0, ob > 0,
+                                    TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, x.hplane());
+                nparts = launch_dw<64, T>(x, dy + 64 * ob, ldg);
+            } else {
+                nparts = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false,
+                                             dy ? dy + 64 * ob : nullptr, ldg, ob > 0, TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw);
+            }
             if (mode == 2) {
                 ProfScope prof(KC_DW_REDUCE, x.s);
                 hipLaunchKernelGGL(k_dw_reduce, dim3(64), dim3(1024), 0, x.s, (const float*)x.dw_partial(), (int)nparts, 64 * 64,
@@ -1306,8 +1424,15 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
             if (in_step) out_tie = x.tie_seg(layer, 0);
         }
         launch_hub_both<DG, T>(x, x.rec(i - 1, layer), dy.grp(i - 1), dy.ld);
-        const unsigned nparts =
-            launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld, true);
+        unsigned nparts;
+        if constexpr (split_dw<T>()) {
+            // X_i = Y_i - f_i(Y_{i-1}) with H kept for the weight gradient, then dW_i = H^T dY_i
+            launch_block<DG, T>(x, 1, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, nullptr, 0, true,
+                                TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, DG, x.hplane());
+            nparts = launch_dw<DG, T>(x, dy.grp(i - 1), dy.ld);
+        } else {
+            nparts = launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld, true);
+        }
         if (out.mask) launch_tie_fixup<DG, T>(x, out_tie, y.grp(i - 1), y.ld, out);
         // dW_i is summed from the partials by the first job of the gradient kernel that follows, unless that kernel
         // has so few tiles per wave that it could not make up for the late start of those workgroups (measured on

@@ -35,6 +35,8 @@ def kernel_class(name: str):
         return "block_backward" if m.group(2) == "true" else "block_inverse"
     if "k_grad<" in name:
         return "grad"
+    if "k_dw<" in name:
+        return "weight_gradient"
     if "k_sum<" in name:
         return "group_sum"
     if "k_copy_planes<" in name:
