@@ -260,7 +260,7 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     w.hub_partial2 = off;
     off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
     w.h = off;               // (float32 storage only: the bf16 backward keeps H on chip)
-    if (b == 4) off += align_up(n * dgs * sizeof(float));
+    if (b == 4 && g->split_backward) off += align_up(n * dgs * sizeof(float));
     w.total = off;
     return w;
 }
@@ -495,6 +495,7 @@ static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz,
     const int64_t hub_threshold = options().hub_threshold > 0 ? options().hub_threshold : ((long_rows || few_tiles) ? 64 : 512);
     const int64_t hub_chunk = options().hub_chunk > 0 ? options().hub_chunk : (long_rows ? 256 : 64);
     g->hub_threshold = (int32_t)hub_threshold;
+    g->split_backward = !(long_rows || (n + 15) / 16 < (int64_t)4 * g->grid);    // (not with fewer tiles than resident waves)
 
     gsr_status_t st = upload_csr(a, n, hub_threshold, hub_chunk, &g->a);
     if (st == GSR_OK) {

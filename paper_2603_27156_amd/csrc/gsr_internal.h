@@ -97,6 +97,7 @@ struct gsr_graph {
     gsr::Csr at;             // A^T (aliases `a` when symmetric)
     bool symmetric = false;
     bool has_transpose = false;
+    bool split_backward = true;   // float32: the backward of a block as inverse kernel + k_dw (large graphs), else fused
     bool long_rows = false;  // the mean row has 64 stored entries or more: nearly every row goes through the first pass
     int32_t hub_threshold = 512;
     int device = 0;

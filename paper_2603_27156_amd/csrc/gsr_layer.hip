@@ -129,7 +129,7 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
         // float32 forward: the sums in ordinary arithmetic (329 us against 370 through the matrix cores on the 1M-node
         // workload).  The inverse kernels keep the matrix product: at two waves per SIMD the row sums' LDS round trips are
         // not hidden (531 us against 513), and the plain and the fused inverse must rebuild the same bits.
-        if constexpr (sizeof(T) == 4 && !WITH_DW) {
+        if constexpr (sizeof(T) == 4) {
             tile_gather_rows<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
                 gather_records_rows<DG, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
                                            __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
@@ -1105,8 +1105,13 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
 // H^T dY_i in a pass of its own: 476 -> 320 + 112 us per block on the 1M-node workload (-3.8 % on the step) for 512 more
 // bytes per row.  bf16 storage: the fused kernel (inverse + dW accumulators at eight waves per compute unit), whose
 // neighbour sums hide on the bf16 pipe: split 253 + 80 us against 337 fused at 1M nodes, 1,243 + 228 against 1,205 at 8M.
+// Graphs with fewer tiles than resident waves, or with all rows in the first pass (a launch there is at most one short
+// tile per wave, and two more launches per block cost more than the occupancy gains: 0.56 against 0.70 ms per step on
+// the 2,000-node workload, 487 against 496 ms on the Table-1-shaped one) keep the fused kernel in float32 as well; it
+// uses the same row-wise sums, so whichever way a block's backward runs it rebuilds the bits the plain inverse
+// rebuilds.  (The 100k-node workload, 1.5 tiles per wave, is better split: 12.0 against 12.3 ms.)
 template <typename T>
-constexpr bool split_dw() { return sizeof(T) == 4; }
+static bool split_dw(const gsr_graph_t* g) { return sizeof(T) == 4 && g->split_backward; }
 
 // mode 0: forward (+), 1: inverse (-), 2: inverse (-) with dW
 template <int DG, typename T>
@@ -1143,7 +1148,7 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     } else if (mode == 1) {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false, false, true>, 512);
         go(k_block<DG, T, -1, false, false, true>, k_block<DG, T, -1, false, true, true>, per_cu);
-    } else if constexpr (!split_dw<T>()) {
+    } else {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true, false, true>, 256);
         go(k_block<DG, T, -1, true, false, true>, k_block<DG, T, -1, true, true, true>, per_cu);
     }
@@ -1278,7 +1283,7 @@ static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, co
         for (int ob = 0; ob < S; ++ob) {
             const float* wsub = wi + (size_t)mb * 64 * dgw + 64 * ob;
             unsigned nparts = 0;
-            if (mode == 2 && split_dw<T>()) {
+            if (mode == 2 && split_dw<T>(x.g)) {
                 launch_block<64, T>(x, 1, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false, nullptr, 0, ob > 0,
                                     TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, x.hplane());
                 nparts = launch_dw<64, T>(x, dy + 64 * ob, ldg);
@@ -1425,7 +1430,7 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         }
         launch_hub_both<DG, T>(x, x.rec(i - 1, layer), dy.grp(i - 1), dy.ld);
         unsigned nparts;
-        if constexpr (split_dw<T>()) {
+        if (split_dw<T>(x.g)) {
             // X_i = Y_i - f_i(Y_{i-1}) with H kept for the weight gradient, then dW_i = H^T dY_i
             launch_block<DG, T>(x, 1, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, nullptr, 0, true,
                                 TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, DG, x.hplane());
