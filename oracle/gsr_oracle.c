@@ -42,9 +42,15 @@
  *   orc_head          output layer y = f(X^L) in R^N of Section 3 as a linear map to a
  *                     scalar per node, with mean-squared-error loss (workload's choice).
  *
- * No pin exists for the literal gradient example at the end of Section 4.4 (its
- * numbers follow no consistent rule) nor for the conventional backward example of
- * Section 4.1 (4 of 16 entries are misprinted): parity unpinned for those two.
+ *   orc_gs_near_tie   which rows select at a near-tie (gap at the selection boundary against a
+ *                     tolerance times the row's largest magnitude, in float32), for the selective
+ *                     form of Section 4.2's save: indices kept for those rows only.
+ *
+ * Every function here is pinned by tests that do not call it to check itself (printed examples,
+ * brute force, closed forms, finite differences, variants against each other).  Two printed
+ * examples are not used as pins because their numbers follow no consistent rule: the gradient
+ * matrices that end Section 4.4 and the conventional backward example of Section 4.1 (4 of 16
+ * entries misprinted).
  */
 #include <math.h>
 #include <stdint.h>
