@@ -163,7 +163,7 @@ gsr_status_t gsr_graph_destroy(gsr_graph_t* g);
 /* ---- operators exposed as the paper defines them ----
  *
  * GS(X, k) -> (V, I), Section 4.1.  x: device, n rows of dg values of `dtype`, row stride ld
- * elements; dg in [1, 64].  vals_out: device n*k of `dtype`; idx_out: device n*k int32, slots
+ * elements; dg in [1, 256].  vals_out: device n*k of `dtype`; idx_out: device n*k int32, slots
  * in ascending column order.  Largest by signed value; ties to the lowest column; -0 == +0;
  * inputs must be finite.  norm/eps as in gsr_norm_t (V is the scaled value). */
 gsr_status_t gsr_group_sparse(const void* x, int64_t n, int32_t dg, int64_t ld, int32_t k, int32_t dtype,

@@ -51,6 +51,81 @@ __global__ __launch_bounds__(256) void k_group_sparse(const T* __restrict__ x, i
     }
 }
 
+// Rows of 65 to 256 columns: one wave per row, lane c owning columns c, c + 64, c + 128, c + 192 (those past dg hold
+// padding that can never be kept ahead of a real column).  The k-th largest value is found by bisection on the
+// order-preserving integer image of the values, count = the popcounts of up to four ballots; ties go to the lowest
+// columns of the row.
+template <typename T>
+__global__ __launch_bounds__(256) void k_group_sparse_wide(const T* __restrict__ x, int64_t n, int dg, int64_t ld, int k,
+                                                           int norm, float eps, T* __restrict__ vals, int32_t* __restrict__ idx) {
+    const int lane = lane_id();
+    const int ns = (dg + 63) / 64;
+    const int64_t nwaves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t row = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; row < n; row += nwaves) {
+        float v[4];
+        uint32_t key[4];
+        float ss = 0.f;
+        uint32_t top = 0u;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int c = 64 * s + lane;
+            const bool real = s < ns && c < dg;
+            v[s] = real ? to_float(x[row * ld + c]) : 0.f;
+            ss += v[s] * v[s];
+            uint32_t u = __float_as_uint(v[s]);
+            if (u == 0x80000000u) u = 0u;                                   // -0 -> +0
+            key[s] = real ? ((u & 0x80000000u) ? ~u : (u | 0x80000000u)) : 0u;      // padding: below every finite value
+            top = max(top, key[s]);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) top = max(top, (uint32_t)__shfl_xor((int)top, off, 64));
+        auto count_ge = [&](uint32_t t) {
+            int cnt = 0;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) cnt += __popcll(ballot(key[s] >= t));
+            return cnt;
+        };
+        uint32_t lo = 0u, hi = top + 1u;                 // at least k keys are >= lo, fewer than k are >= hi
+        if (k < dg) {
+            for (int round = 0; round < 33 && hi - lo > 1u; ++round) {
+                const uint32_t mid = lo + ((hi - lo) >> 1);
+                const int cnt = count_ge(mid);
+                if (cnt >= k) lo = mid; else hi = mid;
+                if (cnt == k) break;
+            }
+        }
+        // kept: every key above lo, and of those equal to lo the lowest columns (padding keys are 0 = lo only when k >= dg,
+        // where every real column is kept and none of the padding)
+        int need = k;
+        uint64_t gt[4], eq[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bool real = s < ns && 64 * s + lane < dg;
+            gt[s] = ballot(real && key[s] > lo);
+            eq[s] = ballot(real && key[s] == lo);
+            need -= __popcll(gt[s]);
+        }
+        const float scale = norm == GSR_NORM_RMS ? __builtin_amdgcn_rsqf(sub_sum<64>(ss) * (1.0f / (float)dg) + eps) : 1.f;
+        const uint64_t below = ((uint64_t)1 << lane) - 1;
+        int pos0 = 0;                                     // kept columns in the sub-rows before s
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int ties = __popcll(eq[s]);
+            const int take = need < 0 ? 0 : (need < ties ? need : ties);
+            // the `take` lowest lanes of eq[s]
+            const bool tie_kept = ((eq[s] >> lane) & 1ull) && __popcll(eq[s] & below) < take;
+            const uint64_t kept = gt[s] | ballot(tie_kept);
+            if ((kept >> lane) & 1ull) {
+                const int pos = pos0 + __popcll(kept & below);
+                vals[row * k + pos] = from_float<T>(norm == GSR_NORM_RMS ? v[s] * scale : v[s]);
+                idx[row * k + pos] = 64 * s + lane;
+            }
+            pos0 += __popcll(kept);
+            need -= take;
+        }
+    }
+}
+
 // ---- dense aggregation Y = A X, eq. (2) -----------------------------------------------------------
 __global__ __launch_bounds__(256) void k_spmm_dense(CsrView g, int64_t n, const float* __restrict__ x, int64_t ldx,
                                                     int width, float* __restrict__ y, int64_t ldy) {
@@ -401,7 +476,7 @@ extern "C" {
 gsr_status_t gsr_group_sparse(const void* x, int64_t n, int32_t dg, int64_t ld, int32_t k, int32_t dtype, int32_t norm,
                               float eps, void* vals_out, int32_t* idx_out, void* stream) {
     if (n < 0) return fail(GSR_ERR_INVALID_ARG, "negative n");
-    if (dg < 1 || dg > 64) return fail(GSR_ERR_UNSUPPORTED, "dg=%d outside [1,64]", dg);
+    if (dg < 1 || dg > 256) return fail(GSR_ERR_UNSUPPORTED, "dg=%d outside [1,256]", dg);
     if (k < 1 || k > dg) return fail(GSR_ERR_UNSUPPORTED, "k=%d outside [1, dg=%d]", k, dg);
     if (ld < dg) return fail(GSR_ERR_INVALID_ARG, "row stride %lld below dg=%d", (long long)ld, dg);
     if (dtype != GSR_F32 && dtype != GSR_BF16) return fail(GSR_ERR_UNSUPPORTED, "dtype %d", dtype);
@@ -430,6 +505,16 @@ gsr_status_t gsr_group_sparse(const void* x, int64_t n, int32_t dg, int64_t ld, 
         return GSR_OK;
     }
     const unsigned blocks = (unsigned)std::min<int64_t>((n + 3) / 4, 8192);
+    if (dg > 64) {
+        if (dtype == GSR_F32)
+            hipLaunchKernelGGL((k_group_sparse_wide<float>), dim3(blocks), dim3(256), 0, s, (const float*)x, n, dg, ld, k, norm, eps,
+                               (float*)vals_out, idx_out);
+        else
+            hipLaunchKernelGGL((k_group_sparse_wide<bf16_t>), dim3(blocks), dim3(256), 0, s, (const bf16_t*)x, n, dg, ld, k, norm, eps,
+                               (bf16_t*)vals_out, idx_out);
+        GSR_HIP_CHECK(hipGetLastError());
+        return GSR_OK;
+    }
     if (dtype == GSR_F32)
         hipLaunchKernelGGL((k_group_sparse<float>), dim3(blocks), dim3(256), 0, s, (const float*)x, n, dg, ld, k, norm, eps,
                            (float*)vals_out, idx_out);

@@ -48,7 +48,7 @@ def test_operator_argument_validation():
     st = lib.gsr_group_sparse(None, C.c_int64(4), C.c_int32(64), C.c_int64(64), C.c_int32(65), C.c_int32(0),
                               C.c_int32(0), C.c_float(1e-5), None, None, None)
     assert st == gsr.GSR_ERR_UNSUPPORTED
-    st = lib.gsr_group_sparse(None, C.c_int64(4), C.c_int32(65), C.c_int64(65), C.c_int32(1), C.c_int32(0),
+    st = lib.gsr_group_sparse(None, C.c_int64(4), C.c_int32(257), C.c_int64(257), C.c_int32(1), C.c_int32(0),
                               C.c_int32(0), C.c_float(1e-5), None, None, None)
     assert st == gsr.GSR_ERR_UNSUPPORTED
     st = lib.gsr_group_sparse(None, C.c_int64(4), C.c_int32(64), C.c_int64(64), C.c_int32(4), C.c_int32(0),

@@ -63,7 +63,8 @@ def gs_inputs(n, dg, seed):
     return Z
 
 
-@pytest.mark.parametrize("dg,k", [(64, 16), (32, 8), (64, 1), (64, 64), (32, 32), (64, 63), (20, 5), (7, 3), (1, 1)])
+@pytest.mark.parametrize("dg,k", [(64, 16), (32, 8), (64, 1), (64, 64), (32, 32), (64, 63), (20, 5), (7, 3), (1, 1),
+                                  (128, 16), (192, 64), (192, 1), (256, 255), (256, 256), (100, 33), (65, 4)])
 @pytest.mark.parametrize("norm", ["none", "rms"])
 def test_group_sparse_f32(dg, k, norm):
     n = 1003
