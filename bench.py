@@ -59,10 +59,11 @@ def algorithmic_bytes(n, nnz, dg, k, c, b, rms):
     bwd = n * (rec + 3 * row + emit_bwd * rec) + csr
     ndst = ((c - 1) + (c - 1)) / c           # block 1 updates C-1 planes, blocks 2..C one plane each
     grad = n * (row + mask + (row if rms else 0) + 2 * row * ndst) + csr
-    # float32 runs the backward's inverse and the weight gradient as two kernels with H (float32) passed through memory:
-    # the bytes those two launches must move (their sum exceeds block_backward, the method's own figure, by 2 H rows)
-    inv = n * (rec + 2 * row + emit_bwd * rec + dg * 4) + csr
-    dwk = n * (dg * 4 + row)
+    # float32 runs the backward's inverse and the weight gradient as two kernels with H (float32) passed through memory.
+    # That H row written and read again is this implementation's doing, not the method's: it is left out, so the two
+    # figures add up to block_backward, the method's own
+    inv = n * (rec + 2 * row + emit_bwd * rec) + csr
+    dwk = n * row
     return {"block_forward": fwd, "block_backward": bwd, "grad": grad, "block_inverse": inv, "weight_gradient": dwk}
 
 
