@@ -74,6 +74,35 @@ def test_wide_step_against_oracle(n, d, c, k, l, layout, save):
         assert torch.equal(a[key], b[key]), key
 
 
+def test_wide_step_with_the_weight_gradient_in_a_pass_of_its_own():
+    """float32 graphs with at least as many tiles as resident waves run a block's backward as two kernels (inverse, then
+    dW = H^T dY from H kept in memory); a small persistent grid brings a 3,001-node graph into that regime."""
+    gsr.gsr_set_option("max_workgroups", 8)
+    try:
+        cs = wide_case(3001, 384, 2, 16, 2, "rms", PLANAR)
+        w = cs.w
+        ref = oracle.step(cs.og, cs.ocfg, w.l, cs.x0_on_grid(), cs.inp.weights, cs.inp.w_out, cs.inp.b_out, cs.inp.target, variant=2)
+        out = run_step(cs, save_indices=1)
+        for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+            assert_close(key, out[key], ref[key])
+        # and the layer call: the rebuilt input equals the plain inverse's bit for bit
+        W = cs.inp.weights[0]
+        Wd = torch.from_numpy(W).to(cs.dev)
+        Y = oracle.layer_forward(cs.og, cs.ocfg, W, cs.x0_on_grid())
+        rng = np.random.default_rng(2)
+        dY = (rng.standard_normal((w.n, w.d)) * 1e-3).astype(np.float32).astype(np.float64)
+        Xb_ref, dX_ref, dW_ref = oracle.layer_backward(cs.og, cs.ocfg, W, Y, dY)
+        yb, dyb, x = cs.to_dev(Y), cs.to_dev(dY), cs.to_dev(Y)
+        dW = torch.empty((w.c, w.dg, w.dg), dtype=torch.float32, device=cs.dev)
+        gsr.gsr_layer_backward(cs.gg, cs.gcfg, Wd, yb, dyb, dW)
+        gsr.gsr_layer_inverse(cs.gg, cs.gcfg, Wd, x)
+        assert torch.equal(yb, x)
+        assert_close("dW", dW.cpu().numpy(), dW_ref)
+        assert_close("dX", cs.to_host(dyb), dX_ref)
+    finally:
+        gsr.gsr_set_option("max_workgroups", 0)
+
+
 def test_wide_groups_on_long_rows():
     """The Table-1-shaped graph (every row through the first pass) scaled down, with the paper's model split: 384
     channels in two groups of 192."""
