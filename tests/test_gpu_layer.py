@@ -343,10 +343,18 @@ def test_directed_graph_with_mean_aggregation(name, layout):
         assert_close(key, out[key], ref[key])
 
 
-def test_step_captured_in_a_graph_replays_bit_identically():
+@pytest.mark.parametrize("save_indices,workgroups", [(0, 0), (2, 0), (2, 8), (1, 8)])
+def test_step_captured_in_a_graph_replays_bit_identically(save_indices, workgroups):
     """gsr_step only launches kernels (no allocation, no memset, no host synchronisation), so it can be captured
-    into a HIP graph.  Replays interleaved with eager steps must give the eager results bit for bit."""
-    c = case("cfg2s", PLANAR)
+    into a HIP graph.  Replays interleaved with eager steps must give the eager results bit for bit: with nothing
+    kept, with the near-tie list (whose counters a small kernel clears at the start of every step), and on a small
+    persistent grid, where the float32 backward runs as inverse kernel + weight-gradient pass."""
+    gsr.gsr_set_option("max_workgroups", workgroups)
+    try:
+        c = Case(workloads()["cfg2s"], 0, PLANAR)
+    finally:
+        gsr.gsr_set_option("max_workgroups", 0)
+    c.gcfg = gsr.Config(**{**c.gcfg.__dict__, "save_indices": save_indices, "tie_tol": 2.0 ** -6, "tie_capacity": c.w.n})
     w = c.w
     dv = c.dev
     f32 = dict(dtype=torch.float32, device=dv)
