@@ -104,7 +104,9 @@ typedef struct gsr_config {
                              (measured on 1M nodes, D/C = 64, float32: rebuilt input off by 2e-4 of its range at
                              L = 448): 2^-12 covers that depth, deeper stacks need more. */
     int32_t tie_capacity; /* save_indices == 2: rows that can be kept per block and layer; 0: N/32 + 1024.
-                             Rows beyond it are not kept and select again (gsr_step_tie_stats counts them). */
+                             Rows beyond it are not kept and select again (gsr_step_tie_stats counts them); which
+                             rows of a block those are depends on the order the waves append in, so results are
+                             bit-reproducible between runs only while nothing is dropped. */
 } gsr_config_t;
 
 const char* gsr_last_error(void);
