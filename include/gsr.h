@@ -99,11 +99,14 @@ typedef struct gsr_config {
                              iff v_k - v_(k+1) <= tie_tol * max|row| (float32 arithmetic; exact ties always
                              are).  Every other row selects again on its rebuilt values, which gives the
                              same set as long as the rebuilt row is off by less than half its gap.  The
-                             workspace grows by (L+1) * C * tie_capacity * (4 + (D/C)/8) bytes. */
+                             workspace grows by (L+1) * C * (2048 + tie_capacity * (4 + (D/C)/8)) bytes. */
     float tie_tol;        /* save_indices == 2: see above; >= 0.  Rounding of the inverse sweep grows with depth
                              (measured on 1M nodes, D/C = 64, float32: rebuilt input off by 2e-4 of its range at
                              L = 448): 2^-12 covers that depth, deeper stacks need more. */
-    int32_t tie_capacity; /* save_indices == 2: rows that can be kept per block and layer; 0: N/32 + 1024.
+    int32_t tie_capacity; /* save_indices == 2: rows that can be kept per block and layer; 0: N/32 + 1024.  Kept as
+                             sixteen sub-lists of tie_capacity / 16 places (rounded up), tile t appending to sub-list
+                             t mod 16, each with its own counter (so a block whose near-tie rows crowd into few
+                             tiles keeps fewer than tie_capacity of them).
                              Rows beyond it are not kept and select again (gsr_step_tie_stats counts them); which
                              rows of a block those are depends on the order the waves append in, so results are
                              bit-reproducible between runs only while nothing is dropped. */

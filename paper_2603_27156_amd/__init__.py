@@ -384,6 +384,7 @@ def gsr_step_tie_stats(g: Graph, cfg: Config, workspace) -> dict:
 def gsr_step_tie_export(g: Graph, cfg: Config, workspace, layer: int, block: int):
     """(rows int32 [m], masks uint64 [m]) kept by the last save_indices == 2 step for the input of `block` of `layer`."""
     cap = cfg.tie_capacity if cfg.tie_capacity > 0 else cfg.n // 32 + 1024
+    cap = (cap + 15) // 16 * 16                    # the library keeps sixteen sub-lists of cap / 16 places, rounded up
     rows = np.zeros(cap, dtype=np.int32)
     masks = np.zeros(cap, dtype=np.uint64)
     cnt = C.c_int64()

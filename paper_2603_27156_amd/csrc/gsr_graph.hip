@@ -283,12 +283,12 @@ StepWs carve_step(const gsr_config_t* cfg, const gsr_graph_t* g) {
     w.tie_counts = w.tie_rows = w.tie_masks = off;
     w.tie_cap = 0;
     if (cfg->save_indices == 2) {
-        w.tie_cap = tie_capacity(cfg);
-        off += align_up(segs * sizeof(int));
+        w.tie_cap = (tie_capacity(cfg) + kTieSub - 1) / kTieSub;           // places per sub-list
+        off += align_up(segs * kTieSub * kTieCounterStride * sizeof(int));
         w.tie_rows = off;
-        off += align_up(segs * (size_t)w.tie_cap * sizeof(uint32_t));
+        off += align_up(segs * kTieSub * (size_t)w.tie_cap * sizeof(uint32_t));
         w.tie_masks = off;
-        off += align_up(segs * (size_t)w.tie_cap * (size_t)(cfg->d / cfg->c / 8));
+        off += align_up(segs * kTieSub * (size_t)w.tie_cap * (size_t)(std::min(cfg->d / cfg->c, 64) / 8));
     }
     w.total = off;
     return w;

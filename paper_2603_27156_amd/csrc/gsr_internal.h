@@ -132,15 +132,16 @@ struct StepWs {
     size_t head;  // [grid][D + 2] float
     size_t layer; // LayerWs starts here
     size_t masks; // [L+1][C][n] column masks kept from the forward sweep (cfg->save_indices == 1), else unused
-    // cfg->save_indices == 2: per segment (layer in 0..L, slot in 0..C-1) a counter and up to tie_cap kept rows
-    size_t tie_counts;  // [(L+1)*C] int
-    size_t tie_rows;    // [(L+1)*C][tie_cap] uint32
-    size_t tie_masks;   // [(L+1)*C][tie_cap] column masks
-    int64_t tie_cap;
+    // cfg->save_indices == 2: per segment (layer in 0..L, slot in 0..C-1) kTieSub sub-lists of up to tie_cap kept rows
+    size_t tie_counts;  // [(L+1)*C][kTieSub] counters, kTieCounterStride ints apart
+    size_t tie_rows;    // [(L+1)*C][kTieSub][tie_cap] uint32
+    size_t tie_masks;   // [(L+1)*C][kTieSub][tie_cap] column masks
+    int64_t tie_cap;    // places per sub-list
     size_t total;
 };
 LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g);
 int64_t tie_capacity(const gsr_config_t* cfg);
+constexpr int kTieSub = 16, kTieCounterStride = 32;     // (device code: TIE_SUB, TIE_COUNTER_STRIDE)
 
 // Tile counters of the dynamic sweeps (device code: tile_draws): 8 XCDs x 64 queues, 128 bytes apart.
 constexpr int kTileCounters = 8 * 64 * 32;

@@ -589,11 +589,13 @@ __global__ __launch_bounds__(256) void k_tie_fixup(TieSeg<DG> tie, const T* __re
     using M = typename MaskOf<DG>::type;
     constexpr int QW = DG / 4;
     const int lane = lane_id(), r = lane & 15, q = lane >> 4;
-    const int listed = *tie.count, cnt = listed < tie.cap ? listed : tie.cap;
+    // wave w of the grid (a multiple of TIE_SUB waves) takes sub-list w mod TIE_SUB, sixteen entries at a time
     const int wave = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6), nwaves = (int)((gridDim.x * blockDim.x) >> 6);
-    for (int e0 = wave * 16; e0 < cnt; e0 += nwaves * 16) {
+    const int sub = wave & (TIE_SUB - 1);
+    const int listed = tie.count[sub * TIE_COUNTER_STRIDE], cnt = listed < tie.cap ? listed : tie.cap;
+    for (int e0 = (wave / TIE_SUB) * 16; e0 < cnt; e0 += (nwaves / TIE_SUB) * 16) {
         const bool ok = e0 + r < cnt;
-        const int e = ok ? e0 + r : cnt - 1;
+        const int e = sub * tie.cap + (ok ? e0 + r : cnt - 1);
         const size_t row = tie.rows[e];
         const M m = tie.masks[e];
         float x[QW];
@@ -1017,7 +1019,8 @@ struct Ctx {
     TieSeg<DG> tie_seg(int layer, int slot) const {
         if (!tie_counts || layer < 0) return TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f};
         const size_t seg = (size_t)layer * cfg->c + slot;
-        return TieSeg<DG>{tie_counts + seg, tie_rows + seg * tie_cap, tie_masks + seg * tie_cap, tie_cap, cfg->tie_tol};
+        return TieSeg<DG>{tie_counts + seg * TIE_SUB * TIE_COUNTER_STRIDE, tie_rows + seg * TIE_SUB * tie_cap,
+                          tie_masks + seg * TIE_SUB * tie_cap, tie_cap, cfg->tie_tol};
     }
     // Record slot `slot` of layer `layer`: the values always live in the slot (they are rebuilt),
     // the mask in the slot, or in the kept store when indices are saved.
@@ -1191,7 +1194,7 @@ template <int DG, typename T>
 static void launch_tie_fixup(const Ctx<DG, T>& x, const TieSeg<DG>& tie, const T* plane, int64_t ld, const Record<DG, T>& out) {
     if (!tie.count) return;
     ProfScope prof(KC_TIE, x.s);
-    const unsigned blocks = (unsigned)std::min((tie.cap + 63) / 64, 1024);
+    const unsigned blocks = (unsigned)std::min((TIE_SUB * tie.cap + 63) / 64 / 4 * 4 + 4, 1024);     // 4 waves each: a multiple of TIE_SUB waves
     hipLaunchKernelGGL((k_tie_fixup<DG, T>), dim3(blocks), dim3(256), 0, x.s, tie, plane, ld, x.cfg->k, x.cfg->norm, x.cfg->eps, out);
 }
 
@@ -1518,8 +1521,8 @@ static gsr_status_t step_impl(const gsr_graph_t* g, const gsr_config_t* cfg, con
         x.tie_rows = (uint32_t*)(base + sw.tie_rows);
         x.tie_masks = (typename MaskOf<DG>::type*)(base + sw.tie_masks);
         x.tie_cap = (int)sw.tie_cap;
-        const int segs = (L + 1) * C;
-        hipLaunchKernelGGL(k_zero_ints, dim3((segs + 255) / 256), dim3(256), 0, s, x.tie_counts, segs);
+        const int ints = (L + 1) * C * TIE_SUB * TIE_COUNTER_STRIDE;
+        hipLaunchKernelGGL(k_zero_ints, dim3((ints + 255) / 256), dim3(256), 0, s, x.tie_counts, ints);
     }
     const int64_t n = cfg->n;
     const int dgw = DG * x.S;            // columns of a group (DG, or 64 S for the groups handled as sub-planes)
@@ -1607,14 +1610,19 @@ gsr_status_t gsr_step_tie_stats(const gsr_graph_t* g, const gsr_config_t* cfg, c
     if (cfg->save_indices != 2) return fail(GSR_ERR_INVALID_ARG, "cfg->save_indices is not 2: nothing was listed");
     const StepWs sw = carve_step(cfg, g);
     const int segs = cfg->l * cfg->c;      // (the set listed for a layer above the last is never used)
-    std::vector<int> counts((size_t)segs);
+    std::vector<int> counts((size_t)segs * TIE_SUB * TIE_COUNTER_STRIDE);
     GSR_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
-    GSR_HIP_CHECK(hipMemcpy(counts.data(), (const char*)workspace + sw.tie_counts, (size_t)segs * sizeof(int), hipMemcpyDeviceToHost));
+    GSR_HIP_CHECK(hipMemcpy(counts.data(), (const char*)workspace + sw.tie_counts, counts.size() * sizeof(int), hipMemcpyDeviceToHost));
     int64_t total = 0, most = 0, lost = 0;
-    for (int c : counts) {
-        total += std::min<int64_t>(c, sw.tie_cap);
-        most = std::max<int64_t>(most, c);
-        lost += std::max<int64_t>(0, c - sw.tie_cap);
+    for (int seg = 0; seg < segs; ++seg) {
+        int64_t in_block = 0;
+        for (int sub = 0; sub < TIE_SUB; ++sub) {
+            const int64_t c = counts[((size_t)seg * TIE_SUB + sub) * TIE_COUNTER_STRIDE];
+            in_block += c;
+            total += std::min<int64_t>(c, sw.tie_cap);
+            lost += std::max<int64_t>(0, c - sw.tie_cap);
+        }
+        most = std::max(most, in_block);
     }
     if (listed) *listed = total;
     if (max_per_block) *max_per_block = most;
@@ -1632,20 +1640,26 @@ gsr_status_t gsr_step_tie_export(const gsr_graph_t* g, const gsr_config_t* cfg, 
     const size_t seg = (size_t)layer * cfg->c + (block - 1);
     const char* base = (const char*)workspace;
     GSR_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
-    int cnt = 0;
-    GSR_HIP_CHECK(hipMemcpy(&cnt, base + sw.tie_counts + seg * sizeof(int), sizeof(int), hipMemcpyDeviceToHost));
-    const int64_t take = std::min<int64_t>(cnt, sw.tie_cap);
-    *count_out = take;
-    if (take == 0) return GSR_OK;
-    GSR_HIP_CHECK(hipMemcpy(rows_out, base + sw.tie_rows + seg * sw.tie_cap * sizeof(uint32_t), (size_t)take * sizeof(uint32_t), hipMemcpyDeviceToHost));
-    const int dg = cfg->d / cfg->c;
-    if (dg == 64) {
-        GSR_HIP_CHECK(hipMemcpy(masks_out, base + sw.tie_masks + seg * sw.tie_cap * 8, (size_t)take * 8, hipMemcpyDeviceToHost));
-    } else {
-        std::vector<uint32_t> m32((size_t)take);
-        GSR_HIP_CHECK(hipMemcpy(m32.data(), base + sw.tie_masks + seg * sw.tie_cap * 4, (size_t)take * 4, hipMemcpyDeviceToHost));
-        for (int64_t i = 0; i < take; ++i) masks_out[i] = m32[(size_t)i];
+    std::vector<int> counts((size_t)TIE_SUB * TIE_COUNTER_STRIDE);
+    GSR_HIP_CHECK(hipMemcpy(counts.data(), base + sw.tie_counts + seg * counts.size() * sizeof(int), counts.size() * sizeof(int), hipMemcpyDeviceToHost));
+    const int dg = std::min(cfg->d / cfg->c, 64);
+    const size_t mbytes = dg == 64 ? 8 : 4;
+    int64_t written = 0;
+    for (int sub = 0; sub < TIE_SUB; ++sub) {
+        const int64_t take = std::min<int64_t>(counts[(size_t)sub * TIE_COUNTER_STRIDE], sw.tie_cap);
+        if (take == 0) continue;
+        const size_t at = (seg * TIE_SUB + sub) * (size_t)sw.tie_cap;
+        GSR_HIP_CHECK(hipMemcpy(rows_out + written, base + sw.tie_rows + at * sizeof(uint32_t), (size_t)take * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        if (mbytes == 8) {
+            GSR_HIP_CHECK(hipMemcpy(masks_out + written, base + sw.tie_masks + at * 8, (size_t)take * 8, hipMemcpyDeviceToHost));
+        } else {
+            std::vector<uint32_t> m32((size_t)take);
+            GSR_HIP_CHECK(hipMemcpy(m32.data(), base + sw.tie_masks + at * 4, (size_t)take * 4, hipMemcpyDeviceToHost));
+            for (int64_t i = 0; i < take; ++i) masks_out[written + i] = m32[(size_t)i];
+        }
+        written += take;
     }
+    *count_out = written;
     return GSR_OK;
 }
 

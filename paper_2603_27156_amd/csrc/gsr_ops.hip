@@ -9,6 +9,7 @@
 namespace gsr {
 
 static_assert(TILE_COUNTERS == kTileCounters, "host and device disagree on the size of a counter set");
+static_assert(TIE_SUB == kTieSub && TIE_COUNTER_STRIDE == kTieCounterStride, "host and device disagree on the near-tie sub-lists");
 
 CsrView make_view(const gsr_graph_t* g, bool transpose);
 CsrView make_view(const gsr_graph_t* g, bool transpose) {

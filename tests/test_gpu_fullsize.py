@@ -277,8 +277,8 @@ def test_cfg3_depth_sweep_memory_and_rebuild():
             del ws, dW, x0r
     assert used[(0, 8)][1] == used[(0, 448)][1]                              # workspace: flat in L
     assert abs(used[(0, 8)][0] - used[(0, 448)][0]) <= 1 << 20               # allocator rounding only
-    cap = w.n // 32 + 1024
-    per_layer = w.c * (4 + cap * (4 + w.dg // 8))
+    cap = (w.n // 32 + 1024 + 15) // 16 * 16
+    per_layer = w.c * (16 * 128 + cap * (4 + w.dg // 8))
     grow = used[(2, 448)][1] - used[(2, 8)][1]
     assert abs(grow - 440 * per_layer) <= 4096
     assert grow <= 0.05 * (440 * w.c * w.n * (w.dg // 8))                    # a twentieth of what keeping all sets costs

@@ -354,7 +354,7 @@ def test_step_captured_in_a_graph_replays_bit_identically(save_indices, workgrou
         c = Case(workloads()["cfg2s"], 0, PLANAR)
     finally:
         gsr.gsr_set_option("max_workgroups", 0)
-    c.gcfg = gsr.Config(**{**c.gcfg.__dict__, "save_indices": save_indices, "tie_tol": 2.0 ** -6, "tie_capacity": c.w.n})
+    c.gcfg = gsr.Config(**{**c.gcfg.__dict__, "save_indices": save_indices, "tie_tol": 2.0 ** -6, "tie_capacity": 16 * c.w.n})
     w = c.w
     dv = c.dev
     f32 = dict(dtype=torch.float32, device=dv)

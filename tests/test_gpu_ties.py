@@ -27,7 +27,7 @@ def test_step_with_near_tie_list_against_oracle(name, layout, tol):
     ref = oracle.step(c.og, c.ocfg, w.l, c.x0_on_grid(), c.inp.weights, c.inp.w_out, c.inp.b_out, c.inp.target, variant=3,
                       tie_tol=tol, want=("yhat", "XL", "X0rec", "dW", "dwout", "dX0", "ties", "I"))
     keep = {}
-    out = run_step(c, save_indices=2, tie_tol=tol, tie_capacity=w.n, keep=keep)
+    out = run_step(c, save_indices=2, tie_tol=tol, tie_capacity=16 * w.n, keep=keep)
     assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
     for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
         assert_close(key, out[key], ref[key])
@@ -59,8 +59,8 @@ def test_step_with_near_tie_list_against_oracle(name, layout, tol):
     if tol > 0:
         assert total > 0
     # reruns are bit-identical, and the forward sweep does not depend on the mode
-    a, b2, plain = (run_step(c, raw=True, save_indices=2, tie_tol=tol, tie_capacity=w.n),
-                    run_step(c, raw=True, save_indices=2, tie_tol=tol, tie_capacity=w.n), run_step(c, raw=True))
+    a, b2, plain = (run_step(c, raw=True, save_indices=2, tie_tol=tol, tie_capacity=16 * w.n),
+                    run_step(c, raw=True, save_indices=2, tie_tol=tol, tie_capacity=16 * w.n), run_step(c, raw=True))
     for key in a:
         assert torch.equal(a[key], b2[key]), key
     assert torch.equal(a["XL"], plain["XL"]) and torch.equal(a["yhat"], plain["yhat"])
@@ -72,17 +72,17 @@ def test_list_of_every_row_equals_all_indices_saved_and_an_empty_list_equals_non
     c = case("cfg2s", PLANAR)
     w = c.w
     keep = {}
-    every = run_step(c, raw=True, save_indices=2, tie_tol=1e30, tie_capacity=w.n, keep=keep)
+    every = run_step(c, raw=True, save_indices=2, tie_tol=1e30, tie_capacity=16 * w.n, keep=keep)
     saved = run_step(c, raw=True, save_indices=1)
-    for key in every:
+    for key in every:                                    # (room for every row in every one of a block's sixteen sub-lists)
         assert torch.equal(every[key], saved[key]), key
     st = gsr.gsr_step_tie_stats(c.gg, keep["cfg"], keep["ws"])
     assert st["dropped"] == 0 and st["max_per_block"] == w.n and st["listed"] >= w.n * w.c * w.l
-    # capacity 1 with a bar of zero: only exact ties are listed, at most one row per block is kept
+    # capacity 1: one place in each of a block's sixteen sub-lists
     keep = {}
     few = run_step(c, raw=True, save_indices=2, tie_tol=1e30, tie_capacity=1, keep=keep)
     st = gsr.gsr_step_tie_stats(c.gg, keep["cfg"], keep["ws"])
-    assert st["listed"] <= w.l * w.c and st["dropped"] > 0
+    assert st["listed"] <= 16 * w.l * w.c and st["dropped"] > 0
     assert torch.equal(few["XL"], saved["XL"])
 
 
@@ -93,7 +93,7 @@ def test_near_tie_list_with_bf16_storage():
     c = Case(w, 0, PLANAR)
     x0 = c.x0_on_grid()
     keep = {}
-    listed = run_step(c, save_indices=2, tie_tol=2.0 ** -4, tie_capacity=w.n, keep=keep)
+    listed = run_step(c, save_indices=2, tie_tol=2.0 ** -4, tie_capacity=16 * w.n, keep=keep)
     saved, again = run_step(c, save_indices=1), run_step(c)
     e = lambda r: np.abs(r["X0rec"] - x0).max()
     st = gsr.gsr_step_tie_stats(c.gg, keep["cfg"], keep["ws"])
@@ -112,8 +112,8 @@ def test_workspace_with_near_tie_list():
         plain = gsr.gsr_workspace_size(c.gg, gsr.Config(**{**c.gcfg.__dict__, "l": L}))[1]
         full = gsr.gsr_workspace_size(c.gg, gsr.Config(**{**c.gcfg.__dict__, "l": L, "save_indices": 1}))[1]
         ties = gsr.gsr_workspace_size(c.gg, gsr.Config(**{**c.gcfg.__dict__, "l": L, "save_indices": 2}))[1]
-        cap = w.n // 32 + 1024
-        want = (L + 1) * w.c * (4 + cap * (4 + w.dg // 8))
+        cap = (w.n // 32 + 1024 + 15) // 16 * 16           # sixteen sub-lists, each with a counter on its own cache line
+        want = (L + 1) * w.c * (16 * 128 + cap * (4 + w.dg // 8))
         assert want <= ties - plain < want + 3 * 256
     with pytest.raises(gsr.GsrError):
         gsr.gsr_workspace_size(c.gg, gsr.Config(**{**c.gcfg.__dict__, "save_indices": 2, "tie_tol": -1.0}))
