@@ -228,6 +228,50 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
     }
 }
 
+// The records of listed rows, written again with the column sets kept from the forward sweep: a wave takes sixteen
+// list entries in the quarter layout of emit_tile (lane = (entry, quarter of the row)) and forms the values exactly
+// as emit_tile does when the set is given.  plane: the rows the record was just taken from, row stride ld.  Called by
+// every wave of a grid of `nwaves` waves (a multiple of TIE_SUB): wave w takes sub-list w mod TIE_SUB.
+template <int DG, typename T>
+__device__ __forceinline__ void tie_fixup_rows(const TieSeg<DG>& tie, const T* __restrict__ plane, int64_t ld, int k, int norm, float eps,
+                                               const Record<DG, T>& out, int wave, int nwaves) {
+    using M = typename MaskOf<DG>::type;
+    constexpr int QW = DG / 4;
+    const int lane = lane_id(), r = lane & 15, q = lane >> 4;
+    const int sub = wave & (TIE_SUB - 1);
+    const int listed = tie.count[sub * TIE_COUNTER_STRIDE], cnt = listed < tie.cap ? listed : tie.cap;
+    for (int e0 = (wave / TIE_SUB) * 16; e0 < cnt; e0 += (nwaves / TIE_SUB) * 16) {
+        const bool ok = e0 + r < cnt;
+        const int e = sub * tie.cap + (ok ? e0 + r : cnt - 1);
+        const size_t row = tie.rows[e];
+        const M m = tie.masks[e];
+        float x[QW];
+#pragma unroll
+        for (int j = 0; j < QW; ++j) x[j] = to_float(plane[row * ld + q * QW + j]);
+        const uint32_t msel = (uint32_t)(m >> (QW * q)) & ((1u << QW) - 1u);
+        uint32_t all[4];
+        quarter_all((uint32_t)__popc(msel), all);
+        size_t slot = row * k;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) slot += i < q ? all[i] : 0u;
+        const float scale = record_scale<DG>(x, norm, eps);
+#pragma unroll
+        for (int j = 0; j < QW; ++j) {
+            const bool bit = (msel >> j) & 1u;
+            if (ok && bit) out.vals[slot] = from_float<T>(x[j] * scale);
+            slot += bit ? 1 : 0;
+        }
+        if (ok && q == 0) out.mask[row] = m;
+    }
+}
+
+template <int DG, typename T>
+__global__ __launch_bounds__(256) void k_tie_fixup(TieSeg<DG> tie, const T* __restrict__ plane, int64_t ld, int k, int norm,
+                                                   float eps, Record<DG, T> out) {
+    tie_fixup_rows<DG, T>(tie, plane, ld, k, norm, eps, out, (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6),
+                          (int)((gridDim.x * blockDim.x) >> 6));
+}
+
 // dW_i = H^T dY_i as a pass of its own over H (left by the inverse kernel) and dY_i: a wave sums over the tiles of a
 // fixed sweep (so the partial sums do not depend on timing), 64 x 64 accumulators in registers, products on the bf16
 // pipe (mfma_outer_b3); workgroup partials as k_block writes them.  The inverse kernel then runs without the 64
@@ -239,10 +283,21 @@ struct DwArgs {
     const T* dy;            // row stride ldg
     int64_t ldg;
     float* dw_partial;      // [gridDim.x][DG*DG]
+    // mode 2 of the step: the record the inverse kernel has just taken again gets the kept column sets of its listed
+    // rows back here (tie.count == NULL: nothing to do), which saves a launch per block
+    TieSeg<DG> tie;
+    const T* fix_plane;
+    int64_t fix_ld;
+    int k, norm;
+    float eps;
+    Record<DG, T> fix_out;
 };
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_dw(DwArgs<DG, T> a) {
+    if (a.tie.count)
+        tie_fixup_rows<DG, T>(a.tie, a.fix_plane, a.fix_ld, a.k, a.norm, a.eps, a.fix_out, (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6),
+                              (int)((gridDim.x * blockDim.x) >> 6));
     constexpr int LR = DG + 1, CPL = DG / 16;
     __shared__ float tile[4][16 * LR];
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tg = lane >> 4, tj = lane & 15;
@@ -579,44 +634,6 @@ struct SumArgs {
     bool out_given;         // out.mask holds the column sets to use
     TieSeg<DG> tie;         // where rows that select at a near-tie are listed (count == NULL: nowhere)
 };
-
-// The records of listed rows, written again with the column sets kept from the forward sweep: a wave takes sixteen
-// list entries in the quarter layout of emit_tile (lane = (entry, quarter of the row)) and forms the values exactly
-// as emit_tile does when the set is given.  plane: the rows the record was just taken from, row stride ld.
-template <int DG, typename T>
-__global__ __launch_bounds__(256) void k_tie_fixup(TieSeg<DG> tie, const T* __restrict__ plane, int64_t ld, int k, int norm,
-                                                   float eps, Record<DG, T> out) {
-    using M = typename MaskOf<DG>::type;
-    constexpr int QW = DG / 4;
-    const int lane = lane_id(), r = lane & 15, q = lane >> 4;
-    // wave w of the grid (a multiple of TIE_SUB waves) takes sub-list w mod TIE_SUB, sixteen entries at a time
-    const int wave = (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6), nwaves = (int)((gridDim.x * blockDim.x) >> 6);
-    const int sub = wave & (TIE_SUB - 1);
-    const int listed = tie.count[sub * TIE_COUNTER_STRIDE], cnt = listed < tie.cap ? listed : tie.cap;
-    for (int e0 = (wave / TIE_SUB) * 16; e0 < cnt; e0 += (nwaves / TIE_SUB) * 16) {
-        const bool ok = e0 + r < cnt;
-        const int e = sub * tie.cap + (ok ? e0 + r : cnt - 1);
-        const size_t row = tie.rows[e];
-        const M m = tie.masks[e];
-        float x[QW];
-#pragma unroll
-        for (int j = 0; j < QW; ++j) x[j] = to_float(plane[row * ld + q * QW + j]);
-        const uint32_t msel = (uint32_t)(m >> (QW * q)) & ((1u << QW) - 1u);
-        uint32_t all[4];
-        quarter_all((uint32_t)__popc(msel), all);
-        size_t slot = row * k;
-#pragma unroll
-        for (int i = 0; i < 3; ++i) slot += i < q ? all[i] : 0u;
-        const float scale = record_scale<DG>(x, norm, eps);
-#pragma unroll
-        for (int j = 0; j < QW; ++j) {
-            const bool bit = (msel >> j) & 1u;
-            if (ok && bit) out.vals[slot] = from_float<T>(x[j] * scale);
-            slot += bit ? 1 : 0;
-        }
-        if (ok && q == 0) out.mask[row] = m;
-    }
-}
 
 __global__ void k_zero_ints(int* p, int count) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1200,9 +1217,13 @@ static void launch_tie_fixup(const Ctx<DG, T>& x, const TieSeg<DG>& tie, const T
 
 // dW_i's workgroup partials from H (in x.hplane()) and dY_i; returns their number
 template <int DG, typename T>
-static unsigned launch_dw(const Ctx<DG, T>& x, const T* dy, int64_t ldg) {
+static unsigned launch_dw(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const TieSeg<DG>& tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f},
+                          const T* fix_plane = nullptr, int64_t fix_ld = 0, const Record<DG, T>* fix_out = nullptr) {
     DwArgs<DG, T> a;
     a.n = (int)x.cfg->n; a.tiles = x.tiles; a.h = x.hplane(); a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
+    a.tie = fix_out ? tie : TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f};
+    a.fix_plane = fix_plane; a.fix_ld = fix_ld; a.k = x.cfg->k; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
+    a.fix_out = fix_out ? *fix_out : x.rec(-1);
     ProfScope prof(KC_DW, x.s);
     static const int per_cu = resident_blocks((const void*)k_dw<DG, T>, 256);
     const unsigned grid = persistent_grid(x.g, per_cu);
@@ -1437,11 +1458,11 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
             // X_i = Y_i - f_i(Y_{i-1}) with H kept for the weight gradient, then dW_i = H^T dY_i
             launch_block<DG, T>(x, 1, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, nullptr, 0, true,
                                 TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, DG, x.hplane());
-            nparts = launch_dw<DG, T>(x, dy.grp(i - 1), dy.ld);
+            nparts = launch_dw<DG, T>(x, dy.grp(i - 1), dy.ld, out_tie, y.grp(i - 1), y.ld, out.mask ? &out : nullptr);
         } else {
             nparts = launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld, true);
+            if (out.mask) launch_tie_fixup<DG, T>(x, out_tie, y.grp(i - 1), y.ld, out);
         }
-        if (out.mask) launch_tie_fixup<DG, T>(x, out_tie, y.grp(i - 1), y.ld, out);
         // dW_i is summed from the partials by the first job of the gradient kernel that follows, unless that kernel
         // has so few tiles per wave that it could not make up for the late start of those workgroups (measured on
         // a 49,600-node graph with 3,100 tiles: +80 us on a 405 us kernel): then by a launch of its own
