@@ -569,6 +569,32 @@ __device__ __forceinline__ void deal_lut_fill(DealLut& l) {
     __syncthreads();
 }
 
+// The same for float32 records and four columns per lane: the window is four words, column c takes word
+// popcount(mask bits below c) if its bit is set.  A word moves whole, so a v_perm_b32 over two words of the window
+// with a selector that copies the lower word, the upper word or zeros does it: column 0 from word 0, column 1 from
+// words (0, 1), columns 2 and 3 from words (0, 1) or-ed with (2, -) and (2, 3).  Six selectors per value of the four
+// mask bits, eight instructions per staged edge and lane instead of a chain of some twenty-five bitwise selects.
+struct alignas(32) DealLutF {
+    uint32_t sel[16][8];      // s0, s1, s2 over (0,1), s2 over (2,-), s3 over (0,1), s3 over (2,3), unused
+};
+__device__ __forceinline__ void deal_lutf_fill(DealLutF& l) {
+    if (threadIdx.x < 16) {
+        constexpr uint32_t LOW = 0x03020100u, HIGH = 0x07060504u, ZERO = 0x0c0c0c0cu;
+        const uint32_t nib = threadIdx.x;
+        const uint32_t p1 = nib & 1u, p2 = (uint32_t)__popc(nib & 3u), p3 = (uint32_t)__popc(nib & 7u);
+        const bool b0 = nib & 1u, b1 = nib & 2u, b2 = nib & 4u, b3 = nib & 8u;
+        uint32_t* e = l.sel[nib];
+        e[0] = b0 ? LOW : ZERO;
+        e[1] = b1 ? (p1 ? HIGH : LOW) : ZERO;
+        e[2] = (b2 && p2 < 2u) ? (p2 ? HIGH : LOW) : ZERO;
+        e[3] = (b2 && p2 == 2u) ? LOW : ZERO;
+        e[4] = (b3 && p3 < 2u) ? (p3 ? HIGH : LOW) : ZERO;
+        e[5] = (b3 && p3 >= 2u) ? (p3 == 3u ? HIGH : LOW) : ZERO;
+        e[6] = ZERO; e[7] = ZERO;
+    }
+    __syncthreads();
+}
+
 // acc += P * scatter(V, I) over the edges [e_a, e_b) of ordinary rows (Section 4.1, eq. (10)).
 // The record of neighbour j is its k kept values in ascending column order plus a DG-bit column
 // mask.  A lane's CPL adjacent columns occupy adjacent slots of the record, starting at
@@ -712,11 +738,11 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
 // the row changes and at the end of the round.  Two groups never add to one row in the same instruction: inside a
 // round only the last run that holds a row sees it end; the sums left at the end of the round are added group by
 // group.  The order of the additions is fixed by the edge list alone.
-template <int DG, int GB>
+template <int DG, int GB, bool LUT = false>
 __device__ __forceinline__ void gather_records_rows(const CsrView& g, const float* __restrict__ vals,
                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
                                                     int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, int lane,
-                                                    float* st) {
+                                                    float* st, const DealLutF* lut = nullptr) {
     using M = typename MaskOf<DG>::type;
     constexpr int CPL = DG / 16, LR = DG + 1;
     const int i16 = lane & 15, kk = lane >> 4, bp = CPL * i16;
@@ -730,8 +756,8 @@ __device__ __forceinline__ void gather_records_rows(const CsrView& g, const floa
         const int j = ok ? __builtin_nontemporal_load(g.ci + e) : 0;
         RecEdge me;
         me.a = ok ? __builtin_nontemporal_load(g.av + e) : 0.f;
-        me.off0 = (uint32_t)j * (uint32_t)k;
         const M m = masks[j];
+        me.off0 = (uint32_t)j * (uint32_t)k;
         me.mlo = (uint32_t)m;
         if constexpr (DG == 64) me.mhi = (uint32_t)(m >> 32);
         else me.mhi = 0u;
@@ -764,8 +790,23 @@ __device__ __forceinline__ void gather_records_rows(const CsrView& g, const floa
                 p[u] = okv ? er.a : 0.f;
                 row[u] = okv ? (int)rbuf[eic] : -1;
             }
+            constexpr bool PERM = LUT && CPL == 4;
+            uint4 sa_next = make_uint4(0u, 0u, 0u, 0u);      // selectors of the edge after the present one
+            uint2 sb_next = make_uint2(0u, 0u);
+            if constexpr (PERM) {
+                sa_next = *reinterpret_cast<const uint4*>(lut->sel[nib[0]]);
+                sb_next = *reinterpret_cast<const uint2*>(lut->sel[nib[0]] + 4);
+            }
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
+                const uint4 sa = sa_next;
+                const uint2 sb = sb_next;
+                if constexpr (PERM) {
+                    if (u + 1 < GB) {
+                        sa_next = *reinterpret_cast<const uint4*>(lut->sel[nib[u + 1 < GB ? u + 1 : u]]);
+                        sb_next = *reinterpret_cast<const uint2*>(lut->sel[nib[u + 1 < GB ? u + 1 : u]] + 4);
+                    }
+                }
                 if (row[u] >= 0 && row[u] != cur) {     // the row of this run has ended: its sum joins the tile
 #pragma unroll
                     for (int cb = 0; cb < CPL; ++cb) {
@@ -773,6 +814,17 @@ __device__ __forceinline__ void gather_records_rows(const CsrView& g, const floa
                         run[cb] = 0.f;
                     }
                     cur = row[u];
+                }
+                if constexpr (PERM) {
+                    const uint32_t b0 = __builtin_amdgcn_perm(0u, w[u][0], sa.x);
+                    const uint32_t b1 = __builtin_amdgcn_perm(w[u][1], w[u][0], sa.y);
+                    const uint32_t b2 = __builtin_amdgcn_perm(w[u][1], w[u][0], sa.z) | __builtin_amdgcn_perm(0u, w[u][2], sa.w);
+                    const uint32_t b3 = __builtin_amdgcn_perm(w[u][1], w[u][0], sb.x) | __builtin_amdgcn_perm(w[u][3], w[u][2], sb.y);
+                    run[0] = __builtin_fmaf(p[u], __uint_as_float(b0), run[0]);
+                    run[1] = __builtin_fmaf(p[u], __uint_as_float(b1), run[1]);
+                    run[2] = __builtin_fmaf(p[u], __uint_as_float(b2), run[2]);
+                    run[3] = __builtin_fmaf(p[u], __uint_as_float(b3), run[3]);
+                    continue;
                 }
                 uint32_t q[CPL];
 #pragma unroll
@@ -1111,32 +1163,113 @@ struct Record {
     M* mask;        // [n]
 };
 
+// ---- the k-th largest key of a row when k is a quarter of its width -------------------------------
+// (k = 16 of 64 columns, k = 8 of 32: the shapes of the benchmark configurations.)  A selection network of fixed
+// cost instead of a search whose length depends on the data (Section 4.1: the k largest entries of a row).
+// Lane (r, q) holds QW = k keys of row r.
+//   1. every lane sorts its keys (Batcher's odd-even merge sort): even quarters descending, odd quarters ascending
+//      in register order;
+//   2. quarters (0,1) and (2,3): u[i] = max(even[i], odd[i]) pairs the i-th largest of one with the i-th smallest of
+//      the other, so u is the set of the k largest of the two quarters, and a bitonic sequence; the even lane keeps
+//      u[0 .. k/2), the odd lane the rest;
+//   3. a bitonic merge sorts u over the two lanes: quarters (0,1) descending, quarters (2,3) ascending;
+//   4. the same pairing over the halves leaves the k largest of the whole row; their minimum is the answer.
+// A compare-exchange whose direction depends on the lane is two v_med3_u32 with a third operand of all ones
+// (the median is then the larger of the two) or zero (the smaller).
+constexpr int SORT8[19][2] = {{0, 1}, {2, 3}, {4, 5}, {6, 7}, {0, 2}, {1, 3}, {4, 6}, {5, 7}, {1, 2}, {5, 6},
+                              {0, 4}, {1, 5}, {2, 6}, {3, 7}, {2, 4}, {3, 5}, {1, 2}, {3, 4}, {5, 6}};
+constexpr int SORT16[63][2] = {
+    {0, 1}, {2, 3}, {4, 5}, {6, 7}, {8, 9}, {10, 11}, {12, 13}, {14, 15}, {0, 2}, {1, 3}, {4, 6}, {5, 7}, {8, 10},
+    {9, 11}, {12, 14}, {13, 15}, {1, 2}, {5, 6}, {9, 10}, {13, 14}, {0, 4}, {1, 5}, {2, 6}, {3, 7}, {8, 12}, {9, 13},
+    {10, 14}, {11, 15}, {2, 4}, {3, 5}, {10, 12}, {11, 13}, {1, 2}, {3, 4}, {5, 6}, {9, 10}, {11, 12}, {13, 14}, {0, 8},
+    {1, 9}, {2, 10}, {3, 11}, {4, 12}, {5, 13}, {6, 14}, {7, 15}, {4, 8}, {5, 9}, {6, 10}, {7, 11}, {2, 4}, {3, 5},
+    {6, 8}, {7, 9}, {10, 12}, {11, 13}, {1, 2}, {3, 4}, {5, 6}, {7, 8}, {9, 10}, {11, 12}, {13, 14}};
+
+__device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t d;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+// a <- the larger of (a, b) where up is all ones, the smaller where it is zero; b <- the other one
+__device__ __forceinline__ void compare_exchange(uint32_t& a, uint32_t& b, uint32_t up) {
+    const uint32_t hi = med3_u32(a, b, up), lo = med3_u32(a, b, ~up);
+    a = hi; b = lo;
+}
+
+template <int QW>
+__device__ __forceinline__ uint32_t kth_largest_quarter(const uint32_t (&key)[QW], int q) {
+    static_assert(QW == 8 || QW == 16, "selection network for 8 or 16 keys per lane");
+    constexpr int H = QW / 2, NCE = QW == 16 ? 63 : 19;
+    uint32_t s[QW];
+#pragma unroll
+    for (int j = 0; j < QW; ++j) s[j] = key[j];
+    const uint32_t up1 = (q & 1) ? 0u : 0xFFFFFFFFu;
+#pragma unroll
+    for (int c = 0; c < NCE; ++c) {
+        if constexpr (QW == 16) compare_exchange(s[SORT16[c][0]], s[SORT16[c][1]], up1);
+        else compare_exchange(s[SORT8[c][0]], s[SORT8[c][1]], up1);
+    }
+    uint32_t t[H];
+#pragma unroll
+    for (int i = 0; i < H; ++i) {
+        const auto a = __builtin_amdgcn_permlane16_swap(s[i], s[i + H], false, false);
+        t[i] = max(a[0], a[1]);
+    }
+    const uint32_t up3 = (q == 0 || q == 3) ? 0xFFFFFFFFu : 0u, upl = q < 2 ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+    for (int i = 0; i < H; ++i) {
+        const auto a = __builtin_amdgcn_permlane16_swap(t[i], t[i], false, false);
+        t[i] = med3_u32(a[0], a[1], up3);
+    }
+#pragma unroll
+    for (int d = H / 2; d >= 1; d >>= 1) {
+#pragma unroll
+        for (int i = 0; i < H; ++i)
+            if ((i & d) == 0) compare_exchange(t[i], t[i + d], upl);
+    }
+    uint32_t m = 0xFFFFFFFFu;
+#pragma unroll
+    for (int i = 0; i < H / 2; ++i) {
+        const auto a = __builtin_amdgcn_permlane32_swap(t[i], t[i + H / 2], false, false);
+        m = min(m, max(a[0], a[1]));
+    }
+    const auto a = __builtin_amdgcn_permlane16_swap(m, m, false, false);
+    const uint32_t m2 = min(a[0], a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap(m2, m2, false, false);
+    return min(b[0], b[1]);
+}
+
 // Bits of the quarter's columns that belong to the row's k largest entries (x: the quarter's QW
 // values; valid: the row exists; q: the quarter).  All four lanes of a row must call it together.
 template <int DG, int KS>
 __device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int k, bool valid, int q) {
     constexpr int QW = DG / 4;
     uint32_t key[QW];
-    uint32_t top = 0u;
 #pragma unroll
     for (int j = 0; j < QW; ++j) {
         const uint32_t u = __float_as_uint(x[j]);
         uint32_t kk = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
         kk = kk == 0x7FFFFFFFu ? 0x80000000u : kk;          // -0 -> +0
         key[j] = kk >> KS;
-        top = max(top, key[j]);
     }
-    top = quarter_max(top);
-    auto count_ge = [&](uint32_t t) {
-        uint32_t cnt = 0u;
+    uint32_t lo;
+    if (k == QW) {
+        lo = kth_largest_quarter<QW>(key, q);          // the k-th largest key itself
+    } else {
+        uint32_t top = 0u;
 #pragma unroll
-        for (int j = 0; j < QW; ++j) cnt += key[j] >= t ? 1u : 0u;
-        return quarter_sum(cnt);
-    };
-    constexpr uint32_t span = (4u << 23) >> KS;
-    const uint32_t uk = (uint32_t)k;
-    uint32_t lo = top > span ? top - span : 0u, hi = top + 1u;
-    {
+        for (int j = 0; j < QW; ++j) top = max(top, key[j]);
+        top = quarter_max(top);
+        auto count_ge = [&](uint32_t t) {
+            uint32_t cnt = 0u;
+#pragma unroll
+            for (int j = 0; j < QW; ++j) cnt += key[j] >= t ? 1u : 0u;
+            return quarter_sum(cnt);
+        };
+        constexpr uint32_t span = (4u << 23) >> KS;
+        const uint32_t uk = (uint32_t)k;
+        uint32_t hi = top + 1u;
+        lo = top > span ? top - span : 0u;
         const uint32_t cnt = count_ge(lo);
         lo = (cnt >= uk && k < DG) ? lo : 0u;
         uint32_t open = (cnt != uk && k < DG && valid) ? 1u : 0u;
@@ -1148,15 +1281,18 @@ __device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int
             open = (c2 == uk || hi - lo <= 1u) ? 0u : open;
         }
     }
-    // column sets of this quarter: above the threshold, at the threshold
-    uint32_t mgt = 0u, meq = 0u;
+    // Column set of this quarter at or above the threshold, built as a shift register (a compare and an add with
+    // carry per key).  It is the answer unless the row has more than k keys there: then several keys equal the
+    // threshold (which is a key of the row in that case) and the lowest columns among them win.
+    uint32_t mge = 0u;
 #pragma unroll
-    for (int j = 0; j < QW; ++j) {
-        mgt |= key[j] > lo ? 1u << j : 0u;
-        meq |= key[j] == lo ? 1u << j : 0u;
-    }
-    uint32_t msel;
-    {
+    for (int j = QW - 1; j >= 0; --j) mge = mge + mge + (key[j] >= lo ? 1u : 0u);
+    uint32_t msel = mge;
+    if (ballot(quarter_sum((uint32_t)__popc(mge)) != (uint32_t)k) != 0ull) {
+        uint32_t mgt = 0u;
+#pragma unroll
+        for (int j = QW - 1; j >= 0; --j) mgt = mgt + mgt + (key[j] > lo ? 1u : 0u);
+        const uint32_t meq = mge & ~mgt;
         const uint32_t cg = __popc(mgt), ce = __popc(meq);
         uint32_t all[4];
         quarter_all(cg | ce << 8, all);
@@ -1165,16 +1301,12 @@ __device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int
 #pragma unroll
         for (int i = 0; i < 3; ++i) before += i < q ? (int)(all[i] >> 8) : 0;
         int take = min(max(need - before, 0), (int)ce);
-        if (ballot(take != (int)ce) == 0ull) {
-            msel = mgt | meq;
-        } else {
-            msel = mgt;
+        msel = mgt;
 #pragma unroll
-            for (int j = 0; j < QW; ++j) {
-                const uint32_t s = ((meq >> j) & 1u) & (take > 0 ? 1u : 0u);
-                msel |= s << j;
-                take -= (int)s;
-            }
+        for (int j = 0; j < QW; ++j) {
+            const uint32_t s1 = ((meq >> j) & 1u) & (take > 0 ? 1u : 0u);
+            msel |= s1 << j;
+            take -= (int)s1;
         }
     }
     return msel;

@@ -74,8 +74,9 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
     WaveLds<DG, 1>& L = lds[wave];
     float* st_h = L.st[0];
     __shared__ typename std::conditional<B3, WLdsB3<DG>, WLds<DG>>::type wl;
-    __shared__ DealLut dlut;
+    __shared__ typename std::conditional<sizeof(T) == 2, DealLut, DealLutF>::type dlut;
     if constexpr (sizeof(T) == 2) deal_lut_fill(dlut);
+    else deal_lutf_fill(dlut);
     if constexpr (B3) load_w_lds_b3<DG>(a.w, a.ldw, false, wl);
     else load_w_lds<DG>(a.w, a.ldw, false, wl);
     f32x4 dw[WITH_DW ? DG / 16 : 1][WITH_DW ? DG / 16 : 1];
@@ -131,9 +132,9 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
         // not hidden (531 us against 513), and the plain and the fused inverse must rebuild the same bits.
         if constexpr (sizeof(T) == 4) {
             tile_gather_rows<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
-                gather_records_rows<DG, 8>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
-                                           __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf,
-                                           lane, st_h);
+                gather_records_rows<DG, 8, true>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
+                                                 __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf),
+                                                 L.rbuf, lane, st_h, &dlut);
             });
         } else {
             f32x4 hacc[DG / 16];
