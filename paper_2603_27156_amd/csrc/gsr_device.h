@@ -808,9 +808,12 @@ __device__ __forceinline__ void gather_records_rows(const CsrView& g, const floa
                     }
                 }
                 if (row[u] >= 0 && row[u] != cur) {     // the row of this run has ended: its sum joins the tile
+                    float was[CPL];            // (all reads before the writes: one LDS round trip, not one per pair)
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) was[cb] = mine[cur * LR + cb];
 #pragma unroll
                     for (int cb = 0; cb < CPL; ++cb) {
-                        mine[cur * LR + cb] += run[cb];
+                        mine[cur * LR + cb] = was[cb] + run[cb];
                         run[cb] = 0.f;
                     }
                     cur = row[u];
@@ -894,9 +897,12 @@ __device__ __forceinline__ void gather_dense_rows(const CsrView& g, const float*
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
                 if (row[u] >= 0 && row[u] != cur) {
+                    float was[CPL];            // (all reads before the writes: one LDS round trip, not one per pair)
+#pragma unroll
+                    for (int cb = 0; cb < CPL; ++cb) was[cb] = mine[cur * LR + cb];
 #pragma unroll
                     for (int cb = 0; cb < CPL; ++cb) {
-                        mine[cur * LR + cb] += run[cb];
+                        mine[cur * LR + cb] = was[cb] + run[cb];
                         run[cb] = 0.f;
                     }
                     cur = row[u];

@@ -109,16 +109,23 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
         const int r0 = t * 16;
         wave_sync();
         const int rpv = tile_rp_load(a.g, r0, a.n, lane);
-        // The tile's own rows (X_i, and dY_i for the weight gradient) are requested first, in the
-        // tile register layout, and arrive while the neighbour records are gathered.
+        // The tile's own rows (X_i, and dY_i for the weight gradient), in the tile register layout.  Requested before
+        // the gather they arrive while it runs, but hold sixteen registers through it; where the gather is short of
+        // registers they are requested after it and arrive during the weight product (1M-node workload, float32:
+        // forward 291 -> 274 us, inverse 326 -> 309 us, spilled registers 14 -> 4; measured per variant: the fused
+        // inverse + dW kernel gains at D/C = 32 and loses at 64, the 16-bit forward kernel the other way round).
+        constexpr bool OWN_LATE = WITH_DW ? DG == 32 : (sizeof(T) == 4 || DG == 64);
         float xy[4][CPL], gy[WITH_DW ? 4 : 1][CPL];
+        auto own_rows = [&]() {
 #pragma unroll
-        for (int reg = 0; reg < 4; ++reg) {
-            const int row = r0 + 4 * reg + tg;
-            const size_t rowc = (size_t)(row < a.n ? row : a.n - 1);
-            load_cols<CPL, T>(a.plane + rowc * a.ld + CPL * tj, xy[reg]);
-            if constexpr (WITH_DW) load_cols<CPL, T>(a.dy + rowc * a.ldg + CPL * tj, gy[reg]);
-        }
+            for (int reg = 0; reg < 4; ++reg) {
+                const int row = r0 + 4 * reg + tg;
+                const size_t rowc = (size_t)(row < a.n ? row : a.n - 1);
+                load_cols<CPL, T>(a.plane + rowc * a.ld + CPL * tj, xy[reg]);
+                if constexpr (WITH_DW) load_cols<CPL, T>(a.dy + rowc * a.ldg + CPL * tj, gy[reg]);
+            }
+        };
+        if constexpr (!OWN_LATE) own_rows();
         const bool has_hub = tile_begin(a.g, rpv, L.rp, lane);
         if constexpr (DEAL) {
             if (!deal.on && tile_is_heavy(a.g, rpv, L.rp, has_hub)) {      // dealt out before the sweep
@@ -144,6 +151,7 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
                                               lane, hacc, &dlut);
             });
         }
+        if constexpr (OWN_LATE) own_rows();
         if constexpr (WITH_DW) {
 #pragma unroll
             for (int reg = 0; reg < 4; ++reg)

@@ -239,8 +239,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
         float st[sizeof(T) == 4 ? 16 * LR : 1];
     };
     __shared__ Wave lds[4];
-    __shared__ DealLut dlut;
+    __shared__ typename std::conditional<sizeof(T) == 2, DealLut, DealLutF>::type dlut;
     if constexpr (sizeof(T) == 2) deal_lut_fill(dlut);
+    else deal_lutf_fill(dlut);
     Wave& W = lds[threadIdx.x >> 6];
     TileLds& L = W.t;
     const int lane = lane_id();
@@ -254,8 +255,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void k
         if (walk.dealt(g, rpv, L.rp, has_hub)) { walk.next(g); continue; }
         if constexpr (sizeof(T) == 4) {
             tile_gather_rows<DG>(g, hub_part, has_hub, r0, L.rp, W.st, lane, [&](int e_a, int e_b) {
-                gather_records_rows<DG, 8>(g, vals, masks, k, __builtin_amdgcn_readfirstlane(e_a), __builtin_amdgcn_readfirstlane(e_b),
-                                           L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf, lane, W.st);
+                gather_records_rows<DG, 8, true>(g, vals, masks, k, __builtin_amdgcn_readfirstlane(e_a), __builtin_amdgcn_readfirstlane(e_b),
+                                                 L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf, lane, W.st, &dlut);
             });
             wave_sync();
             const int rows = n - r0 < 16 ? n - r0 : 16;
