@@ -139,7 +139,7 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
         // not hidden (531 us against 513), and the plain and the fused inverse must rebuild the same bits.
         if constexpr (sizeof(T) == 4) {
             tile_gather_rows<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
-                gather_records_rows<DG, 8, true>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
+                gather_records_rows<DG, 4, true>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
                                                  __builtin_amdgcn_readfirstlane(e_b), L.rp, reinterpret_cast<RecEdge*>(L.ebuf),
                                                  L.rbuf, lane, st_h, &dlut);
             });
