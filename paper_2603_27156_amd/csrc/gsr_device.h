@@ -1253,9 +1253,8 @@ __device__ __forceinline__ uint32_t select_quarter(const float (&x)[DG / 4], int
     uint32_t key[QW];
 #pragma unroll
     for (int j = 0; j < QW; ++j) {
-        const uint32_t u = __float_as_uint(x[j]);
-        uint32_t kk = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
-        kk = kk == 0x7FFFFFFFu ? 0x80000000u : kk;          // -0 -> +0
+        const uint32_t u = __float_as_uint(x[j] + 0.0f);    // -0 -> +0, every other value as it is
+        const uint32_t kk = u ^ ((uint32_t)((int32_t)u >> 31) | 0x80000000u);
         key[j] = kk >> KS;
     }
     uint32_t lo;
@@ -1415,12 +1414,15 @@ __device__ __forceinline__ void emit_tile(float* st, int r0, int n, int k, int n
     }
     const float scale = record_scale<DG>(x, norm, eps);
     wave_sync();   // every lane holds its quarter: the tile can be reused for the compacted values
+    // a kept value goes to its slot, a dropped one to the lane's dump word: word number = dump + bit * (slot - dump)
+    const int dump = 16 * LR + lane;
+    int ahead = slot - dump;
 #pragma unroll
     for (int j = 0; j < QW; ++j) {
-        const uint32_t bit = (msel >> j) & 1u;
-        st[bit ? slot : 16 * LR + lane] = x[j] * scale;      // dropped columns go to the dump words
-        if (idx_out && bit) ist[slot] = q * QW + j;
-        slot += (int)bit;
+        const int bit = (int)((msel >> j) & 1u);
+        st[dump + __mul24(bit, ahead)] = x[j] * scale;
+        if (idx_out && bit) ist[dump + ahead] = q * QW + j;
+        ahead += bit;
     }
     wave_sync();
     const int rows = min(16, n - r0), total = rows * k;
