@@ -606,8 +606,10 @@ template <int DG, typename T, int MAXB, bool ONE_ROW = false>
 __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* __restrict__ vals,
                                                     const typename MaskOf<DG>::type* __restrict__ masks, int k, int e_a,
                                                     int e_b, const int* s_rp, RecEdge* ebuf, uint8_t* rbuf, int lane,
-                                                    f32x4 (&acc)[DG / 16], const DealLut* lut = nullptr) {
+                                                    f32x4 (&acc)[DG / 16], const DealLut* lut = nullptr,
+                                                    const DealLutF* lutf = nullptr) {
     constexpr bool PERM = sizeof(T) == 2 && !ONE_ROW;     // (callers of that case pass the table)
+    constexpr bool PERMF = sizeof(T) == 4 && ONE_ROW && DG == 64;   // float32 chunk sums: the table of DealLutF (passed too)
     using M = typename MaskOf<DG>::type;
     constexpr int CPL = DG / 16, NW = sizeof(T) == 4 ? CPL : CPL / 2 + 1;
     const int i16 = lane & 15, kk = lane >> 4, bp = CPL * i16;
@@ -680,6 +682,22 @@ __device__ __forceinline__ void gather_records_mfma(const CsrView& g, const T* _
                         acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pm, b, acc[cb], 0, 0, 0);
                         acc[cb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(pl, b, acc[cb], 0, 0, 0);
                     }
+                }
+                return;
+            }
+            if constexpr (PERMF) {
+#pragma unroll
+                for (int u = 0; u < GB; ++u) {
+                    const uint4 sa = *reinterpret_cast<const uint4*>(lutf->sel[nib[u]]);
+                    const uint2 sb = *reinterpret_cast<const uint2*>(lutf->sel[nib[u]] + 4);
+                    const uint32_t b0 = __builtin_amdgcn_perm(0u, w[u][0], sa.x);
+                    const uint32_t b1 = __builtin_amdgcn_perm(w[u][1], w[u][0], sa.y);
+                    const uint32_t b2 = __builtin_amdgcn_perm(w[u][1], w[u][0], sa.z) | __builtin_amdgcn_perm(0u, w[u][2], sa.w);
+                    const uint32_t b3 = __builtin_amdgcn_perm(w[u][1], w[u][0], sb.x) | __builtin_amdgcn_perm(w[u][3], w[u][2], sb.y);
+                    acc[0][0] = __builtin_fmaf(p[u], __uint_as_float(b0), acc[0][0]);
+                    acc[1][0] = __builtin_fmaf(p[u], __uint_as_float(b1), acc[1][0]);
+                    acc[2][0] = __builtin_fmaf(p[u], __uint_as_float(b2), acc[2][0]);
+                    acc[3][0] = __builtin_fmaf(p[u], __uint_as_float(b3), acc[3][0]);
                 }
                 return;
             }
@@ -1626,7 +1644,8 @@ __device__ __forceinline__ void hub_chunk_store(const f32x4 (&acc)[DG / 16], flo
 template <int DG, typename T>
 __device__ __forceinline__ void hub_records_pass(const CsrView& g, const HubChunks& h, const T* __restrict__ vals,
                                                  const typename MaskOf<DG>::type* __restrict__ masks, int k,
-                                                 float* __restrict__ part, HubLds& L, int first_wave, int nwaves) {
+                                                 float* __restrict__ part, HubLds& L, int first_wave, int nwaves,
+                                                 const DealLutF* lutf) {
     const int lane = lane_id();
     for (int q = first_wave; q < h.n_chunks; q += nwaves) {
         const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
@@ -1634,7 +1653,8 @@ __device__ __forceinline__ void hub_records_pass(const CsrView& g, const HubChun
         f32x4 acc[DG / 16];
 #pragma unroll
         for (int cb = 0; cb < DG / 16; ++cb) acc[cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-        gather_records_mfma<DG, T, 16, true>(g, vals, masks, k, e0, e1, L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf, lane, acc);
+        gather_records_mfma<DG, T, 16, true>(g, vals, masks, k, e0, e1, L.rp, reinterpret_cast<RecEdge*>(L.ebuf), L.rbuf, lane, acc,
+                                             nullptr, lutf);
 #pragma unroll
         for (int cb = 0; cb < DG / 16; ++cb) acc[cb][0] = quarter_sum(acc[cb][0]);
         hub_chunk_store<DG>(acc, part + (size_t)q * DG, lane);
@@ -1662,8 +1682,10 @@ __global__ __launch_bounds__(256) void k_hub_records(CsrView g, HubChunks h, con
                                                      const typename MaskOf<DG>::type* __restrict__ masks, int k,
                                                      float* __restrict__ part) {
     __shared__ HubLds lds[4];
+    __shared__ DealLutF dlut;
+    deal_lutf_fill(dlut);
     hub_records_pass<DG, T>(g, h, vals, masks, k, part, lds[threadIdx.x >> 6], (blockIdx.x * blockDim.x + threadIdx.x) >> 6,
-                            (gridDim.x * blockDim.x) >> 6);
+                            (gridDim.x * blockDim.x) >> 6, &dlut);
 }
 
 template <int DG, typename T>
@@ -1682,8 +1704,10 @@ __global__ __launch_bounds__(256) void k_hub_both(CsrView ga, HubChunks ha, cons
                                                   float* __restrict__ part_a, CsrView gt, HubChunks ht,
                                                   const T* __restrict__ x, int64_t ld, float* __restrict__ part_t) {
     __shared__ HubLds lds[4];
+    __shared__ DealLutF dlut;
+    deal_lutf_fill(dlut);
     const int first = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nwaves = (gridDim.x * blockDim.x) >> 6;
-    if (blockIdx.y == 0) hub_records_pass<DG, T>(ga, ha, vals, masks, k, part_a, lds[threadIdx.x >> 6], first, nwaves);
+    if (blockIdx.y == 0) hub_records_pass<DG, T>(ga, ha, vals, masks, k, part_a, lds[threadIdx.x >> 6], first, nwaves, &dlut);
     else hub_dense_pass<DG, T>(gt, ht, x, ld, part_t, lds[threadIdx.x >> 6], first, nwaves);
 }
 
