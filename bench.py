@@ -378,6 +378,7 @@ def main() -> int:
         del plane, vv, ii
 
     cpu_baseline = None
+    parity = None
     if not args.no_cpu_baseline:
         import oracle
         # bounded sample: the first layers of the same recipe, at most 1M nodes (10-30 s of CPU work)
@@ -388,10 +389,43 @@ def main() -> int:
         ocfg = oracle.Cfg(sw.d, sw.c, sw.k, oracle.NORM_RMS if sw.norm == "rms" else oracle.NORM_NONE, 1e-5,
                           oracle.STORE_BF16 if bf16 else oracle.STORE_F32)
         variant = {"none": 0, "all": 2, "near-ties": 3}[mode_name]
+        same_graph = sw.n == w.n and not wide      # then the library's graph serves the sample as well
         tc = time.perf_counter()
-        oracle.step(og, ocfg, sw.l, sinp.x0, sinp.weights, sinp.w_out, 0.0, sinp.target, variant=variant, want=(),
-                    tie_tol=args.tie_tol)
+        ref = oracle.step(og, ocfg, sw.l, sinp.x0, sinp.weights, sinp.w_out, 0.0, sinp.target, variant=variant,
+                          want=("X0rec", "dW", "dwout", "dX0") if same_graph else (), tie_tol=args.tie_tol)
         tc = time.perf_counter() - tc
+        if same_graph:
+            # the same sample through the library, compared with the oracle just timed (element-wise bar of the
+            # parity tests: |a - b| <= atol + rtol |b|; rows a near-tie decides differently are not taken out here)
+            scfg = gsr.Config(n=sw.n, d=sw.d, c=sw.c, k=sw.k, l=sw.l, dtype=gsr.GSR_BF16 if bf16 else gsr.GSR_F32,
+                              norm=gsr.GSR_NORM_RMS if sw.norm == "rms" else gsr.GSR_NORM_NONE, eps=1e-5,
+                              layout=gsr.GSR_LAYOUT_GROUP_PLANAR, save_indices=INDEX_MODES[mode_name], tie_tol=args.tie_tol)
+            sx0 = torch.from_numpy(sinp.x0).to(dev).view(sw.n, sw.c, sw.dg).permute(1, 0, 2).contiguous()
+            sx0 = sx0.to(torch.bfloat16) if bf16 else sx0
+            sW = torch.from_numpy(sinp.weights).to(dev)
+            sloss, sdb = torch.zeros(1, **f32), torch.zeros(1, **f32)
+            sdW, sdw = torch.empty_like(sW), torch.empty(sw.d, **f32)
+            sdx0, sx0r = torch.empty_like(sx0), torch.empty_like(sx0)
+            sws = torch.empty(gsr.gsr_workspace_size(g, scfg)[1], dtype=torch.uint8, device=dev)
+            gsr.gsr_step(g, scfg, sx0, sW, torch.from_numpy(sinp.w_out).to(dev), torch.zeros(1, **f32),
+                         torch.from_numpy(sinp.target).to(dev), sloss, sdW, sdw, sdb, dx0_out=sdx0, x0_rebuilt_out=sx0r,
+                         workspace=sws)
+            torch.cuda.synchronize()
+            rtol, atol = (1e-2, 1e-2) if bf16 else (1e-4, 1e-5)
+
+            def cmp(got, want):
+                got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+                diff = np.abs(got - want)
+                return {"max_abs_err": float(diff.max()), "rel_norm_err": float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300)),
+                        "fraction_outside_bar": float(np.mean(diff > atol + rtol * np.abs(want)))}
+
+            rows = lambda t: t.float().permute(1, 0, 2).reshape(sw.n, sw.d).cpu().numpy()
+            parity = {"rtol": rtol, "atol": atol, "loss_rel_err": abs(float(sloss.item()) - ref["loss"]) / abs(ref["loss"]),
+                      "dW": cmp(sdW.cpu().numpy(), ref["dW"]), "dw_out": cmp(sdw.cpu().numpy(), ref["dwout"]),
+                      "dX0": cmp(rows(sdx0), ref["dX0"]), "X0_rebuilt": cmp(rows(sx0r), ref["X0rec"]),
+                      "near_tie_rows_listed": {"library": gsr.gsr_step_tie_stats(g, scfg, sws)["listed"] if mode_name == "near-ties" else None,
+                                               "oracle": int(ref["n_listed"]) if mode_name == "near-ties" else None}}
+            del sws, sx0, sdx0, sx0r, ref
         cpu_baseline = {"value": sw.n * sw.l / tc, "unit": "node-layers/s", "cores": oracle.num_threads(),
                         "kind": "oracle", "seconds": tc,
                         "sample": f"same recipe at N={sw.n} nodes, L={sw.l} layers (D={sw.d}, C={sw.c}, k={sw.k}), one full step, "
@@ -407,7 +441,7 @@ def main() -> int:
                    "index_mode": mode_name, "tie_tol": args.tie_tol if mode_name == "near-ties" else None},
         "ms_per_step_with_kernel_events": ms_per_step_profiled, "hip_graph": bool(args.graph),
         "roofline": roofline, "step_roofline": step_roofline, "cpu_baseline": cpu_baseline, "kernels": kernels,
-        "fidelity": fidelity, "depth_sweep": depth_sweep, "variants": variants or None, "operators": operators,
+        "parity_vs_oracle": parity, "fidelity": fidelity, "depth_sweep": depth_sweep, "variants": variants or None, "operators": operators,
         "peak_hbm_bytes": peak_hbm, "workspace_bytes": int(main_run.ws_bytes),
         "loss": float(main_run.loss.item()), "x0_rebuild_max_abs_err": rebuilt_err, "setup_seconds": t_gen,
     }
