@@ -1372,8 +1372,9 @@ __device__ __forceinline__ float record_scale(const float (&x)[DG / 4], int norm
 // GS of the 16 rows of an LDS tile and their records (Section 4.1; record layout of Section 4.3).
 // st holds the rows as they read back from memory (16 x (DG+1) floats, rows past the end zero).
 // Lane (r, q) takes the quarter q of row r into registers, so the 16 searches for the k-th largest
-// key run side by side in vector registers: interval bisection on an order-preserving integer
-// image of the values, count = own compares + the three partner quarters.  Invariant per row: at
+// key run side by side in vector registers on an order-preserving integer image of the values
+// (select_quarter): a selection network when k is a quarter of the width, else interval bisection,
+// count = own compares + the three partner quarters.  Invariant per row of the bisection: at
 // least k keys are >= lo and fewer than k are >= hi; hi starts just above the row maximum, lo four
 // binades below it (0 when a count says that is too high).  A row closes when a candidate splits
 // off exactly k keys or the interval is down to one value (a tie at the k-th position); ties go

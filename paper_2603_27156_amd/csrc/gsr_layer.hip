@@ -134,9 +134,9 @@ __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgp
                 continue;
             }
         }
-        // float32 forward: the sums in ordinary arithmetic (329 us against 370 through the matrix cores on the 1M-node
-        // workload).  The inverse kernels keep the matrix product: at two waves per SIMD the row sums' LDS round trips are
-        // not hidden (531 us against 513), and the plain and the fused inverse must rebuild the same bits.
+        // float32: the sums in ordinary arithmetic (forward 329 us against 370 through the matrix cores on the 1M-node
+        // workload), in the forward and in both inverse kernels alike, so that f_i is recomputed by the instructions that
+        // computed it; four window loads in flight per lane group (eight cost registers: inverse 310 us against 297).
         if constexpr (sizeof(T) == 4) {
             tile_gather_rows<DG>(a.g, a.hub_part, has_hub, r0, L.rp, st_h, lane, [&](int e_a, int e_b) {
                 gather_records_rows<DG, 4, true>(a.g, a.in.vals, a.in.mask, a.k, __builtin_amdgcn_readfirstlane(e_a),
