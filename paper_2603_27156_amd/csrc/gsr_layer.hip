@@ -370,22 +370,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 }
 
 // dW_i[e] = sum over workgroup partials, as a launch of its own (used when the gradient kernel that follows has too
-// few tiles per wave to absorb the work, see layer_backward_impl).  A block owns 64 entries; its 16 thread rows each sum a
-// contiguous sixteenth of the partials in ascending order, then the 16 sums are added in order.
-__global__ __launch_bounds__(1024) void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems,
-                                                    float* __restrict__ out, int cols, int ld_out) {
-    __shared__ float red[16][64];
-    const int e = blockIdx.x * 64 + (threadIdx.x & 63), seg = threadIdx.x >> 6;
+// few tiles per wave to absorb the work, see layer_backward_impl).  A block of 256 threads owns 16 entries; its 16
+// thread rows each sum a contiguous sixteenth of the partials in ascending order, then the 16 sums are added in order.
+// (Blocks of 64 entries left three quarters of the compute units idle on a 64 x 64 matrix: 18 us per launch.)
+constexpr int DW_REDUCE_ENTRIES = 16;
+__global__ __launch_bounds__(256) void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems,
+                                                   float* __restrict__ out, int cols, int ld_out) {
+    __shared__ float red[16][DW_REDUCE_ENTRIES];
+    const int j = threadIdx.x & (DW_REDUCE_ENTRIES - 1), seg = threadIdx.x / DW_REDUCE_ENTRIES;
+    const int e = blockIdx.x * DW_REDUCE_ENTRIES + j;
     const int per = (nparts + 15) / 16, p0 = seg * per, p1 = min(nparts, p0 + per);
     float acc = 0.f;
-    if (e < elems)
-        for (int p = p0; p < p1; ++p) acc += partial[(size_t)p * elems + e];
-    red[seg][threadIdx.x & 63] = acc;
+    if (e < elems) {
+        int p = p0;
+        for (; p + 8 <= p1; p += 8) {           // eight loads in flight, added in ascending order
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(p + u) * elems + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; p < p1; ++p) acc += partial[(size_t)p * elems + e];
+    }
+    red[seg][j] = acc;
     __syncthreads();
     if (seg == 0 && e < elems) {
-        float s = red[0][threadIdx.x];
+        float s = red[0][j];
 #pragma unroll
-        for (int q = 1; q < 16; ++q) s += red[q][threadIdx.x];
+        for (int q = 1; q < 16; ++q) s += red[q][j];
         out[(size_t)(e / cols) * ld_out + e % cols] = s;       // entry (e / cols, e % cols) of a matrix of row stride ld_out
     }
 }
@@ -1326,7 +1338,7 @@ static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, co
             }
             if (mode == 2) {
                 ProfScope prof(KC_DW_REDUCE, x.s);
-                hipLaunchKernelGGL(k_dw_reduce, dim3(64), dim3(1024), 0, x.s, (const float*)x.dw_partial(), (int)nparts, 64 * 64,
+                hipLaunchKernelGGL(k_dw_reduce, dim3(64 * 64 / DW_REDUCE_ENTRIES), dim3(256), 0, x.s, (const float*)x.dw_partial(), (int)nparts, 64 * 64,
                                    dw_i + (size_t)mb * 64 * dgw + 64 * ob, 64, dgw);
             }
         }
@@ -1478,7 +1490,7 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         float* dwi = dw_out + (size_t)(i - 1) * DG * DG;
         if (x.tiles < 4 * 4 * x.g->grid) {
             ProfScope prof(KC_DW_REDUCE, x.s);
-            hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + 63) / 64), dim3(1024), 0, x.s, (const float*)x.dw_partial(),
+            hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + DW_REDUCE_ENTRIES - 1) / DW_REDUCE_ENTRIES), dim3(256), 0, x.s, (const float*)x.dw_partial(),
                                (int)nparts, DG * DG, dwi, DG, DG);
             dwi = nullptr;
         }
