@@ -486,16 +486,24 @@ static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz,
     g->num_cus = prop.multiProcessorCount;
     int grid = options().max_workgroups > 0 ? (int)options().max_workgroups : g->num_cus * 4;
     g->grid = std::max(8, grid / 8 * 8);
+    const int full_grid = g->grid;
+    // A graph of a few hundred tiles is served best by a workgroup per two tiles (every workgroup of a layer kernel
+    // first loads and splits W_i): on the 2,000-node workload, 125 tiles, the step takes 0.35 ms with 64 workgroups
+    // per launch against 0.47 with 512, 0.37 with 256, 0.40 with 16.
+    if (options().max_workgroups <= 0) {
+        const int64_t by_tiles = std::max<int64_t>(64, ((n + 15) / 16 / 2 + 7) / 8 * 8);
+        if (by_tiles < g->grid) g->grid = (int)by_tiles;
+    }
     // Small graphs (fewer than four tiles per resident wave: a launch is as long as its longest tile, and the heavy
     // tiles are not dealt out first) are cut at 64 as well, with chunks of 64: on the 100k-node workload (6,250 tiles
     // for 4,096 waves, rows of up to 575 entries) the step takes 11.5 ms against 16.0 with the cut at 512, while the
     // 1M-node workload (15 tiles per wave) is best left at 512 (79.0 ms per 16 layers against 79.7 / 82.4 / 82.7 at
     // 256 / 128 / 64).
-    const bool few_tiles = (n + 15) / 16 < (int64_t)16 * g->grid;
+    const bool few_tiles = (n + 15) / 16 < (int64_t)16 * full_grid;
     const int64_t hub_threshold = options().hub_threshold > 0 ? options().hub_threshold : ((long_rows || few_tiles) ? 64 : 512);
     const int64_t hub_chunk = options().hub_chunk > 0 ? options().hub_chunk : (long_rows ? 256 : 64);
     g->hub_threshold = (int32_t)hub_threshold;
-    g->split_backward = !(long_rows || (n + 15) / 16 < (int64_t)4 * g->grid);    // (not with fewer tiles than resident waves)
+    g->split_backward = !(long_rows || (n + 15) / 16 < (int64_t)4 * full_grid);    // (not with fewer tiles than resident waves)
 
     gsr_status_t st = upload_csr(a, n, hub_threshold, hub_chunk, &g->a);
     if (st == GSR_OK) {
