@@ -259,8 +259,8 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
     w.hub_partial2 = off;
     off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
-    w.h = off;               // (float32 storage only: the bf16 backward keeps H on chip)
-    if (b == 4 && g->split_backward) off += align_up(n * dgs * sizeof(float));
+    w.h = off;               // (not for 16-bit storage at 32 columns: that backward keeps H on chip)
+    if ((b == 4 || dgs == 64) && g->split_backward) off += align_up(n * dgs * sizeof(float));
     w.total = off;
     return w;
 }

@@ -1144,15 +1144,17 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
 // How the backward of a block takes dW_i.  float32: the inverse kernel (sixteen waves per compute unit, row-wise sums as
 // in the forward kernel, so f_i is recomputed in the arithmetic it was computed in) leaves H in memory and k_dw takes
 // H^T dY_i in a pass of its own: 476 -> 320 + 112 us per block on the 1M-node workload (-3.8 % on the step) for 512 more
-// bytes per row.  bf16 storage: the fused kernel (inverse + dW accumulators at eight waves per compute unit), whose
-// neighbour sums hide on the bf16 pipe: split 253 + 80 us against 337 fused at 1M nodes, 1,243 + 228 against 1,205 at 8M.
+// bytes per row.  bf16 storage at D/C = 64: split as well (240 + 81 us against 340 fused at 1M nodes once the inverse
+// requested its own rows after the gather; 253 + 80 against 337 before).  bf16 storage at D/C = 32: the fused kernel
+// (inverse + dW accumulators at eight waves per compute unit), whose neighbour sums hide on the bf16 pipe: 1,243 + 228 us
+// split against 1,205 fused at 8M nodes (1,150 fused now).
 // Graphs with fewer tiles than resident waves, or with all rows in the first pass (a launch there is at most one short
 // tile per wave, and two more launches per block cost more than the occupancy gains: 0.56 against 0.70 ms per step on
 // the 2,000-node workload, 487 against 496 ms on the Table-1-shaped one) keep the fused kernel in float32 as well; it
 // uses the same row-wise sums, so whichever way a block's backward runs it rebuilds the bits the plain inverse
 // rebuilds.  (The 100k-node workload, 1.5 tiles per wave, is better split: 12.0 against 12.3 ms.)
-template <typename T>
-static bool split_dw(const gsr_graph_t* g) { return sizeof(T) == 4 && g->split_backward; }
+template <int DG, typename T>
+static bool split_dw(const gsr_graph_t* g) { return (sizeof(T) == 4 || DG == 64) && g->split_backward; }
 
 // mode 0: forward (+), 1: inverse (-), 2: inverse (-) with dW
 template <int DG, typename T>
@@ -1328,7 +1330,7 @@ static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, co
         for (int ob = 0; ob < S; ++ob) {
             const float* wsub = wi + (size_t)mb * 64 * dgw + 64 * ob;
             unsigned nparts = 0;
-            if (mode == 2 && split_dw<T>(x.g)) {
+            if (mode == 2 && split_dw<64, T>(x.g)) {
                 launch_block<64, T>(x, 1, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false, nullptr, 0, ob > 0,
                                     TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, x.hplane());
                 nparts = launch_dw<64, T>(x, dy + 64 * ob, ldg);
@@ -1475,7 +1477,7 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         }
         launch_hub_both<DG, T>(x, x.rec(i - 1, layer), dy.grp(i - 1), dy.ld);
         unsigned nparts;
-        if (split_dw<T>(x.g)) {
+        if (split_dw<DG, T>(x.g)) {
             // X_i = Y_i - f_i(Y_{i-1}) with H kept for the weight gradient, then dW_i = H^T dY_i
             launch_block<DG, T>(x, 1, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, nullptr, 0, true,
                                 TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, DG, x.hplane());
