@@ -771,23 +771,28 @@ __device__ __forceinline__ void gather_records_rows(const CsrView& g, const floa
     for (int eb = e_a; eb < e_b; eb += 64) {
         const int e = eb + lane;
         const bool ok = e < e_b;
-        const int j = ok ? __builtin_nontemporal_load(g.ci + e) : 0;
+        const int ec = ok ? e : e_b - 1;
+        const int j = __builtin_nontemporal_load(g.ci + ec);
         RecEdge me;
-        me.a = ok ? __builtin_nontemporal_load(g.av + e) : 0.f;
+        me.a = ok ? __builtin_nontemporal_load(g.av + ec) : 0.f;
         const M m = masks[j];
         me.off0 = (uint32_t)j * (uint32_t)k;
         me.mlo = (uint32_t)m;
         if constexpr (DG == 64) me.mhi = (uint32_t)(m >> 32);
         else me.mhi = 0u;
-        const int r = tile_row_of(s_rp, e);
+        // The places of the round past its last edge are staged too: the last edge once more with a_ij = 0.
+        // A run is a whole number of batches, so every place a lane group reads is staged and adds what it should: no
+        // test per edge for the end of the run or of the round.
+        const int r = tile_row_of(s_rp, ec);
         wave_sync();          // readers of the previous round are done
         ebuf[lane] = me;
         rbuf[lane] = (uint8_t)r;
         wave_sync();
         const int cnt = e_b - eb < 64 ? e_b - eb : 64;     // wave-uniform
-        const int steps = (cnt + 3) >> 2;                  // edges per run
+        const int steps = (((cnt + 3) >> 2) + GB - 1) / GB * GB;      // edges per run (at most 16: GB divides 16)
+        static_assert(16 % GB == 0, "a run must end inside the 64 staged places");
         const int first = kk * steps;
-        int cur = (int)rbuf[first < cnt ? first : cnt - 1];
+        int cur = (int)rbuf[first];
         float run[CPL];
 #pragma unroll
         for (int cb = 0; cb < CPL; ++cb) run[cb] = 0.f;
@@ -798,15 +803,13 @@ __device__ __forceinline__ void gather_records_rows(const CsrView& g, const floa
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
                 const int ei = first + s0 + u;
-                const bool okv = s0 + u < steps && ei < cnt;
-                const int eic = okv ? ei : cnt - 1;
-                const RecEdge er = ebuf[eic];
+                const RecEdge er = ebuf[ei];
                 const uint32_t word = upper ? er.mhi : er.mlo;
                 const uint32_t at = er.off0 + (uint32_t)__popc(er.mlo & below_lo) + (uint32_t)__popc(er.mhi & below_hi);
                 nib[u] = (word >> sh) & ((1u << CPL) - 1u);
                 load_words<CPL>(vals + (size_t)at, w[u]);
-                p[u] = okv ? er.a : 0.f;
-                row[u] = okv ? (int)rbuf[eic] : -1;
+                p[u] = er.a;
+                row[u] = (int)rbuf[ei];
             }
             constexpr bool PERM = LUT && CPL == 4;
             uint4 sa_next = make_uint4(0u, 0u, 0u, 0u);      // selectors of the edge after the present one
@@ -825,7 +828,7 @@ __device__ __forceinline__ void gather_records_rows(const CsrView& g, const floa
                         sb_next = *reinterpret_cast<const uint2*>(lut->sel[nib[u + 1 < GB ? u + 1 : u]] + 4);
                     }
                 }
-                if (row[u] >= 0 && row[u] != cur) {     // the row of this run has ended: its sum joins the tile
+                if (row[u] != cur) {     // the row of this run has ended: its sum joins the tile
                     float was[CPL];            // (all reads before the writes: one LDS round trip, not one per pair)
 #pragma unroll
                     for (int cb = 0; cb < CPL; ++cb) was[cb] = mine[cur * LR + cb];
@@ -885,17 +888,19 @@ __device__ __forceinline__ void gather_dense_rows(const CsrView& g, const float*
         const int e = eb + lane;
         const bool ok = e < e_b;
         EdgeRec me;
-        me.j = ok ? __builtin_nontemporal_load(g.ci + e) : 0;
-        me.a = ok ? __builtin_nontemporal_load(g.av + e) : 0.f;
-        me.r = tile_row_of(s_rp, e);
+        const int ec = ok ? e : e_b - 1;                 // (places past the last edge: the last edge once more with a_ij = 0)
+        me.j = __builtin_nontemporal_load(g.ci + ec);
+        me.a = ok ? __builtin_nontemporal_load(g.av + ec) : 0.f;
+        me.r = tile_row_of(s_rp, ec);
         me.pad = 0;
         wave_sync();          // readers of the previous round are done
         ebuf[lane] = me;
         wave_sync();
         const int cnt = e_b - eb < 64 ? e_b - eb : 64;
-        const int steps = (cnt + 3) >> 2;
+        const int steps = (((cnt + 3) >> 2) + GB - 1) / GB * GB;
+        static_assert(16 % GB == 0, "a run must end inside the 64 staged places");
         const int first = kk * steps;
-        int cur = ebuf[first < cnt ? first : cnt - 1].r;
+        int cur = ebuf[first].r;
         float run[CPL];
 #pragma unroll
         for (int cb = 0; cb < CPL; ++cb) run[cb] = 0.f;
@@ -905,16 +910,14 @@ __device__ __forceinline__ void gather_dense_rows(const CsrView& g, const float*
             int row[GB];
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
-                const int ei = first + s0 + u;
-                const bool okv = s0 + u < steps && ei < cnt;
-                const EdgeRec er = ebuf[okv ? ei : cnt - 1];
+                const EdgeRec er = ebuf[first + s0 + u];
                 load_words<CPL>(xl + (size_t)(uint32_t)er.j * ldu, w[u]);
-                p[u] = okv ? er.a : 0.f;
-                row[u] = okv ? er.r : -1;
+                p[u] = er.a;
+                row[u] = er.r;
             }
 #pragma unroll
             for (int u = 0; u < GB; ++u) {
-                if (row[u] >= 0 && row[u] != cur) {
+                if (row[u] != cur) {
                     float was[CPL];            // (all reads before the writes: one LDS round trip, not one per pair)
 #pragma unroll
                     for (int cb = 0; cb < CPL; ++cb) was[cb] = mine[cur * LR + cb];
