@@ -96,6 +96,8 @@ def main() -> int:
     ap.add_argument("--save-indices", action="store_true", help="same as --index-mode all")
     ap.add_argument("--tie-tol", type=float, default=2.0 ** -12)
     ap.add_argument("--hub-threshold", type=int, default=0, help="rows longer than this are reduced in two passes")
+    ap.add_argument("--hub-values", type=int, default=0, choices=[0, 1, 2],
+                    help="first pass over float32 records: 1 a lane per value, 2 a lane per column group, 0 chosen per graph")
     ap.add_argument("--graph", action="store_true", help="capture the step into a HIP graph and time replays")
     ap.add_argument("--hub-chunk", type=int, default=0, help="neighbours per first-pass partial sum of such rows")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -131,6 +133,8 @@ def main() -> int:
         gsr.gsr_set_option("max_workgroups", args.max_workgroups)
     if args.hub_threshold:
         gsr.gsr_set_option("hub_threshold", args.hub_threshold)
+    if args.hub_values:
+        gsr.gsr_set_option("hub_values", args.hub_values)
     if args.hub_chunk:
         gsr.gsr_set_option("hub_chunk", args.hub_chunk)
     t_gen = time.time()

@@ -1715,4 +1715,145 @@ __global__ __launch_bounds__(256) void k_hub_both(CsrView ga, HubChunks ha, cons
     else hub_dense_pass<DG, T>(gt, ht, x, ld, part_t, lds[threadIdx.x >> 6], first, nwaves);
 }
 
+// ---- first pass over the chunks, value by value (float32 records) ---------------------------------
+// On graphs where nearly every row is split the first pass is the step, and dealing a record to the lanes that own
+// its columns (sixteen lanes, a four-slot window each: four times the record's bytes through the vector cache, some
+// thirty instructions per four edges) is what it spends.  Here a lane owns a *value* instead: LPE = 2^LG lanes per
+// edge, lane t of them loads value t (+ LPE, + 2 LPE .. below k) of the record and the number of its column - one
+// byte per value, written from the column mask by k_record_columns before the pass (0xFF for a slot the record does
+// not use: a column block of a wide group keeps between 0 and k values) - and writes a_ij * value to that
+// column of its edge place's row in LDS (64 / LPE places, each a row of DG floats, zero elsewhere; the places of one
+// instruction are different rows and the values of one record different columns, so no two lanes meet).  Then every lane
+// reads four adjacent floats of the rows - whole 16-byte reads, no dealing - adds them to its four running sums, and the
+// writers put their zeros back.  LDS float atomics instead of the write / read / clear were four times slower than
+// the dealing (one such instruction takes some 140 cycles).  The order of the additions is fixed by the edge list.
+template <int DG>
+__global__ __launch_bounds__(256) void k_record_columns(int n, int k, const typename MaskOf<DG>::type* __restrict__ masks,
+                                                        uint8_t* __restrict__ cols) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    uint64_t m = (uint64_t)masks[j];
+    uint8_t* o = cols + (size_t)j * k;
+    if ((k & 3) == 0) {
+        for (int t = 0; t < k; t += 4) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t c = m ? (uint32_t)__builtin_ctzll(m) : 0xFFu;
+                m &= m - 1;
+                w |= c << (8 * b);
+            }
+            *reinterpret_cast<uint32_t*>(o + t) = w;
+        }
+    } else {
+        for (int t = 0; t < k; ++t) {
+            o[t] = m ? (uint8_t)__builtin_ctzll(m) : (uint8_t)0xFF;
+            m &= m - 1;
+        }
+    }
+}
+
+template <int DG, int LG>
+struct HubValLds {
+    uint2 ebuf[64];          // (j * k, a_ij) of the staged edges
+    float rows[(64 >> LG) * DG];   // a dense row per edge place; all zero between two instructions' worth of edges
+    float red[256];          // the lanes' sums at the end of a chunk
+};
+
+template <int DG, int LG, int KQ>
+__device__ __forceinline__ void hub_values_pass(const CsrView& g, const HubChunks& h, const float* __restrict__ vals,
+                                                const uint8_t* __restrict__ cols, int k, float* __restrict__ part,
+                                                HubValLds<DG, LG>& L, int first_wave, int nwaves) {
+    constexpr int LPE = 1 << LG, NE = 64 >> LG;          // lanes per edge, edges per instruction
+    constexpr int MAXS = 64 / NE;                        // instructions per round of 64 staged edges
+    constexpr int GB = KQ == 1 ? (MAXS < 8 ? MAXS : 8) : KQ == 2 ? 4 : 2;
+    constexpr int TOT = NE * DG, NR = (TOT + 255) / 256; // floats of the dense rows, float4 reads per lane
+    static_assert(MAXS % GB == 0, "a round is a whole number of batches");
+    static_assert(256 % DG == 0, "a lane's four floats are the same columns in every read");
+    const int lane = lane_id();
+    const int place = lane >> LG, t = lane & (LPE - 1);
+    float* mine = L.rows + place * DG;
+    for (int i = lane; i < TOT; i += 64) L.rows[i] = 0.f;
+    for (int q = first_wave; q < h.n_chunks; q += nwaves) {
+        const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int eb = e0; eb < e1; eb += 64) {
+            // places past the last edge: the last edge once more with a_ij = 0
+            const int e = eb + lane;
+            const bool ok = e < e1;
+            const int ec = ok ? e : e1 - 1;
+            const int j = __builtin_nontemporal_load(g.ci + ec);
+            const float a = ok ? __builtin_nontemporal_load(g.av + ec) : 0.f;
+            wave_sync();          // readers of the previous round are done
+            L.ebuf[lane] = make_uint2((uint32_t)j * (uint32_t)k, __float_as_uint(a));
+            wave_sync();
+            const int cnt = e1 - eb < 64 ? e1 - eb : 64;
+            const int steps = ((cnt + NE - 1) / NE + GB - 1) / GB * GB;
+            for (int s0 = 0; s0 < steps; s0 += GB) {
+                float v[GB][KQ];
+                uint32_t c[GB][KQ];
+#pragma unroll
+                for (int u = 0; u < GB; ++u) {
+                    const uint2 er = L.ebuf[(s0 + u) * NE + place];
+#pragma unroll
+                    for (int w = 0; w < KQ; ++w) {
+                        // (a lane past the record's last slot takes slot 0 again: it writes what slot 0's lane writes)
+                        const int tt = t + w * LPE;
+                        const uint32_t at = er.x + (uint32_t)(tt < k ? tt : 0);
+                        v[u][w] = vals[at] * __uint_as_float(er.y);
+                        c[u][w] = cols[at];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < GB; ++u) {
+#pragma unroll
+                    for (int w = 0; w < KQ; ++w)
+                        if (c[u][w] != 0xFFu) mine[c[u][w]] = v[u][w];
+                    wave_sync();
+#pragma unroll
+                    for (int r = 0; r < NR; ++r) {
+                        const int at = 4 * (r * 64 + lane);
+                        if (TOT % 256 == 0 || at < TOT) {
+                            const f32x4 d = *reinterpret_cast<const f32x4*>(L.rows + at);
+                            acc += d;
+                        }
+                    }
+                    wave_sync();
+#pragma unroll
+                    for (int w = 0; w < KQ; ++w)
+                        if (c[u][w] != 0xFFu) mine[c[u][w]] = 0.f;
+                }
+            }
+        }
+        // lane l holds columns (4 l .. 4 l + 3) mod DG: the 256 / DG lanes of a column are added in lane order
+        wave_sync();
+        *reinterpret_cast<f32x4*>(L.red + 4 * lane) = acc;
+        wave_sync();
+        if (lane < DG) {
+            float s = 0.f;
+#pragma unroll
+            for (int gq = 0; gq < 256 / DG; ++gq) s += L.red[gq * DG + lane];
+            part[(size_t)q * DG + lane] = s;
+        }
+    }
+}
+
+// Lanes per edge and values per lane for k kept values: (4, 1), (8, 1), (16, 1), (16, 2), (16, 4).
+template <typename F>
+inline void hub_values_variant(int k, F&& f) {
+    if (k <= 4) f(std::integral_constant<int, 2>{}, std::integral_constant<int, 1>{});
+    else if (k <= 8) f(std::integral_constant<int, 3>{}, std::integral_constant<int, 1>{});
+    else if (k <= 16) f(std::integral_constant<int, 4>{}, std::integral_constant<int, 1>{});
+    else if (k <= 32) f(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
+    else f(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
+}
+
+template <int DG, int LG, int KQ>
+__global__ __launch_bounds__(256) void k_hub_values(CsrView g, HubChunks h, const float* __restrict__ vals,
+                                                    const uint8_t* __restrict__ cols, int k, float* __restrict__ part) {
+    __shared__ HubValLds<DG, LG> lds[4];
+    hub_values_pass<DG, LG, KQ>(g, h, vals, cols, k, part, lds[threadIdx.x >> 6], (blockIdx.x * blockDim.x + threadIdx.x) >> 6,
+                                (gridDim.x * blockDim.x) >> 6);
+}
+
 }  // namespace gsr

@@ -259,6 +259,8 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
     w.hub_partial2 = off;
     off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
+    w.hub_cols = off;
+    if (b == 4 && g->hub_values) off += align_up(n * (size_t)cfg->k + 16);
     w.h = off;               // (not for 16-bit storage at 32 columns: that backward keeps H on chip)
     if ((b == 4 || dgs == 64) && g->split_backward) off += align_up(n * dgs * sizeof(float));
     w.total = off;
@@ -343,6 +345,9 @@ gsr_status_t gsr_set_option(const char* key, int64_t value) {
     } else if (!strcmp(key, "hub_chunk")) {
         if (value < 0) return fail(GSR_ERR_INVALID_ARG, "hub_chunk must be >= 0");
         o.hub_chunk = value;
+    } else if (!strcmp(key, "hub_values")) {
+        if (value < 0 || value > 2) return fail(GSR_ERR_INVALID_ARG, "hub_values must be 0, 1 or 2");
+        o.hub_values = value;
     } else if (!strcmp(key, "max_workgroups")) {
         if (value < 0 || value % 8 != 0) return fail(GSR_ERR_INVALID_ARG, "max_workgroups must be a multiple of 8");
         o.max_workgroups = value;
@@ -506,6 +511,7 @@ static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz,
                                   : long_rows ? 64 : very_few_tiles ? 16 : few_tiles ? 64 : 512;
     const int64_t hub_chunk = options().hub_chunk > 0 ? options().hub_chunk : (long_rows ? 256 : 64);
     g->hub_threshold = (int32_t)hub_threshold;
+    g->hub_values = options().hub_values == 1 ? 2 : (options().hub_values == 0 && long_rows) ? 1 : 0;
     g->split_backward = !(long_rows || (n + 15) / 16 < (int64_t)4 * full_grid);    // (not with fewer tiles than resident waves)
 
     gsr_status_t st = upload_csr(a, n, hub_threshold, hub_chunk, &g->a);

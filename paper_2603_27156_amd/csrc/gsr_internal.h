@@ -33,6 +33,7 @@ struct Options {
     int64_t hub_chunk = 0;        // neighbours per first-pass partial (0: chosen per graph)
     int64_t max_workgroups = 0;   // 0: derive from the device (multiple of 8)
     int64_t profile = 0;          // bit i set: time kernel class i with HIP events
+    int64_t hub_values = 0;       // first pass over float32 records value by value: 0 on long-row graphs, 1 always, 2 never
 };
 Options& options();
 
@@ -99,6 +100,9 @@ struct gsr_graph {
     bool has_transpose = false;
     bool split_backward = true;   // float32: the backward of a block as inverse kernel + k_dw (large graphs), else fused
     bool long_rows = false;  // the mean row has 64 stored entries or more: nearly every row goes through the first pass
+    int hub_values = 0;      // the first pass over float32 records runs value by value (k_hub_values): 0 never, 1 while
+                             // 2 k <= D/C (beyond that the dealing of the tile kernels is faster: 650 against 490 ms per step
+                             // at k = D/C = 64 on the Table-1-shaped graph, 464 against 473 at k = 32), 2 always
     int32_t hub_threshold = 512;
     int device = 0;
     int num_cus = 256;
@@ -124,6 +128,7 @@ struct LayerWs {
     size_t dw_partial;   // [grid][dg*dg] float
     size_t hub_partial;  // [max(n_chunks A, n_chunks A^T)][dg] float
     size_t hub_partial2; // same size: the backward's two first passes of a block run as one launch
+    size_t hub_cols;     // [n][k] bytes: column of every record value, for the value-by-value first pass (float32)
     size_t total;
 };
 struct StepWs {

@@ -1075,6 +1075,8 @@ struct Ctx {
     float* dw_partial() const { return (float*)(ws + lw.dw_partial); }
     float* hub_part() const { return (float*)(ws + lw.hub_partial); }
     float* hub_part2() const { return (float*)(ws + lw.hub_partial2); }
+    uint8_t* hub_cols() const { return (uint8_t*)(ws + lw.hub_cols); }
+    bool hub_by_value() const { return g->hub_values == 2 || (g->hub_values == 1 && 2 * cfg->k <= DG); }
 };
 
 // Workgroups of 256 threads one CU keeps resident for a kernel, and the persistent grid that
@@ -1111,6 +1113,18 @@ static void launch_hub_records(const Ctx<DG, T>& x, const Record<DG, T>& in) {
     if (h.n_chunks == 0) return;
     HubChunks hc{h.ce0, h.ce1, h.n_chunks};
     ProfScope prof(KC_HUB, x.s);
+    if constexpr (sizeof(T) == 4) {
+        if (x.hub_by_value()) {
+            hipLaunchKernelGGL((k_record_columns<DG>), dim3((unsigned)((x.cfg->n + 255) / 256)), dim3(256), 0, x.s, (int)x.cfg->n,
+                               x.cfg->k, (const typename MaskOf<DG>::type*)in.mask, x.hub_cols());
+            hub_values_variant(x.cfg->k, [&](auto lg, auto kq) {
+                hipLaunchKernelGGL((k_hub_values<DG, decltype(lg)::value, decltype(kq)::value>),
+                                   dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s, make_view(x.g, false), hc,
+                                   (const float*)in.vals, (const uint8_t*)x.hub_cols(), x.cfg->k, x.hub_part());
+            });
+            return;
+        }
+    }
     hipLaunchKernelGGL((k_hub_records<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
                        make_view(x.g, false), hc, (const T*)in.vals, (const typename MaskOf<DG>::type*)in.mask, x.cfg->k,
                        x.hub_part());
@@ -1135,6 +1149,24 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
     HubChunks ca{ha.ce0, ha.ce1, ha.n_chunks}, ct{ht.ce0, ht.ce1, ht.n_chunks};
     ProfScope prof(KC_HUB, x.s);
     const unsigned gx = (unsigned)std::min((std::max(ha.n_chunks, ht.n_chunks) + 3) / 4, 4096);
+    if constexpr (sizeof(T) == 4) {
+        if (x.hub_by_value()) {
+            hipLaunchKernelGGL((k_record_columns<DG>), dim3((unsigned)((x.cfg->n + 255) / 256)), dim3(256), 0, x.s, (int)x.cfg->n,
+                               x.cfg->k, (const typename MaskOf<DG>::type*)in.mask, x.hub_cols());
+            // (two launches: as the two rows of one grid, as the dealing variant runs them, they took 50 us longer on the
+            // Table-1-shaped graph than one after the other)
+            if (ha.n_chunks > 0)
+                hub_values_variant(x.cfg->k, [&](auto lg, auto kq) {
+                    hipLaunchKernelGGL((k_hub_values<DG, decltype(lg)::value, decltype(kq)::value>),
+                                       dim3((unsigned)std::min((ha.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s, make_view(x.g, false),
+                                       ca, (const float*)in.vals, (const uint8_t*)x.hub_cols(), x.cfg->k, x.hub_part());
+                });
+            if (ht.n_chunks > 0)
+                hipLaunchKernelGGL((k_hub_dense<DG, T>), dim3((unsigned)std::min((ht.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
+                                   make_view(x.g, true), ct, dy, ldg, x.hub_part2());
+            return true;
+        }
+    }
     hipLaunchKernelGGL((k_hub_both<DG, T>), dim3(gx, 2), dim3(256), 0, x.s, make_view(x.g, false), ca, (const T*)in.vals,
                        (const typename MaskOf<DG>::type*)in.mask, x.cfg->k, x.hub_part(), make_view(x.g, true), ct, dy, ldg,
                        x.hub_part2());

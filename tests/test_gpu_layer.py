@@ -510,6 +510,33 @@ def test_graph_of_long_rows_goes_through_the_first_pass(dtype, threshold):
         gsr.gsr_set_option("hub_threshold", 0)
 
 
+@pytest.mark.parametrize("dg,c,k,chunk", [(64, 2, 3, 4), (64, 2, 8, 100), (64, 4, 16, 100), (64, 2, 24, 4), (64, 2, 40, 100),
+                                          (64, 2, 64, 4), (32, 3, 8, 100), (32, 2, 20, 4), (192, 2, 16, 100)])
+def test_first_pass_value_by_value(dg, c, k, chunk):
+    """The first pass over float32 records with a lane per record value (option "hub_values" = 1; the default on
+    long-row graphs, forced here on a small graph with rows cut at 6 entries): 4, 8 or 16 lanes per edge and one to
+    four values per lane depending on k, chunks shorter and longer than a round of 64 staged edges."""
+    print(f"[case] dg={dg} C={c} k={k} chunk={chunk}", flush=True)
+    gsr.gsr_set_option("hub_values", 1)
+    gsr.gsr_set_option("hub_threshold", 6)
+    gsr.gsr_set_option("hub_chunk", chunk)
+    try:
+        base = synth.workload(2)
+        w = synth.scaled(base, 700, levels=6, d=dg * c, c=c, k=k, l=2, hubs=2)
+        cs = Case(w, 11, PLANAR)
+        info = gsr.gsr_graph_info(cs.gg)
+        assert info["n_hub_rows"] > 0 and info["max_degree"] > 64
+        ref = oracle.step(cs.og, cs.ocfg, w.l, cs.x0_on_grid(), cs.inp.weights, cs.inp.w_out, cs.inp.b_out, cs.inp.target)
+        out = run_step(cs)
+    finally:
+        gsr.gsr_set_option("hub_values", 0)
+        gsr.gsr_set_option("hub_threshold", 0)
+        gsr.gsr_set_option("hub_chunk", 0)
+    assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
+    for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
+        assert_close(key, out[key], ref[key])
+
+
 def _long_rows_case(dtype, threshold, sp):
     rng = np.random.default_rng(21)
     n, deg = 1203, 90
