@@ -1755,9 +1755,9 @@ __global__ __launch_bounds__(256) void k_record_columns(int n, int k, const type
 
 template <int DG, int LG>
 struct HubValLds {
-    uint2 ebuf[64];          // (j * k, a_ij) of the staged edges
-    float rows[(64 >> LG) * DG];   // a dense row per edge place; all zero between two instructions' worth of edges
-    float red[256];          // the lanes' sums at the end of a chunk
+    uint2 ebuf[64];                   // (j * k, a_ij) of the staged edges
+    float rows[2][(64 >> LG) * DG];   // two rows of sums per edge place (even and odd instructions of a batch)
+    float spare[64];                  // where a lane without a value adds its zero
 };
 
 template <int DG, int LG, int KQ>
@@ -1767,16 +1767,15 @@ __device__ __forceinline__ void hub_values_pass(const CsrView& g, const HubChunk
     constexpr int LPE = 1 << LG, NE = 64 >> LG;          // lanes per edge, edges per instruction
     constexpr int MAXS = 64 / NE;                        // instructions per round of 64 staged edges
     constexpr int GB = KQ == 1 ? (MAXS < 8 ? MAXS : 8) : KQ == 2 ? 4 : 2;
-    constexpr int TOT = NE * DG, NR = (TOT + 255) / 256; // floats of the dense rows, float4 reads per lane
-    static_assert(MAXS % GB == 0, "a round is a whole number of batches");
-    static_assert(256 % DG == 0, "a lane's four floats are the same columns in every read");
+    constexpr int TOT = NE * DG;
+    static_assert(MAXS % GB == 0 && GB % 2 == 0, "a round is a whole number of batches, a batch of pairs");
     const int lane = lane_id();
     const int place = lane >> LG, t = lane & (LPE - 1);
-    float* mine = L.rows + place * DG;
-    for (int i = lane; i < TOT; i += 64) L.rows[i] = 0.f;
+    float* base = &L.rows[0][0];
+    const int spare = (int)(&L.spare[lane] - base);
+    for (int i = lane; i < 2 * TOT; i += 64) base[i] = 0.f;
     for (int q = first_wave; q < h.n_chunks; q += nwaves) {
         const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
-        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int eb = e0; eb < e1; eb += 64) {
             // places past the last edge: the last edge once more with a_ij = 0
             const int e = eb + lane;
@@ -1797,44 +1796,47 @@ __device__ __forceinline__ void hub_values_pass(const CsrView& g, const HubChunk
                     const uint2 er = L.ebuf[(s0 + u) * NE + place];
 #pragma unroll
                     for (int w = 0; w < KQ; ++w) {
-                        // (a lane past the record's last slot takes slot 0 again: it writes what slot 0's lane writes)
+                        // (a lane past the record's last slot takes slot 0 again: with one value per lane it writes
+                        // what slot 0's lane writes)
                         const int tt = t + w * LPE;
                         const uint32_t at = er.x + (uint32_t)(tt < k ? tt : 0);
                         v[u][w] = vals[at] * __uint_as_float(er.y);
                         c[u][w] = cols[at];
                     }
                 }
+                // sum += value, read and written back: the lanes of an instruction hold different places or different
+                // columns of one record, so no two of them meet; even and odd instructions keep rows of their own so
+                // that two read - add - write chains are in flight
 #pragma unroll
-                for (int u = 0; u < GB; ++u) {
+                for (int u = 0; u < GB; u += 2) {
 #pragma unroll
-                    for (int w = 0; w < KQ; ++w)
-                        if (c[u][w] != 0xFFu) mine[c[u][w]] = v[u][w];
-                    wave_sync();
-#pragma unroll
-                    for (int r = 0; r < NR; ++r) {
-                        const int at = 4 * (r * 64 + lane);
-                        if (TOT % 256 == 0 || at < TOT) {
-                            const f32x4 d = *reinterpret_cast<const f32x4*>(L.rows + at);
-                            acc += d;
-                        }
+                    for (int w = 0; w < KQ; ++w) {
+                        const bool has = KQ == 1 || t + w * LPE < k;      // (else slot 0 once more: not added again)
+                        const bool h0 = has && c[u][w] != 0xFFu, h1 = has && c[u + 1][w] != 0xFFu;
+                        const int i0 = h0 ? place * DG + (int)c[u][w] : spare;
+                        const int i1 = h1 ? TOT + place * DG + (int)c[u + 1][w] : spare;
+                        const float o0 = base[i0];
+                        const float o1 = base[i1];
+                        wave_sync();
+                        base[i0] = o0 + (h0 ? v[u][w] : 0.f);
+                        base[i1] = o1 + (h1 ? v[u + 1][w] : 0.f);
+                        wave_sync();
                     }
-                    wave_sync();
-#pragma unroll
-                    for (int w = 0; w < KQ; ++w)
-                        if (c[u][w] != 0xFFu) mine[c[u][w]] = 0.f;
                 }
             }
         }
-        // lane l holds columns (4 l .. 4 l + 3) mod DG: the 256 / DG lanes of a column are added in lane order
-        wave_sync();
-        *reinterpret_cast<f32x4*>(L.red + 4 * lane) = acc;
+        // the sums of the places are added in place order, even rows before odd rows, and the rows cleared
         wave_sync();
         if (lane < DG) {
             float s = 0.f;
 #pragma unroll
-            for (int gq = 0; gq < 256 / DG; ++gq) s += L.red[gq * DG + lane];
+            for (int pl = 0; pl < 2 * NE; ++pl) {
+                s += base[pl * DG + lane];
+                base[pl * DG + lane] = 0.f;
+            }
             part[(size_t)q * DG + lane] = s;
         }
+        wave_sync();
     }
 }
 
