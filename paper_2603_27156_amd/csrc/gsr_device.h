@@ -1721,12 +1721,14 @@ __global__ __launch_bounds__(256) void k_hub_both(CsrView ga, HubChunks ha, cons
 // thirty instructions per four edges) is what it spends.  Here a lane owns a *value* instead: LPE = 2^LG lanes per
 // edge, lane t of them loads value t (+ LPE, + 2 LPE .. below k) of the record and the number of its column - one
 // byte per value, written from the column mask by k_record_columns before the pass (0xFF for a slot the record does
-// not use: a column block of a wide group keeps between 0 and k values) - and writes a_ij * value to that
-// column of its edge place's row in LDS (64 / LPE places, each a row of DG floats, zero elsewhere; the places of one
-// instruction are different rows and the values of one record different columns, so no two lanes meet).  Then every lane
-// reads four adjacent floats of the rows - whole 16-byte reads, no dealing - adds them to its four running sums, and the
-// writers put their zeros back.  LDS float atomics instead of the write / read / clear were four times slower than
-// the dealing (one such instruction takes some 140 cycles).  The order of the additions is fixed by the edge list.
+// not use: a column block of a wide group keeps between 0 and k values) - and adds a_ij * value to that
+// column of its edge place's row in LDS (64 / LPE places, each a row of DG floats; the places of one instruction are
+// different rows and the values of one record different columns, so no two lanes meet): the sum is read, added to
+// and written back by the lane, and stays in the row for the whole chunk.  Even and odd instructions of a batch keep
+// rows of their own, so two such chains are in flight.  At the end of a chunk the rows of the places are added in
+// place order and cleared.  Scattering into zeroed rows, reading them back sixteen bytes wide into running sums and
+// clearing them again was 3 % slower; LDS float atomics were four times slower than the dealing (one such
+// instruction takes some 140 cycles).  The order of the additions is fixed by the edge list and the lane layout.
 template <int DG>
 __global__ __launch_bounds__(256) void k_record_columns(int n, int k, const typename MaskOf<DG>::type* __restrict__ masks,
                                                         uint8_t* __restrict__ cols) {

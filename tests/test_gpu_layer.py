@@ -6,7 +6,7 @@ import pytest
 import oracle
 import paper_2603_27156_amd as gsr
 from paper_2603_27156_amd import synth
-from gpu_util import Case, assert_close, rel_norm, BF16_REL
+from gpu_util import Case, assert_close, rel_norm, BF16_REL, audit_layer_forward, audit_layer_backward, bf16_bar
 
 pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
@@ -252,6 +252,25 @@ def test_bf16_storage_variant():
     assert np.isclose(out["loss"], ref["loss"], rtol=BF16_REL)
     for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
         assert rel_norm(out[key], ref[key]) <= BF16_REL, (key, rel_norm(out[key], ref[key]))
+
+
+@pytest.mark.parametrize("base,n,layout", [(4, 4001, PLANAR), (2, 3001, PLANAR), (2, 2005, ROW)])
+def test_bf16_layer_row_by_row(base, n, layout):
+    """bf16 storage judged element by element rather than in norm: one layer forward and its backward under the
+    audits of the full-size tests (bar of two bf16 steps of the value plus one of the row's largest entry).  A row
+    may leave the bar only where a provable near-tie of the selection reaches it; in the backward the oracle is
+    handed the library's selection for the rows of block 1 that are such near-ties, and every element must agree."""
+    w = synth.scaled(synth.workload(base, dtype="bf16"), n, l=2)
+    c = Case(w, 1, layout)
+    X, W = c.x0_on_grid(), c.inp.weights[0]
+    Wd = torch.from_numpy(W).to(c.dev)
+    y = c.to_dev(X)
+    gsr.gsr_layer_forward(c.gg, c.gcfg, Wd, y)
+    Y = c.to_host(y)
+    tag = f"bf16 dg {w.dg} C {w.c} n {n}"
+    audit_layer_forward(c, X, Y, oracle.layer_forward(c.og, c.ocfg, W, X), tag, bar=bf16_bar, max_reachable=0.5)
+    dY = synth.to_bf16_grid(np.random.default_rng(7).standard_normal((w.n, w.d)).astype(np.float32)).astype(np.float64)
+    audit_layer_backward(c, W, Y, dY, tag, bar=bf16_bar, dw_rtol=2e-2, max_flips=0.2)
 
 
 def test_layer_calls_reject_what_the_kernels_cannot_take():
