@@ -1625,6 +1625,25 @@ struct HubChunks {
     int32_t n_chunks;
 };
 
+// Which chunks a wave takes.  The chunks are listed in row order and the hardware deals workgroups to the XCDs
+// round-robin, so XCD x takes the x-th eighth of the list and its waves walk that eighth side by side: the rows its
+// L2 has to hold are the neighbourhood of a narrow band of rows (on a graph of long rows a few thousand rows) and not
+// that of every row in flight on the chip.  Any grid is covered (fewer than eight workgroups: one part each); what a
+// chunk's partial row holds does not depend on the wave that sums it.
+struct HubSweep {
+    int q, end, step;
+};
+__device__ __forceinline__ HubSweep hub_sweep(int n_chunks) {
+    const int parts = gridDim.x < 8 ? (int)gridDim.x : 8;
+    const int part = (int)blockIdx.x % parts, wg = (int)blockIdx.x / parts;
+    const int wgs = ((int)gridDim.x - part + parts - 1) / parts, wpw = (int)blockDim.x >> 6;
+    HubSweep w;
+    w.q = (int)((int64_t)n_chunks * part / parts) + wg * wpw + ((int)threadIdx.x >> 6);
+    w.end = (int)((int64_t)n_chunks * (part + 1) / parts);
+    w.step = wgs * wpw;
+    return w;
+}
+
 struct HubLds {
     EdgeRec ebuf[64];
     int rp[20];
@@ -1648,10 +1667,10 @@ __device__ __forceinline__ void hub_chunk_store(const f32x4 (&acc)[DG / 16], flo
 template <int DG, typename T>
 __device__ __forceinline__ void hub_records_pass(const CsrView& g, const HubChunks& h, const T* __restrict__ vals,
                                                  const typename MaskOf<DG>::type* __restrict__ masks, int k,
-                                                 float* __restrict__ part, HubLds& L, int first_wave, int nwaves,
+                                                 float* __restrict__ part, HubLds& L, const HubSweep w,
                                                  const DealLutF* lutf) {
     const int lane = lane_id();
-    for (int q = first_wave; q < h.n_chunks; q += nwaves) {
+    for (int q = w.q; q < w.end; q += w.step) {
         const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
         hub_chunk_begin(L, e0, e1, lane);
         f32x4 acc[DG / 16];
@@ -1666,9 +1685,9 @@ __device__ __forceinline__ void hub_records_pass(const CsrView& g, const HubChun
 }
 template <int DG, typename T>
 __device__ __forceinline__ void hub_dense_pass(const CsrView& g, const HubChunks& h, const T* __restrict__ x, int64_t ld,
-                                               float* __restrict__ part, HubLds& L, int first_wave, int nwaves) {
+                                               float* __restrict__ part, HubLds& L, const HubSweep w) {
     const int lane = lane_id();
-    for (int q = first_wave; q < h.n_chunks; q += nwaves) {
+    for (int q = w.q; q < w.end; q += w.step) {
         const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
         hub_chunk_begin(L, e0, e1, lane);
         f32x4 acc[DG / 16];
@@ -1688,16 +1707,14 @@ __global__ __launch_bounds__(256) void k_hub_records(CsrView g, HubChunks h, con
     __shared__ HubLds lds[4];
     __shared__ DealLutF dlut;
     deal_lutf_fill(dlut);
-    hub_records_pass<DG, T>(g, h, vals, masks, k, part, lds[threadIdx.x >> 6], (blockIdx.x * blockDim.x + threadIdx.x) >> 6,
-                            (gridDim.x * blockDim.x) >> 6, &dlut);
+    hub_records_pass<DG, T>(g, h, vals, masks, k, part, lds[threadIdx.x >> 6], hub_sweep(h.n_chunks), &dlut);
 }
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_hub_dense(CsrView g, HubChunks h, const T* __restrict__ x, int64_t ld,
                                                    float* __restrict__ part) {
     __shared__ HubLds lds[4];
-    hub_dense_pass<DG, T>(g, h, x, ld, part, lds[threadIdx.x >> 6], (blockIdx.x * blockDim.x + threadIdx.x) >> 6,
-                          (gridDim.x * blockDim.x) >> 6);
+    hub_dense_pass<DG, T>(g, h, x, ld, part, lds[threadIdx.x >> 6], hub_sweep(h.n_chunks));
 }
 
 // Both first passes of one block's backward in one launch: blockIdx.y = 0 takes the records over A (for the
@@ -1710,9 +1727,8 @@ __global__ __launch_bounds__(256) void k_hub_both(CsrView ga, HubChunks ha, cons
     __shared__ HubLds lds[4];
     __shared__ DealLutF dlut;
     deal_lutf_fill(dlut);
-    const int first = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nwaves = (gridDim.x * blockDim.x) >> 6;
-    if (blockIdx.y == 0) hub_records_pass<DG, T>(ga, ha, vals, masks, k, part_a, lds[threadIdx.x >> 6], first, nwaves, &dlut);
-    else hub_dense_pass<DG, T>(gt, ht, x, ld, part_t, lds[threadIdx.x >> 6], first, nwaves);
+    if (blockIdx.y == 0) hub_records_pass<DG, T>(ga, ha, vals, masks, k, part_a, lds[threadIdx.x >> 6], hub_sweep(ha.n_chunks), &dlut);
+    else hub_dense_pass<DG, T>(gt, ht, x, ld, part_t, lds[threadIdx.x >> 6], hub_sweep(ht.n_chunks));
 }
 
 // ---- first pass over the chunks, value by value (float32 records) ---------------------------------
@@ -1765,7 +1781,7 @@ struct HubValLds {
 template <int DG, int LG, int KQ>
 __device__ __forceinline__ void hub_values_pass(const CsrView& g, const HubChunks& h, const float* __restrict__ vals,
                                                 const uint8_t* __restrict__ cols, int k, float* __restrict__ part,
-                                                HubValLds<DG, LG>& L, int first_wave, int nwaves) {
+                                                HubValLds<DG, LG>& L, const HubSweep w) {
     constexpr int LPE = 1 << LG, NE = 64 >> LG;          // lanes per edge, edges per instruction
     constexpr int MAXS = 64 / NE;                        // instructions per round of 64 staged edges
     constexpr int GB = KQ == 1 ? (MAXS < 8 ? MAXS : 8) : KQ == 2 ? 4 : 2;
@@ -1776,7 +1792,7 @@ __device__ __forceinline__ void hub_values_pass(const CsrView& g, const HubChunk
     float* base = &L.rows[0][0];
     const int spare = (int)(&L.spare[lane] - base);
     for (int i = lane; i < 2 * TOT; i += 64) base[i] = 0.f;
-    for (int q = first_wave; q < h.n_chunks; q += nwaves) {
+    for (int q = w.q; q < w.end; q += w.step) {
         const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
         for (int eb = e0; eb < e1; eb += 64) {
             // places past the last edge: the last edge once more with a_ij = 0
@@ -1856,8 +1872,7 @@ template <int DG, int LG, int KQ>
 __global__ __launch_bounds__(256) void k_hub_values(CsrView g, HubChunks h, const float* __restrict__ vals,
                                                     const uint8_t* __restrict__ cols, int k, float* __restrict__ part) {
     __shared__ HubValLds<DG, LG> lds[4];
-    hub_values_pass<DG, LG, KQ>(g, h, vals, cols, k, part, lds[threadIdx.x >> 6], (blockIdx.x * blockDim.x + threadIdx.x) >> 6,
-                                (gridDim.x * blockDim.x) >> 6);
+    hub_values_pass<DG, LG, KQ>(g, h, vals, cols, k, part, lds[threadIdx.x >> 6], hub_sweep(h.n_chunks));
 }
 
 }  // namespace gsr

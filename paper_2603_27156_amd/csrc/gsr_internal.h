@@ -166,6 +166,12 @@ inline bool heavy_first(int n_heavy, int tiles, unsigned grid) {
 }
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+// Workgroups of four waves for a first pass over n_chunks chunks: a wave per chunk up to 4,096 workgroups, a whole
+// number of eights (the kernels give every XCD one contiguous eighth of the chunk list).
+inline unsigned hub_grid(int n_chunks) {
+    const int wgs = (n_chunks + 3) / 4 < 4096 ? (n_chunks + 3) / 4 : 4096;
+    return (unsigned)((wgs + 7) / 8 * 8);
+}
 // A group wider than one 64-column tile is handled as D/C / 64 sub-planes of 64 columns.
 inline int sub_planes(const gsr_config_t* cfg) { const int dg = cfg->d / cfg->c; return dg > 64 ? dg / 64 : 1; }
 inline size_t dtype_size(int32_t dtype) { return dtype == GSR_BF16 ? 2 : 4; }

@@ -1119,13 +1119,13 @@ static void launch_hub_records(const Ctx<DG, T>& x, const Record<DG, T>& in) {
                                x.cfg->k, (const typename MaskOf<DG>::type*)in.mask, x.hub_cols());
             hub_values_variant(x.cfg->k, [&](auto lg, auto kq) {
                 hipLaunchKernelGGL((k_hub_values<DG, decltype(lg)::value, decltype(kq)::value>),
-                                   dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s, make_view(x.g, false), hc,
+                                   dim3(hub_grid(h.n_chunks)), dim3(256), 0, x.s, make_view(x.g, false), hc,
                                    (const float*)in.vals, (const uint8_t*)x.hub_cols(), x.cfg->k, x.hub_part());
             });
             return;
         }
     }
-    hipLaunchKernelGGL((k_hub_records<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
+    hipLaunchKernelGGL((k_hub_records<DG, T>), dim3(hub_grid(h.n_chunks)), dim3(256), 0, x.s,
                        make_view(x.g, false), hc, (const T*)in.vals, (const typename MaskOf<DG>::type*)in.mask, x.cfg->k,
                        x.hub_part());
 }
@@ -1136,7 +1136,7 @@ static void launch_hub_dense(const Ctx<DG, T>& x, const T* plane, int64_t ld) {
     if (h.n_chunks == 0) return;
     HubChunks hc{h.ce0, h.ce1, h.n_chunks};
     ProfScope prof(KC_HUB, x.s);
-    hipLaunchKernelGGL((k_hub_dense<DG, T>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
+    hipLaunchKernelGGL((k_hub_dense<DG, T>), dim3(hub_grid(h.n_chunks)), dim3(256), 0, x.s,
                        make_view(x.g, true), hc, plane, ld, x.hub_part());
 }
 
@@ -1148,7 +1148,7 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
     if (ha.n_chunks == 0 && ht.n_chunks == 0) return false;
     HubChunks ca{ha.ce0, ha.ce1, ha.n_chunks}, ct{ht.ce0, ht.ce1, ht.n_chunks};
     ProfScope prof(KC_HUB, x.s);
-    const unsigned gx = (unsigned)std::min((std::max(ha.n_chunks, ht.n_chunks) + 3) / 4, 4096);
+    const unsigned gx = hub_grid(std::max(ha.n_chunks, ht.n_chunks));
     if constexpr (sizeof(T) == 4) {
         if (x.hub_by_value()) {
             hipLaunchKernelGGL((k_record_columns<DG>), dim3((unsigned)((x.cfg->n + 255) / 256)), dim3(256), 0, x.s, (int)x.cfg->n,
@@ -1158,11 +1158,11 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
             if (ha.n_chunks > 0)
                 hub_values_variant(x.cfg->k, [&](auto lg, auto kq) {
                     hipLaunchKernelGGL((k_hub_values<DG, decltype(lg)::value, decltype(kq)::value>),
-                                       dim3((unsigned)std::min((ha.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s, make_view(x.g, false),
+                                       dim3(hub_grid(ha.n_chunks)), dim3(256), 0, x.s, make_view(x.g, false),
                                        ca, (const float*)in.vals, (const uint8_t*)x.hub_cols(), x.cfg->k, x.hub_part());
                 });
             if (ht.n_chunks > 0)
-                hipLaunchKernelGGL((k_hub_dense<DG, T>), dim3((unsigned)std::min((ht.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s,
+                hipLaunchKernelGGL((k_hub_dense<DG, T>), dim3(hub_grid(ht.n_chunks)), dim3(256), 0, x.s,
                                    make_view(x.g, true), ct, dy, ldg, x.hub_part2());
             return true;
         }

@@ -178,7 +178,7 @@ template <int W>
 static void launch_slot_tile(const Lit& x, const SlotArgs& a, const HubPlan& h) {
     if (h.n_chunks > 0) {
         HubChunks hc{h.ce0, h.ce1, h.n_chunks};
-        hipLaunchKernelGGL((k_hub_dense<W, float>), dim3((unsigned)std::min((h.n_chunks + 3) / 4, 4096)), dim3(256), 0, x.s, a.g, hc,
+        hipLaunchKernelGGL((k_hub_dense<W, float>), dim3(hub_grid(h.n_chunks)), dim3(256), 0, x.s, a.g, hc,
                            a.P, (int64_t)W, x.g->scratch);
     }
     // as many workgroups as stay resident with this much LDS, at most the graph's persistent grid
