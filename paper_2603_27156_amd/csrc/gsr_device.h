@@ -1623,23 +1623,35 @@ struct HubChunks {
     const int32_t* ce0;
     const int32_t* ce1;
     int32_t n_chunks;
+    int32_t banded = 0;      // every XCD takes a contiguous eighth of the list (hub_sweep)
 };
 
-// Which chunks a wave takes.  The chunks are listed in row order and the hardware deals workgroups to the XCDs
-// round-robin, so XCD x takes the x-th eighth of the list and its waves walk that eighth side by side: the rows its
-// L2 has to hold are the neighbourhood of a narrow band of rows (on a graph of long rows a few thousand rows) and not
-// that of every row in flight on the chip.  Any grid is covered (fewer than eight workgroups: one part each); what a
-// chunk's partial row holds does not depend on the wave that sums it.
+// Which chunks a wave takes; what a chunk's partial row holds does not depend on the wave that sums it.  The chunks
+// are listed in row order and the hardware deals workgroups to the XCDs round-robin.  On a graph of long rows (nearly
+// every row split, chunks alike in cost, neighbours within a few thousand rows) the sweep is banded: XCD x takes the
+// x-th eighth of the list and its waves walk that eighth side by side, so the rows its L2 has to hold are the
+// neighbourhood of a narrow band of rows and not that of every row in flight on the chip.  Elsewhere the split rows are
+// few and unlike (a handful of rows with tens of thousands of neighbours from all over the graph, listed first, then
+// rows of a few hundred): there the chunks go to the waves of the whole grid in turn, which shares the costly ones out
+// (banded, the 8M-node workload's first passes took 117 us against 88).  Any grid is covered (banded with fewer than
+// eight workgroups: one part each).
 struct HubSweep {
     int q, end, step;
 };
-__device__ __forceinline__ HubSweep hub_sweep(int n_chunks) {
+__device__ __forceinline__ HubSweep hub_sweep(const HubChunks& h) {
+    const int wpw = (int)blockDim.x >> 6;
+    HubSweep w;
+    if (!h.banded) {
+        w.q = (int)blockIdx.x * wpw + ((int)threadIdx.x >> 6);
+        w.end = h.n_chunks;
+        w.step = (int)gridDim.x * wpw;
+        return w;
+    }
     const int parts = gridDim.x < 8 ? (int)gridDim.x : 8;
     const int part = (int)blockIdx.x % parts, wg = (int)blockIdx.x / parts;
-    const int wgs = ((int)gridDim.x - part + parts - 1) / parts, wpw = (int)blockDim.x >> 6;
-    HubSweep w;
-    w.q = (int)((int64_t)n_chunks * part / parts) + wg * wpw + ((int)threadIdx.x >> 6);
-    w.end = (int)((int64_t)n_chunks * (part + 1) / parts);
+    const int wgs = ((int)gridDim.x - part + parts - 1) / parts;
+    w.q = (int)((int64_t)h.n_chunks * part / parts) + wg * wpw + ((int)threadIdx.x >> 6);
+    w.end = (int)((int64_t)h.n_chunks * (part + 1) / parts);
     w.step = wgs * wpw;
     return w;
 }
@@ -1707,14 +1719,14 @@ __global__ __launch_bounds__(256) void k_hub_records(CsrView g, HubChunks h, con
     __shared__ HubLds lds[4];
     __shared__ DealLutF dlut;
     deal_lutf_fill(dlut);
-    hub_records_pass<DG, T>(g, h, vals, masks, k, part, lds[threadIdx.x >> 6], hub_sweep(h.n_chunks), &dlut);
+    hub_records_pass<DG, T>(g, h, vals, masks, k, part, lds[threadIdx.x >> 6], hub_sweep(h), &dlut);
 }
 
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_hub_dense(CsrView g, HubChunks h, const T* __restrict__ x, int64_t ld,
                                                    float* __restrict__ part) {
     __shared__ HubLds lds[4];
-    hub_dense_pass<DG, T>(g, h, x, ld, part, lds[threadIdx.x >> 6], hub_sweep(h.n_chunks));
+    hub_dense_pass<DG, T>(g, h, x, ld, part, lds[threadIdx.x >> 6], hub_sweep(h));
 }
 
 // Both first passes of one block's backward in one launch: blockIdx.y = 0 takes the records over A (for the
@@ -1727,8 +1739,8 @@ __global__ __launch_bounds__(256) void k_hub_both(CsrView ga, HubChunks ha, cons
     __shared__ HubLds lds[4];
     __shared__ DealLutF dlut;
     deal_lutf_fill(dlut);
-    if (blockIdx.y == 0) hub_records_pass<DG, T>(ga, ha, vals, masks, k, part_a, lds[threadIdx.x >> 6], hub_sweep(ha.n_chunks), &dlut);
-    else hub_dense_pass<DG, T>(gt, ht, x, ld, part_t, lds[threadIdx.x >> 6], hub_sweep(ht.n_chunks));
+    if (blockIdx.y == 0) hub_records_pass<DG, T>(ga, ha, vals, masks, k, part_a, lds[threadIdx.x >> 6], hub_sweep(ha), &dlut);
+    else hub_dense_pass<DG, T>(gt, ht, x, ld, part_t, lds[threadIdx.x >> 6], hub_sweep(ht));
 }
 
 // ---- first pass over the chunks, value by value (float32 records) ---------------------------------
@@ -1796,6 +1808,8 @@ __device__ __forceinline__ void hub_values_pass(const CsrView& g, const HubChunk
         const int e0 = __builtin_amdgcn_readfirstlane(h.ce0[q]), e1 = __builtin_amdgcn_readfirstlane(h.ce1[q]);
         for (int eb = e0; eb < e1; eb += 64) {
             // places past the last edge: the last edge once more with a_ij = 0
+            // (with sixteen lanes per edge a place is a row of sixteen lanes, and an instruction could take its edge
+            // from a lane of the row by a DPP row broadcast instead of from LDS: measured 2.5 % slower)
             const int e = eb + lane;
             const bool ok = e < e1;
             const int ec = ok ? e : e1 - 1;
@@ -1872,7 +1886,7 @@ template <int DG, int LG, int KQ>
 __global__ __launch_bounds__(256) void k_hub_values(CsrView g, HubChunks h, const float* __restrict__ vals,
                                                     const uint8_t* __restrict__ cols, int k, float* __restrict__ part) {
     __shared__ HubValLds<DG, LG> lds[4];
-    hub_values_pass<DG, LG, KQ>(g, h, vals, cols, k, part, lds[threadIdx.x >> 6], hub_sweep(h.n_chunks));
+    hub_values_pass<DG, LG, KQ>(g, h, vals, cols, k, part, lds[threadIdx.x >> 6], hub_sweep(h));
 }
 
 }  // namespace gsr

@@ -1111,7 +1111,7 @@ template <int DG, typename T>
 static void launch_hub_records(const Ctx<DG, T>& x, const Record<DG, T>& in) {
     const HubPlan& h = x.g->a.hub;
     if (h.n_chunks == 0) return;
-    HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+    HubChunks hc{h.ce0, h.ce1, h.n_chunks, x.g->long_rows};
     ProfScope prof(KC_HUB, x.s);
     if constexpr (sizeof(T) == 4) {
         if (x.hub_by_value()) {
@@ -1134,7 +1134,7 @@ template <int DG, typename T>
 static void launch_hub_dense(const Ctx<DG, T>& x, const T* plane, int64_t ld) {
     const HubPlan& h = x.g->at.hub;
     if (h.n_chunks == 0) return;
-    HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+    HubChunks hc{h.ce0, h.ce1, h.n_chunks, x.g->long_rows};
     ProfScope prof(KC_HUB, x.s);
     hipLaunchKernelGGL((k_hub_dense<DG, T>), dim3(hub_grid(h.n_chunks)), dim3(256), 0, x.s,
                        make_view(x.g, true), hc, plane, ld, x.hub_part());
@@ -1146,7 +1146,7 @@ template <int DG, typename T>
 static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const T* dy, int64_t ldg) {
     const HubPlan &ha = x.g->a.hub, &ht = x.g->at.hub;
     if (ha.n_chunks == 0 && ht.n_chunks == 0) return false;
-    HubChunks ca{ha.ce0, ha.ce1, ha.n_chunks}, ct{ht.ce0, ht.ce1, ht.n_chunks};
+    HubChunks ca{ha.ce0, ha.ce1, ha.n_chunks, x.g->long_rows}, ct{ht.ce0, ht.ce1, ht.n_chunks, x.g->long_rows};
     ProfScope prof(KC_HUB, x.s);
     const unsigned gx = hub_grid(std::max(ha.n_chunks, ht.n_chunks));
     if constexpr (sizeof(T) == 4) {

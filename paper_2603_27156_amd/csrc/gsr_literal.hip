@@ -177,7 +177,7 @@ static gsr_status_t lit_gs(const Lit& x, const float* plane, int64_t ld, float* 
 template <int W>
 static void launch_slot_tile(const Lit& x, const SlotArgs& a, const HubPlan& h) {
     if (h.n_chunks > 0) {
-        HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+        HubChunks hc{h.ce0, h.ce1, h.n_chunks, x.g->long_rows};
         hipLaunchKernelGGL((k_hub_dense<W, float>), dim3(hub_grid(h.n_chunks)), dim3(256), 0, x.s, a.g, hc,
                            a.P, (int64_t)W, x.g->scratch);
     }

@@ -367,7 +367,7 @@ static gsr_status_t aggregate_impl(const gsr_graph_t* g, const void* vals, const
     if (bad_h) return fail(GSR_ERR_INVALID_ARG, "idx holds a column outside [0,dg) or a repeated column");
     CsrView v = make_view(g, false);
     if (g->a.hub.n_chunks > 0) {
-        HubChunks hc{g->a.hub.ce0, g->a.hub.ce1, g->a.hub.n_chunks};
+        HubChunks hc{g->a.hub.ce0, g->a.hub.ce1, g->a.hub.n_chunks, g->long_rows};
         hipLaunchKernelGGL((k_hub_records<DG, T>), dim3(hub_grid(g->a.hub.n_chunks)), dim3(256), 0, s, v, hc,
                            (const T*)v_rec, (const M*)m_rec, k, part);
     }
@@ -409,7 +409,7 @@ static gsr_status_t spmm_launch(const gsr_graph_t* g, const float* x, int64_t ld
         const HubPlan& h = transpose ? g->at.hub : g->a.hub;
         const int tiles = (int)((g->n + 15) / 16);
         if (h.n_chunks > 0) {
-            HubChunks hc{h.ce0, h.ce1, h.n_chunks};
+            HubChunks hc{h.ce0, h.ce1, h.n_chunks, g->long_rows};
             const dim3 hg(hub_grid(h.n_chunks));
             if (width == 64) hipLaunchKernelGGL((k_hub_dense<64, float>), hg, dim3(256), 0, s, view, hc, x, ldx, hub_part);
             else if (width == 32) hipLaunchKernelGGL((k_hub_dense<32, float>), hg, dim3(256), 0, s, view, hc, x, ldx, hub_part);
