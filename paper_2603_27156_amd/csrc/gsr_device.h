@@ -252,6 +252,7 @@ struct CsrView {
     // split plan of very long rows
     const int32_t* hub_rows;
     const int32_t* hub_cptr;
+    const int32_t* hub_tile0;     // [tiles + 1]: split rows before row 16 t
     int32_t n_hub;
     int32_t hub_threshold;
     // tiles with more than heavy_edges stored entries, ascending (see TileDeal)
@@ -943,36 +944,92 @@ __device__ __forceinline__ void gather_dense_rows(const CsrView& g, const float*
     }
 }
 
+template <int DG, bool FAST = true>
+__device__ __forceinline__ void hub_rows_fill(const CsrView& g, const float* __restrict__ hub_part, int r0, const int* s_rp,
+                                              float* st, int lane);
+
 // H of the tile into st through gather_records_rows: st is cleared, the runs of ordinary rows are added into it,
 // split rows receive the sum of their first-pass partial rows afterwards.
-template <int DG, typename Range>
+template <int DG, bool FAST = true, typename Range>
 __device__ __forceinline__ void tile_gather_rows(const CsrView& g, const float* __restrict__ hub_part, bool has_hub, int r0,
                                                  const int* s_rp, float* st, int lane, Range range) {
     for (int i = lane; i < 16 * (DG + 1); i += 64) st[i] = 0.f;
     wave_sync();
     tile_ranges(g, has_hub, s_rp, range);
     wave_sync();
-    if (has_hub) hub_rows_fill<DG>(g, hub_part, r0, s_rp, st, lane);
+    if (has_hub) hub_rows_fill<DG, FAST>(g, hub_part, r0, s_rp, st, lane);
 }
 
-// sum of the first-pass partial rows of every split row of the tile into st.  The sixteen rows look up their chunk
-// ranges side by side (lane r for row r: one chain of dependent loads instead of sixteen), then each split row's
-// partial rows are added in chunk order, sixteen loads in flight.
-template <int DG>
+// sum of the first-pass partial rows of every split row of the tile into st, each row's in chunk order.  On a graph of
+// long rows every row of every tile is split, into one or two chunks, and a tile is all a wave has to do in a launch:
+// what counts is the number of memory round trips in a row.  So the sixteen rows find their places in the list of
+// split rows from one number per tile (split rows before the tile) and a count over the lanes before them, not by a
+// search each; the first and the second partial row of all sixteen are requested together; and only rows of more
+// than two chunks go on one by one, sixteen loads in flight (Table-1-shaped graph: block kernels 41 - 51 us -> see
+// the design notes).  The additions of a row are 0 + p_0 + p_1 + .. in this order whatever the batching.
+constexpr int HUB_FILL_ROWS = 16;     // rows whose partial rows are requested together
+template <int DG, bool FAST>
 __device__ __forceinline__ void hub_rows_fill(const CsrView& g, const float* __restrict__ hub_part, int r0, const int* s_rp,
                                               float* st, int lane) {
+    // (FAST = false: a search per row and the rows one by one - for kernels that have no register to spare; same
+    // additions)
+    if constexpr (!FAST) {
+        int q0s = 0, q1s = 0;
+        if (lane < 16 && (s_rp[lane + 1] - s_rp[lane]) > g.hub_threshold) {
+            const int h = find_hub(g, r0 + lane);
+            q0s = g.hub_cptr[h];
+            q1s = g.hub_cptr[h + 1];
+        }
+        for (int r = 0; r < 16; ++r) {
+            int q = __builtin_amdgcn_readlane(q0s, r);
+            const int q1 = __builtin_amdgcn_readlane(q1s, r);
+            if (q1 <= q) continue;                 // not a split row
+            const int cc = lane < DG ? lane : 0;
+            float acc = 0.f;
+            for (; q + 16 <= q1; q += 16) {
+                float v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) v[u] = hub_part[(size_t)(q + u) * DG + cc];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) acc += v[u];
+            }
+            for (; q < q1; ++q) acc += hub_part[(size_t)q * DG + cc];
+            if (lane < DG) st[r * (DG + 1) + lane] = acc;
+        }
+        return;
+    }
+    const bool split = lane < 16 && (s_rp[lane + 1] - s_rp[lane]) > g.hub_threshold;
+    const uint64_t splits = __builtin_amdgcn_ballot_w64(split);
     int q0v = 0, q1v = 0;
-    if (lane < 16 && (s_rp[lane + 1] - s_rp[lane]) > g.hub_threshold) {
-        const int h = find_hub(g, r0 + lane);
+    if (split) {
+        const int h = g.hub_tile0[r0 >> 4] + __popcll(splits & (((uint64_t)1 << lane) - 1));
         q0v = g.hub_cptr[h];
         q1v = g.hub_cptr[h + 1];
     }
+    const int c = lane < DG ? lane : 0;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+#pragma unroll
+        for (int rb = 0; rb < 16; rb += HUB_FILL_ROWS) {
+            float v[HUB_FILL_ROWS];
+#pragma unroll
+            for (int u = 0; u < HUB_FILL_ROWS; ++u) {
+                const int q = __builtin_amdgcn_readlane(q0v, rb + u) + j, q1 = __builtin_amdgcn_readlane(q1v, rb + u);
+                v[u] = hub_part[(size_t)(q < q1 ? q : 0) * DG + c];        // (no chunk j: any row, not used)
+            }
+#pragma unroll
+            for (int u = 0; u < HUB_FILL_ROWS; ++u) {
+                const int r = rb + u;
+                const int q = __builtin_amdgcn_readlane(q0v, r) + j, q1 = __builtin_amdgcn_readlane(q1v, r);
+                if (q < q1 && lane < DG) st[r * (DG + 1) + lane] = (j == 0 ? 0.f : st[r * (DG + 1) + lane]) + v[u];
+            }
+        }
+    }
     for (int r = 0; r < 16; ++r) {
-        int q = __builtin_amdgcn_readlane(q0v, r);
+        int q = __builtin_amdgcn_readlane(q0v, r) + 2;
         const int q1 = __builtin_amdgcn_readlane(q1v, r);
-        if (q1 <= q) continue;                 // not a split row
-        const int c = lane < DG ? lane : 0;
-        float acc = 0.f;
+        if (q1 <= q) continue;                 // no more than two chunks
+        float acc = st[r * (DG + 1) + c];
         for (; q + 16 <= q1; q += 16) {
             float v[16];
 #pragma unroll
@@ -1005,7 +1062,7 @@ __device__ __forceinline__ void tile_ranges(const CsrView& g, bool has_hub, cons
 // H of the tile into st (16 rows of DG+1 floats): the runs of ordinary rows go through
 // `range(e_a, e_b)`, which accumulates into acc (D[4 (lane / 16) + reg][j] of column block cb,
 // column = CPL j + cb); split rows receive the sum of their first-pass partial rows afterwards.
-template <int DG, typename Range>
+template <int DG, bool FAST = true, typename Range>
 __device__ __forceinline__ void tile_gather(const CsrView& g, const float* __restrict__ hub_part, bool has_hub, int r0,
                                             const int* s_rp, float* st, int lane, f32x4 (&acc)[DG / 16], Range range) {
     constexpr int CPL = DG / 16, LR = DG + 1;
@@ -1016,7 +1073,7 @@ __device__ __forceinline__ void tile_gather(const CsrView& g, const float* __res
     for (int cb = 0; cb < CPL; ++cb)
 #pragma unroll
         for (int r = 0; r < 4; ++r) st[(4 * (lane >> 4) + r) * LR + CPL * (lane & 15) + cb] = acc[cb][r];
-    if (has_hub) hub_rows_fill<DG>(g, hub_part, r0, s_rp, st, lane);
+    if (has_hub) hub_rows_fill<DG, FAST>(g, hub_part, r0, s_rp, st, lane);
 }
 
 // ---- 16-row MFMA tiles -------------------------------------------------------------------------

@@ -131,6 +131,7 @@ static void free_csr(Csr& c) {
     if (c.av) (void)hipFree(c.av);
     if (c.hub.rows) (void)hipFree(c.hub.rows);
     if (c.hub.cptr) (void)hipFree(c.hub.cptr);
+    if (c.hub.tile0) (void)hipFree(c.hub.tile0);
     if (c.hub.crow) (void)hipFree(c.hub.crow);
     if (c.hub.ce0) (void)hipFree(c.hub.ce0);
     if (c.hub.ce1) (void)hipFree(c.hub.ce1);
@@ -161,9 +162,10 @@ static gsr_status_t upload_csr(const HostCsr& h, int64_t n, int64_t threshold, i
     GSR_TRY(upload(h.rp, &out->rp));
     GSR_TRY(upload(h.ci, &out->ci));
     GSR_TRY(upload(h.av, &out->av));
-    std::vector<int32_t> rows, cptr, crow, ce0, ce1;
+    std::vector<int32_t> rows, cptr, crow, ce0, ce1, tile0;
     cptr.push_back(0);
     for (int64_t i = 0; i < n; ++i) {
+        if ((i & 15) == 0) tile0.push_back((int32_t)rows.size());
         int64_t len = h.rp[i + 1] - h.rp[i];
         if (len <= threshold) continue;
         rows.push_back((int32_t)i);
@@ -174,8 +176,10 @@ static gsr_status_t upload_csr(const HostCsr& h, int64_t n, int64_t threshold, i
         }
         cptr.push_back((int32_t)crow.size());
     }
+    tile0.push_back((int32_t)rows.size());
     out->hub.n_hub = (int32_t)rows.size();
     out->hub.n_chunks = (int32_t)crow.size();
+    GSR_TRY(upload(tile0, &out->hub.tile0));
     GSR_TRY(upload(rows, &out->hub.rows));
     GSR_TRY(upload(cptr, &out->hub.cptr));
     GSR_TRY(upload(crow, &out->hub.crow));

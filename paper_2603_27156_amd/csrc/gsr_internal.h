@@ -70,6 +70,7 @@ struct HubPlan {
     int32_t n_chunks = 0;     // chunks over all hub rows
     int32_t* rows = nullptr;  // device [n_hub]    ascending row ids
     int32_t* cptr = nullptr;  // device [n_hub+1]  first chunk of each hub row
+    int32_t* tile0 = nullptr; // device [tiles+1]  hub rows before row 16 t (the place in `rows` of tile t's first hub row)
     int32_t* crow = nullptr;  // device [n_chunks] row of the chunk
     int32_t* ce0 = nullptr;   // device [n_chunks] first edge
     int32_t* ce1 = nullptr;   // device [n_chunks] one past the last edge

@@ -475,6 +475,9 @@ template <int DG, typename T, bool DEAL, bool B3, bool ACC = false>
 __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
     constexpr int CPL = DG / 16;
     constexpr int GRAD_WAVES = grad_waves(B3);
+    // the partial rows of a tile's split rows requested together (hub_rows_fill) only where that spills no register:
+    // these kernels sit at their 128 registers
+    constexpr bool FILL_FAST = ACC || (!DEAL && sizeof(T) == 4 && DG == 64);
     __shared__ WaveLds<DG, 1> lds[GRAD_WAVES];
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tg = lane >> 4, tj = lane & 15;
     WaveLds<DG, 1>& L = lds[wave];
@@ -519,13 +522,13 @@ __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_pe
         // float32: Q in ordinary arithmetic, a run of the staged edges per lane group (322 us against 378 through the
         // matrix cores on the 1M-node workload; sixteen steps in flight instead of eight spill)
         if constexpr (sizeof(T) == 4) {
-            tile_gather_rows<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, [&](int e_a, int e_b) {
+            tile_gather_rows<DG, FILL_FAST>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, [&](int e_a, int e_b) {
                 gather_dense_rows<DG, 8>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
                                                __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, lane, st);
             });
         } else {
             f32x4 qacc[DG / 16];
-            tile_gather<DG>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, qacc, [&](int e_a, int e_b) {
+            tile_gather<DG, FILL_FAST>(a.gt, a.hub_part, has_hub, r0, L.rp, st, lane, qacc, [&](int e_a, int e_b) {
                 gather_dense_mfma<DG, T, (sizeof(T) == 4 || DG == 32) ? 16 : 8>(a.gt, a.dy, a.ldg, __builtin_amdgcn_readfirstlane(e_a),
                                          __builtin_amdgcn_readfirstlane(e_b), L.rp, L.ebuf, lane, qacc);
             });

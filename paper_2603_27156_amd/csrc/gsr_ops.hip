@@ -16,7 +16,7 @@ CsrView make_view(const gsr_graph_t* g, bool transpose) {
     const Csr& c = transpose ? g->at : g->a;
     CsrView v;
     v.rp = c.rp; v.ci = c.ci; v.av = c.av;
-    v.hub_rows = c.hub.rows; v.hub_cptr = c.hub.cptr; v.n_hub = c.hub.n_hub;
+    v.hub_rows = c.hub.rows; v.hub_cptr = c.hub.cptr; v.hub_tile0 = c.hub.tile0; v.n_hub = c.hub.n_hub;
     v.hub_threshold = g->hub_threshold;
     v.heavy = c.heavy; v.n_heavy = c.n_heavy; v.heavy_edges = kHeavyTileEdges;
     return v;
