@@ -964,10 +964,12 @@ __device__ __forceinline__ void tile_gather_rows(const CsrView& g, const float* 
 // long rows every row of every tile is split, into one or two chunks, and a tile is all a wave has to do in a launch:
 // what counts is the number of memory round trips in a row.  So the sixteen rows find their places in the list of
 // split rows from one number per tile (split rows before the tile) and a count over the lanes before them, not by a
-// search each; the first and the second partial row of all sixteen are requested together; and only rows of more
-// than two chunks go on one by one, sixteen loads in flight (Table-1-shaped graph: block kernels 41 - 51 us -> see
+// search each; the first partial rows of all sixteen are requested together, then the second ones, up to the fourth;
+// and only rows of more than four chunks go on one by one, sixteen loads in flight (Table-1-shaped graph: block kernels 41 - 51 us -> see
 // the design notes).  The additions of a row are 0 + p_0 + p_1 + .. in this order whatever the batching.
 constexpr int HUB_FILL_ROWS = 16;     // rows whose partial rows are requested together
+constexpr int HUB_FILL_DEPTH = 4;     // partial rows per row taken that way (the launch of a long-row graph ends with the
+                                      // tile whose rows go on one by one: 26 us against a median of 6)
 template <int DG, bool FAST>
 __device__ __forceinline__ void hub_rows_fill(const CsrView& g, const float* __restrict__ hub_part, int r0, const int* s_rp,
                                               float* st, int lane) {
@@ -1007,8 +1009,9 @@ __device__ __forceinline__ void hub_rows_fill(const CsrView& g, const float* __r
         q1v = g.hub_cptr[h + 1];
     }
     const int c = lane < DG ? lane : 0;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    // partial row j of every row that has one, j = 0 .. HUB_FILL_DEPTH - 1, while any row has one
+    for (int j = 0; j < HUB_FILL_DEPTH; ++j) {
+        if (__builtin_amdgcn_ballot_w64(q1v - q0v > j) == 0) break;
 #pragma unroll
         for (int rb = 0; rb < 16; rb += HUB_FILL_ROWS) {
             float v[HUB_FILL_ROWS];
@@ -1025,10 +1028,11 @@ __device__ __forceinline__ void hub_rows_fill(const CsrView& g, const float* __r
             }
         }
     }
+    // rows of more chunks than that go on one by one, sixteen loads in flight
     for (int r = 0; r < 16; ++r) {
-        int q = __builtin_amdgcn_readlane(q0v, r) + 2;
+        int q = __builtin_amdgcn_readlane(q0v, r) + HUB_FILL_DEPTH;
         const int q1 = __builtin_amdgcn_readlane(q1v, r);
-        if (q1 <= q) continue;                 // no more than two chunks
+        if (q1 <= q) continue;
         float acc = st[r * (DG + 1) + c];
         for (; q + 16 <= q1; q += 16) {
             float v[16];

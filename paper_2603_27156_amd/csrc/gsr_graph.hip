@@ -483,7 +483,9 @@ static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz,
     // very long rows: 512 / 64.  Graphs whose mean row is long (the 49,600-node, 11.7M-entry workload shaped like the
     // paper's Table 1: 871 ms per step with 512 / 64, 661 with 64 / 64, 566 with 64 / 256) are better served when nearly
     // every row goes through the first pass, whose lanes add a row's entries in ordinary arithmetic instead of spending
-    // a 16-row matrix product on them.
+    // a 16-row matrix product on them.  Every row of two entries or more, in fact: a launch of a tile kernel is one
+    // tile per wave there, and it ended with the few tiles that still had short rows to gather themselves (that stage
+    // 6 us at the median, 26 us at most; 503 ms per step with the cut at 64, 460 at 32, 445 at 8, 443 at 1).
     const bool long_rows = g->nnz >= 64 * n;
     g->long_rows = long_rows;
 
@@ -512,7 +514,7 @@ static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz,
     // 12 / 8: 9.6 / 9.8; chunks of 32 instead of 64: 9.7).
     const bool few_tiles = (n + 15) / 16 < (int64_t)16 * full_grid, very_few_tiles = (n + 15) / 16 < (int64_t)8 * full_grid;
     const int64_t hub_threshold = options().hub_threshold > 0 ? options().hub_threshold
-                                  : long_rows ? 64 : very_few_tiles ? 16 : few_tiles ? 64 : 512;
+                                  : long_rows ? 1 : very_few_tiles ? 16 : few_tiles ? 64 : 512;
     const int64_t hub_chunk = options().hub_chunk > 0 ? options().hub_chunk : (long_rows ? 256 : 64);
     g->hub_threshold = (int32_t)hub_threshold;
     g->hub_values = options().hub_values == 1 ? 2 : (options().hub_values == 0 && long_rows) ? 1 : 0;
