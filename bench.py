@@ -42,7 +42,7 @@ def measured_counters(workload_name, kernel):
     if not w or kernel not in w.get("kernels", {}):
         return None, None
     k = w["kernels"][kernel]
-    return k, {"commit": rec.get("commit"), "file": "profiles/gsr_step_counters.json"}
+    return k, {"commit": w.get("commit", rec.get("commit")), "file": "profiles/gsr_step_counters.json", "summary": w.get("summary")}
 
 
 def algorithmic_bytes(n, nnz, dg, k, c, b, rms):

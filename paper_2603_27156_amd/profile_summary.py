@@ -199,7 +199,7 @@ def main():
         rec["commit"] = commit
         rec["written_by"] = "python -m paper_2603_27156_amd.profile_summary"
         rec["workloads"][args.workload] = {"summary": os.path.relpath(args.md, os.path.dirname(os.path.abspath(args.json)) + "/.."),
-                                           "kernels": classes}
+                                           "commit": commit, "kernels": classes}
         with open(args.json, "w") as f:
             json.dump(rec, f, indent=1, sort_keys=True)
             f.write("\n")
