@@ -1895,6 +1895,36 @@ __global__ __launch_bounds__(256) void k_record_columns(int n, int k, const type
     }
 }
 
+// The same for a group of S column blocks of 64 (S = 2 or 3: a column number must fit a byte beside the 0xFF of an
+// unused slot): the k values a row keeps over its whole width, taken out of the S records of its column blocks into
+// one list [n][k] with the column in the whole row beside each, so that one first pass serves all S blocks and every
+// lane of it has a value (a pass per column block walks the edges S times with room for k values in each).
+template <int S>
+struct WideRecords {
+    const float* vals[S];
+    const uint64_t* mask[S];
+};
+template <int S>
+__global__ __launch_bounds__(256) void k_record_columns_wide(int n, int k, WideRecords<S> r, float* __restrict__ vals,
+                                                             uint8_t* __restrict__ cols) {
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    float* v = vals + (size_t)j * k;
+    uint8_t* o = cols + (size_t)j * k;
+    int pos = 0;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+        uint64_t m = r.mask[s][j];
+        const float* src = r.vals[s] + (size_t)j * k;
+        for (int t = 0; m && pos < k; ++t, ++pos) {
+            v[pos] = src[t];
+            o[pos] = (uint8_t)(64 * s + __builtin_ctzll(m));
+            m &= m - 1;
+        }
+    }
+    for (; pos < k; ++pos) { v[pos] = 0.f; o[pos] = (uint8_t)0xFF; }
+}
+
 template <int DG, int LG>
 struct HubValLds {
     uint2 ebuf[64];                   // (j * k, a_ij) of the staged edges
@@ -1970,15 +2000,21 @@ __device__ __forceinline__ void hub_values_pass(const CsrView& g, const HubChunk
             }
         }
         // the sums of the places are added in place order, even rows before odd rows, and the rows cleared
+        // (DG > 64, a group of column blocks: part is [DG / 64][n_chunks][64], one array of partial rows per block)
         wave_sync();
-        if (lane < DG) {
-            float s = 0.f;
 #pragma unroll
-            for (int pl = 0; pl < 2 * NE; ++pl) {
-                s += base[pl * DG + lane];
-                base[pl * DG + lane] = 0.f;
+        for (int c0 = 0; c0 < DG; c0 += 64) {
+            const int c = c0 + lane;
+            if (c < DG) {
+                float s = 0.f;
+#pragma unroll
+                for (int pl = 0; pl < 2 * NE; ++pl) {
+                    s += base[pl * DG + c];
+                    base[pl * DG + c] = 0.f;
+                }
+                if (DG > 64) part[((size_t)(c0 >> 6) * h.n_chunks + q) * 64 + lane] = s;
+                else part[(size_t)q * DG + lane] = s;
             }
-            part[(size_t)q * DG + lane] = s;
         }
         wave_sync();
     }
@@ -1989,6 +2025,15 @@ template <typename F>
 inline void hub_values_variant(int k, F&& f) {
     if (k <= 4) f(std::integral_constant<int, 2>{}, std::integral_constant<int, 1>{});
     else if (k <= 8) f(std::integral_constant<int, 3>{}, std::integral_constant<int, 1>{});
+    else if (k <= 16) f(std::integral_constant<int, 4>{}, std::integral_constant<int, 1>{});
+    else if (k <= 32) f(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
+    else f(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
+}
+
+// The same for a group of column blocks (rows of 128 or 192 sums per edge place in LDS): at least eight lanes per edge.
+template <typename F>
+inline void hub_values_variant_wide(int k, F&& f) {
+    if (k <= 8) f(std::integral_constant<int, 3>{}, std::integral_constant<int, 1>{});
     else if (k <= 16) f(std::integral_constant<int, 4>{}, std::integral_constant<int, 1>{});
     else if (k <= 32) f(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
     else f(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});

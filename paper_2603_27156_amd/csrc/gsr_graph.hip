@@ -260,11 +260,15 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     off += align_up((size_t)g->grid * dgs * dgs * sizeof(float));
     w.hub_partial = off;
     size_t chunks = (size_t)std::max(g->a.hub.n_chunks, g->at.hub.n_chunks);
-    off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
+    // (wide groups summed value by value: the partial rows of all S column blocks from one pass, [S][chunks][64])
+    const bool wide_values = S > 1 && b == 4 && g->hub_values;
+    off += align_up(std::max<size_t>(chunks, 1) * dgs * (wide_values ? S : 1) * sizeof(float));
     w.hub_partial2 = off;
     off += align_up(std::max<size_t>(chunks, 1) * dgs * sizeof(float));
     w.hub_cols = off;
     if (b == 4 && g->hub_values) off += align_up(n * (size_t)cfg->k + 16);
+    w.hub_vals = off;
+    if (wide_values) off += align_up(n * (size_t)cfg->k * sizeof(float) + 16);
     w.h = off;               // (not for 16-bit storage at 32 columns: that backward keeps H on chip)
     if ((b == 4 || dgs == 64) && g->split_backward) off += align_up(n * dgs * sizeof(float));
     w.total = off;

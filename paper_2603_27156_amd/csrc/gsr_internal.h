@@ -130,6 +130,7 @@ struct LayerWs {
     size_t hub_partial;  // [max(n_chunks A, n_chunks A^T)][dg] float
     size_t hub_partial2; // same size: the backward's two first passes of a block run as one launch
     size_t hub_cols;     // [n][k] bytes: column of every record value, for the value-by-value first pass (float32)
+    size_t hub_vals;     // wide groups, same pass: [n][k] float, the kept values of a whole row side by side
     size_t total;
 };
 struct StepWs {

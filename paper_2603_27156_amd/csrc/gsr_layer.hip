@@ -1079,6 +1079,7 @@ struct Ctx {
     float* hub_part() const { return (float*)(ws + lw.hub_partial); }
     float* hub_part2() const { return (float*)(ws + lw.hub_partial2); }
     uint8_t* hub_cols() const { return (uint8_t*)(ws + lw.hub_cols); }
+    float* hub_vals() const { return (float*)(ws + lw.hub_vals); }
     bool hub_by_value() const { return g->hub_values == 2 || (g->hub_values == 1 && 2 * cfg->k <= DG); }
 };
 
@@ -1195,7 +1196,8 @@ static bool split_dw(const gsr_graph_t* g) { return (sizeof(T) == 4 || DG == 64)
 template <int DG, typename T>
 static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>& in, const float* w, T* plane, int64_t ld,
                              const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg, bool first_pass_done = false,
-                             TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, int ldw = DG, float* h_out = nullptr) {
+                             TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, int ldw = DG, float* h_out = nullptr,
+                             const float* hub_part = nullptr) {
     if (!first_pass_done) launch_hub_records<DG, T>(x, in);
     BlockArgs<DG, T> a;
     a.tie = tie;
@@ -1203,7 +1205,7 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     a.g = make_view(x.g, false);
     a.n = (int)x.cfg->n; a.tiles = x.tiles;
     a.in = in; a.k = x.cfg->k;
-    a.hub_part = x.hub_part(); a.w = w; a.ldw = ldw; a.plane = plane; a.ld = ld;
+    a.hub_part = hub_part ? hub_part : x.hub_part(); a.w = w; a.ldw = ldw; a.plane = plane; a.ld = ld;
     a.out = out; a.out_given = out_given;
     a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
     if (mode != 2) tile_counters(x.g, &a.draws, &a.draws_done);
@@ -1354,6 +1356,44 @@ static void launch_epi_wide(const Ctx<64, T>& x, int slot, int layer, const T* z
     else launch_epi_wide_s<4, T>(x, slot, layer, z, ldz, z_sub, dst, ldd, dst_gs, ndst);
 }
 
+// First pass over the records of a wide group's S column blocks in one launch, value by value (float32 records, S = 2
+// or 3, 2 k <= D/C, a graph whose first pass runs that way): the row's k kept values are collected from the S records
+// with their columns in the whole row (k_record_columns_wide), and one pass sums them into rows of D/C sums per
+// chunk, written as S arrays of partial rows [chunks][64].  Returns false where it does not apply (then each column
+// block has a first pass of its own).
+template <typename T>
+static bool launch_hub_values_wide(const Ctx<64, T>& x, int in_slot, int layer) {
+    if constexpr (sizeof(T) != 4) {
+        return false;
+    } else {
+        const HubPlan& h = x.g->a.hub;
+        const int S = x.S, k = x.cfg->k;
+        if (!x.g->hub_values || S < 2 || S > 3 || 2 * k > 64 * S || h.n_chunks == 0) return false;
+        HubChunks hc{h.ce0, h.ce1, h.n_chunks, x.g->long_rows};
+        ProfScope prof(KC_HUB, x.s);
+        const unsigned rows_grid = (unsigned)((x.cfg->n + 255) / 256);
+        auto go = [&](auto sc) {
+            constexpr int SS = decltype(sc)::value;
+            WideRecords<SS> r;
+            for (int sub = 0; sub < SS; ++sub) {
+                const Record<64, T> rec = x.rec(in_slot, layer, sub);
+                r.vals[sub] = (const float*)rec.vals;
+                r.mask[sub] = (const uint64_t*)rec.mask;
+            }
+            hipLaunchKernelGGL((k_record_columns_wide<SS>), dim3(rows_grid), dim3(256), 0, x.s, (int)x.cfg->n, k, r, x.hub_vals(),
+                               x.hub_cols());
+            hub_values_variant_wide(k, [&](auto lg, auto kq) {
+                hipLaunchKernelGGL((k_hub_values<64 * SS, decltype(lg)::value, decltype(kq)::value>), dim3(hub_grid(h.n_chunks)),
+                                   dim3(256), 0, x.s, make_view(x.g, false), hc, (const float*)x.hub_vals(),
+                                   (const uint8_t*)x.hub_cols(), k, x.hub_part());
+            });
+        };
+        if (S == 2) go(std::integral_constant<int, 2>{});
+        else go(std::integral_constant<int, 3>{});
+        return true;
+    }
+}
+
 // plane (+/-)= f_i(Y_{i-1}) for one group: S x S launches of the 64-column block kernel.  mode as launch_block;
 // dw_i (mode 2): D/C x D/C, receives dW_i block by block.
 template <typename T>
@@ -1361,17 +1401,23 @@ static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, co
                        int64_t ldg, float* dw_i) {
     const int S = x.S, dgw = 64 * S;
     const Record<64, T> none = x.rec(-1);
+    // the first pass over the records of all S column blocks at once where it runs value by value (float32, two or
+    // three blocks): the partial rows of block mb are then at hub_part + mb * chunks * 64
+    const bool one_pass = launch_hub_values_wide<T>(x, in_slot, layer);
+    const size_t part_stride = (size_t)x.g->a.hub.n_chunks * 64;
     for (int mb = 0; mb < S; ++mb)
         for (int ob = 0; ob < S; ++ob) {
             const float* wsub = wi + (size_t)mb * 64 * dgw + 64 * ob;
+            const float* part = one_pass ? x.hub_part() + mb * part_stride : nullptr;
             unsigned nparts = 0;
             if (mode == 2 && split_dw<64, T>(x.g)) {
-                launch_block<64, T>(x, 1, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false, nullptr, 0, ob > 0,
-                                    TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, x.hplane());
+                launch_block<64, T>(x, 1, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false, nullptr, 0, one_pass || ob > 0,
+                                    TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, x.hplane(), part);
                 nparts = launch_dw<64, T>(x, dy + 64 * ob, ldg);
             } else {
                 nparts = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false,
-                                             dy ? dy + 64 * ob : nullptr, ldg, ob > 0, TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw);
+                                             dy ? dy + 64 * ob : nullptr, ldg, one_pass || ob > 0,
+                                             TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, nullptr, part);
             }
             if (mode == 2) {
                 ProfScope prof(KC_DW_REDUCE, x.s);

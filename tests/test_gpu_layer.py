@@ -530,11 +530,14 @@ def test_graph_of_long_rows_goes_through_the_first_pass(dtype, threshold):
 
 
 @pytest.mark.parametrize("dg,c,k,chunk", [(64, 2, 3, 4), (64, 2, 8, 100), (64, 4, 16, 100), (64, 2, 24, 4), (64, 2, 40, 100),
-                                          (64, 2, 64, 4), (32, 3, 8, 100), (32, 2, 20, 4), (192, 2, 16, 100)])
+                                          (64, 2, 64, 4), (32, 3, 8, 100), (32, 2, 20, 4), (192, 2, 16, 100),
+                                          (192, 2, 4, 4), (192, 2, 64, 100), (128, 2, 8, 4), (128, 3, 40, 100), (256, 2, 16, 4)])
 def test_first_pass_value_by_value(dg, c, k, chunk):
     """The first pass over float32 records with a lane per record value (option "hub_values" = 1; the default on
     long-row graphs, forced here on a small graph with rows cut at 6 entries): 4, 8 or 16 lanes per edge and one to
-    four values per lane depending on k, chunks shorter and longer than a round of 64 staged edges."""
+    four values per lane depending on k, chunks shorter and longer than a round of 64 staged edges.  Groups of 128 and
+    192 columns take one such pass for all their column blocks (the kept values of a whole row side by side), 256 a
+    pass per block."""
     print(f"[case] dg={dg} C={c} k={k} chunk={chunk}", flush=True)
     gsr.gsr_set_option("hub_values", 1)
     gsr.gsr_set_option("hub_threshold", 6)
