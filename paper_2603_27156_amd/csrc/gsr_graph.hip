@@ -522,7 +522,7 @@ static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz,
     const int64_t hub_chunk = options().hub_chunk > 0 ? options().hub_chunk : (long_rows ? 256 : 64);
     g->hub_threshold = (int32_t)hub_threshold;
     g->hub_values = options().hub_values == 1 ? 2 : (options().hub_values == 0 && long_rows) ? 1 : 0;
-    g->split_backward = !(long_rows || (n + 15) / 16 < (int64_t)4 * full_grid);    // (not with fewer tiles than resident waves)
+    g->split_backward = !(long_rows || (n + 15) / 16 < (int64_t)8 * full_grid);    // (not with fewer than two tiles per resident wave)
 
     gsr_status_t st = upload_csr(a, n, hub_threshold, hub_chunk, &g->a);
     if (st == GSR_OK) {

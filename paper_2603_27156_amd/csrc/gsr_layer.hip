@@ -1184,11 +1184,12 @@ static bool launch_hub_both(const Ctx<DG, T>& x, const Record<DG, T>& in, const 
 // requested its own rows after the gather; 253 + 80 against 337 before).  bf16 storage at D/C = 32: the fused kernel
 // (inverse + dW accumulators at eight waves per compute unit), whose neighbour sums hide on the bf16 pipe: 1,243 + 228 us
 // split against 1,205 fused at 8M nodes (1,150 fused now).
-// Graphs with fewer tiles than resident waves, or with all rows in the first pass (a launch there is at most one short
-// tile per wave, and two more launches per block cost more than the occupancy gains: 0.56 against 0.70 ms per step on
-// the 2,000-node workload, 487 against 496 ms on the Table-1-shaped one) keep the fused kernel in float32 as well; it
-// uses the same row-wise sums, so whichever way a block's backward runs it rebuilds the bits the plain inverse
-// rebuilds.  (The 100k-node workload, 1.5 tiles per wave, is better split: 12.0 against 12.3 ms.)
+// Graphs with fewer than two tiles per resident wave, or with all rows in the first pass (a launch there is one or two
+// short tiles per wave, and two more launches per block cost more than the occupancy gains: 0.56 against 0.70 ms per
+// step on the 2,000-node workload, 487 against 496 ms on the Table-1-shaped one, 8.7 against 9.0 ms on the 100k-node
+// one - which was better split, 12.0 against 12.3 ms, while a tile's split rows still cost a memory round trip each)
+// keep the fused kernel in float32 as well; it uses the same row-wise sums, so whichever way a block's backward runs
+// it rebuilds the bits the plain inverse rebuilds.
 template <int DG, typename T>
 static bool split_dw(const gsr_graph_t* g) { return (sizeof(T) == 4 || DG == 64) && g->split_backward; }
 
