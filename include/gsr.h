@@ -124,7 +124,9 @@ const char* gsr_version(void);
  *   "hub_values"      how the first pass sums float32 records (layer and step calls): 1 = a lane per record value,
  *                     through a byte per value naming its column that a small kernel writes from the masks first;
  *                     2 = a lane per group of columns, as the tile kernels do; 0, the default: 1 on graphs whose mean
- *                     row has 64 stored entries or more, while 2 k <= D/C.  Read when a graph is created
+ *                     row has 64 stored entries or more, while 2 k <= D/C (groups of 128 or 192 columns: one such
+ *                     pass for all their column blocks; of 256: a pass per block of 64 while 2 k <= 64).  Read when
+ *                     a graph is created
  *   "max_workgroups"  workgroups of the persistent kernels, multiple of 8 (0: as many as stay resident, at most 4 per CU)
  *   "profile"         bit mask of kernel classes to time (see gsr_profile_read); read at once */
 gsr_status_t gsr_set_option(const char* key, int64_t value);
