@@ -103,17 +103,36 @@ def test_wide_step_with_the_weight_gradient_in_a_pass_of_its_own():
         gsr.gsr_set_option("max_workgroups", 0)
 
 
-def test_wide_groups_on_long_rows():
+@pytest.mark.parametrize("c,k,save", [(2, 16, 0), (2, 16, 1), (3, 8, 1), (2, 40, 0)])
+def test_wide_groups_on_long_rows(c, k, save):
     """The Table-1-shaped graph (every row through the first pass) scaled down, with the paper's model split: 384
-    channels in two groups of 192."""
-    w = synth.scaled(synth.workload(5), 1200, levels=6, l=2, c=2, k=16)
+    channels in two groups of 192 (also three of 128).  The first pass over the records of such a group runs once for
+    all its column blocks, value by value: the step with nothing kept and with all column sets kept, then the layer
+    calls on the same graph."""
+    w = synth.scaled(synth.workload(5), 1200, levels=6, l=2, c=c, k=k)
     cs = Case(w, 0, PLANAR)
-    assert w.dg == 192 and gsr.gsr_graph_info(cs.gg)["n_hub_rows"] > 1000
-    ref = oracle.step(cs.og, cs.ocfg, w.l, cs.x0_on_grid(), cs.inp.weights, cs.inp.w_out, cs.inp.b_out, cs.inp.target)
-    out = run_step(cs)
+    assert w.dg == 384 // c and gsr.gsr_graph_info(cs.gg)["n_hub_rows"] > 1000
+    ref = oracle.step(cs.og, cs.ocfg, w.l, cs.x0_on_grid(), cs.inp.weights, cs.inp.w_out, cs.inp.b_out, cs.inp.target,
+                      variant=2 if save else 0)
+    out = run_step(cs, save_indices=save)
     assert np.isclose(out["loss"], ref["loss"], rtol=1e-4)
     for key in ("yhat", "XL", "X0rec", "dW", "dwout", "dX0"):
         assert_close(key, out[key], ref[key])
+    W = cs.inp.weights[0]
+    Wd = torch.from_numpy(W).to(cs.dev)
+    X = cs.x0_on_grid()
+    Y_ref = oracle.layer_forward(cs.og, cs.ocfg, W, X)
+    y = cs.to_dev(X)
+    gsr.gsr_layer_forward(cs.gg, cs.gcfg, Wd, y)
+    assert_close("Y", cs.to_host(y), Y_ref)
+    dY = (np.random.default_rng(5).standard_normal((w.n, w.d)) * 1e-3).astype(np.float32).astype(np.float64)
+    Xb_ref, dX_ref, dW_ref = oracle.layer_backward(cs.og, cs.ocfg, W, Y_ref, dY)
+    yb, dyb = cs.to_dev(Y_ref), cs.to_dev(dY)
+    dW = torch.empty((w.c, w.dg, w.dg), dtype=torch.float32, device=cs.dev)
+    gsr.gsr_layer_backward(cs.gg, cs.gcfg, Wd, yb, dyb, dW)
+    assert_close("X rebuilt (backward)", cs.to_host(yb), Xb_ref)
+    assert_close("dX", cs.to_host(dyb), dX_ref)
+    assert_close("dW", dW.cpu().numpy(), dW_ref)
 
 
 def test_wide_groups_with_bf16_storage():
