@@ -965,8 +965,9 @@ __device__ __forceinline__ void tile_gather_rows(const CsrView& g, const float* 
 // what counts is the number of memory round trips in a row.  So the sixteen rows find their places in the list of
 // split rows from one number per tile (split rows before the tile) and a count over the lanes before them, not by a
 // search each; the first partial rows of all sixteen are requested together, then the second ones, up to the fourth;
-// and only rows of more than four chunks go on one by one, sixteen loads in flight (Table-1-shaped graph: block kernels 41 - 51 us -> see
-// the design notes).  The additions of a row are 0 + p_0 + p_1 + .. in this order whatever the batching.
+// and only rows of more than four chunks go on one by one, sixteen loads in flight (Table-1-shaped graph: forward
+// kernel 43 -> 38 us per launch, fused inverse + dW 51 -> 46 us).  The additions of a row are 0 + p_0 + p_1 + .. in this
+// order whatever the batching.
 constexpr int HUB_FILL_ROWS = 16;     // rows whose partial rows are requested together
 constexpr int HUB_FILL_DEPTH = 4;     // partial rows per row taken that way (the launch of a long-row graph ends with the
                                       // tile whose rows go on one by one: 26 us against a median of 6)
