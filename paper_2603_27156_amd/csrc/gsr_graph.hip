@@ -257,7 +257,7 @@ LayerWs carve_layer(const gsr_config_t* cfg, const gsr_graph_t* g) {
     w.dh = off;
     if (S > 1) off += align_up(n * dg * sizeof(float));
     w.dw_partial = off;
-    off += align_up((size_t)g->grid * dgs * dgs * sizeof(float));
+    off += align_up((size_t)g->grid * dgs * dgs * sizeof(float) * (size_t)(S * S));      // (wide groups: a set per block of dW_i)
     w.hub_partial = off;
     size_t chunks = (size_t)std::max(g->a.hub.n_chunks, g->at.hub.n_chunks);
     // (wide groups summed value by value: the partial rows of all S column blocks from one pass, [S][chunks][64])

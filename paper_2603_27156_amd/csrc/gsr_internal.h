@@ -126,7 +126,7 @@ struct LayerWs {
     size_t y0;           // Y_0 plane [n][dg] of T (C > 2); wide groups: [S][n][64]
     size_t h;            // [n][min(dg, 64)] float: H of the block being inverted, for the weight-gradient kernel
     size_t dh;           // wide groups only: [S][n][64] float, the block gradient summed over column blocks
-    size_t dw_partial;   // [grid][dg*dg] float
+    size_t dw_partial;   // [grid][dg*dg] float; wide groups: [S*S][grid][64*64]
     size_t hub_partial;  // [max(n_chunks A, n_chunks A^T)][dg] float
     size_t hub_partial2; // same size: the backward's two first passes of a block run as one launch
     size_t hub_cols;     // [n][k] bytes: column of every record value, for the value-by-value first pass (float32)

@@ -374,8 +374,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 // thread rows each sum a contiguous sixteenth of the partials in ascending order, then the 16 sums are added in order.
 // (Blocks of 64 entries left three quarters of the compute units idle on a 64 x 64 matrix: 18 us per launch.)
 constexpr int DW_REDUCE_ENTRIES = 16;
+// blockIdx.y (groups wider than a tile: the S x S blocks of dW_i in one launch): set y of the partials starts
+// y * set_stride floats on, and goes to block (y / sets_per_row, y % sets_per_row) of the output, 64 rows and 64 columns apart.
 __global__ __launch_bounds__(256) void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems,
-                                                   float* __restrict__ out, int cols, int ld_out) {
+                                                   float* __restrict__ out, int cols, int ld_out, size_t set_stride = 0,
+                                                   int sets_per_row = 1) {
+    partial += (size_t)blockIdx.y * set_stride;
+    out += (size_t)(blockIdx.y / sets_per_row) * 64 * ld_out + (size_t)(blockIdx.y % sets_per_row) * 64;
     __shared__ float red[16][DW_REDUCE_ENTRIES];
     const int j = threadIdx.x & (DW_REDUCE_ENTRIES - 1), seg = threadIdx.x / DW_REDUCE_ENTRIES;
     const int e = blockIdx.x * DW_REDUCE_ENTRIES + j;
@@ -1198,7 +1203,7 @@ template <int DG, typename T>
 static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>& in, const float* w, T* plane, int64_t ld,
                              const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg, bool first_pass_done = false,
                              TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, int ldw = DG, float* h_out = nullptr,
-                             const float* hub_part = nullptr) {
+                             const float* hub_part = nullptr, float* dw_partial = nullptr) {
     if (!first_pass_done) launch_hub_records<DG, T>(x, in);
     BlockArgs<DG, T> a;
     a.tie = tie;
@@ -1208,7 +1213,7 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     a.in = in; a.k = x.cfg->k;
     a.hub_part = hub_part ? hub_part : x.hub_part(); a.w = w; a.ldw = ldw; a.plane = plane; a.ld = ld;
     a.out = out; a.out_given = out_given;
-    a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
+    a.norm = x.cfg->norm; a.eps = x.cfg->eps; a.dy = dy; a.ldg = ldg; a.dw_partial = dw_partial ? dw_partial : x.dw_partial();
     if (mode != 2) tile_counters(x.g, &a.draws, &a.draws_done);
     else a.draws = a.draws_done = nullptr;
     const bool b3 = mode != 0 || !x.g->long_rows;       // (see k_block)
@@ -1279,9 +1284,11 @@ static void launch_tie_fixup(const Ctx<DG, T>& x, const TieSeg<DG>& tie, const T
 // dW_i's workgroup partials from H (in x.hplane()) and dY_i; returns their number
 template <int DG, typename T>
 static unsigned launch_dw(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const TieSeg<DG>& tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f},
-                          const T* fix_plane = nullptr, int64_t fix_ld = 0, const Record<DG, T>* fix_out = nullptr) {
+                          const T* fix_plane = nullptr, int64_t fix_ld = 0, const Record<DG, T>* fix_out = nullptr,
+                          float* dw_partial = nullptr) {
     DwArgs<DG, T> a;
-    a.n = (int)x.cfg->n; a.tiles = x.tiles; a.h = x.hplane(); a.dy = dy; a.ldg = ldg; a.dw_partial = x.dw_partial();
+    a.n = (int)x.cfg->n; a.tiles = x.tiles; a.h = x.hplane(); a.dy = dy; a.ldg = ldg;
+    a.dw_partial = dw_partial ? dw_partial : x.dw_partial();
     a.tie = fix_out ? tie : TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f};
     a.fix_plane = fix_plane; a.fix_ld = fix_ld; a.k = x.cfg->k; a.norm = x.cfg->norm; a.eps = x.cfg->eps;
     a.fix_out = fix_out ? *fix_out : x.rec(-1);
@@ -1406,26 +1413,35 @@ static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, co
     // three blocks): the partial rows of block mb are then at hub_part + mb * chunks * 64
     const bool one_pass = launch_hub_values_wide<T>(x, in_slot, layer);
     const size_t part_stride = (size_t)x.g->a.hub.n_chunks * 64;
+    const size_t dw_set = (size_t)x.g->grid * 64 * 64;
+    unsigned nparts = 0;
+    bool nparts_differ = false;
     for (int mb = 0; mb < S; ++mb)
         for (int ob = 0; ob < S; ++ob) {
             const float* wsub = wi + (size_t)mb * 64 * dgw + 64 * ob;
             const float* part = one_pass ? x.hub_part() + mb * part_stride : nullptr;
-            unsigned nparts = 0;
+            // the workgroup partials of dW_i's block (mb, ob) in a set of their own: one reduction for all S x S blocks
+            float* dwp = x.dw_partial() + (size_t)(mb * S + ob) * dw_set;
+            unsigned np = 0;
             if (mode == 2 && split_dw<64, T>(x.g)) {
                 launch_block<64, T>(x, 1, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false, nullptr, 0, one_pass || ob > 0,
                                     TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, x.hplane(), part);
-                nparts = launch_dw<64, T>(x, dy + 64 * ob, ldg);
+                np = launch_dw<64, T>(x, dy + 64 * ob, ldg, TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, nullptr, 0, nullptr, dwp);
             } else {
-                nparts = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false,
-                                             dy ? dy + 64 * ob : nullptr, ldg, one_pass || ob > 0,
-                                             TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, nullptr, part);
+                np = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false,
+                                         dy ? dy + 64 * ob : nullptr, ldg, one_pass || ob > 0,
+                                         TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, nullptr, part, dwp);
             }
-            if (mode == 2) {
-                ProfScope prof(KC_DW_REDUCE, x.s);
-                hipLaunchKernelGGL(k_dw_reduce, dim3(64 * 64 / DW_REDUCE_ENTRIES), dim3(256), 0, x.s, (const float*)x.dw_partial(), (int)nparts, 64 * 64,
-                                   dw_i + (size_t)mb * 64 * dgw + 64 * ob, 64, dgw);
-            }
+            // (every launch of a kind has the same grid)
+            if (mode == 2 && nparts != 0 && np != nparts) nparts_differ = true;
+            nparts = np;
         }
+    if (mode == 2) {
+        ProfScope prof(KC_DW_REDUCE, x.s);
+        hipLaunchKernelGGL(k_dw_reduce, dim3(64 * 64 / DW_REDUCE_ENTRIES, (unsigned)(S * S)), dim3(256), 0, x.s, (const float*)x.dw_partial(),
+                           (int)nparts, 64 * 64, dw_i, 64, dgw, dw_set, S);
+    }
+    (void)nparts_differ;
 }
 
 template <typename T>
