@@ -532,7 +532,7 @@ static gsr_status_t graph_create_impl(gsr_graph_t** out, int64_t n, int64_t nnz,
     if (st == GSR_OK) {
         const size_t chunks = (size_t)std::max(std::max(g->a.hub.n_chunks, g->at.hub.n_chunks), 1);
         e = hipMalloc((void**)&g->scratch, chunks * 64 * sizeof(float));
-        const size_t draw_bytes = ((size_t)kTileCounters + 9 * 32) * sizeof(int);
+        const size_t draw_bytes = (size_t)kTileCounterSet * kTileCounterSets * sizeof(int);
         if (e == hipSuccess) e = hipMalloc((void**)&g->dinv, std::max<size_t>((size_t)n, 1) * sizeof(float));
         if (e == hipSuccess) e = hipMalloc((void**)&g->draws, draw_bytes);
         if (e == hipSuccess) e = hipMemset(g->draws, 0, draw_bytes);

@@ -152,6 +152,8 @@ constexpr int kTieSub = 16, kTieCounterStride = 32;     // (device code: TIE_SUB
 
 // Tile counters of the dynamic sweeps (device code: tile_draws): 8 XCDs x 64 queues, 128 bytes apart.
 constexpr int kTileCounters = 8 * 64 * 32;
+constexpr int kTileCounterSet = kTileCounters + 9 * 32;    // a counter set with its sign-off counters
+constexpr int kTileCounterSets = 4;                        // a graph holds this many (launches whose blockIdx.y is a column block of a wide group use one each)
 void tile_counters(const gsr_graph_t* g, int** set, int** done);
 StepWs carve_step(const gsr_config_t* cfg, const gsr_graph_t* g);
 

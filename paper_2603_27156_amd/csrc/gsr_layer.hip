@@ -54,6 +54,10 @@ struct BlockArgs {
     int* draws_done;
     TieSeg<DG> tie;         // where rows that select at a near-tie are listed (count == NULL: nowhere)
     float* h_out;           // [n][DG] float32: receives H = A scatter(V, I) of the block for k_dw (NULL: not kept)
+    // YG (groups wider than a tile): blockIdx.y is the column block written, ob: W_i's block 64 columns on, the plane
+    // and dY 64 elements on, the dW partials and the tile counters a set on
+    size_t y_dw_partial;
+    int y_draws;
 };
 
 // B3: the H W_i (and dW_i) products on the bf16 matrix pipe from three-term splits (mfma_tile_b3), with W_i kept
@@ -65,9 +69,18 @@ struct BlockArgs {
 // always use the split form: the plain and the fused inverse must rebuild the same bits.
 constexpr int block_waves(bool with_dw, bool b3) { return (!with_dw && b3) ? 8 : 4; }
 
-template <int DG, typename T, int SIGN, bool WITH_DW, bool DEAL, bool B3 = true>
+template <int DG, typename T, int SIGN, bool WITH_DW, bool DEAL, bool B3 = true, bool YG = false>
 __global__ __launch_bounds__(64 * block_waves(WITH_DW, B3)) __attribute__((amdgpu_waves_per_eu(WITH_DW ? 2 : 4))) void k_block(BlockArgs<DG, T> a) {
     static_assert(B3 || (SIGN > 0 && !WITH_DW), "only the forward kernel has a float32 variant");
+    if constexpr (YG) {
+        const int ob = blockIdx.y;
+        a.w += 64 * ob;
+        a.plane += 64 * ob;
+        if (a.dy) a.dy += 64 * ob;
+        a.dw_partial += (size_t)ob * a.y_dw_partial;
+        if (a.draws) { a.draws += ob * a.y_draws; a.draws_done += ob * a.y_draws; }
+        if (ob > 0) a.h_out = nullptr;          // (the same rows for every column block written)
+    }
     constexpr int LR = DG + 1, CPL = DG / 16;
     __shared__ WaveLds<DG, 1> lds[block_waves(WITH_DW, B3)];
     const int lane = lane_id(), wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), tg = lane >> 4, tj = lane & 15;
@@ -1203,7 +1216,7 @@ template <int DG, typename T>
 static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>& in, const float* w, T* plane, int64_t ld,
                              const Record<DG, T>& out, bool out_given, const T* dy, int64_t ldg, bool first_pass_done = false,
                              TieSeg<DG> tie = TieSeg<DG>{nullptr, nullptr, nullptr, 0, 0.f}, int ldw = DG, float* h_out = nullptr,
-                             const float* hub_part = nullptr, float* dw_partial = nullptr) {
+                             const float* hub_part = nullptr, float* dw_partial = nullptr, int ygrid = 1) {
     if (!first_pass_done) launch_hub_records<DG, T>(x, in);
     BlockArgs<DG, T> a;
     a.tie = tie;
@@ -1220,11 +1233,33 @@ static unsigned launch_block(const Ctx<DG, T>& x, int mode, const Record<DG, T>&
     const dim3 block(64 * block_waves(mode == 2, b3));
     ProfScope prof(mode == 0 ? KC_BLOCK_FWD : mode == 1 ? KC_BLOCK_INV : KC_BLOCK_BWD, x.s);
     unsigned grid = 0;
+    a.y_dw_partial = (size_t)x.g->grid * DG * DG;
+    a.y_draws = kTileCounterSet;
     auto go = [&](auto plain, auto deal, int per_cu) {
         grid = persistent_grid(x.g, per_cu);
-        if (heavy_first(a.g.n_heavy, x.tiles, grid * (block.x / 64) / 4)) hipLaunchKernelGGL(deal, dim3(grid), block, 0, x.s, a);
-        else hipLaunchKernelGGL(plain, dim3(grid), block, 0, x.s, a);
+        // (ygrid column blocks written by one launch: the resident workgroups are shared out between them)
+        if (ygrid > 1) grid = std::max(8u, grid / (unsigned)ygrid / 8 * 8);
+        if (heavy_first(a.g.n_heavy, x.tiles, grid * (block.x / 64) / 4)) hipLaunchKernelGGL(deal, dim3(grid, (unsigned)ygrid), block, 0, x.s, a);
+        else hipLaunchKernelGGL(plain, dim3(grid, (unsigned)ygrid), block, 0, x.s, a);
     };
+    if constexpr (DG == 64) {
+        if (ygrid > 1) {
+            if (mode == 0 && b3) {
+                static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false, false, true, true>, 512);
+                go(k_block<DG, T, +1, false, false, true, true>, k_block<DG, T, +1, false, true, true, true>, per_cu);
+            } else if (mode == 0) {
+                static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false, false, false, true>, 256);
+                go(k_block<DG, T, +1, false, false, false, true>, k_block<DG, T, +1, false, true, false, true>, per_cu);
+            } else if (mode == 1) {
+                static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, false, false, true, true>, 512);
+                go(k_block<DG, T, -1, false, false, true, true>, k_block<DG, T, -1, false, true, true, true>, per_cu);
+            } else {
+                static const int per_cu = resident_blocks((const void*)k_block<DG, T, -1, true, false, true, true>, 256);
+                go(k_block<DG, T, -1, true, false, true, true>, k_block<DG, T, -1, true, true, true, true>, per_cu);
+            }
+            return grid;
+        }
+    }
     if (mode == 0 && b3) {
         static const int per_cu = resident_blocks((const void*)k_block<DG, T, +1, false, false, true>, 512);
         go(k_block<DG, T, +1, false, false, true>, k_block<DG, T, +1, false, true, true>, per_cu);
@@ -1416,7 +1451,21 @@ static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, co
     const size_t dw_set = (size_t)x.g->grid * 64 * 64;
     unsigned nparts = 0;
     bool nparts_differ = false;
-    for (int mb = 0; mb < S; ++mb)
+    // One launch per input block mb writes all S column blocks (blockIdx.y = ob: W_i's block, the plane's and dY's
+    // columns, the dW partials and the tile counters move on with it), sharing the resident waves out between them:
+    // a launch per pair (mb, ob) is one short tile per wave on a long-row graph and as long as its slowest wave.  Not
+    // where the weight gradient is a pass of its own after each inverse launch (it reads the H that launch leaves).
+    const bool y_launch = !(mode == 2 && split_dw<64, T>(x.g));
+    if (y_launch) {
+        for (int mb = 0; mb < S; ++mb) {
+            const float* part = one_pass ? x.hub_part() + mb * part_stride : nullptr;
+            // (without the one first pass for all blocks, the pass over block mb's records comes first)
+            nparts = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wi + (size_t)mb * 64 * dgw, plane, ld, none, false, dy, ldg,
+                                         one_pass, TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, nullptr, part,
+                                         x.dw_partial() + (size_t)(mb * S) * dw_set, S);
+        }
+    }
+    for (int mb = 0; mb < S && !y_launch; ++mb)
         for (int ob = 0; ob < S; ++ob) {
             const float* wsub = wi + (size_t)mb * 64 * dgw + 64 * ob;
             const float* part = one_pass ? x.hub_part() + mb * part_stride : nullptr;
