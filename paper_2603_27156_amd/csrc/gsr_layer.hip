@@ -450,6 +450,8 @@ struct GradArgs {
     // dh [n][DG] float32 receives dH = Q W^T (dh_first) or has it added
     float* dh;
     bool dh_first;
+    // ACC: blockIdx.y is the block mb of dH written: W_i's block 64 rows on, dh a plane of [n][64] on, the tile counters a set on
+    int y_draws;
 };
 
 // dW_i[e] = sum over the workgroup partials, in a fixed order: a workgroup takes 64 entries at a time; its four
@@ -493,6 +495,13 @@ template <int DG, typename T, bool DEAL, bool B3, bool ACC = false>
 __global__ __launch_bounds__(64 * grad_waves(B3)) __attribute__((amdgpu_waves_per_eu(4))) void k_grad(GradArgs<DG, T> a) {
     constexpr int CPL = DG / 16;
     constexpr int GRAD_WAVES = grad_waves(B3);
+    if constexpr (ACC) {
+        const int mb = blockIdx.y;
+        a.w += (size_t)mb * 64 * a.ldw;
+        a.dh += (size_t)mb * a.n * 64;
+        a.draws += mb * a.y_draws;
+        a.draws_done += mb * a.y_draws;
+    }
     // the partial rows of a tile's split rows requested together (hub_rows_fill) only where that spills no register:
     // these kernels sit at their 128 registers
     constexpr bool FILL_FAST = ACC || (!DEAL && sizeof(T) == 4 && DG == 64);
@@ -1342,7 +1351,7 @@ static unsigned launch_dw(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const T
 // dH_mb (+)= (A^T dY_ob) W_i[mb][ob]^T: the gradient kernel without its epilogue (always the bf16-pipe variant)
 template <typename T>
 static void launch_grad_acc(const Ctx<64, T>& x, const T* dy, int64_t ldg, const float* w, int ldw, float* dh, bool first,
-                            bool first_pass_done) {
+                            bool first_pass_done, int ygrid = 1) {
     if (!first_pass_done) launch_hub_dense<64, T>(x, dy, ldg);
     GradArgs<64, T> a;
     a.gt = make_view(x.g, true);
@@ -1352,12 +1361,15 @@ static void launch_grad_acc(const Ctx<64, T>& x, const T* dy, int64_t ldg, const
     a.dst = nullptr; a.ldd = 0; a.dst_gs = 0; a.ndst = 0;
     a.dw_partial = nullptr; a.dw_parts = 0; a.dw_out = nullptr;
     a.dh = dh; a.dh_first = first;
+    a.y_draws = kTileCounterSet;
     tile_counters(x.g, &a.draws, &a.draws_done);
     ProfScope prof(KC_GRAD, x.s);
     static const int per_cu = resident_blocks((const void*)k_grad<64, T, false, true, true>, 512);
-    const unsigned grid = persistent_grid(x.g, per_cu);
-    if (heavy_first(a.gt.n_heavy, x.tiles, grid * 2)) hipLaunchKernelGGL((k_grad<64, T, true, true, true>), dim3(grid), dim3(512), 0, x.s, a);
-    else hipLaunchKernelGGL((k_grad<64, T, false, true, true>), dim3(grid), dim3(512), 0, x.s, a);
+    unsigned grid = persistent_grid(x.g, per_cu);
+    // (ygrid blocks of dH from one launch, blockIdx.y = mb: the resident workgroups are shared out between them)
+    if (ygrid > 1) grid = std::max(8u, grid / (unsigned)ygrid / 8 * 8);
+    if (heavy_first(a.gt.n_heavy, x.tiles, grid * 2)) hipLaunchKernelGGL((k_grad<64, T, true, true, true>), dim3(grid, (unsigned)ygrid), dim3(512), 0, x.s, a);
+    else hipLaunchKernelGGL((k_grad<64, T, false, true, true>), dim3(grid, (unsigned)ygrid), dim3(512), 0, x.s, a);
 }
 
 // GS over the whole rows of a wide group (sum of nsrc groups first when nsrc > 1), records of slot `slot`
@@ -1542,10 +1554,9 @@ static void wide_backward(const Ctx<64, T>& x, const float* w, const Planes<T>& 
             launch_gs_wide<T>(x, y.grp(i - 1), y.ld, y.gs, 1, nullptr, 0, layer, given);      // X_2 = Y_0 of this layer
         }
         // dH_mb = sum_ob (A^T dY_i[:, ob]) W_i[mb][ob]^T, then back through GS of the whole row
+        // (one launch per column block ob of dY_i for all S blocks of dH: blockIdx.y = mb)
         for (int ob = 0; ob < S; ++ob)
-            for (int mb = 0; mb < S; ++mb)
-                launch_grad_acc<T>(x, dy.grp(i - 1) + 64 * ob, dy.ld, wi + (size_t)mb * 64 * dgw + 64 * ob, dgw, x.dh() + (size_t)mb * n * 64,
-                                   ob == 0, mb > 0);
+            launch_grad_acc<T>(x, dy.grp(i - 1) + 64 * ob, dy.ld, wi + 64 * ob, dgw, x.dh(), ob == 0, false, S);
         if (i >= 2) launch_epi_wide<T>(x, i - 1, layer, z, ldz, z_sub, dy.grp(i - 2), dy.ld, dy.gs, 1);
         else launch_epi_wide<T>(x, 0, layer, z, ldz, z_sub, dy.grp(1), dy.ld, dy.gs, C - 1);
     }
