@@ -1449,60 +1449,47 @@ static bool launch_hub_values_wide(const Ctx<64, T>& x, int in_slot, int layer) 
     }
 }
 
-// plane (+/-)= f_i(Y_{i-1}) for one group: S x S launches of the 64-column block kernel.  mode as launch_block;
-// dw_i (mode 2): D/C x D/C, receives dW_i block by block.
+// plane (+/-)= f_i(Y_{i-1}) for one group: the S x S products of 64 x 64 blocks as S launches of the 64-column block
+// kernel.  mode as launch_block; dw_i (mode 2): D/C x D/C, receives dW_i.
 template <typename T>
 static void wide_block(const Ctx<64, T>& x, int mode, int in_slot, int layer, const float* wi, T* plane, int64_t ld, const T* dy,
                        int64_t ldg, float* dw_i) {
     const int S = x.S, dgw = 64 * S;
     const Record<64, T> none = x.rec(-1);
+    const TieSeg<64> no_tie{nullptr, nullptr, nullptr, 0, 0.f};
     // the first pass over the records of all S column blocks at once where it runs value by value (float32, two or
     // three blocks): the partial rows of block mb are then at hub_part + mb * chunks * 64
     const bool one_pass = launch_hub_values_wide<T>(x, in_slot, layer);
     const size_t part_stride = (size_t)x.g->a.hub.n_chunks * 64;
     const size_t dw_set = (size_t)x.g->grid * 64 * 64;
     unsigned nparts = 0;
-    bool nparts_differ = false;
     // One launch per input block mb writes all S column blocks (blockIdx.y = ob: W_i's block, the plane's and dY's
     // columns, the dW partials and the tile counters move on with it), sharing the resident waves out between them:
-    // a launch per pair (mb, ob) is one short tile per wave on a long-row graph and as long as its slowest wave.  Not
-    // where the weight gradient is a pass of its own after each inverse launch (it reads the H that launch leaves).
-    const bool y_launch = !(mode == 2 && split_dw<64, T>(x.g));
-    if (y_launch) {
-        for (int mb = 0; mb < S; ++mb) {
-            const float* part = one_pass ? x.hub_part() + mb * part_stride : nullptr;
-            // (without the one first pass for all blocks, the pass over block mb's records comes first)
-            nparts = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wi + (size_t)mb * 64 * dgw, plane, ld, none, false, dy, ldg,
-                                         one_pass, TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, nullptr, part,
-                                         x.dw_partial() + (size_t)(mb * S) * dw_set, S);
+    // a launch per pair (mb, ob) is one short tile per wave on a long-row graph and as long as its slowest wave.
+    // (Without the one first pass for all blocks, the pass over block mb's records comes first, inside launch_block.)
+    const bool split = mode == 2 && split_dw<64, T>(x.g);
+    for (int mb = 0; mb < S; ++mb) {
+        const float* part = one_pass ? x.hub_part() + mb * part_stride : nullptr;
+        const float* wmb = wi + (size_t)mb * 64 * dgw;
+        if (split) {
+            // the inverse of all column blocks, leaving H_mb (written once, by the workgroups of ob = 0), then dW_i's
+            // blocks (mb, ob) = H_mb^T dY_i[:, ob], a pass over H_mb each, into partial sets of their own
+            launch_block<64, T>(x, 1, x.rec(in_slot, layer, mb), wmb, plane, ld, none, false, nullptr, 0, one_pass, no_tie, dgw,
+                                x.hplane(), part, nullptr, S);
+            for (int ob = 0; ob < S; ++ob)
+                nparts = launch_dw<64, T>(x, dy + 64 * ob, ldg, no_tie, nullptr, 0, nullptr,
+                                          x.dw_partial() + (size_t)(mb * S + ob) * dw_set);
+        } else {
+            nparts = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wmb, plane, ld, none, false, dy, ldg, one_pass, no_tie,
+                                         dgw, nullptr, part, x.dw_partial() + (size_t)(mb * S) * dw_set, S);
         }
     }
-    for (int mb = 0; mb < S && !y_launch; ++mb)
-        for (int ob = 0; ob < S; ++ob) {
-            const float* wsub = wi + (size_t)mb * 64 * dgw + 64 * ob;
-            const float* part = one_pass ? x.hub_part() + mb * part_stride : nullptr;
-            // the workgroup partials of dW_i's block (mb, ob) in a set of their own: one reduction for all S x S blocks
-            float* dwp = x.dw_partial() + (size_t)(mb * S + ob) * dw_set;
-            unsigned np = 0;
-            if (mode == 2 && split_dw<64, T>(x.g)) {
-                launch_block<64, T>(x, 1, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false, nullptr, 0, one_pass || ob > 0,
-                                    TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, x.hplane(), part);
-                np = launch_dw<64, T>(x, dy + 64 * ob, ldg, TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, nullptr, 0, nullptr, dwp);
-            } else {
-                np = launch_block<64, T>(x, mode, x.rec(in_slot, layer, mb), wsub, plane + 64 * ob, ld, none, false,
-                                         dy ? dy + 64 * ob : nullptr, ldg, one_pass || ob > 0,
-                                         TieSeg<64>{nullptr, nullptr, nullptr, 0, 0.f}, dgw, nullptr, part, dwp);
-            }
-            // (every launch of a kind has the same grid)
-            if (mode == 2 && nparts != 0 && np != nparts) nparts_differ = true;
-            nparts = np;
-        }
+    // dW_i: its S x S blocks from their partial sets in one launch (every launch of a kind has the same grid)
     if (mode == 2) {
         ProfScope prof(KC_DW_REDUCE, x.s);
         hipLaunchKernelGGL(k_dw_reduce, dim3(64 * 64 / DW_REDUCE_ENTRIES, (unsigned)(S * S)), dim3(256), 0, x.s, (const float*)x.dw_partial(),
                            (int)nparts, 64 * 64, dw_i, 64, dgw, dw_set, S);
     }
-    (void)nparts_differ;
 }
 
 template <typename T>
