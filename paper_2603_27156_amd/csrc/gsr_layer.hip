@@ -287,11 +287,59 @@ __device__ __forceinline__ void tie_fixup_rows(const TieSeg<DG>& tie, const T* _
     }
 }
 
+// dW_i[e] = sum over workgroup partials, as a launch of its own (used when the gradient kernel that follows has too
+// few tiles per wave to absorb the work, see layer_backward_impl).  A block of 256 threads owns 16 entries; its 16
+// thread rows each sum a contiguous sixteenth of the partials in ascending order, then the 16 sums are added in order.
+// (Blocks of 64 entries left three quarters of the compute units idle on a 64 x 64 matrix: 18 us per launch.)
+constexpr int DW_REDUCE_ENTRIES = 16;
+__device__ __forceinline__ void dw_reduce_block(int block, const float* __restrict__ partial, int nparts, int elems,
+                                                float* __restrict__ out, int cols, int ld_out) {
+    __shared__ float red[16][DW_REDUCE_ENTRIES];
+    const int j = threadIdx.x & (DW_REDUCE_ENTRIES - 1), seg = threadIdx.x / DW_REDUCE_ENTRIES;
+    const int e = block * DW_REDUCE_ENTRIES + j;
+    const int per = (nparts + 15) / 16, p0 = seg * per, p1 = min(nparts, p0 + per);
+    float acc = 0.f;
+    if (e < elems) {
+        int p = p0;
+        for (; p + 8 <= p1; p += 8) {           // eight loads in flight, added in ascending order
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(p + u) * elems + e];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; p < p1; ++p) acc += partial[(size_t)p * elems + e];
+    }
+    red[seg][j] = acc;
+    __syncthreads();
+    if (seg == 0 && e < elems) {
+        float s = red[0][j];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) s += red[q][j];
+        out[(size_t)(e / cols) * ld_out + e % cols] = s;       // entry (e / cols, e % cols) of a matrix of row stride ld_out
+    }
+}
+
+// What a launch of k_tie_fixup may take along: the reduction of dW_i's workgroup partials (its workgroups from
+// fix_blocks on do that; out == NULL: nothing), which saves a launch per block on small graphs.
+struct DwReduceJob {
+    const float* partial;
+    int nparts, elems;
+    float* out;
+    int cols, ld_out;
+    int fix_blocks;
+};
+
 template <int DG, typename T>
 __global__ __launch_bounds__(256) void k_tie_fixup(TieSeg<DG> tie, const T* __restrict__ plane, int64_t ld, int k, int norm,
-                                                   float eps, Record<DG, T> out) {
+                                                   float eps, Record<DG, T> out, DwReduceJob red) {
+    if (red.out && (int)blockIdx.x >= red.fix_blocks) {
+        dw_reduce_block((int)blockIdx.x - red.fix_blocks, red.partial, red.nparts, red.elems, red.out, red.cols, red.ld_out);
+        return;
+    }
+    const int blocks = red.out ? red.fix_blocks : (int)gridDim.x;
     tie_fixup_rows<DG, T>(tie, plane, ld, k, norm, eps, out, (int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6),
-                          (int)((gridDim.x * blockDim.x) >> 6));
+                          (int)((blocks * blockDim.x) >> 6));
 }
 
 // dW_i = H^T dY_i as a pass of its own over H (left by the inverse kernel) and dY_i: a wave sums over the tiles of a
@@ -382,11 +430,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     for (int i = threadIdx.x; i < DG * DG; i += 256) a.dw_partial[(size_t)blockIdx.x * DG * DG + i] = red[i];
 }
 
-// dW_i[e] = sum over workgroup partials, as a launch of its own (used when the gradient kernel that follows has too
-// few tiles per wave to absorb the work, see layer_backward_impl).  A block of 256 threads owns 16 entries; its 16
-// thread rows each sum a contiguous sixteenth of the partials in ascending order, then the 16 sums are added in order.
-// (Blocks of 64 entries left three quarters of the compute units idle on a 64 x 64 matrix: 18 us per launch.)
-constexpr int DW_REDUCE_ENTRIES = 16;
 // blockIdx.y (groups wider than a tile: the S x S blocks of dW_i in one launch): set y of the partials starts
 // y * set_stride floats on, and goes to block (y / sets_per_row, y % sets_per_row) of the output, 64 rows and 64 columns apart.
 __global__ __launch_bounds__(256) void k_dw_reduce(const float* __restrict__ partial, int nparts, int elems,
@@ -394,30 +437,7 @@ __global__ __launch_bounds__(256) void k_dw_reduce(const float* __restrict__ par
                                                    int sets_per_row = 1) {
     partial += (size_t)blockIdx.y * set_stride;
     out += (size_t)(blockIdx.y / sets_per_row) * 64 * ld_out + (size_t)(blockIdx.y % sets_per_row) * 64;
-    __shared__ float red[16][DW_REDUCE_ENTRIES];
-    const int j = threadIdx.x & (DW_REDUCE_ENTRIES - 1), seg = threadIdx.x / DW_REDUCE_ENTRIES;
-    const int e = blockIdx.x * DW_REDUCE_ENTRIES + j;
-    const int per = (nparts + 15) / 16, p0 = seg * per, p1 = min(nparts, p0 + per);
-    float acc = 0.f;
-    if (e < elems) {
-        int p = p0;
-        for (; p + 8 <= p1; p += 8) {           // eight loads in flight, added in ascending order
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(p + u) * elems + e];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc += v[u];
-        }
-        for (; p < p1; ++p) acc += partial[(size_t)p * elems + e];
-    }
-    red[seg][j] = acc;
-    __syncthreads();
-    if (seg == 0 && e < elems) {
-        float s = red[0][j];
-#pragma unroll
-        for (int q = 1; q < 16; ++q) s += red[q][j];
-        out[(size_t)(e / cols) * ld_out + e % cols] = s;       // entry (e / cols, e % cols) of a matrix of row stride ld_out
-    }
+    dw_reduce_block((int)blockIdx.x, partial, nparts, elems, out, cols, ld_out);
 }
 
 // ---- block: data gradient ---------------------------------------------------------------------------
@@ -1318,11 +1338,21 @@ static void launch_grad(const Ctx<DG, T>& x, const T* dy, int64_t ldg, const flo
 // After a record was taken again from rebuilt rows during the inverse sweep: the rows listed for that application of
 // GS in the forward sweep get their kept column sets back (values from the same rebuilt rows).
 template <int DG, typename T>
-static void launch_tie_fixup(const Ctx<DG, T>& x, const TieSeg<DG>& tie, const T* plane, int64_t ld, const Record<DG, T>& out) {
-    if (!tie.count) return;
+// (red: a reduction of dW_i's partials for the launch to take along, or NULL; returns whether it was taken)
+static bool launch_tie_fixup(const Ctx<DG, T>& x, const TieSeg<DG>& tie, const T* plane, int64_t ld, const Record<DG, T>& out,
+                             const DwReduceJob* red = nullptr) {
+    if (!tie.count) return false;
     ProfScope prof(KC_TIE, x.s);
     const unsigned blocks = (unsigned)std::min((TIE_SUB * tie.cap + 63) / 64 / 4 * 4 + 4, 1024);     // 4 waves each: a multiple of TIE_SUB waves
-    hipLaunchKernelGGL((k_tie_fixup<DG, T>), dim3(blocks), dim3(256), 0, x.s, tie, plane, ld, x.cfg->k, x.cfg->norm, x.cfg->eps, out);
+    DwReduceJob job{nullptr, 0, 0, nullptr, 0, 0, 0};
+    unsigned more = 0;
+    if (red) {
+        job = *red;
+        job.fix_blocks = (int)blocks;
+        more = (unsigned)((job.elems + DW_REDUCE_ENTRIES - 1) / DW_REDUCE_ENTRIES);
+    }
+    hipLaunchKernelGGL((k_tie_fixup<DG, T>), dim3(blocks + more), dim3(256), 0, x.s, tie, plane, ld, x.cfg->k, x.cfg->norm, x.cfg->eps, out, job);
+    return red != nullptr;
 }
 
 // dW_i's workgroup partials from H (in x.hplane()) and dY_i; returns their number
@@ -1622,6 +1652,8 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
         }
         launch_hub_both<DG, T>(x, x.rec(i - 1, layer), dy.grp(i - 1), dy.ld);
         unsigned nparts;
+        const bool own_reduce = x.tiles < 4 * 4 * x.g->grid;
+        bool dw_reduced = false;
         if (split_dw<DG, T>(x.g)) {
             // X_i = Y_i - f_i(Y_{i-1}) with H kept for the weight gradient, then dW_i = H^T dY_i
             launch_block<DG, T>(x, 1, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, nullptr, 0, true,
@@ -1629,13 +1661,17 @@ static void layer_backward_impl(const Ctx<DG, T>& x, const float* w, const Plane
             nparts = launch_dw<DG, T>(x, dy.grp(i - 1), dy.ld, out_tie, y.grp(i - 1), y.ld, out.mask ? &out : nullptr);
         } else {
             nparts = launch_block<DG, T>(x, 2, x.rec(i - 1, layer), wi, y.grp(i - 1), y.ld, out, given, dy.grp(i - 1), dy.ld, true);
-            if (out.mask) launch_tie_fixup<DG, T>(x, out_tie, y.grp(i - 1), y.ld, out);
+            // (on a small graph the launch that restores the listed rows' column sets also sums dW_i's partials)
+            const DwReduceJob job{x.dw_partial(), (int)nparts, DG * DG, dw_out + (size_t)(i - 1) * DG * DG, DG, DG, 0};
+            if (out.mask) dw_reduced = launch_tie_fixup<DG, T>(x, out_tie, y.grp(i - 1), y.ld, out, own_reduce ? &job : nullptr);
         }
         // dW_i is summed from the partials by the first job of the gradient kernel that follows, unless that kernel
         // has so few tiles per wave that it could not make up for the late start of those workgroups (measured on
         // a 49,600-node graph with 3,100 tiles: +80 us on a 405 us kernel): then by a launch of its own
         float* dwi = dw_out + (size_t)(i - 1) * DG * DG;
-        if (x.tiles < 4 * 4 * x.g->grid) {
+        if (dw_reduced) {
+            dwi = nullptr;
+        } else if (own_reduce) {
             ProfScope prof(KC_DW_REDUCE, x.s);
             hipLaunchKernelGGL(k_dw_reduce, dim3((DG * DG + DW_REDUCE_ENTRIES - 1) / DW_REDUCE_ENTRIES), dim3(256), 0, x.s, (const float*)x.dw_partial(),
                                (int)nparts, DG * DG, dwi, DG, DG);
