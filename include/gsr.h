@@ -120,7 +120,7 @@ const char* gsr_version(void);
  *                     with more than 8,000 neighbours); 0, the default: 512; 64 or 16 on graphs with fewer than
  *                     four / two 16-row tiles per resident wave; 1 on graphs whose mean row has 64 stored entries or
  *                     more (every row of two entries or more then goes through the first pass)
- *   "hub_chunk"       neighbours per first-pass partial sum; 0, the default: 64, or 256 on graphs of long rows
+ *   "hub_chunk"       neighbours per first-pass partial sum; 0, the default: 64, or 512 on graphs of long rows
  *   "hub_values"      how the first pass sums float32 records (layer and step calls): 1 = a lane per record value,
  *                     through a byte per value naming its column that a small kernel writes from the masks first;
  *                     2 = a lane per group of columns, as the tile kernels do; 0, the default: 1 on graphs whose mean
