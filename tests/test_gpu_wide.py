@@ -167,3 +167,61 @@ def test_wide_groups_refuse_the_near_tie_list():
     with pytest.raises(gsr.GsrError) as e:
         run_step(cs, save_indices=2)
     assert e.value.status == gsr.GSR_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("long_rows", [False, True])
+def test_wide_step_replays_from_a_graph(long_rows):
+    """Groups of 192 columns: a launch's second grid dimension is the column block written, and each column block draws
+    its tiles from a counter set of its own, all of which a launch leaves clear.  A captured step must replay bit for
+    bit, on a sparse graph (weight gradient in a pass of its own on a small persistent grid) and on a graph of long
+    rows (one first pass for the three column blocks, fused inverse + dW)."""
+    if long_rows:
+        w = synth.scaled(synth.workload(5), 1200, levels=6, l=2, c=2, k=16)
+        cs = Case(w, 0, PLANAR)
+    else:
+        gsr.gsr_set_option("max_workgroups", 8)
+        try:
+            cs = wide_case(3001, 384, 2, 16, 2, "rms", PLANAR)
+        finally:
+            gsr.gsr_set_option("max_workgroups", 0)
+    cs.gcfg = gsr.Config(**{**cs.gcfg.__dict__, "save_indices": 1})
+    w, dv = cs.w, cs.dev
+    f32 = dict(dtype=torch.float32, device=dv)
+    x0 = cs.to_dev(cs.inp.x0)
+    W = torch.from_numpy(np.ascontiguousarray(cs.inp.weights[:w.l])).to(dv)
+    w_out = torch.from_numpy(cs.inp.w_out).to(dv)
+    b_out, target = torch.zeros(1, **f32), torch.from_numpy(cs.inp.target).to(dv)
+    ws = torch.empty(gsr.gsr_workspace_size(cs.gg, cs.gcfg)[1], dtype=torch.uint8, device=dv)
+
+    def buffers():
+        return dict(loss=torch.zeros(1, **f32), dW=torch.empty_like(W), dw=torch.empty(w.d, **f32), db=torch.zeros(1, **f32),
+                    dx0=torch.empty_like(x0), x0r=torch.empty_like(x0))
+
+    def step(b):
+        gsr.gsr_step(cs.gg, cs.gcfg, x0, W, w_out, b_out, target, b["loss"], b["dW"], b["dw"], b["db"], dx0_out=b["dx0"],
+                     x0_rebuilt_out=b["x0r"], workspace=ws)
+
+    eager = buffers()
+    step(eager)
+    torch.cuda.synchronize()
+    want = {k: v.clone() for k, v in eager.items()}
+    ref = oracle.step(cs.og, cs.ocfg, w.l, cs.x0_on_grid(), cs.inp.weights, cs.inp.w_out, cs.inp.b_out, cs.inp.target, variant=2)
+    assert_close("dW", want["dW"].cpu().numpy(), ref["dW"])
+    captured = buffers()
+    stream = torch.cuda.Stream()
+    stream.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            step(captured)
+    for rep in range(3):
+        for v in captured.values():
+            v.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in want:
+            assert torch.equal(captured[k], want[k]), (rep, k)
+        step(eager)                                   # eager work between the replays
+        torch.cuda.synchronize()
+        for k in want:
+            assert torch.equal(eager[k], want[k]), (rep, k)
